@@ -1,0 +1,179 @@
+/*
+ * distrifusion.h - C ABI of the displaced-patch hot path for AMD MI355X (gfx950).
+ *
+ * One device's view of displaced patch parallelism (DistriFusion, Section 4):
+ * the image is split into N horizontal patches; this device computes patch
+ * `patch_idx` fresh, and every layer that mixes information across space takes
+ * the context of the other patches from full-shape buffers of stale activations
+ * left by the previous denoising step.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  Inputs are
+ *     never modified; outputs are fully overwritten.  Activations are
+ *     channels-last: [B, rows, W, C], equivalently [B, tokens, C].
+ *   - `dtype` is DF_F32 or DF_BF16 and applies to activations and to matrix /
+ *     convolution weights.  Biases, norm scale/shift and statistics are float.
+ *     bf16 kernels accumulate in float.
+ *   - `stream` is a hipStream_t (0 = default stream).  Calls are asynchronous
+ *     on that stream and return after enqueueing.
+ *   - Patches: a full tensor of H rows is split into N strips of R = H / N
+ *     rows; patch i owns rows [i*R, (i+1)*R).  H % N must be 0.
+ *   - Return value: DF_OK, or a negative error; nothing is launched on error.
+ *     The library may keep a small per-device scratch allocation (GroupNorm
+ *     partial sums, split-K partials); it is created on first use.
+ *   - Calls on different streams must not share that scratch concurrently:
+ *     issue the library's calls for one device from one stream at a time.
+ */
+#ifndef DISTRIFUSION_H
+#define DISTRIFUSION_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { DF_F32 = 0, DF_BF16 = 1 };
+
+enum {
+  DF_OK = 0,
+  DF_EINVAL = -1, /* null pointer, bad enum value, misaligned pointer */
+  DF_ESHAPE = -2, /* shape the kernels do not support (H % N, C % G, head dim, ...) */
+  DF_EHIP = -3,   /* a HIP runtime call or launch failed */
+  DF_ENOMEM = -4  /* scratch or workspace too small / allocation failed */
+};
+
+/* GroupNorm statistic modes (Section 4, Corrected asynchronous GroupNorm; Section 5.3, GroupNorm) */
+enum {
+  DF_GN_SUMS = 0,     /* statistics of the scatter output: fresh own sums + stale sums of the other patches */
+  DF_GN_EQ2 = 1,      /* Eq. 2 as printed, with the negative-variance fallback to the fresh local variance */
+  DF_GN_SEPARATE = 2, /* fresh patch only ("Separate GN") */
+  DF_GN_STALE = 3     /* stale global statistics only ("Stale GN") */
+};
+
+enum { DF_MODE_FULL = 0, DF_MODE_DISPLACED = 1 };
+
+const char* df_strerror(int err);
+
+/*
+ * Stale-buffer refresh (Section 4: after a layer's fresh activation is known it
+ * replaces this patch's region of the full-shape buffer that the next step will
+ * read as stale; on several devices this is the local part of the AllGather).
+ *   dst_full  [B, full_elems_per_batch]   full-shape buffer (modified: rows of the patch only)
+ *   src_patch [B, full_elems_per_batch/N] the fresh patch
+ * Copies src_patch[b] to dst_full[b] at element offset patch_idx * full/N.
+ * full_elems_per_batch % N must be 0.  Source and destination must not overlap.
+ */
+int df_buffer_refresh(void* dst_full, const void* src_patch, int B, long long full_elems_per_batch,
+                      int patch_idx, int N, int dtype, void* stream);
+
+/*
+ * Corrected asynchronous GroupNorm of one patch (Section 4, Eq. 2).
+ *   x_fresh         [B, R, W, C]  fresh patch
+ *   y               [B, R, W, C]  normalised output, same dtype
+ *   stale_stats     [N, B, G, 2]  float: per patch (sum, sum of squares) cached from the previous step
+ *   fresh_stats_out [B, G, 2]     float: this patch's fresh (sum, sum of squares); may be NULL.
+ *                                 May point at stale_stats + patch_idx*B*G*2 to refresh in place.
+ *   gamma, beta     [C]           float
+ * Statistics are combined according to stat_mode (DF_GN_*), variance is biased,
+ * y = (x - mean) * rsqrt(var + eps) * gamma + beta, then SiLU if fuse_silu.
+ * C % G == 0; C % 8 == 0 (bf16) or C % 4 == 0 (f32).
+ */
+int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out,
+                       const float* gamma, const float* beta, int B, int R, int W, int C, int G,
+                       int patch_idx, int N, float eps, int stat_mode, int fuse_silu, int dtype, void* stream);
+
+/*
+ * Sparse 3x3 convolution of one patch (Section 4, Sparse operations; Section 5.3:
+ * only the rows at the patch boundary come from other patches).
+ *   x_fresh    [B, R, W, Cin]      fresh input rows s..e-1, R = H/N, s = patch_idx*R
+ *   stale_full [B, H, W, Cin]      stale full-shape input; only rows s-1 and e are read
+ *                                  (zero beyond the image).  May be NULL when N == 1.
+ *   w          [Cout, 3, 3, Cin]   dtype
+ *   bias       [Cout] float, may be NULL
+ *   y          [B, R/stride, W/stride, Cout]
+ * Zero padding 1; stride 1 or 2 (then R and W must be even; only the row above
+ * the patch is needed).  act: 0 none, 1 SiLU.
+ */
+int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y,
+                    int B, int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act,
+                    int dtype, void* stream);
+
+/*
+ * Self-attention as cross-attention of the fresh queries against the whole
+ * feature map (Section 4, Sparse operations): keys/values of the patch's own
+ * token rows [patch_idx*Lq, (patch_idx+1)*Lq) are read from k_fresh/v_fresh, all
+ * other rows from the stale buffers.  Lq = L / N.
+ *   q, k_fresh, v_fresh [B, Lq, heads*d]
+ *   k_stale, v_stale    [B, L,  heads*d]   may be NULL when N == 1
+ *   out                 [B, Lq, heads*d]
+ * out = softmax(q k^T * scale) v per head, no mask.  d is 64 for DF_BF16,
+ * at most 128 for DF_F32.
+ */
+int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
+                      const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
+                      float scale, int dtype, void* stream);
+
+/* ---- whole UNet step --------------------------------------------------------------------- */
+
+typedef struct df_unet_cfg {
+  int H, W;          /* full latent size */
+  int N;             /* number of row patches */
+  int B;             /* batch */
+  int in_ch;         /* latent channels */
+  int n_levels;      /* <= 4 */
+  int levels[4];     /* channels per level */
+  int depths[4];     /* transformer depth per level (0: no attention) */
+  int head_dim;      /* 64 */
+  int groups;        /* GroupNorm groups */
+  int emb_dim;       /* width of the conditioning embedding vector */
+  int text_len, text_dim;
+  int res_per_level; /* residual blocks per down level (up levels have one more) */
+} df_unet_cfg;
+
+typedef struct df_unet df_unet;
+
+/* Parameter list the plan expects, in order.  Matrices and conv kernels (ndim 2 or 4) are bf16,
+ * vectors (ndim 1) are float.  Returns the count / fills one entry; DF_EINVAL if idx is out of range. */
+int df_unet_num_weights(const df_unet_cfg* cfg);
+int df_unet_weight_info(const df_unet_cfg* cfg, int idx, char* name, int name_cap, int* ndim, long long dims[4]);
+
+/* Bytes of device workspace (activations of one step in either mode) and of the stale-state blob. */
+size_t df_unet_workspace_bytes(const df_unet_cfg* cfg);
+size_t df_unet_stale_bytes(const df_unet_cfg* cfg);
+
+/* Builds the execution plan.  `weights[i]` are device pointers in df_unet_weight_info order and must
+ * outlive the plan; `workspace` is device memory of at least df_unet_workspace_bytes, 256-byte aligned. */
+int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* weights, int n_weights,
+                   void* workspace, size_t workspace_bytes);
+void df_unet_destroy(df_unet* u);
+
+/* Location of one named stale buffer inside the blob (tests and tools).  Names: "<conv>.in" (boundary
+ * rows [B, N, 2, W, Cin] bf16: first and last input row of every patch), "<attn>.k", "<attn>.v"
+ * ([B, L, C] bf16), "<gn>.stats" ([N, B, G, 2] float). */
+int df_unet_stale_lookup(const df_unet* u, const char* name, size_t* offset, size_t* bytes);
+int df_unet_num_stale(const df_unet* u);
+int df_unet_stale_name(const df_unet* u, int idx, char* name, int name_cap);
+
+/*
+ * One UNet forward for one patch (Section 4; Section 3, Eq. 1: eps = eps_theta(x_t, t, c)).
+ *   mode DF_MODE_FULL       x [B, H, W, in_ch] float: the synchronous first step on the whole image;
+ *                           fills every stale buffer.  patch_idx is ignored.
+ *   mode DF_MODE_DISPLACED  x [B, H/N, W, in_ch] float: patch `patch_idx` with stale context; if
+ *                           `refresh`, the patch's own rows of every stale buffer are overwritten.
+ *   emb [B, emb_dim] float, text [B, text_len, text_dim] bf16, stale: blob of df_unet_stale_bytes,
+ *   eps_out: float, same shape as x.
+ */
+int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* text, void* stale,
+                       void* eps_out, int patch_idx, int mode, int refresh, void* stream);
+
+/* Sampler update on the patch's latent rows (Section 3, Eq. 1; Euler step): x += (sigma_next - sigma) * eps. */
+int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream);
+
+/* Plain device-to-device copy of `bytes` bytes with the refresh kernel (bandwidth calibration). */
+int df_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

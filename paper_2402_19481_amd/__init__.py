@@ -1,0 +1,242 @@
+"""Thin Python binding of libdistrifusion.so (hand-written HIP for MI355X / gfx950).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, passes their device pointers and the current HIP stream to
+the C entry point of the same name, and raises on a non-zero return code.
+PyTorch provides device memory and streams, nothing else.  There is no
+fallback: if the shared library is missing or not built, importing a function
+raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdistrifusion.so")
+
+DF_F32, DF_BF16 = 0, 1
+GN_SUMS, GN_EQ2, GN_SEPARATE, GN_STALE = 0, 1, 2, 3
+MODE_FULL, MODE_DISPLACED = 0, 1
+
+_lib = None
+
+
+class DfError(RuntimeError):
+    pass
+
+
+class UNetCfgC(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int), ("W", ctypes.c_int), ("N", ctypes.c_int), ("B", ctypes.c_int),
+                ("in_ch", ctypes.c_int), ("n_levels", ctypes.c_int), ("levels", ctypes.c_int * 4),
+                ("depths", ctypes.c_int * 4), ("head_dim", ctypes.c_int), ("groups", ctypes.c_int),
+                ("emb_dim", ctypes.c_int), ("text_len", ctypes.c_int), ("text_dim", ctypes.c_int),
+                ("res_per_level", ctypes.c_int)]
+
+
+def lib():
+    """Loads the shared library once; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise DfError(f"{LIB_PATH} not found: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, f, ll, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_longlong, ctypes.c_size_t
+    L.df_strerror.restype = ctypes.c_char_p
+    L.df_strerror.argtypes = [i]
+    L.df_copy_bytes.argtypes = [vp, vp, sz, vp]
+    L.df_buffer_refresh.argtypes = [vp, vp, i, ll, i, i, i, vp]
+    L.df_groupnorm_stale.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, i, i, vp]
+    L.df_conv3x3_halo.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]
+    L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
+    L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
+    cfgp = ctypes.POINTER(UNetCfgC)
+    if not hasattr(L, "df_patch_unet_step"):
+        raise DfError("libdistrifusion.so is stale: rebuild it")
+    L.df_unet_num_weights.argtypes = [cfgp]
+    L.df_unet_weight_info.argtypes = [cfgp, i, ctypes.c_char_p, i, ctypes.POINTER(i), ctypes.POINTER(ll)]
+    L.df_unet_workspace_bytes.restype = sz
+    L.df_unet_workspace_bytes.argtypes = [cfgp]
+    L.df_unet_stale_bytes.restype = sz
+    L.df_unet_stale_bytes.argtypes = [cfgp]
+    L.df_unet_create.argtypes = [ctypes.POINTER(vp), cfgp, ctypes.POINTER(vp), i, vp, sz]
+    L.df_unet_destroy.restype = None
+    L.df_unet_destroy.argtypes = [vp]
+    L.df_unet_stale_lookup.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.df_unet_num_stale.argtypes = [vp]
+    L.df_unet_stale_name.argtypes = [vp, i, ctypes.c_char_p, i]
+    L.df_patch_unet_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
+    for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
+                 "df_euler_update", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step"):
+        getattr(L, name).restype = i
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise DfError(f"libdistrifusion: {lib().df_strerror(rc).decode()} ({rc})")
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return DF_F32
+    if t.dtype == torch.bfloat16:
+        return DF_BF16
+    raise DfError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise DfError("tensors must be contiguous and on the GPU")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def copy_bytes(dst, src):
+    _check(lib().df_copy_bytes(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream()))
+
+
+def buffer_refresh(dst_full, src_patch, patch_idx, N):
+    """dst_full [B, ...full...] <- src_patch [B, ...full/N...] at the patch's region (in place)."""
+    B = dst_full.shape[0]
+    _check(lib().df_buffer_refresh(_ptr(dst_full), _ptr(src_patch), B, dst_full.numel() // B, patch_idx, N,
+                                   _dt(dst_full), _stream()))
+    return dst_full
+
+
+def groupnorm_stale(x_fresh, stale_stats, gamma, beta, G, patch_idx, N, eps=1e-5, stat_mode=GN_SUMS,
+                    fuse_silu=False, fresh_stats_out=None):
+    """Returns (y, fresh_stats [B,G,2])."""
+    B, R, W, C = x_fresh.shape
+    y = torch.empty_like(x_fresh)
+    if fresh_stats_out is None:
+        fresh_stats_out = torch.empty(B, G, 2, dtype=torch.float32, device=x_fresh.device)
+    _check(lib().df_groupnorm_stale(_ptr(x_fresh), _ptr(y), _ptr(stale_stats), _ptr(fresh_stats_out), _ptr(gamma),
+                                    _ptr(beta), B, R, W, C, G, patch_idx, N, eps, stat_mode, int(fuse_silu),
+                                    _dt(x_fresh), _stream()))
+    return y, fresh_stats_out
+
+
+def conv3x3_halo(x_fresh, stale_full, w, bias, patch_idx, N, stride=1, act=0):
+    B, R, W, Cin = x_fresh.shape
+    Cout = w.shape[0]
+    H = R * N
+    y = torch.empty(B, R // stride, W // stride, Cout, dtype=x_fresh.dtype, device=x_fresh.device)
+    _check(lib().df_conv3x3_halo(_ptr(x_fresh), _ptr(stale_full), _ptr(w), _ptr(bias), _ptr(y), B, H, W, Cin, Cout,
+                                 patch_idx, N, stride, act, _dt(x_fresh), _stream()))
+    return y
+
+
+def attn_displaced(q, k_fresh, v_fresh, k_stale, v_stale, heads, patch_idx, N, scale=None, out=None):
+    B, Lq, C = q.shape
+    d = C // heads
+    L = Lq * N
+    if scale is None:
+        scale = d ** -0.5
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib().df_attn_displaced(_ptr(q), _ptr(k_fresh), _ptr(v_fresh), _ptr(k_stale), _ptr(v_stale), _ptr(out), B,
+                                   L, heads, d, patch_idx, N, scale, _dt(q), _stream()))
+    return out
+
+
+def euler_update(x, eps, sigma, sigma_next):
+    _check(lib().df_euler_update(_ptr(x), _ptr(eps), sigma, sigma_next, x.numel(), _stream()))
+    return x
+
+
+def make_cfg(cfg, B=1):
+    """df_inputs.unet_table.UNetCfg (or anything with the same fields) -> C struct."""
+    c = UNetCfgC()
+    c.H, c.W, c.N, c.B, c.in_ch = cfg.H, cfg.W, cfg.N, B, cfg.in_ch
+    c.n_levels = len(cfg.levels)
+    for k in range(c.n_levels):
+        c.levels[k] = cfg.levels[k]
+        c.depths[k] = cfg.depths[k]
+    c.head_dim, c.groups, c.emb_dim = cfg.head_dim, cfg.groups, cfg.emb_dim
+    c.text_len, c.text_dim, c.res_per_level = cfg.text_len, cfg.text_dim, cfg.res_per_level
+    return c
+
+
+def unet_weight_specs(ccfg):
+    """[(name, shape)] of the parameters the plan expects, in order."""
+    L = lib()
+    n = L.df_unet_num_weights(ctypes.byref(ccfg))
+    if n < 0:
+        _check(n)
+    out = []
+    buf = ctypes.create_string_buffer(128)
+    nd = ctypes.c_int()
+    dims = (ctypes.c_longlong * 4)()
+    for k in range(n):
+        _check(L.df_unet_weight_info(ctypes.byref(ccfg), k, buf, 128, ctypes.byref(nd), dims))
+        out.append((buf.value.decode(), tuple(int(dims[j]) for j in range(nd.value))))
+    return out
+
+
+class PatchUNet:
+    """Owns the plan, its workspace and the stale-state blob of one UNet on one GPU."""
+
+    def __init__(self, cfg, weights, B=1, device="cuda:0"):
+        """weights: list of device tensors in `unet_weight_specs` order (bf16 matrices, float vectors)."""
+        L = lib()
+        self.cfg, self.ccfg, self.B = cfg, make_cfg(cfg, B), B
+        self.device = torch.device(device)
+        self.weights = list(weights)
+        specs = unet_weight_specs(self.ccfg)
+        if len(specs) != len(self.weights):
+            raise DfError("wrong number of weight tensors")
+        for (name, shape), w in zip(specs, self.weights):
+            want = torch.bfloat16 if len(shape) > 1 else torch.float32
+            if tuple(w.shape) != shape or w.dtype != want or not w.is_cuda or not w.is_contiguous():
+                raise DfError(f"weight {name}: expected {shape} {want}, got {tuple(w.shape)} {w.dtype}")
+        ws = L.df_unet_workspace_bytes(ctypes.byref(self.ccfg))
+        ss = L.df_unet_stale_bytes(ctypes.byref(self.ccfg))
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.device)
+        self.stale = torch.zeros(ss, dtype=torch.uint8, device=self.device)
+        arr = (ctypes.c_void_p * len(self.weights))(*[w.data_ptr() for w in self.weights])
+        h = ctypes.c_void_p()
+        _check(L.df_unet_create(ctypes.byref(h), ctypes.byref(self.ccfg), arr, len(self.weights),
+                                self.workspace.data_ptr(), ws))
+        self.handle = h
+
+    def step(self, x, emb, text, patch_idx=0, mode=MODE_DISPLACED, refresh=True, out=None):
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().df_patch_unet_step(self.handle, _ptr(x), _ptr(emb), _ptr(text), self.stale.data_ptr(), _ptr(out),
+                                        patch_idx, mode, int(refresh), _stream()))
+        return out
+
+    def stale_names(self):
+        L = lib()
+        buf = ctypes.create_string_buffer(128)
+        out = []
+        for k in range(L.df_unet_num_stale(self.handle)):
+            _check(L.df_unet_stale_name(self.handle, k, buf, 128))
+            out.append(buf.value.decode())
+        return out
+
+    def stale_view(self, name):
+        """uint8 view of one named stale buffer inside the blob."""
+        off, nb = ctypes.c_size_t(), ctypes.c_size_t()
+        _check(lib().df_unet_stale_lookup(self.handle, name.encode(), ctypes.byref(off), ctypes.byref(nb)))
+        return self.stale[off.value:off.value + nb.value]
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().df_unet_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,146 @@
+// C ABI of the layer operations: argument validation and translation into the
+// internal launch structures.  No arithmetic happens here.
+#include <mutex>
+
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+struct DevScratch {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+DevScratch g_scratch[64];
+std::mutex g_scratch_mu;
+}  // namespace
+
+// Grown on demand.  Growing frees the old buffer after a device synchronise, so it must
+// not happen while a stream is being captured: plans reserve their maximum up front.
+void* scratch_get(size_t bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  DevScratch& s = g_scratch[dev];
+  if (s.bytes >= bytes) return s.ptr;
+  size_t want = bytes < (8u << 20) ? (8u << 20) : bytes;
+  want = (want + 255) / 256 * 256;
+  if (s.ptr) {
+    if (hipDeviceSynchronize() != hipSuccess) return nullptr;
+    (void)hipFree(s.ptr);
+    s.ptr = nullptr;
+    s.bytes = 0;
+  }
+  void* p = nullptr;
+  if (hipMalloc(&p, want) != hipSuccess) return nullptr;
+  if (hipMemset(p, 0, kScratchCounterBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipFree(p);
+    return nullptr;
+  }
+  s.ptr = p;
+  s.bytes = want;
+  return p;
+}
+
+}  // namespace df
+
+using namespace df;
+
+static inline bool bad_dtype(int dt) { return dt != DF_F32 && dt != DF_BF16; }
+static inline size_t esize(int dt) { return dt == DF_BF16 ? 2 : 4; }
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* df_strerror(int err) {
+  switch (err) {
+    case DF_OK: return "ok";
+    case DF_EINVAL: return "invalid argument (null or misaligned pointer, bad enum)";
+    case DF_ESHAPE: return "unsupported shape";
+    case DF_EHIP: return "HIP runtime error";
+    case DF_ENOMEM: return "out of device scratch or workspace";
+    default: return "unknown error";
+  }
+}
+
+int df_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return DF_EINVAL;
+  return launch_copy_rows(dst, src, 1, (long long)bytes, (long long)bytes, (long long)bytes, (hipStream_t)stream);
+}
+
+int df_buffer_refresh(void* dst_full, const void* src_patch, int B, long long full_elems_per_batch, int patch_idx,
+                      int N, int dtype, void* stream) {
+  if (!dst_full || !src_patch || bad_dtype(dtype)) return DF_EINVAL;
+  if (B <= 0 || N <= 0 || full_elems_per_batch < 0 || full_elems_per_batch % N) return DF_ESHAPE;
+  if (patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  const long long chunk = full_elems_per_batch / N * (long long)esize(dtype);
+  const long long full = full_elems_per_batch * (long long)esize(dtype);
+  char* dst = (char*)dst_full + (long long)patch_idx * chunk;
+  return launch_copy_rows(dst, src_patch, B, chunk, full, chunk, (hipStream_t)stream);
+}
+
+int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out,
+                       const float* gamma, const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N,
+                       float eps, int stat_mode, int fuse_silu, int dtype, void* stream) {
+  if (!x_fresh || !y || !gamma || !beta || bad_dtype(dtype)) return DF_EINVAL;
+  if (stat_mode < DF_GN_SUMS || stat_mode > DF_GN_STALE) return DF_EINVAL;
+  if (B <= 0 || R <= 0 || W <= 0 || C <= 0 || G <= 0 || N <= 0 || patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  if ((N > 1 || stat_mode == DF_GN_STALE) && !stale_stats) return DF_EINVAL;
+  if (((uintptr_t)x_fresh % 16) || ((uintptr_t)y % 16)) return DF_EINVAL;
+  GnArgs a = {};
+  a.x = x_fresh; a.y = y; a.stale = stale_stats; a.sums_out = fresh_stats_out; a.gamma = gamma; a.beta = beta;
+  a.B = B; a.Rseg = R; a.W = W; a.C = C; a.G = G; a.nseg = 1; a.patch_idx = patch_idx; a.N = N; a.eps = eps;
+  a.stat_mode = stat_mode; a.silu = fuse_silu ? 1 : 0; a.in_dtype = dtype; a.out_dtype = dtype;
+  return launch_groupnorm(a, (hipStream_t)stream);
+}
+
+int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,
+                    int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act, int dtype,
+                    void* stream) {
+  if (!x_fresh || !w || !y || bad_dtype(dtype)) return DF_EINVAL;
+  if (act != 0 && act != 1) return DF_EINVAL;
+  if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || N <= 0 || H % N) return DF_ESHAPE;
+  if (patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  if (N > 1 && !stale_full) return DF_EINVAL;
+  const int R = H / N;
+  const long long row = (long long)W * Cin;
+  const size_t es = esize(dtype);
+  ConvArgs a = {};
+  a.x = x_fresh; a.w = w; a.bias = bias; a.y = y;
+  a.B = B; a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = act;
+  a.dtype = dtype; a.out_dtype = dtype;
+  a.halo_bstride = (long long)H * row;
+  const int s = patch_idx * R, e = s + R;
+  a.halo_top = (s > 0) ? (const char*)stale_full + (size_t)(s - 1) * row * es : nullptr;
+  a.halo_bot = (e < H && stride == 1) ? (const char*)stale_full + (size_t)e * row * es : nullptr;
+  return launch_conv3x3(a, (hipStream_t)stream);
+}
+
+int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
+                      const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
+                      float scale, int dtype, void* stream) {
+  if (!q || !k_fresh || !v_fresh || !out || bad_dtype(dtype)) return DF_EINVAL;
+  if (B <= 0 || L <= 0 || heads <= 0 || d <= 0 || N <= 0 || L % N) return DF_ESHAPE;
+  if (patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  if (N > 1 && (!k_stale || !v_stale)) return DF_EINVAL;
+  const int Lq = L / N;
+  const long long C = (long long)heads * d;
+  AttnArgs a = {};
+  a.q = q; a.k_fresh = k_fresh; a.v_fresh = v_fresh; a.k_stale = k_stale; a.v_stale = v_stale; a.out = out;
+  a.B = B; a.Lq = Lq; a.L = L; a.heads = heads; a.d = d;
+  a.own_lo = patch_idx * Lq; a.own_n = Lq;
+  a.ldq = a.ldkf = a.ldvf = a.ldks = a.ldvs = a.ldo = C;
+  a.bsq = a.bskf = a.bsvf = a.bso = (long long)Lq * C;
+  a.bsks = a.bsvs = (long long)L * C;
+  a.scale = scale; a.dtype = dtype;
+  return launch_attention(a, (hipStream_t)stream);
+}
+
+int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream) {
+  if (!x || !eps) return DF_EINVAL;
+  if (n < 0) return DF_ESHAPE;
+  return launch_axpy(x, eps, sigma_next - sigma, n, (hipStream_t)stream);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,379 @@
+// Displaced self-attention (Section 4, Sparse operations): fresh queries of one
+// patch against keys/values of the whole feature map, where the patch's own
+// rows are read from the fresh tensors and every other row from the stale
+// buffers.  The splice happens in the tile loader; no scattered copy exists.
+//
+// bf16 kernel (head dim 64): flash-style, one workgroup = 4 waves x 32 queries,
+// 64-key K/V tiles staged through LDS and shared by the 4 waves.  Each wave
+// computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 so that a lane owns one
+// query column: the online-softmax row statistics are lane-local plus one
+// exchange with lane^32.  The rows of the K tile are assigned to MFMA rows in
+// a permuted order chosen so that the exponentiated accumulators are, without
+// any data movement, the B operand (P^T) of O^T = V^T P^T, and the matching
+// V^T operand is one 16-byte read from a transposed, XOR-swizzled V tile.
+// Small query counts are spread over the chip by splitting the key range
+// across workgroups; partial (O, m, l) are merged by a second kernel.
+//
+// f32 kernel: one wave per query, lanes stride over keys; for the small
+// full-precision configuration only.
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnParams {
+  const void* q; const void* kf; const void* vf; const void* ks; const void* vs;
+  void* out;
+  float* part_o;   // [nsplit][B][heads][Lq][d] float (split mode)
+  float* part_ml;  // [nsplit][B][heads][Lq][2]
+  int B, Lq, L, heads;
+  int own_lo, own_n;
+  long long ldq, ldkf, ldvf, ldks, ldvs, ldo;
+  long long bsq, bskf, bsvf, bsks, bsvs, bso;
+  float scale;
+  int nsplit, keys_per_split;
+};
+
+__device__ __forceinline__ const bf16_t* key_row(const bf16_t* fresh, const bf16_t* stale, long long ldf, long long lds,
+                                                 int own_lo, int own_n, int j) {
+  const int rel = j - own_lo;
+  return (rel >= 0 && rel < own_n) ? fresh + (long long)rel * ldf : stale + (long long)j * lds;
+}
+
+// physical key (0..31) loaded into MFMA row rho of a 32-key block
+__device__ __forceinline__ int key_of_mfma_row(int rho) {
+  const int j = rho >> 3, g = (rho >> 2) & 1, r = rho & 3;
+  return 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
+}
+
+__global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
+  constexpr int D = 64, TK = 64;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[2][TK * D];   // [key][d], 16-byte chunks XOR-swizzled by row
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * TK];   // [d][key], swizzled
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, c = lane & 31;
+  const int h = blockIdx.y;
+  const int b = blockIdx.z / p.nsplit, split = blockIdx.z % p.nsplit;
+  const int q0 = blockIdx.x * 128 + wave * 32;
+  const int kv_lo = split * p.keys_per_split;
+  int kv_hi = kv_lo + p.keys_per_split;
+  if (kv_hi > p.L) kv_hi = p.L;
+  const int ntiles = (kv_hi - kv_lo + TK - 1) / TK;
+
+  const bf16_t* kf = (const bf16_t*)p.kf + (long long)b * p.bskf + h * D;
+  const bf16_t* vf = (const bf16_t*)p.vf + (long long)b * p.bsvf + h * D;
+  const bf16_t* ks = p.ks ? (const bf16_t*)p.ks + (long long)b * p.bsks + h * D : nullptr;
+  const bf16_t* vs = p.vs ? (const bf16_t*)p.vs + (long long)b * p.bsvs + h * D : nullptr;
+
+  // Q^T operand: lane (g, c) holds Q[q0 + c][16*ks + 8*g .. +7] for ks = 0..3
+  bf16x8 qreg[4];
+  {
+    const int qi = q0 + c;
+    const bf16_t* qp = (const bf16_t*)p.q + (long long)b * p.bsq + (long long)qi * p.ldq + h * D;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (qi < p.Lq) t = *reinterpret_cast<const u32x4*>(qp + 16 * s + 8 * g);
+      qreg[s] = __builtin_bit_cast(bf16x8, t);
+    }
+  }
+
+  // cooperative tile loads: K: lane -> (key = tid/8 (+32), chunk = tid%8); V: keys 2*kap, 2*kap+1, chunk = tid%8
+  const int ld_key = tid >> 3, ld_ch = tid & 7;
+  u32x4 kreg[2], vreg[2];
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  auto load_tile = [&](int t) {
+    const int base = kv_lo + t * TK;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int jk = base + ld_key + 32 * i;
+      kreg[i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, jk) + ld_ch * 8)
+                           : zero4;
+      const int jv = base + 2 * ld_key + i;
+      vreg[i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, jv) + ld_ch * 8)
+                           : zero4;
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = ld_key + 32 * i;
+      const int f = (row & 3) | (((row >> 3) & 1) << 2);
+      *reinterpret_cast<u32x4*>(&Ks[buf][row * D + ((ld_ch ^ f) * 8)]) = kreg[i];
+    }
+    // V transposed: dword (keys 2*kap, 2*kap+1) of row d goes to chunk (kap/4) ^ (d%8) ^ (d/8), dword kap%4
+    const int kap = ld_key;
+    unsigned int* vt = reinterpret_cast<unsigned int*>(&Vt[buf][0]);
+    const unsigned int a[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
+    const unsigned int bq[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int d = ld_ch * 8 + e;
+      const unsigned int lo = (e & 1) ? (a[e >> 1] >> 16) : (a[e >> 1] & 0xffffu);
+      const unsigned int hi = (e & 1) ? (bq[e >> 1] & 0xffff0000u) : (bq[e >> 1] << 16);
+      const int chunk = (kap >> 2) ^ (d & 7) ^ (d >> 3);
+      vt[d * 32 + chunk * 4 + (kap & 3)] = lo | hi;
+    }
+  };
+
+  f32x16 o_acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = p.scale * kLog2e;
+
+  if (ntiles > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ntiles) load_tile(t + 1);
+
+    // ---- S^T = K Q^T for two 32-key blocks ----
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+      const int row = 32 * kb + key_of_mfma_row(c);
+      const int f = (row & 3) | (((row >> 3) & 1) << 2);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8 kfrag = *reinterpret_cast<const bf16x8*>(&Ks[buf][row * D + (((2 * s + g) ^ f) * 8)]);
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qreg[s], s_acc[kb], 0, 0, 0);
+      }
+    }
+    // accumulator e = 4*j + r of block kb is key  base + 32*kb + 16*(j/2) + 8*g + 4*(j%2) + r  for query c
+    const int tile_base = kv_lo + t * TK;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int j = e >> 2, r = e & 3;
+        const int key = tile_base + 32 * kb + 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
+        float v = s_acc[kb][e] * sc;
+        if (key >= kv_hi) v = -INFINITY;
+        s_acc[kb][e] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);           // finite: every tile holds at least one valid key
+    const float alpha = exp2f(m_run - m_new);       // exp2(-inf) = 0 on the first tile
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = exp2f(s_acc[kb][e] - m_new);
+        s_acc[kb][e] = pv;
+        rs += pv;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * alpha + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+
+    // ---- O^T += V^T P^T : four 16-key steps; lane supplies P for its query and key slots 8g..8g+7 ----
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      const int kb = ts >> 1, half = ts & 1;
+      u32x4 pk;
+      pk.x = pack_bf2(s_acc[kb][8 * half + 0], s_acc[kb][8 * half + 1]);
+      pk.y = pack_bf2(s_acc[kb][8 * half + 2], s_acc[kb][8 * half + 3]);
+      pk.z = pack_bf2(s_acc[kb][8 * half + 4], s_acc[kb][8 * half + 5]);
+      pk.w = pack_bf2(s_acc[kb][8 * half + 6], s_acc[kb][8 * half + 7]);
+      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
+      const int kchunk = 4 * kb + 2 * half + g;     // keys 32*kb + 16*half + 8*g .. +7
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const int d = 32 * db + c;
+        const int chunk = kchunk ^ (d & 7) ^ (d >> 3);
+        const bf16x8 vfrag = *reinterpret_cast<const bf16x8*>(&Vt[buf][d * TK + chunk * 8]);
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pfrag, o_acc[db], 0, 0, 0);
+      }
+    }
+    if (t + 1 < ntiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- write: lane (g, c) holds O[q0 + c][32*db + 8*j + 4*g + r] ----
+  const int qi = q0 + c;
+  if (qi >= p.Lq) return;
+  if (p.nsplit == 1) {
+    const float inv = 1.0f / l_run;
+    bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x2 t = {pack_bf2(o_acc[db][4 * j] * inv, o_acc[db][4 * j + 1] * inv),
+                   pack_bf2(o_acc[db][4 * j + 2] * inv, o_acc[db][4 * j + 3] * inv)};
+        *reinterpret_cast<u32x2*>(op + 32 * db + 8 * j + 4 * g) = t;
+      }
+  } else {
+    const long long row = (((long long)split * p.B + b) * p.heads + h) * p.Lq + qi;
+    float* po = p.part_o + row * D;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4 t = {o_acc[db][4 * j], o_acc[db][4 * j + 1], o_acc[db][4 * j + 2], o_acc[db][4 * j + 3]};
+        *reinterpret_cast<f32x4*>(po + 32 * db + 8 * j + 4 * g) = t;
+      }
+    if (g == 0) {
+      p.part_ml[row * 2] = m_run;      // in log2 units
+      p.part_ml[row * 2 + 1] = l_run;
+    }
+  }
+}
+
+// merges the per-split partials: one lane per (query, 4 consecutive d)
+__global__ __launch_bounds__(256) void attn_combine_d64(AttnParams p) {
+  constexpr int D = 64;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long rows = (long long)p.B * p.heads * p.Lq;
+  if (idx >= rows * (D / 4)) return;
+  const long long row = idx / (D / 4);
+  const int d4 = (int)(idx % (D / 4)) * 4;
+  float m = -INFINITY;
+  for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, p.part_ml[(s * rows + row) * 2]);
+  float l = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < p.nsplit; ++s) {
+    const float w = exp2f(p.part_ml[(s * rows + row) * 2] - m);
+    l += w * p.part_ml[(s * rows + row) * 2 + 1];
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p.part_o + (s * rows + row) * D + d4);
+    o += t * w;
+  }
+  const float inv = 1.0f / l;
+  const int qi = (int)(row % p.Lq);
+  const int h = (int)((row / p.Lq) % p.heads);
+  const int b = (int)(row / ((long long)p.Lq * p.heads));
+  bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D + d4;
+  u32x2 t = {pack_bf2(o.x * inv, o.y * inv), pack_bf2(o.z * inv, o.w * inv)};
+  *reinterpret_cast<u32x2*>(op) = t;
+}
+
+// ---- f32: one wave per (batch, head, query); lanes stride over keys ----
+template <int D>
+__global__ __launch_bounds__(256) void attn_f32(AttnParams p) {
+  const int lane = threadIdx.x & 63;
+  const long long wid = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long total = (long long)p.B * p.heads * p.Lq;
+  if (wid >= total) return;
+  const int qi = (int)(wid % p.Lq);
+  const int h = (int)((wid / p.Lq) % p.heads);
+  const int b = (int)(wid / ((long long)p.Lq * p.heads));
+  const float* qp = (const float*)p.q + (long long)b * p.bsq + (long long)qi * p.ldq + h * D;
+  const float* kf = (const float*)p.kf + (long long)b * p.bskf + h * D;
+  const float* vf = (const float*)p.vf + (long long)b * p.bsvf + h * D;
+  const float* ks = p.ks ? (const float*)p.ks + (long long)b * p.bsks + h * D : nullptr;
+  const float* vs = p.vs ? (const float*)p.vs + (long long)b * p.bsvs + h * D : nullptr;
+  float qv[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) qv[i] = qp[i];
+  float m = -INFINITY, l = 0.f, acc[D];
+#pragma unroll
+  for (int i = 0; i < D; ++i) acc[i] = 0.f;
+  for (int j = lane; j < p.L; j += 64) {
+    const int rel = j - p.own_lo;
+    const bool own = rel >= 0 && rel < p.own_n;
+    const float* kr = own ? kf + (long long)rel * p.ldkf : ks + (long long)j * p.ldks;
+    const float* vr = own ? vf + (long long)rel * p.ldvf : vs + (long long)j * p.ldvs;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < D; ++i) s = fmaf(qv[i], kr[i], s);
+    s *= p.scale;
+    const float mn = fmaxf(m, s);
+    const float a = expf(m - mn), e = expf(s - mn);
+    l = l * a + e;
+#pragma unroll
+    for (int i = 0; i < D; ++i) acc[i] = fmaf(acc[i], a, e * vr[i]);
+    m = mn;
+  }
+  const float mg = wave_max(m);
+  const float w = (m == -INFINITY) ? 0.f : expf(m - mg);
+  l = wave_sum(l * w);
+  float* op = (float*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D;
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    const float v = wave_sum(acc[i] * w);
+    if (lane == (i & 63)) op[i] = v / l;
+  }
+}
+
+int pick_splits(int B, int Lq, int L, int heads) {
+  const long long blocks = (long long)cdiv(Lq, 128) * heads * B;
+  int ns = 1;
+  // aim at >= 512 workgroups (two per compute unit) while keeping >= 4 key tiles per split
+  while (blocks * ns < 512 && L / (ns * 2) >= 256 && ns < 16) ns *= 2;
+  return ns;
+}
+
+}  // namespace
+
+size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d) {
+  const int ns = pick_splits(B, Lq, L, heads);
+  if (ns == 1) return kScratchCounterBytes;
+  return kScratchCounterBytes + (size_t)ns * B * heads * Lq * (d + 2) * sizeof(float) + 256;
+}
+
+int launch_attention(const AttnArgs& a, hipStream_t st) {
+  if (a.B <= 0 || a.Lq <= 0 || a.L <= 0 || a.heads <= 0) return DF_ESHAPE;
+  const bool own_all = a.own_lo <= 0 && a.own_lo + a.own_n >= a.L;
+  if (!own_all && (!a.k_stale || !a.v_stale)) return DF_EINVAL;
+  AttnParams p = {};
+  p.q = a.q; p.kf = a.k_fresh; p.vf = a.v_fresh; p.ks = a.k_stale; p.vs = a.v_stale; p.out = a.out;
+  p.B = a.B; p.Lq = a.Lq; p.L = a.L; p.heads = a.heads; p.own_lo = a.own_lo; p.own_n = a.own_n;
+  p.ldq = a.ldq; p.ldkf = a.ldkf; p.ldvf = a.ldvf; p.ldks = a.ldks; p.ldvs = a.ldvs; p.ldo = a.ldo;
+  p.bsq = a.bsq; p.bskf = a.bskf; p.bsvf = a.bsvf; p.bsks = a.bsks; p.bsvs = a.bsvs; p.bso = a.bso;
+  p.scale = a.scale;
+  p.nsplit = 1; p.keys_per_split = a.L;
+  if (a.dtype == DF_F32) {
+    const long long waves = (long long)a.B * a.heads * a.Lq;
+    dim3 grid((unsigned)((waves + 3) / 4));
+    if (a.d == 32) hipLaunchKernelGGL(attn_f32<32>, grid, dim3(256), 0, st, p);
+    else if (a.d == 64) hipLaunchKernelGGL(attn_f32<64>, grid, dim3(256), 0, st, p);
+    else return DF_ESHAPE;
+    DF_LAUNCH_CHECK();
+    return DF_OK;
+  }
+  if (a.d != 64) return DF_ESHAPE;
+  const long long lds[] = {a.ldq, a.ldkf, a.ldvf, a.ldks, a.ldvs, a.ldo, a.bsq, a.bskf, a.bsvf, a.bsks, a.bsvs, a.bso};
+  for (long long v : lds) if (v % 8) return DF_EINVAL;
+  const void* ptrs[] = {a.q, a.k_fresh, a.v_fresh, a.k_stale, a.v_stale, a.out};
+  for (const void* q : ptrs) if ((uintptr_t)q % 16) return DF_EINVAL;
+  const int ns = pick_splits(a.B, a.Lq, a.L, a.heads);
+  if ((long long)a.B * ns > 65535) return DF_ESHAPE;
+  if (ns > 1) {
+    char* scr = (char*)scratch_get(attention_scratch_bytes(a.B, a.Lq, a.L, a.heads, a.d));
+    if (!scr) return DF_ENOMEM;
+    p.nsplit = ns;
+    p.keys_per_split = cdiv(cdiv(a.L, ns), 64) * 64;
+    p.part_o = (float*)(scr + kScratchCounterBytes);
+    p.part_ml = p.part_o + (size_t)ns * a.B * a.heads * a.Lq * 64;
+  }
+  dim3 grid(cdiv(a.Lq, 128), a.heads, a.B * p.nsplit);
+  hipLaunchKernelGGL(attn_bf16_d64, grid, dim3(256), 0, st, p);
+  DF_LAUNCH_CHECK();
+  if (ns > 1) {
+    const long long n = (long long)a.B * a.heads * a.Lq * 16;
+    hipLaunchKernelGGL(attn_combine_d64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
+    DF_LAUNCH_CHECK();
+  }
+  return DF_OK;
+}
+
+}  // namespace df

@@ -1,0 +1,374 @@
+// bf16 MFMA tile kernel shared by the linear layers and the 3x3 convolution,
+// plus the direct convolution kernels for shapes that are not worth a tile.
+//
+// Sparse convolution of one patch (Section 4, Sparse operations): an implicit
+// GEMM over M = B*Ro*Wo output pixels of the patch, N = Cout, K = 9*Cin.  The
+// A-operand loader gathers each 32-channel slice of a tap straight from the
+// fresh patch, or - for the row above / below the patch - from the stale halo
+// row (Section 5.3: only boundary rows come from other patches), or zero at the
+// image border.  The scatter is never materialised.
+//
+// Tile: BM x BN x 32, 256 lanes = 4 waves in a 2x2 grid, each wave owns
+// (BM/2)x(BN/2) as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  Operands are
+// staged through LDS with an 80-byte row pitch (conflict-free for 16-byte
+// reads), double buffered, next tile prefetched into registers during compute.
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+
+constexpr int BK = 32;
+constexpr int LDS_PITCH = 40;  // bf16 elements per LDS row: 32 + 8 pad
+
+struct TileParams {
+  // GEMM view
+  const bf16_t* A;
+  const bf16_t* Wt;
+  const float* bias;
+  const float* residual;
+  const float* chan_add;
+  void* out;
+  int M, N, K;
+  long long lda, ldw, ldr, ldo;
+  int act;
+  // convolution geometry (kConv only)
+  const bf16_t* top;
+  const bf16_t* bot;
+  long long halo_bs;
+  int R, W, Cin, Ro, Wo, stride;
+};
+
+template <int BM, int BN, bool kConv, typename OutT>
+__global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
+  constexpr int TM = BM / 64, TN = BN / 64;      // 32x32 blocks per wave in each direction
+  constexpr int A_CH = BM * 4 / 256, B_CH = BN * 4 / 256;  // 16-byte chunks per lane per tile
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_PITCH];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int KT = p.K / BK;
+
+  // ---- per-lane source description of its A and B chunks ----
+  int a_row[A_CH], a_kc[A_CH];
+  long long a_off[A_CH];          // GEMM: element offset of (row, kc*8); conv: unused
+  int a_b[A_CH], a_ro[A_CH], a_co[A_CH];
+  bool a_ok[A_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int q = tid + i * 256;
+    a_row[i] = q >> 2;
+    a_kc[i] = q & 3;
+    const int m = m0 + a_row[i];
+    a_ok[i] = m < p.M;
+    if constexpr (kConv) {
+      const int per = p.Ro * p.Wo;
+      const int mm = a_ok[i] ? m : 0;
+      a_b[i] = mm / per;
+      const int rem = mm - a_b[i] * per;
+      a_ro[i] = rem / p.Wo;
+      a_co[i] = rem - a_ro[i] * p.Wo;
+      a_off[i] = 0;
+    } else {
+      a_off[i] = (long long)m * p.lda + a_kc[i] * 8;
+      a_b[i] = a_ro[i] = a_co[i] = 0;
+    }
+  }
+  long long b_off[B_CH];
+  bool b_ok[B_CH];
+  int b_row[B_CH], b_kc[B_CH];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int q = tid + i * 256;
+    b_row[i] = q >> 2;
+    b_kc[i] = q & 3;
+    const int n = n0 + b_row[i];
+    b_ok[i] = n < p.N;
+    b_off[i] = (long long)n * p.ldw + b_kc[i] * 8;
+  }
+
+  u32x4 a_reg[A_CH], b_reg[B_CH];
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+  auto load_tile = [&](int kt) {
+    const int k0 = kt * BK;
+    if constexpr (kConv) {
+      const int tap = k0 / p.Cin;
+      const int cin0 = k0 - tap * p.Cin;
+      const int ky = tap / 3, kx = tap - ky * 3;
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) {
+        const int ri = a_ro[i] * p.stride + ky - 1;
+        const int ci = a_co[i] * p.stride + kx - 1;
+        const bf16_t* src = nullptr;
+        if (a_ok[i] && ci >= 0 && ci < p.W) {
+          if (ri < 0) {
+            if (p.top) src = p.top + a_b[i] * p.halo_bs + (long long)ci * p.Cin;
+          } else if (ri >= p.R) {
+            if (p.bot) src = p.bot + a_b[i] * p.halo_bs + (long long)ci * p.Cin;
+          } else {
+            src = p.A + (((long long)a_b[i] * p.R + ri) * p.W + ci) * p.Cin;
+          }
+        }
+        a_reg[i] = src ? *reinterpret_cast<const u32x4*>(src + cin0 + a_kc[i] * 8) : zero4;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i)
+        a_reg[i] = a_ok[i] ? *reinterpret_cast<const u32x4*>(p.A + a_off[i] + k0) : zero4;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+      b_reg[i] = b_ok[i] ? *reinterpret_cast<const u32x4*>(p.Wt + b_off[i] + k0) : zero4;
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i)
+      *reinterpret_cast<u32x4*>(&As[buf][a_row[i] * LDS_PITCH + a_kc[i] * 8]) = a_reg[i];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i)
+      *reinterpret_cast<u32x4*>(&Bs[buf][b_row[i] * LDS_PITCH + b_kc[i] * 8]) = b_reg[i];
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  const int lrow = lane & 31, lk = (lane >> 5) * 8;
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_tile(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(&As[buf][(wm * (BM / 2) + i * 32 + lrow) * LDS_PITCH + ks * 16 + lk]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(wn * (BN / 2) + j * 32 + lrow) * LDS_PITCH + ks * 16 + lk]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator element 4*j+r of a 32x32 block sits at row 8*j + 4*(lane/32) + r, column lane%32 ----
+  OutT* out = reinterpret_cast<OutT*>(p.out);
+  const int per = kConv ? p.Ro * p.Wo : 1;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int col = n0 + wn * (BN / 2) + tn * 32 + (lane & 31);
+    if (col >= p.N) continue;
+    const float bias = p.bias ? p.bias[col] : 0.f;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (row >= p.M) continue;
+        float v = acc[tm][tn][e] + bias;
+        if constexpr (kConv) {
+          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.N + col];
+        }
+        if (p.residual) v += p.residual[(long long)row * p.ldr + col];
+        if (p.act == 1) v = silu_f(v);
+        Elem<OutT>::st(out + (long long)row * p.ldo + col, v);
+      }
+    }
+  }
+}
+
+// ---- direct convolutions for tiny or narrow shapes ----
+
+// One lane per (output pixel, output channel).
+template <typename T, typename OutT>
+__global__ __launch_bounds__(256) void conv3x3_direct(const T* __restrict__ x, const T* __restrict__ top,
+                                                      const T* __restrict__ bot, long long halo_bs,
+                                                      const T* __restrict__ w, const float* __restrict__ bias,
+                                                      const float* __restrict__ chan_add,
+                                                      const float* __restrict__ residual, OutT* __restrict__ y, int B,
+                                                      int R, int W, int Cin, int Cout, int Ro, int Wo, int stride,
+                                                      int act) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)B * Ro * Wo * Cout;
+  if (idx >= total) return;
+  const int co = (int)(idx % Cout);
+  long long pix = idx / Cout;
+  const int c = (int)(pix % Wo);
+  pix /= Wo;
+  const int r = (int)(pix % Ro);
+  const int b = (int)(pix / Ro);
+  float acc = bias ? bias[co] : 0.f;
+  for (int ky = 0; ky < 3; ++ky) {
+    const int ri = r * stride + ky - 1;
+    const T* rowp;
+    if (ri < 0) {
+      if (!top) continue;
+      rowp = top + b * halo_bs;
+    } else if (ri >= R) {
+      if (!bot) continue;
+      rowp = bot + b * halo_bs;
+    } else {
+      rowp = x + ((long long)b * R + ri) * W * Cin;
+    }
+    for (int kx = 0; kx < 3; ++kx) {
+      const int ci = c * stride + kx - 1;
+      if (ci < 0 || ci >= W) continue;
+      const T* xp = rowp + (long long)ci * Cin;
+      const T* wp = w + (((long long)co * 3 + ky) * 3 + kx) * Cin;
+      float s = 0.f;
+      for (int i = 0; i < Cin; ++i) s = fmaf(Elem<T>::ld(xp + i), Elem<T>::ld(wp + i), s);
+      acc += s;
+    }
+  }
+  if (chan_add) acc += chan_add[(long long)b * Cout + co];
+  if (residual) acc += residual[idx];
+  if (act == 1) acc = silu_f(acc);
+  Elem<OutT>::st(y + idx, acc);
+}
+
+// One wave per output pixel, lanes split the 9*Cin reduction; for wide inputs and few outputs (Cout <= 8).
+template <typename T, typename OutT, int CO>
+__global__ __launch_bounds__(256) void conv3x3_wave(const T* __restrict__ x, const T* __restrict__ top,
+                                                    const T* __restrict__ bot, long long halo_bs,
+                                                    const T* __restrict__ w, const float* __restrict__ bias,
+                                                    const float* __restrict__ residual, OutT* __restrict__ y, int B,
+                                                    int R, int W, int Cin, int Cout, int Ro, int Wo, int stride,
+                                                    int act) {
+  const int lane = threadIdx.x & 63;
+  const long long pix = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (pix >= (long long)B * Ro * Wo) return;
+  const int c = (int)(pix % Wo);
+  const int r = (int)((pix / Wo) % Ro);
+  const int b = (int)(pix / ((long long)Wo * Ro));
+  float acc[CO];
+#pragma unroll
+  for (int o = 0; o < CO; ++o) acc[o] = 0.f;
+  for (int ky = 0; ky < 3; ++ky) {
+    const int ri = r * stride + ky - 1;
+    const T* rowp;
+    if (ri < 0) {
+      if (!top) continue;
+      rowp = top + b * halo_bs;
+    } else if (ri >= R) {
+      if (!bot) continue;
+      rowp = bot + b * halo_bs;
+    } else {
+      rowp = x + ((long long)b * R + ri) * W * Cin;
+    }
+    for (int kx = 0; kx < 3; ++kx) {
+      const int ci = c * stride + kx - 1;
+      if (ci < 0 || ci >= W) continue;
+      const T* xp = rowp + (long long)ci * Cin;
+      for (int i = lane; i < Cin; i += 64) {
+        const float xv = Elem<T>::ld(xp + i);
+#pragma unroll
+        for (int o = 0; o < CO; ++o)
+          if (o < Cout) acc[o] = fmaf(xv, Elem<T>::ld(w + (((long long)o * 3 + ky) * 3 + kx) * Cin + i), acc[o]);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 0; o < CO; ++o) acc[o] = wave_sum(acc[o]);
+  if (lane == 0) {
+#pragma unroll
+    for (int o = 0; o < CO; ++o) {
+      if (o >= Cout) break;
+      float v = acc[o] + (bias ? bias[o] : 0.f);
+      if (residual) v += residual[pix * Cout + o];
+      if (act == 1) v = silu_f(v);
+      Elem<OutT>::st(y + pix * Cout + o, v);
+    }
+  }
+}
+
+template <int BM, int BN, bool kConv>
+int launch_tile(const TileParams& p, int out_dtype, hipStream_t st) {
+  dim3 grid(cdiv(p.N, BN), cdiv(p.M, BM));
+  if (grid.y > 65535) return DF_ESHAPE;
+  if (out_dtype == DF_BF16)
+    hipLaunchKernelGGL((mfma_tile_kernel<BM, BN, kConv, bf16_t>), grid, dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL((mfma_tile_kernel<BM, BN, kConv, float>), grid, dim3(256), 0, st, p);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+template <bool kConv>
+int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
+  // big tiles only when they still give every compute unit work; otherwise 64x64 to expose parallelism
+  const long long big = (long long)cdiv(p.M, 128) * cdiv(p.N, 128);
+  if (big >= 384) return launch_tile<128, 128, kConv>(p, out_dtype, st);
+  return launch_tile<64, 64, kConv>(p, out_dtype, st);
+}
+
+}  // namespace
+
+int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0 || a.K % BK) return DF_ESHAPE;
+  if (a.lda % 8 || a.ldw % 8 || ((uintptr_t)a.A % 16) || ((uintptr_t)a.W % 16)) return DF_EINVAL;
+  TileParams p = {};
+  p.A = (const bf16_t*)a.A; p.Wt = (const bf16_t*)a.W; p.bias = a.bias; p.residual = a.residual; p.out = a.out;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldw = a.ldw; p.ldr = a.ldr; p.ldo = a.ldo; p.act = a.act;
+  return pick_tile<false>(p, a.out_dtype, st);
+}
+
+int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
+  if (a.stride != 1 && a.stride != 2) return DF_ESHAPE;
+  if (a.stride == 2 && ((a.R & 1) || (a.W & 1))) return DF_ESHAPE;
+  const int Ro = a.R / a.stride, Wo = a.W / a.stride;
+  const long long M = (long long)a.B * Ro * Wo;
+  if (M <= 0 || M > 0x7fffffffLL) return DF_ESHAPE;
+  const bool mfma = a.dtype == DF_BF16 && a.Cin % BK == 0 && a.Cout % 32 == 0 && ((uintptr_t)a.x % 16 == 0) &&
+                    ((uintptr_t)a.w % 16 == 0) && ((uintptr_t)a.halo_top % 16 == 0) &&
+                    ((uintptr_t)a.halo_bot % 16 == 0) && (a.halo_bstride % 8 == 0);
+  if (mfma) {
+    TileParams p = {};
+    p.A = (const bf16_t*)a.x; p.Wt = (const bf16_t*)a.w; p.bias = a.bias; p.residual = a.residual;
+    p.chan_add = a.chan_add; p.out = a.y;
+    p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin; p.lda = 0; p.ldw = 9LL * a.Cin; p.ldr = a.Cout; p.ldo = a.Cout;
+    p.act = a.act;
+    p.top = (const bf16_t*)a.halo_top; p.bot = (const bf16_t*)a.halo_bot; p.halo_bs = a.halo_bstride;
+    p.R = a.R; p.W = a.W; p.Cin = a.Cin; p.Ro = Ro; p.Wo = Wo; p.stride = a.stride;
+    return pick_tile<true>(p, a.out_dtype, st);
+  }
+  const long long total = M * a.Cout;
+#define DF_DIRECT(T, OT)                                                                                              \
+  hipLaunchKernelGGL((conv3x3_direct<T, OT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a.x, \
+                     (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.w, a.bias, a.chan_add,  \
+                     a.residual, (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, Ro, Wo, a.stride, a.act)
+#define DF_WAVE(T, OT)                                                                                                \
+  hipLaunchKernelGGL((conv3x3_wave<T, OT, 8>), dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, (const T*)a.x,        \
+                     (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.w, a.bias, a.residual,  \
+                     (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, Ro, Wo, a.stride, a.act)
+  if ((total + 255) / 256 > 0x7fffffffLL) return DF_ESHAPE;
+  const bool wave = a.Cout <= 8 && a.Cin >= 64 && !a.chan_add;
+  if (a.dtype == DF_F32) {
+    if (a.out_dtype != DF_F32) return DF_ESHAPE;
+    if (wave) DF_WAVE(float, float); else DF_DIRECT(float, float);
+  } else {
+    if (a.out_dtype == DF_BF16) { if (wave) DF_WAVE(bf16_t, bf16_t); else DF_DIRECT(bf16_t, bf16_t); }
+    else { if (wave) DF_WAVE(bf16_t, float); else DF_DIRECT(bf16_t, float); }
+  }
+#undef DF_DIRECT
+#undef DF_WAVE
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+}  // namespace df

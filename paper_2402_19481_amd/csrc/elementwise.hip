@@ -1,0 +1,185 @@
+// Per-token layers that need no cross-patch data (Section 4, Sparse operations:
+// they run on the fresh tokens only): LayerNorm, GEGLU gating, casts, skip
+// concatenation, nearest 2x upsampling, and the sampler's element-wise update
+// (Section 3, Eq. 1).  All are HBM-streaming kernels with 8/16-byte accesses.
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+
+// one wave per row; float in, bf16 out; two passes over registers (mean, then centred variance)
+template <int PER>  // float4 loads per lane: C <= 64*4*PER
+__global__ __launch_bounds__(256) void layernorm_rows(const float* __restrict__ x, bf16_t* __restrict__ y,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      int M, int C, float eps) {
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const float* xr = x + row * C;
+  f32x4 v[PER];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < C) {
+      v[i] = *reinterpret_cast<const f32x4*>(xr + c);
+      s += v[i].x + v[i].y + v[i].z + v[i].w;
+    } else {
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  }
+  const float mean = wave_sum(s) / (float)C;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < C) {
+      const f32x4 d = v[i] - mean;
+      q += d.x * d.x + d.y * d.y + d.z * d.z + d.w * d.w;
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)C + eps);
+  bf16_t* yr = y + row * C;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = (i * 64 + lane) * 4;
+    if (c < C) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(gamma + c);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(beta + c);
+      const f32x4 o = (v[i] - mean) * rstd * g + b;
+      u32x2 t = {pack_bf2(o.x, o.y), pack_bf2(o.z, o.w)};
+      *reinterpret_cast<u32x2*>(yr + c) = t;
+    }
+  }
+}
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+// h [M, 2F] bf16 (value half, gate half) -> out [M, F] = value * gelu(gate)
+__global__ __launch_bounds__(256) void geglu_kernel(const bf16_t* __restrict__ h, bf16_t* __restrict__ out, long long M,
+                                                    int F) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int fv = F / 8;
+  if (idx >= M * fv) return;
+  const long long row = idx / fv;
+  const int f0 = (int)(idx % fv) * 8;
+  float a[8], g[8];
+  ld_vec(h + row * 2 * F + f0, a);
+  ld_vec(h + row * 2 * F + F + f0, g);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] *= gelu_erf(g[i]);
+  st_vec(out + row * F + f0, a);
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ x, bf16_t* __restrict__ y,
+                                                        long long n4, int silu) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  f32x4 v = *reinterpret_cast<const f32x4*>(x + i * 4);
+  if (silu) { v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w); }
+  u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+  *reinterpret_cast<u32x2*>(y + i * 4) = t;
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_tail(const float* __restrict__ x, bf16_t* __restrict__ y,
+                                                      long long lo, long long n, int silu) {
+  const long long i = lo + (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float v = x[i];
+  y[i] = f2bf(silu ? silu_f(v) : v);
+}
+
+// out[p, 0:Ca] = a[p], out[p, Ca:Ca+Cb] = b[p]; float4 granularity
+__global__ __launch_bounds__(256) void concat_kernel(const float* __restrict__ a, int Ca4, const float* __restrict__ b,
+                                                     int Cb4, float* __restrict__ out, long long pixels) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int C4 = Ca4 + Cb4;
+  if (idx >= pixels * C4) return;
+  const long long p = idx / C4;
+  const int c = (int)(idx % C4);
+  const f32x4 v = c < Ca4 ? *reinterpret_cast<const f32x4*>(a + (p * Ca4 + c) * 4)
+                          : *reinterpret_cast<const f32x4*>(b + (p * Cb4 + (c - Ca4)) * 4);
+  *reinterpret_cast<f32x4*>(out + idx * 4) = v;
+}
+
+// x [B,R,W,C] float -> y [B,2R,2W,C] bf16, each pixel repeated 2x2
+__global__ __launch_bounds__(256) void upsample2x_kernel(const float* __restrict__ x, bf16_t* __restrict__ y, int B,
+                                                         int R, int W, int C4) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)B * 2 * R * 2 * W * C4;
+  if (idx >= total) return;
+  const int c = (int)(idx % C4);
+  long long t = idx / C4;
+  const int wo = (int)(t % (2 * W));
+  t /= 2 * W;
+  const int ro = (int)(t % (2 * R));
+  const int b = (int)(t / (2 * R));
+  const f32x4 v = *reinterpret_cast<const f32x4*>(x + ((((long long)b * R + (ro >> 1)) * W + (wo >> 1)) * C4 + c) * 4);
+  u32x2 o = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+  *reinterpret_cast<u32x2*>(y + idx * 4) = o;
+}
+
+__global__ __launch_bounds__(256) void axpy_kernel(float* __restrict__ x, const float* __restrict__ e, float alpha,
+                                                   long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) x[i] = fmaf(alpha, e[i], x[i]);
+}
+
+inline unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
+
+}  // namespace
+
+int launch_layernorm(const float* x, bf16_t* y, const float* gamma, const float* beta, int M, int C, float eps,
+                     hipStream_t st) {
+  if (C % 4 || C > 64 * 4 * 8) return DF_ESHAPE;
+  dim3 grid((M + 3) / 4);
+  const int per = cdiv(C, 256);
+  if (per <= 1) hipLaunchKernelGGL(layernorm_rows<1>, grid, dim3(256), 0, st, x, y, gamma, beta, M, C, eps);
+  else if (per <= 3) hipLaunchKernelGGL(layernorm_rows<3>, grid, dim3(256), 0, st, x, y, gamma, beta, M, C, eps);
+  else if (per <= 5) hipLaunchKernelGGL(layernorm_rows<5>, grid, dim3(256), 0, st, x, y, gamma, beta, M, C, eps);
+  else hipLaunchKernelGGL(layernorm_rows<8>, grid, dim3(256), 0, st, x, y, gamma, beta, M, C, eps);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_geglu(const bf16_t* h, bf16_t* out, int M, int F, hipStream_t st) {
+  if (F % 8) return DF_ESHAPE;
+  const long long n = (long long)M * (F / 8);
+  hipLaunchKernelGGL(geglu_kernel, dim3(blocks_for(n)), dim3(256), 0, st, h, out, (long long)M, F);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_cast_bf16(const float* x, bf16_t* y, long long n, int silu, hipStream_t st) {
+  const long long n4 = n / 4;
+  if (n4 > 0) hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n4)), dim3(256), 0, st, x, y, n4, silu);
+  if (n4 * 4 < n) hipLaunchKernelGGL(cast_bf16_tail, dim3(1), dim3(256), 0, st, x, y, n4 * 4, n, silu);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, long long pixels, hipStream_t st) {
+  if (Ca % 4 || Cb % 4) return DF_ESHAPE;
+  const long long n = pixels * ((Ca + Cb) / 4);
+  hipLaunchKernelGGL(concat_kernel, dim3(blocks_for(n)), dim3(256), 0, st, a, Ca / 4, b, Cb / 4, out, pixels);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C, hipStream_t st) {
+  if (C % 4) return DF_ESHAPE;
+  const long long n = (long long)B * 4 * R * W * (C / 4);
+  hipLaunchKernelGGL(upsample2x_kernel, dim3(blocks_for(n)), dim3(256), 0, st, x, y, B, R, W, C / 4);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st) {
+  if (n <= 0) return DF_OK;
+  hipLaunchKernelGGL(axpy_kernel, dim3(blocks_for(n)), dim3(256), 0, st, x, e, alpha, n);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+}  // namespace df

@@ -1,0 +1,270 @@
+// Corrected asynchronous GroupNorm (Section 4, Eq. 2) for channels-last patches.
+//
+// Two launches, both HBM-bound streaming passes with 16-byte accesses:
+//   gn_stats  every block sums a strip of pixels into per-group (sum, sum of
+//             squares) partials; the last block to finish (per batch item)
+//             adds the partials in a fixed order, emits the fresh per-patch
+//             sums, combines them with the stale sums of the other patches
+//             according to the statistic mode and stores mean / rstd.
+//   gn_apply  y = (x - mean) * rstd * gamma + beta (+ SiLU), second read of x
+//             comes from L2 / Infinity Cache at the sizes of one patch.
+// A lane keeps a fixed channel offset for its whole strip, so gamma/beta and
+// the statistics are fetched once per lane.
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+
+constexpr int kMaxG = 64;
+
+struct GnLayout {
+  int tp;        // lanes per pixel (C / vec)
+  int ppb;       // pixels per block iteration
+  int threads;   // tp * ppb
+  int nblk;      // blocks per segment
+  int pix_per_blk;
+};
+
+template <typename Tin>
+__global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial, unsigned int* __restrict__ counters,
+                         float* __restrict__ meanrstd, const float* __restrict__ stale, float* __restrict__ sums_out,
+                         int pix_seg, int C, int G, int tp, int ppb, int pix_per_blk, int nseg, int patch_idx, int N,
+                         float eps, int stat_mode) {
+  constexpr int V = Elem<Tin>::kVec;
+  __shared__ float s_sum[kMaxG], s_sq[kMaxG];
+  __shared__ float s_red[2][16][kMaxG];
+  __shared__ int s_last;
+  const int blk = blockIdx.x, seg = blockIdx.y, b = blockIdx.z;
+  const int nblk = gridDim.x, B = gridDim.z;
+  const int cg = C / G;
+  const int tid = threadIdx.x;
+  if (tid < G) { s_sum[tid] = 0.f; s_sq[tid] = 0.f; }
+  __syncthreads();
+
+  const int c0 = (tid % tp) * V;
+  const int psub = tid / tp;
+  const long long seg_base = ((long long)b * nseg + seg) * pix_seg;
+  const int p_lo = blk * pix_per_blk;
+  int p_hi = p_lo + pix_per_blk;
+  if (p_hi > pix_seg) p_hi = pix_seg;
+  float s[V], q[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) { s[i] = 0.f; q[i] = 0.f; }
+  for (int p = p_lo + psub; p < p_hi; p += ppb) {
+    float v[V];
+    ld_vec(x + (seg_base + p) * C + c0, v);
+#pragma unroll
+    for (int i = 0; i < V; ++i) { s[i] += v[i]; q[i] = fmaf(v[i], v[i], q[i]); }
+  }
+  // fold the lane's channels into their groups (neighbouring channels mostly share one)
+  {
+    int g_prev = c0 / cg;
+    float ss = 0.f, qq = 0.f;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const int g = (c0 + i) / cg;
+      if (g != g_prev) {
+        atomicAdd(&s_sum[g_prev], ss);
+        atomicAdd(&s_sq[g_prev], qq);
+        ss = 0.f; qq = 0.f; g_prev = g;
+      }
+      ss += s[i]; qq += q[i];
+    }
+    atomicAdd(&s_sum[g_prev], ss);
+    atomicAdd(&s_sq[g_prev], qq);
+  }
+  __syncthreads();
+  float* my = partial + ((((long long)b * nseg + seg) * nblk + blk) * G) * 2;
+  if (tid < G) { my[2 * tid] = s_sum[tid]; my[2 * tid + 1] = s_sq[tid]; }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned int total = (unsigned int)(nblk * nseg);
+    const unsigned int prev = atomicAdd(&counters[b], 1u);
+    s_last = (prev == total - 1);
+    if (s_last) counters[b] = 0u;  // leave the counter at zero for the next launch
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+
+  // ---- last block of this batch item: ordered reduction of all partials ----
+  const int parts = blockDim.x / G < 16 ? blockDim.x / G : 16;
+  const int g = tid % G, part = tid / G;
+  float tot_s = 0.f, tot_q = 0.f;  // over all segments (valid on part == 0 lanes)
+  for (int sg = 0; sg < nseg; ++sg) {
+    float a = 0.f, c = 0.f;
+    if (part < parts) {
+      const float* base = partial + (((long long)b * nseg + sg) * nblk) * G * 2;
+      for (int k = part; k < nblk; k += parts) {
+        a += __builtin_nontemporal_load(base + ((long long)k * G + g) * 2);
+        c += __builtin_nontemporal_load(base + ((long long)k * G + g) * 2 + 1);
+      }
+      s_red[0][part][g] = a;
+      s_red[1][part][g] = c;
+    }
+    __syncthreads();
+    if (part == 0) {
+      float fs = 0.f, fq = 0.f;
+      for (int k = 0; k < parts; ++k) { fs += s_red[0][k][g]; fq += s_red[1][k][g]; }
+      tot_s += fs; tot_q += fq;
+      if (nseg > 1) {
+        float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
+        o[0] = fs; o[1] = fq;
+      }
+    }
+    __syncthreads();
+  }
+  if (part != 0) return;
+  const float n_loc = (float)pix_seg * (float)cg;
+  float mean, var;
+  if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
+    // the whole image is fresh: exact statistics
+    const float n = n_loc * (float)nseg;
+    mean = tot_s / n;
+    var = fmaxf(tot_q / n - mean * mean, 0.f);
+  } else {
+    const float n_glob = n_loc * (float)N;
+    float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+    for (int j = 0; j < N; ++j) {
+      const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
+      const float a = sp[0], c = sp[1];
+      if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
+    }
+    const float loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
+    if (stat_mode == DF_GN_SUMS) {
+      mean = (tot_s + st_s) / n_glob;
+      var = fmaxf((tot_q + st_q) / n_glob - mean * mean, 0.f);
+    } else if (stat_mode == DF_GN_EQ2) {
+      mean = (st_s + own_s) / n_glob + (loc_m - own_s / n_loc);
+      const float m2 = (st_q + own_q) / n_glob + (loc_m2 - own_q / n_loc);
+      var = m2 - mean * mean;
+      if (var < 0.f) var = loc_m2 - loc_m * loc_m;
+    } else if (stat_mode == DF_GN_SEPARATE) {
+      mean = loc_m;
+      var = fmaxf(loc_m2 - loc_m * loc_m, 0.f);
+    } else {
+      mean = (st_s + own_s) / n_glob;
+      var = fmaxf((st_q + own_q) / n_glob - mean * mean, 0.f);
+    }
+  }
+  if (nseg == 1 && sums_out != nullptr) {  // written after the stale sums were read: may alias the own slot
+    float* o = sums_out + ((long long)b * G + g) * 2;
+    o[0] = tot_s; o[1] = tot_q;
+  }
+  float* mr = meanrstd + ((long long)b * G + g) * 2;
+  mr[0] = mean;
+  mr[1] = 1.0f / sqrtf(var + eps);
+}
+
+template <typename Tin, typename Tout>
+__global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const float* __restrict__ meanrstd,
+                         const float* __restrict__ gamma, const float* __restrict__ beta, int pix_b, int C, int G,
+                         int tp, int ppb, int pix_per_blk, int silu) {
+  constexpr int V = Elem<Tin>::kVec;
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int c0 = (tid % tp) * V;
+  const int psub = tid / tp;
+  const int cg = C / G;
+  float sc[V], sh[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    const int c = c0 + i;
+    const int g = c / cg;
+    const float mean = meanrstd[((long long)b * G + g) * 2];
+    const float rstd = meanrstd[((long long)b * G + g) * 2 + 1];
+    sc[i] = rstd * gamma[c];
+    sh[i] = beta[c] - mean * sc[i];
+  }
+  const long long base = (long long)b * pix_b;
+  const int p_lo = blockIdx.x * pix_per_blk;
+  int p_hi = p_lo + pix_per_blk;
+  if (p_hi > pix_b) p_hi = pix_b;
+  for (int p = p_lo + psub; p < p_hi; p += ppb) {
+    float v[V];
+    ld_vec(x + (base + p) * C + c0, v);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float t = fmaf(v[i], sc[i], sh[i]);
+      v[i] = silu ? silu_f(t) : t;
+    }
+    Tout* o = y + (base + p) * C + c0;
+    if constexpr (sizeof(Tout) == sizeof(Tin)) {
+      st_vec(o, v);
+    } else {  // float in, bf16 out: 4 values = 8 bytes
+      u32x2 t = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])};
+      *reinterpret_cast<u32x2*>(o) = t;
+    }
+  }
+}
+
+GnLayout gn_layout(int C, int vec, long long pix, int target_blocks) {
+  GnLayout L;
+  L.tp = C / vec;
+  L.ppb = 256 / L.tp;
+  if (L.ppb < 1) L.ppb = 1;
+  L.threads = L.tp * L.ppb;
+  long long per = (pix + target_blocks - 1) / target_blocks;
+  long long min_per = (long long)L.ppb * 4;
+  if (per < min_per) per = min_per;
+  per = (per + L.ppb - 1) / L.ppb * L.ppb;
+  L.pix_per_blk = (int)per;
+  L.nblk = (int)((pix + per - 1) / per);
+  return L;
+}
+
+}  // namespace
+
+size_t groupnorm_scratch_bytes(int B, int nseg, int G) {
+  // partials for at most 2048 blocks per batch item + mean/rstd
+  return kScratchCounterBytes + ((size_t)B * 2048 * G * 2 + (size_t)B * G * 2) * sizeof(float) + 1024;
+}
+
+int launch_groupnorm(const GnArgs& a, hipStream_t st) {
+  const int vec = a.in_dtype == DF_BF16 ? 8 : 4;
+  if (a.C % a.G || a.C % vec || a.G > kMaxG || a.C / vec > 1024) return DF_ESHAPE;
+  if (a.in_dtype == DF_BF16 && a.out_dtype != DF_BF16) return DF_ESHAPE;
+  if (a.B > 1024) return DF_ESHAPE;
+  const long long pix_seg = (long long)a.Rseg * a.W;
+  if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
+  int target = 1024 / a.nseg;
+  if (target < 1) target = 1;
+  GnLayout L = gn_layout(a.C, vec, pix_seg, target);
+  if ((long long)L.nblk * a.nseg > 2048) return DF_ESHAPE;
+  if (L.threads < a.G) return DF_ESHAPE;
+  char* scr = (char*)scratch_get(groupnorm_scratch_bytes(a.B, a.nseg, a.G));
+  if (!scr) return DF_ENOMEM;
+  unsigned int* counters = (unsigned int*)scr;
+  float* meanrstd = (float*)(scr + kScratchCounterBytes);
+  float* partial = meanrstd + (size_t)a.B * a.G * 2;
+  dim3 gs(L.nblk, a.nseg, a.B);
+  if (a.in_dtype == DF_BF16) {
+    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), 0, st, (const bf16_t*)a.x, partial, counters, meanrstd,
+                       a.stale, a.sums_out, (int)pix_seg, a.C, a.G, L.tp, L.ppb, L.pix_per_blk, a.nseg, a.patch_idx,
+                       a.N, a.eps, a.stat_mode);
+  } else {
+    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), 0, st, (const float*)a.x, partial, counters, meanrstd,
+                       a.stale, a.sums_out, (int)pix_seg, a.C, a.G, L.tp, L.ppb, L.pix_per_blk, a.nseg, a.patch_idx,
+                       a.N, a.eps, a.stat_mode);
+  }
+  DF_LAUNCH_CHECK();
+  const long long pix_b = pix_seg * a.nseg;
+  GnLayout A = gn_layout(a.C, vec, pix_b, 2048);
+  dim3 ga(A.nblk, a.B);
+  if (a.in_dtype == DF_BF16) {
+    hipLaunchKernelGGL((gn_apply<bf16_t, bf16_t>), ga, dim3(A.threads), 0, st, (const bf16_t*)a.x, (bf16_t*)a.y,
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+  } else if (a.out_dtype == DF_BF16) {
+    hipLaunchKernelGGL((gn_apply<float, bf16_t>), ga, dim3(A.threads), 0, st, (const float*)a.x, (bf16_t*)a.y,
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+  } else {
+    hipLaunchKernelGGL((gn_apply<float, float>), ga, dim3(A.threads), 0, st, (const float*)a.x, (float*)a.y, meanrstd,
+                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+  }
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+}  // namespace df

@@ -1,0 +1,93 @@
+// Internal launch interface of the gfx950 kernels.  Every function enqueues on
+// `st` and returns a DF_* code; shapes are validated by the callers in api.cpp
+// and unet.cpp, so these check only what the kernels themselves assume.
+#pragma once
+#include "common.h"
+
+namespace df {
+
+// ---- device scratch owned by the library (one per device, grown on demand) ----
+// Returns a 256-byte aligned device buffer of at least `bytes`, or nullptr.
+// The first 4 KiB are counters that kernels leave at zero.
+void* scratch_get(size_t bytes);
+constexpr size_t kScratchCounterBytes = 4096;
+
+// ---- refresh.hip ----
+int launch_copy_rows(void* dst, const void* src, long long rows, long long row_bytes, long long dst_stride_bytes,
+                     long long src_stride_bytes, hipStream_t st);
+
+// ---- groupnorm.hip ----
+struct GnArgs {
+  const void* x;        // [B, nseg*Rseg, W, C]
+  void* y;              // same shape, out dtype
+  const float* stale;   // [N,B,G,2] or nullptr (nseg > 1 or N == 1)
+  float* sums_out;      // nseg == 1: [B,G,2] (may be null); nseg > 1: [nseg,B,G,2]
+  const float* gamma;
+  const float* beta;
+  int B, Rseg, W, C, G;
+  int nseg;             // 1: one patch (displaced); >1: full image split into nseg patches, exact statistics
+  int patch_idx, N;
+  float eps;
+  int stat_mode, silu;
+  int in_dtype, out_dtype;
+};
+int launch_groupnorm(const GnArgs& a, hipStream_t st);
+size_t groupnorm_scratch_bytes(int B, int nseg, int G);
+
+// ---- conv.hip / gemm ----
+struct ConvArgs {
+  const void* x;         // fresh rows [B, R, W, Cin]
+  const void* halo_top;  // row above the patch [B][W*Cin] with batch stride halo_bstride elements, or nullptr (zero)
+  const void* halo_bot;  // row below the patch, or nullptr
+  long long halo_bstride;
+  const void* w;         // [Cout, 3, 3, Cin]
+  const float* bias;     // [Cout] or nullptr
+  const float* chan_add; // [B, Cout] added per batch item and channel, or nullptr
+  const float* residual; // [B, Ro, Wo, Cout] float added before the activation, or nullptr
+  void* y;               // [B, Ro, Wo, Cout]
+  int B, R, W, Cin, Cout, stride, act;
+  int dtype;             // of x, halos and w
+  int out_dtype;
+};
+int launch_conv3x3(const ConvArgs& a, hipStream_t st);
+
+struct GemmArgs {
+  const void* A;  // [M, K] bf16, row stride lda
+  const void* W;  // [N, K] bf16, row stride ldw
+  const float* bias;      // [N] or nullptr
+  const float* residual;  // [M, N] float, row stride ldr, or nullptr (may alias out when out is float)
+  void* out;              // [M, N], row stride ldo
+  int M, N, K;
+  long long lda, ldw, ldr, ldo;
+  int act;        // 0 none, 1 SiLU
+  int out_dtype;
+};
+int launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
+
+// ---- attn.hip ----
+struct AttnArgs {
+  const void* q;        // [B, Lq, heads*d], row stride ldq, batch stride bsq
+  const void* k_fresh;  // rows [own_lo, own_lo + own_n) of the key set
+  const void* v_fresh;
+  const void* k_stale;  // all other rows, indexed by absolute key row; may be null if own range covers everything
+  const void* v_stale;
+  void* out;            // [B, Lq, heads*d]
+  int B, Lq, L, heads, d;
+  int own_lo, own_n;    // key rows [own_lo, own_lo+own_n) come from the fresh tensors (row 0 of fresh = key own_lo)
+  long long ldq, ldkf, ldvf, ldks, ldvs, ldo;
+  long long bsq, bskf, bsvf, bsks, bsvs, bso;  // batch strides in elements
+  float scale;
+  int dtype;
+};
+int launch_attention(const AttnArgs& a, hipStream_t st);
+size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d);
+
+// ---- elementwise.hip ----
+int launch_layernorm(const float* x, bf16_t* y, const float* gamma, const float* beta, int M, int C, float eps, hipStream_t st);
+int launch_geglu(const bf16_t* h, bf16_t* out, int M, int F, hipStream_t st);  // h [M, 2F] -> out [M, F]
+int launch_cast_bf16(const float* x, bf16_t* y, long long n, int silu, hipStream_t st);
+int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, long long pixels, hipStream_t st);
+int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C, hipStream_t st);
+int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st);
+
+}  // namespace df

@@ -1,0 +1,614 @@
+// One UNet denoising step for one patch under displaced patch parallelism
+// (Section 4): the plan walks the SDXL-shaped block list and enqueues the layer
+// kernels.  Layers that mix space (3x3 convolutions, self-attention, GroupNorm)
+// take cross-patch context from the stale-state blob; per-token layers run on
+// the fresh tokens only.
+//
+// Stale state kept per layer (what differs from a literal full-shape copy of the
+// input activation is noted):
+//   convolution     the first and last input row of every patch, [B, N, 2, W, Cin]
+//                   bf16 - the only rows another patch can ever read (Section 5.3)
+//   self-attention  projected keys and values, [B, L, C] bf16 each; projection is
+//                   per token, so projecting the scattered activation equals
+//                   scattering the projections
+//   GroupNorm       per-patch (sum, sum of squares), [N, B, G, 2] float
+//
+// FULL mode is the synchronous first step: the whole image is one fresh patch and
+// every buffer is filled for all N patches.  DISPLACED computes patch i and, with
+// refresh, overwrites the patch's own part of each buffer (never read by itself).
+//
+// Precision: matrix operands bf16, accumulation float; the residual stream
+// (block outputs, transformer hidden state) stays float so that rounding does
+// not accumulate over the 70 transformer blocks.
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace df;
+
+namespace {
+
+struct WeightSpec {
+  std::string name;
+  int ndim;
+  long long dims[4];
+};
+
+struct BlockDesc {
+  enum Kind { CONV_IN, RES, XF, PUSH, DOWN, UP, OUT } kind;
+  std::string name;
+  int cin = 0, cout = 0, level = 0, depth = 0;
+  bool concat = false;
+};
+
+bool cfg_ok(const df_unet_cfg* c) {
+  if (!c) return false;
+  if (c->n_levels < 1 || c->n_levels > 4 || c->B < 1 || c->N < 1 || c->H < 1 || c->W < 1) return false;
+  if (c->head_dim != 64 || c->groups < 1 || c->groups > 64 || c->in_ch < 1 || c->res_per_level < 1) return false;
+  if (c->emb_dim % 32 || c->text_dim % 32 || c->text_len < 1 || c->in_ch % 4) return false;
+  const int down = 1 << (c->n_levels - 1);
+  if (c->H % (c->N * down) || c->W % down) return false;
+  for (int l = 0; l < c->n_levels; ++l) {
+    const int ch = c->levels[l];
+    if (ch % 64 || ch % c->groups || c->depths[l] < 0) return false;
+    if (l + 1 < c->n_levels && ((c->H >> l) / c->N) % 2) return false;  // stride-2 conv needs even patch rows
+  }
+  return true;
+}
+
+std::vector<BlockDesc> build_blocks(const df_unet_cfg& c) {
+  std::vector<BlockDesc> out;
+  std::vector<int> skips;
+  auto add = [&](BlockDesc::Kind k, const std::string& n, int cin, int cout, int level, int depth, bool cat) {
+    BlockDesc b; b.kind = k; b.name = n; b.cin = cin; b.cout = cout; b.level = level; b.depth = depth; b.concat = cat;
+    out.push_back(b);
+  };
+  const int nl = c.n_levels;
+  int cur = c.levels[0];
+  add(BlockDesc::CONV_IN, "conv_in", c.in_ch, cur, 0, 0, false);
+  add(BlockDesc::PUSH, "", 0, 0, 0, 0, false);
+  skips.push_back(cur);
+  for (int li = 0; li < nl; ++li) {
+    const int ch = c.levels[li];
+    for (int j = 0; j < c.res_per_level; ++j) {
+      const std::string base = "down" + std::to_string(li);
+      add(BlockDesc::RES, base + ".res" + std::to_string(j), cur, ch, li, 0, false);
+      cur = ch;
+      if (c.depths[li] > 0) add(BlockDesc::XF, base + ".xf" + std::to_string(j), ch, ch, li, c.depths[li], false);
+      add(BlockDesc::PUSH, "", 0, 0, 0, 0, false);
+      skips.push_back(cur);
+    }
+    if (li + 1 < nl) {
+      add(BlockDesc::DOWN, "down" + std::to_string(li) + ".down", cur, cur, li, 0, false);
+      add(BlockDesc::PUSH, "", 0, 0, 0, 0, false);
+      skips.push_back(cur);
+    }
+  }
+  const int lm = nl - 1;
+  add(BlockDesc::RES, "mid.res0", cur, cur, lm, 0, false);
+  if (c.depths[lm] > 0) add(BlockDesc::XF, "mid.xf", cur, cur, lm, c.depths[lm], false);
+  add(BlockDesc::RES, "mid.res1", cur, cur, lm, 0, false);
+  for (int li = nl - 1; li >= 0; --li) {
+    const int ch = c.levels[li];
+    const std::string base = "up" + std::to_string(li);
+    for (int j = 0; j < c.res_per_level + 1; ++j) {
+      const int sk = skips.back();
+      skips.pop_back();
+      add(BlockDesc::RES, base + ".res" + std::to_string(j), cur + sk, ch, li, 0, true);
+      cur = ch;
+      if (c.depths[li] > 0) add(BlockDesc::XF, base + ".xf" + std::to_string(j), ch, ch, li, c.depths[li], false);
+    }
+    if (li > 0) add(BlockDesc::UP, base + ".up", cur, cur, li, 0, false);
+  }
+  add(BlockDesc::OUT, "out", cur, c.in_ch, 0, 0, false);
+  return out;
+}
+
+std::vector<WeightSpec> build_weight_specs(const df_unet_cfg& c) {
+  std::vector<WeightSpec> s;
+  auto vec = [&](const std::string& n, long long d) { s.push_back({n, 1, {d, 0, 0, 0}}); };
+  auto conv = [&](const std::string& n, int cin, int cout) {
+    s.push_back({n + ".w", 4, {cout, 3, 3, cin}});
+    vec(n + ".b", cout);
+  };
+  auto norm = [&](const std::string& n, int ch) { vec(n + ".g", ch); vec(n + ".beta", ch); };
+  auto lin = [&](const std::string& n, int cin, int cout, bool bias) {
+    s.push_back({n + ".w", 2, {cout, cin, 0, 0}});
+    if (bias) vec(n + ".b", cout);
+  };
+  for (const BlockDesc& b : build_blocks(c)) {
+    switch (b.kind) {
+      case BlockDesc::CONV_IN: conv(b.name, b.cin, b.cout); break;
+      case BlockDesc::RES:
+        norm(b.name + ".gn1", b.cin);
+        conv(b.name + ".conv1", b.cin, b.cout);
+        lin(b.name + ".emb", c.emb_dim, b.cout, true);
+        norm(b.name + ".gn2", b.cout);
+        conv(b.name + ".conv2", b.cout, b.cout);
+        if (b.cin != b.cout) lin(b.name + ".sc", b.cin, b.cout, true);
+        break;
+      case BlockDesc::XF: {
+        const int ch = b.cin;
+        norm(b.name + ".gn", ch);
+        lin(b.name + ".pin", ch, ch, true);
+        for (int d = 0; d < b.depth; ++d) {
+          const std::string p = b.name + ".b" + std::to_string(d);
+          norm(p + ".ln1", ch);
+          lin(p + ".attn1.qkv", ch, 3 * ch, false);
+          lin(p + ".attn1.o", ch, ch, true);
+          norm(p + ".ln2", ch);
+          lin(p + ".attn2.q", ch, ch, false);
+          lin(p + ".attn2.kv", c.text_dim, 2 * ch, false);
+          lin(p + ".attn2.o", ch, ch, true);
+          norm(p + ".ln3", ch);
+          lin(p + ".ff1", ch, 8 * ch, true);
+          lin(p + ".ff2", 4 * ch, ch, true);
+        }
+        lin(b.name + ".pout", ch, ch, true);
+        break;
+      }
+      case BlockDesc::DOWN:
+      case BlockDesc::UP: conv(b.name, b.cin, b.cout); break;
+      case BlockDesc::OUT:
+        norm(b.name + ".gn", b.cin);
+        conv(b.name + ".conv", b.cin, b.cout);
+        break;
+      case BlockDesc::PUSH: break;
+    }
+  }
+  return s;
+}
+
+struct StaleEntry {
+  std::string name;
+  size_t off, bytes;
+};
+
+inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+}  // namespace
+
+struct df_unet {
+  df_unet_cfg cfg;
+  std::vector<BlockDesc> blocks;
+  std::map<std::string, const void*> w;
+  std::vector<StaleEntry> stale;
+  std::map<std::string, int> stale_idx;
+  size_t stale_bytes = 0;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+};
+
+namespace {
+
+// Walks the block list.  In dry mode nothing is launched: the walk only sizes the
+// workspace arena, lists the stale buffers and finds the largest scratch request.
+struct Exec {
+  const df_unet_cfg& c;
+  const std::vector<BlockDesc>& blocks;
+  const std::map<std::string, const void*>* w;
+  bool dry;
+  int mode, patch, refresh;
+  hipStream_t st;
+  char* ws;
+  size_t ws_cap;
+  size_t top = 0, high = 0;
+  char* stale_base;
+  std::vector<StaleEntry>* stale_list;          // dry: appended to; live: looked up
+  const std::map<std::string, int>* stale_idx;
+  size_t stale_top = 0;
+  size_t scratch_need = 0;
+  int err = DF_OK;
+
+  int B() const { return c.B; }
+  int N() const { return c.N; }
+  bool full() const { return mode == DF_MODE_FULL; }
+  int rows(int level) const { return full() ? (c.H >> level) : (c.H >> level) / c.N; }
+  int width(int level) const { return c.W >> level; }
+
+  void* alloc(size_t bytes) {
+    bytes = align256(bytes);
+    size_t at = top;
+    top += bytes;
+    if (top > high) high = top;
+    if (!dry && top > ws_cap) { err = DF_ENOMEM; return nullptr; }
+    return dry ? nullptr : ws + at;
+  }
+  const void* weight(const std::string& n) {
+    if (dry) return nullptr;
+    auto it = w->find(n);
+    if (it == w->end()) { err = DF_EINVAL; return nullptr; }
+    return it->second;
+  }
+  char* stale_buf(const std::string& n, size_t bytes) {
+    if (dry) {
+      stale_list->push_back({n, stale_top, bytes});
+      stale_top += align256(bytes);
+      return nullptr;
+    }
+    auto it = stale_idx->find(n);
+    if (it == stale_idx->end() || (*stale_list)[it->second].bytes != bytes) { err = DF_EINVAL; return nullptr; }
+    return stale_base + (*stale_list)[it->second].off;
+  }
+  void run(int rc) { if (err == DF_OK && rc != DF_OK) err = rc; }
+  bool live() const { return !dry && err == DF_OK; }
+
+  // ---- layers ----
+  void gemm(const void* A, long long lda, const std::string& wn, bool bias, const float* residual, long long ldr,
+            void* out, long long ldo, int M, int Nn, int K, int out_dtype) {
+    const void* W = weight(wn + ".w");
+    const float* bp = bias ? (const float*)weight(wn + ".b") : nullptr;
+    if (!live()) return;
+    GemmArgs g = {};
+    g.A = A; g.W = W; g.bias = bp; g.residual = residual; g.out = out;
+    g.M = M; g.N = Nn; g.K = K; g.lda = lda; g.ldw = K; g.ldr = ldr; g.ldo = ldo; g.act = 0; g.out_dtype = out_dtype;
+    run(launch_gemm_bf16(g, st));
+  }
+
+  void groupnorm(const std::string& name, const void* x, int in_dtype, int level_rows, int W, int C, float eps, int silu,
+                 bf16_t* y) {
+    // level_rows: rows of x in this mode
+    const int G = c.groups;
+    float* entry = (float*)stale_buf(name + ".stats", (size_t)N() * B() * G * 2 * sizeof(float));
+    const size_t need = groupnorm_scratch_bytes(B(), full() ? N() : 1, G);
+    if (need > scratch_need) scratch_need = need;
+    const float* gamma = (const float*)weight(name + ".g");
+    const float* beta = (const float*)weight(name + ".beta");
+    if (!live()) return;
+    GnArgs a = {};
+    a.x = x; a.y = y; a.gamma = gamma; a.beta = beta;
+    a.B = B(); a.W = W; a.C = C; a.G = G; a.eps = eps; a.silu = silu; a.in_dtype = in_dtype; a.out_dtype = DF_BF16;
+    a.stat_mode = DF_GN_SUMS;
+    if (full()) {
+      a.nseg = N(); a.Rseg = level_rows / N(); a.N = 1; a.patch_idx = 0; a.stale = nullptr; a.sums_out = entry;
+    } else {
+      a.nseg = 1; a.Rseg = level_rows; a.N = N(); a.patch_idx = patch; a.stale = entry;
+      a.sums_out = refresh ? entry + (size_t)patch * B() * G * 2 : nullptr;
+    }
+    run(launch_groupnorm(a, st));
+  }
+
+  // x: bf16 [B, R, W, Cin] rows of this mode; out: [B, R/stride, W/stride, Cout]
+  void conv(const std::string& name, const bf16_t* x, int R, int W, int Cin, int Cout, int stride, void* out,
+            int out_dtype, const float* chan_add, const float* residual) {
+    const size_t rowe = (size_t)W * Cin;
+    bf16_t* entry = (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * rowe * sizeof(bf16_t));
+    const void* wt = weight(name + ".w");
+    const float* bias = (const float*)weight(name + ".b");
+    if (!live()) return;
+    ConvArgs a = {};
+    a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.residual = residual; a.y = out;
+    a.B = B(); a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = 0;
+    a.dtype = DF_BF16; a.out_dtype = out_dtype;
+    a.halo_bstride = (long long)N() * 2 * rowe;
+    if (!full()) {
+      if (patch > 0) a.halo_top = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;           // last row of the patch above
+      if (patch + 1 < N() && stride == 1) a.halo_bot = entry + ((size_t)(patch + 1) * 2) * rowe;  // first row of the patch below
+    }
+    run(launch_conv3x3(a, st));
+    if (!live()) return;
+    const long long rb = (long long)rowe * sizeof(bf16_t);
+    if (full()) {
+      const int Rp = R / N();
+      for (int which = 0; which < 2; ++which)
+        run(launch_copy_rows(entry + (size_t)which * rowe, x + (size_t)which * (Rp - 1) * rowe, (long long)B() * N(), rb,
+                             2 * rb, (long long)Rp * rb, st));
+    } else if (refresh) {
+      for (int which = 0; which < 2; ++which)
+        run(launch_copy_rows(entry + ((size_t)patch * 2 + which) * rowe, x + (size_t)which * (R - 1) * rowe, B(), rb,
+                             (long long)N() * 2 * rb, (long long)R * rb, st));
+    }
+  }
+
+  void resblock(const BlockDesc& b, const float* x, const bf16_t* emb_act, float* out) {
+    const int R = rows(b.level), W = width(b.level);
+    const size_t px = (size_t)B() * R * W;
+    const size_t mark = top;
+    bf16_t* a1 = (bf16_t*)alloc(px * b.cin * 2);
+    bf16_t* h1 = (bf16_t*)alloc(px * b.cout * 2);
+    bf16_t* a2 = (bf16_t*)alloc(px * b.cout * 2);
+    float* embp = (float*)alloc((size_t)B() * b.cout * 4);
+    groupnorm(b.name + ".gn1", x, DF_F32, R, W, b.cin, 1e-5f, 1, a1);
+    gemm(emb_act, c.emb_dim, b.name + ".emb", true, nullptr, 0, embp, b.cout, B(), b.cout, c.emb_dim, DF_F32);
+    conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr);
+    groupnorm(b.name + ".gn2", h1, DF_BF16, R, W, b.cout, 1e-5f, 1, a2);
+    const float* residual = x;
+    if (b.cin != b.cout) {
+      bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
+      if (live()) run(launch_cast_bf16(x, xb, (long long)px * b.cin, 0, st));
+      gemm(xb, b.cin, b.name + ".sc", true, nullptr, 0, out, b.cout, (int)px, b.cout, b.cin, DF_F32);
+      residual = out;
+    }
+    conv(b.name + ".conv2", a2, R, W, b.cout, b.cout, 1, out, DF_F32, nullptr, residual);
+    top = mark;
+  }
+
+  void transformer(const BlockDesc& b, const float* x, const bf16_t* text, float* out) {
+    const int R = rows(b.level), W = width(b.level), C = b.cin;
+    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int M = B() * Lq;
+    const int TL = c.text_len;
+    const size_t mark = top;
+    bf16_t* nb = (bf16_t*)alloc((size_t)M * C * 2);          // normalised input of the next GEMM
+    float* h = (float*)alloc((size_t)M * C * 4);             // hidden state (residual stream)
+    bf16_t* qkv = (bf16_t*)alloc((size_t)M * 3 * C * 2);
+    bf16_t* ao = (bf16_t*)alloc((size_t)M * C * 2);          // attention output
+    bf16_t* kv2 = (bf16_t*)alloc((size_t)B() * TL * 2 * C * 2);
+    bf16_t* ff = (bf16_t*)alloc((size_t)M * 8 * C * 2);
+    bf16_t* fg = (bf16_t*)alloc((size_t)M * 4 * C * 2);
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nb);
+    gemm(nb, C, b.name + ".pin", true, nullptr, 0, h, C, M, C, C, DF_F32);
+    for (int d = 0; d < b.depth; ++d) {
+      const std::string p = b.name + ".b" + std::to_string(d);
+      // --- self-attention: fresh queries against spliced fresh/stale keys and values ---
+      const float* g1 = (const float*)weight(p + ".ln1.g");
+      const float* b1 = (const float*)weight(p + ".ln1.beta");
+      if (live()) run(launch_layernorm(h, nb, g1, b1, M, C, 1e-5f, st));
+      gemm(nb, C, p + ".attn1.qkv", false, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16);
+      bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
+      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.q = qkv; a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C; a.k_stale = ks; a.v_stale = vs; a.out = ao;
+        a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
+        a.own_lo = full() ? 0 : patch * Lq; a.own_n = Lq;
+        a.ldq = a.ldkf = a.ldvf = 3 * C; a.ldks = a.ldvs = C; a.ldo = C;
+        a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C; a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
+        a.scale = scale; a.dtype = DF_BF16;
+        run(launch_attention(a, st));
+      }
+      if (live() && (full() || refresh)) {
+        // the patch's projected keys/values replace its rows of the stale buffers (read only by later steps)
+        const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+        for (int bi = 0; bi < B(); ++bi) {
+          run(launch_copy_rows(ks + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + C, Lq, C * 2LL, C * 2LL,
+                               3LL * C * 2, st));
+          run(launch_copy_rows(vs + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + 2 * C, Lq, C * 2LL,
+                               C * 2LL, 3LL * C * 2, st));
+        }
+      }
+      gemm(ao, C, p + ".attn1.o", true, h, C, h, C, M, C, C, DF_F32);
+      // --- cross-attention to the text tokens: per token, no cross-patch data ---
+      const float* g2 = (const float*)weight(p + ".ln2.g");
+      const float* b2 = (const float*)weight(p + ".ln2.beta");
+      if (live()) run(launch_layernorm(h, nb, g2, b2, M, C, 1e-5f, st));
+      gemm(nb, C, p + ".attn2.q", false, nullptr, 0, qkv, C, M, C, C, DF_BF16);
+      gemm(text, c.text_dim, p + ".attn2.kv", false, nullptr, 0, kv2, 2 * C, B() * TL, 2 * C, c.text_dim, DF_BF16);
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = ao;
+        a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
+        a.ldq = C; a.ldkf = a.ldvf = 2 * C; a.ldks = a.ldvs = 2 * C; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * 2 * C; a.bso = (long long)Lq * C;
+        a.scale = scale; a.dtype = DF_BF16;
+        run(launch_attention(a, st));
+      }
+      gemm(ao, C, p + ".attn2.o", true, h, C, h, C, M, C, C, DF_F32);
+      // --- GEGLU feed-forward ---
+      const float* g3 = (const float*)weight(p + ".ln3.g");
+      const float* b3 = (const float*)weight(p + ".ln3.beta");
+      if (live()) run(launch_layernorm(h, nb, g3, b3, M, C, 1e-5f, st));
+      gemm(nb, C, p + ".ff1", true, nullptr, 0, ff, 8 * C, M, 8 * C, C, DF_BF16);
+      if (live()) run(launch_geglu(ff, fg, M, 4 * C, st));
+      gemm(fg, 4 * C, p + ".ff2", true, h, C, h, C, M, C, 4 * C, DF_F32);
+    }
+    if (live()) run(launch_cast_bf16(h, nb, (long long)M * C, 0, st));
+    gemm(nb, C, b.name + ".pout", true, x, C, out, C, M, C, C, DF_F32);
+    top = mark;
+  }
+
+  int step(const float* x_in, const float* emb, const bf16_t* text, float* eps_out) {
+    std::vector<const float*> skips;
+    std::vector<int> skip_c;
+    const float* cur = x_in;
+    int cur_c = c.in_ch;
+    bf16_t* emb_act = (bf16_t*)alloc((size_t)B() * c.emb_dim * 2);
+    if (live()) run(launch_cast_bf16(emb, emb_act, (long long)B() * c.emb_dim, 1, st));
+    for (const BlockDesc& b : blocks) {
+      if (err != DF_OK) break;
+      const int R = rows(b.level), W = width(b.level);
+      const size_t px = (size_t)B() * R * W;
+      switch (b.kind) {
+        case BlockDesc::CONV_IN: {
+          float* out = (float*)alloc(px * b.cout * 4);
+          const size_t mark = top;
+          bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
+          if (live()) run(launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st));
+          conv(b.name, xb, R, W, b.cin, b.cout, 1, out, DF_F32, nullptr, nullptr);
+          top = mark;
+          cur = out; cur_c = b.cout;
+          break;
+        }
+        case BlockDesc::PUSH:
+          skips.push_back(cur);
+          skip_c.push_back(cur_c);
+          break;
+        case BlockDesc::RES: {
+          float* out = (float*)alloc(px * b.cout * 4);
+          const size_t mark = top;
+          const float* xin = cur;
+          if (b.concat) {
+            const float* sk = skips.back();
+            const int sc = skip_c.back();
+            skips.pop_back();
+            skip_c.pop_back();
+            float* cat = (float*)alloc(px * (size_t)(cur_c + sc) * 4);
+            if (live()) run(launch_concat(cur, cur_c, sk, sc, cat, (long long)px, st));
+            xin = cat;
+          }
+          resblock(b, xin, emb_act, out);
+          top = mark;
+          cur = out; cur_c = b.cout;
+          break;
+        }
+        case BlockDesc::XF: {
+          float* out = (float*)alloc(px * b.cout * 4);
+          transformer(b, cur, text, out);
+          cur = out;
+          break;
+        }
+        case BlockDesc::DOWN: {
+          const size_t opx = (size_t)B() * (R / 2) * (W / 2);
+          float* out = (float*)alloc(opx * b.cout * 4);
+          const size_t mark = top;
+          bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
+          if (live()) run(launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st));
+          conv(b.name, xb, R, W, b.cin, b.cout, 2, out, DF_F32, nullptr, nullptr);
+          top = mark;
+          cur = out;
+          break;
+        }
+        case BlockDesc::UP: {
+          float* out = (float*)alloc(px * 4 * b.cout * 4);
+          const size_t mark = top;
+          bf16_t* xb = (bf16_t*)alloc(px * 4 * b.cin * 2);
+          if (live()) run(launch_upsample2x_bf16(cur, xb, B(), R, W, b.cin, st));
+          conv(b.name, xb, 2 * R, 2 * W, b.cin, b.cout, 1, out, DF_F32, nullptr, nullptr);
+          top = mark;
+          cur = out;
+          break;
+        }
+        case BlockDesc::OUT: {
+          const size_t mark = top;
+          bf16_t* a = (bf16_t*)alloc(px * b.cin * 2);
+          groupnorm(b.name + ".gn", cur, DF_F32, R, W, b.cin, 1e-5f, 1, a);
+          conv(b.name + ".conv", a, R, W, b.cin, b.cout, 1, eps_out, DF_F32, nullptr, nullptr);
+          top = mark;
+          break;
+        }
+      }
+    }
+    return err;
+  }
+};
+
+struct DryResult {
+  size_t ws_bytes, stale_bytes, scratch;
+  std::vector<StaleEntry> stale;
+};
+
+DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
+  DryResult r = {};
+  for (int mode = 0; mode < 2; ++mode) {
+    std::vector<StaleEntry> list;
+    Exec e{c, blocks, nullptr, true, mode, 0, 1, nullptr, nullptr, 0};
+    e.stale_base = nullptr;
+    e.stale_list = &list;
+    e.stale_idx = nullptr;
+    e.step(nullptr, nullptr, nullptr, nullptr);
+    if (e.high > r.ws_bytes) r.ws_bytes = e.high;
+    if (e.scratch_need > r.scratch) r.scratch = e.scratch_need;
+    if (mode == 0) { r.stale = list; r.stale_bytes = e.stale_top; }
+  }
+  r.ws_bytes += 256;
+  return r;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int df_unet_num_weights(const df_unet_cfg* cfg) {
+  if (!cfg_ok(cfg)) return DF_ESHAPE;
+  return (int)build_weight_specs(*cfg).size();
+}
+
+int df_unet_weight_info(const df_unet_cfg* cfg, int idx, char* name, int name_cap, int* ndim, long long dims[4]) {
+  if (!cfg_ok(cfg)) return DF_ESHAPE;
+  if (!name || !ndim || !dims || name_cap < 1) return DF_EINVAL;
+  const std::vector<WeightSpec> s = build_weight_specs(*cfg);
+  if (idx < 0 || idx >= (int)s.size()) return DF_EINVAL;
+  std::strncpy(name, s[idx].name.c_str(), (size_t)name_cap - 1);
+  name[name_cap - 1] = 0;
+  *ndim = s[idx].ndim;
+  for (int i = 0; i < 4; ++i) dims[i] = s[idx].dims[i];
+  return DF_OK;
+}
+
+size_t df_unet_workspace_bytes(const df_unet_cfg* cfg) {
+  if (!cfg_ok(cfg)) return 0;
+  return dry_run(*cfg, build_blocks(*cfg)).ws_bytes;
+}
+
+size_t df_unet_stale_bytes(const df_unet_cfg* cfg) {
+  if (!cfg_ok(cfg)) return 0;
+  return dry_run(*cfg, build_blocks(*cfg)).stale_bytes;
+}
+
+int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* weights, int n_weights, void* workspace,
+                   size_t workspace_bytes) {
+  if (!out || !weights || !workspace) return DF_EINVAL;
+  if (!cfg_ok(cfg)) return DF_ESHAPE;
+  if ((uintptr_t)workspace % 256) return DF_EINVAL;
+  const std::vector<WeightSpec> specs = build_weight_specs(*cfg);
+  if (n_weights != (int)specs.size()) return DF_EINVAL;
+  df_unet* u = new df_unet();
+  u->cfg = *cfg;
+  u->blocks = build_blocks(*cfg);
+  for (size_t i = 0; i < specs.size(); ++i) {
+    if (!weights[i] || ((uintptr_t)weights[i] % 16)) { delete u; return DF_EINVAL; }
+    u->w[specs[i].name] = weights[i];
+  }
+  DryResult d = dry_run(u->cfg, u->blocks);
+  if (workspace_bytes < d.ws_bytes) { delete u; return DF_ENOMEM; }
+  u->stale = d.stale;
+  for (size_t i = 0; i < u->stale.size(); ++i) u->stale_idx[u->stale[i].name] = (int)i;
+  u->stale_bytes = d.stale_bytes;
+  u->ws = (char*)workspace;
+  u->ws_bytes = workspace_bytes;
+  // reserve the library scratch now, so that no step ever has to grow it
+  if (!scratch_get(d.scratch > kScratchCounterBytes ? d.scratch : kScratchCounterBytes)) { delete u; return DF_ENOMEM; }
+  *out = u;
+  return DF_OK;
+}
+
+void df_unet_destroy(df_unet* u) { delete u; }
+
+int df_unet_num_stale(const df_unet* u) { return u ? (int)u->stale.size() : DF_EINVAL; }
+
+int df_unet_stale_name(const df_unet* u, int idx, char* name, int name_cap) {
+  if (!u || !name || name_cap < 1 || idx < 0 || idx >= (int)u->stale.size()) return DF_EINVAL;
+  std::strncpy(name, u->stale[idx].name.c_str(), (size_t)name_cap - 1);
+  name[name_cap - 1] = 0;
+  return DF_OK;
+}
+
+int df_unet_stale_lookup(const df_unet* u, const char* name, size_t* offset, size_t* bytes) {
+  if (!u || !name || !offset || !bytes) return DF_EINVAL;
+  auto it = u->stale_idx.find(name);
+  if (it == u->stale_idx.end()) return DF_EINVAL;
+  *offset = u->stale[it->second].off;
+  *bytes = u->stale[it->second].bytes;
+  return DF_OK;
+}
+
+int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* text, void* stale, void* eps_out,
+                       int patch_idx, int mode, int refresh, void* stream) {
+  if (!u || !x || !emb || !text || !stale || !eps_out) return DF_EINVAL;
+  if (mode != DF_MODE_FULL && mode != DF_MODE_DISPLACED) return DF_EINVAL;
+  if (mode == DF_MODE_DISPLACED && (patch_idx < 0 || patch_idx >= u->cfg.N)) return DF_ESHAPE;
+  if (((uintptr_t)x % 16) || ((uintptr_t)text % 16) || ((uintptr_t)stale % 256) || ((uintptr_t)eps_out % 16))
+    return DF_EINVAL;
+  Exec e{u->cfg, u->blocks, &u->w, false, mode, mode == DF_MODE_FULL ? 0 : patch_idx, refresh ? 1 : 0,
+         (hipStream_t)stream, u->ws, u->ws_bytes};
+  e.stale_base = (char*)stale;
+  e.stale_list = &u->stale;
+  e.stale_idx = &u->stale_idx;
+  return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,271 @@
+"""GPU parity of the layer kernels against the CPU oracle, through the C ABI.
+
+Error metric: relative L2 error over the whole output, 1e-5 for float32 and
+2e-2 for bf16 inputs (float accumulation); bf16 cases feed the oracle the same
+bf16-rounded inputs.  Integer-like work (the refresh copy) is bit exact.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2402_19481_amd as df
+from df_inputs import configs, normal, round_bf16
+from oracle import ops
+from gpu_util import DEV, TOL_BF16, TOL_F32, dev, host, max_rel, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ refresh
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape,N", [((2, 8, 5, 24), 4), ((1, 64, 64, 640), 4), ((3, 6, 1, 7), 3), ((1, 4, 3, 1), 2)])
+def test_buffer_refresh_bit_exact(dtype, shape, N):
+    say("refresh", dtype, shape, N)
+    g = torch.Generator().manual_seed(5)
+    full = torch.randn(shape, generator=g).to(dtype).to(DEV)
+    R = shape[1] // N
+    for i in range(N):
+        patch = torch.randn((shape[0], R) + shape[2:], generator=g).to(dtype).to(DEV)
+        want = full.clone()
+        want[:, i * R:(i + 1) * R] = patch
+        got = df.buffer_refresh(full.clone(), patch, i, N)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                           want.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+
+
+def test_refresh_and_errors():
+    x = torch.zeros(1, 8, 4, device=DEV)
+    with pytest.raises(df.DfError):
+        df.buffer_refresh(x, x[:, :2].contiguous(), 4, 4)          # patch index out of range
+    with pytest.raises(df.DfError):
+        df.buffer_refresh(torch.zeros(1, 7, 3, device=DEV), x[:, :2].contiguous(), 0, 4)   # elements not divisible
+    with pytest.raises(df.DfError):
+        df.groupnorm_stale(torch.zeros(1, 2, 2, 6, device=DEV), None, torch.ones(6, device=DEV),
+                           torch.zeros(6, device=DEV), 4, 0, 1)     # C % G != 0
+    with pytest.raises(df.DfError):
+        df.attn_displaced(torch.zeros(1, 4, 48, device=DEV), torch.zeros(1, 4, 48, device=DEV),
+                          torch.zeros(1, 4, 48, device=DEV), None, None, 1, 0, 1)   # head dim 48 unsupported
+
+
+# ------------------------------------------------------------------ GroupNorm
+
+def _gn_case(seed, B, H, W, C, G, N, bf16, noise=0.05, shift=0.3):
+    full = normal(seed, "full", (B, H, W, C)) * 1.5 + shift
+    stale = full + normal(seed, "noise", (B, H, W, C), std=noise)
+    if bf16:
+        full, stale = round_bf16(full), round_bf16(stale)
+    gamma = normal(seed, "g", (C,), std=0.1, mean=1.0)
+    beta = normal(seed, "b", (C,), std=0.1)
+    st = ops.patch_group_sums(stale, G, N).astype(np.float32)
+    return full, st, gamma, beta
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("silu", [False, True])
+def test_groupnorm_tiny_f32_all_modes(mode, silu):
+    say("gn tiny f32 mode", mode, silu)
+    B, H, W, C, G, N = 1, 16, 16, 32, 8, 2
+    full, st, gamma, beta = _gn_case(1, B, H, W, C, G, N, False)
+    for i in range(N):
+        xf = full[:, i * 8:(i + 1) * 8]
+        ref, ref_fs = ops.groupnorm_stale(xf, st, gamma, beta, G, i, N, 1e-5, mode, silu)
+        y, fs = df.groupnorm_stale(dev(xf), dev(st), dev(gamma), dev(beta), G, i, N, 1e-5, mode, silu)
+        assert rel_l2(host(y), ref) < TOL_F32
+        assert rel_l2(host(fs), ref_fs) < TOL_F32
+
+
+@pytest.mark.parametrize("B,H,W,C,G,N,patch,bf16", [
+    (2, 9, 7, 24, 3, 3, 1, False),      # ragged pixel counts, group size 8
+    (1, 12, 5, 40, 4, 4, 3, False),     # group size 10: lanes straddle groups
+    (2, 8, 6, 80, 8, 2, 0, True),       # bf16, group size 10
+    (1, 128, 128, 320, 32, 4, 1, True),  # configuration 3
+    (1, 40, 48, 960, 32, 8, 3, True),   # widest concat input of the UNet, group size 30
+    (1, 4, 4, 1280, 32, 1, 0, False),
+])
+def test_groupnorm_shapes(B, H, W, C, G, N, patch, bf16):
+    say("gn", B, H, W, C, G, N, patch, bf16)
+    full, st, gamma, beta = _gn_case(3, B, H, W, C, G, N, bf16, noise=0.02)
+    R = H // N
+    xf = full[:, patch * R:(patch + 1) * R]
+    tol = TOL_BF16 if bf16 else TOL_F32
+    for mode, silu in ((0, True), (1, False)):
+        ref, ref_fs = ops.groupnorm_stale(xf, st, gamma, beta, G, patch, N, 1e-5, mode, silu)
+        y, fs = df.groupnorm_stale(dev(xf, bf16), dev(st), dev(gamma), dev(beta), G, patch, N, 1e-5, mode, silu)
+        e = rel_l2(host(y), ref)
+        say("   mode", mode, "rel_l2", e)
+        assert e < tol
+        assert rel_l2(host(fs), ref_fs) < 1e-5
+
+
+def test_groupnorm_negative_variance_fallback_and_in_place_stats():
+    # own stale slot with a huge second moment drives Eq. 2's variance negative
+    B, R, W, C, G, N = 1, 4, 4, 8, 2, 2
+    x = normal(7, "x", (B, R, W, C), std=0.1, mean=1.0)
+    st = np.zeros((N, B, G, 2), dtype=np.float32)
+    st[0, :, :, 1] = 1e4
+    gamma, beta = np.ones(C, np.float32), np.zeros(C, np.float32)
+    ref, ref_fs = ops.groupnorm_stale(x, st, gamma, beta, G, 0, N, 1e-5, ops.STAT_EQ2)
+    st_d = dev(st)
+    y, fs = df.groupnorm_stale(dev(x), st_d, dev(gamma), dev(beta), G, 0, N, 1e-5, df.GN_EQ2,
+                               fresh_stats_out=st_d[0])
+    assert rel_l2(host(y), ref) < 1e-4
+    np.testing.assert_allclose(host(st_d)[0], ref_fs, rtol=1e-5)      # refreshed in place after being read
+    np.testing.assert_array_equal(host(st_d)[1], st[1])
+
+
+# ------------------------------------------------------------------ convolution
+
+def _conv_case(seed, B, H, W, Cin, Cout, bf16, noise=0.5):
+    full = normal(seed, "full", (B, H, W, Cin))
+    stale = full + normal(seed, "noise", (B, H, W, Cin), std=noise)
+    w = normal(seed, "w", (Cout, 3, 3, Cin), std=1.0 / math.sqrt(9 * Cin))
+    b = normal(seed, "b", (Cout,), std=0.1)
+    if bf16:
+        full, stale, w = round_bf16(full), round_bf16(stale), round_bf16(w)
+    return full, stale, w, b
+
+
+@pytest.mark.parametrize("B,H,W,Cin,Cout,N,stride,bf16", [
+    (1, 16, 16, 32, 32, 2, 1, False),    # configuration 1
+    (2, 12, 6, 5, 7, 3, 1, False),       # odd channel counts
+    (1, 16, 8, 8, 12, 4, 2, False),      # stride 2
+    (1, 8, 8, 4, 64, 2, 1, True),        # conv_in-like: 4 input channels (direct kernel)
+    (1, 8, 8, 128, 4, 2, 1, True),       # conv_out-like: 4 output channels (wave kernel)
+    (2, 16, 12, 64, 96, 4, 1, True),     # MFMA tile path, ragged M and N tiles
+    (1, 16, 24, 96, 64, 4, 2, True),     # MFMA, stride 2
+    (1, 32, 40, 64, 320, 2, 1, True),    # MFMA, several N tiles
+])
+def test_conv_halo_all_patches(B, H, W, Cin, Cout, N, stride, bf16):
+    say("conv", B, H, W, Cin, Cout, N, stride, bf16)
+    full, stale, w, b = _conv_case(11, B, H, W, Cin, Cout, bf16)
+    R = H // N
+    tol = TOL_BF16 if bf16 else TOL_F32
+    for i in range(N):
+        xf = full[:, i * R:(i + 1) * R]
+        for act in (0, 1):
+            ref = ops.conv3x3_halo(xf, stale, w, b, i, N, stride, act)
+            y = df.conv3x3_halo(dev(xf, bf16), dev(stale, bf16), dev(w, bf16), dev(b), i, N, stride, act)
+            e = rel_l2(host(y), ref)
+            say("   patch", i, "act", act, "rel_l2", e)
+            assert e < tol
+    # one patch: the full-image convolution, no stale buffer needed
+    ref = ops.conv3x3_full(full, w, b, stride)
+    y = df.conv3x3_halo(dev(full, bf16), None, dev(w, bf16), dev(b), 0, 1, stride, 0)
+    assert rel_l2(host(y), ref) < tol
+
+
+def test_conv_config3_full_size():
+    t = configs.conv_gn_stage()
+    m = t["meta"]
+    N, R = m["N"], m["H"] // m["N"]
+    say("conv cfg3", m)
+    for i in (0, 1, 3):
+        xf = t["x_full"][:, i * R:(i + 1) * R]
+        ref = ops.conv3x3_halo(xf, t["x_stale"], t["conv_w"], t["conv_b"], i, N, 1, 1)
+        y = df.conv3x3_halo(dev(xf, True), dev(t["x_stale"], True), dev(t["conv_w"], True), dev(t["conv_b"]), i, N, 1, 1)
+        e = rel_l2(host(y), ref)
+        say("   patch", i, "rel_l2", e, "max_rel", max_rel(host(y), ref))
+        assert e < TOL_BF16
+
+
+# ------------------------------------------------------------------ attention
+
+def _attn_case(seed, B, L, C, N, patch, bf16, stale_std=0.5):
+    Lq = L // N
+    rnd = round_bf16 if bf16 else (lambda a: a)
+    kfull = normal(seed, "k", (B, L, C))
+    vfull = normal(seed, "v", (B, L, C))
+    sl = slice(patch * Lq, (patch + 1) * Lq)
+    return dict(q=rnd(normal(seed, "q", (B, Lq, C))), kf=rnd(kfull[:, sl].copy()), vf=rnd(vfull[:, sl].copy()),
+                ks=rnd(kfull + normal(seed, "kn", (B, L, C), std=stale_std)),
+                vs=rnd(vfull + normal(seed, "vn", (B, L, C), std=stale_std)))
+
+
+@pytest.mark.parametrize("B,L,C,heads,N,patch,bf16", [
+    (1, 256, 32, 1, 2, 0, False),       # configuration 1
+    (2, 96, 128, 2, 3, 1, False),       # d = 64 in float32, fewer keys than two waves' stride
+    (1, 512, 128, 2, 4, 2, True),       # bf16 MFMA kernel
+    (2, 600, 64, 1, 4, 3, True),        # ragged: 150 queries, 600 keys (partial tiles), batch 2
+    (1, 2400, 192, 3, 8, 5, True),      # level-2 shape of the 1280x1920 share: 300 queries, split keys
+    (1, 77 * 1, 128, 2, 1, 0, True),    # 77 keys, everything fresh (cross-attention shape)
+])
+def test_attention_displaced(B, L, C, heads, N, patch, bf16):
+    say("attn", B, L, C, heads, N, patch, bf16)
+    t = _attn_case(21, B, L, C, N, patch, bf16)
+    ref = ops.attn_displaced(t["q"], t["kf"], t["vf"], t["ks"], t["vs"], heads, patch, N)
+    o = df.attn_displaced(dev(t["q"], bf16), dev(t["kf"], bf16), dev(t["vf"], bf16), dev(t["ks"], bf16),
+                          dev(t["vs"], bf16), heads, patch, N)
+    e = rel_l2(host(o), ref)
+    say("   rel_l2", e, "max_rel", max_rel(host(o), ref))
+    assert e < (TOL_BF16 if bf16 else TOL_F32)
+    # own rows of the stale buffers must not be read
+    ks2, vs2 = t["ks"].copy(), t["vs"].copy()
+    Lq = L // N
+    ks2[:, patch * Lq:(patch + 1) * Lq] = 50.0
+    vs2[:, patch * Lq:(patch + 1) * Lq] = -50.0
+    o2 = df.attn_displaced(dev(t["q"], bf16), dev(t["kf"], bf16), dev(t["vf"], bf16), dev(ks2, bf16), dev(vs2, bf16),
+                           heads, patch, N)
+    np.testing.assert_array_equal(host(o2), host(o))
+
+
+def test_attention_config2_full_size():
+    t = configs.attn_core()
+    m = t["meta"]
+    say("attn cfg2", m)
+    ref = ops.attn_displaced(t["q"], t["k_fresh"], t["v_fresh"], t["k_stale"], t["v_stale"], m["heads"],
+                             m["patch_idx"], m["N"])
+    o = df.attn_displaced(dev(t["q"], True), dev(t["k_fresh"], True), dev(t["v_fresh"], True), dev(t["k_stale"], True),
+                          dev(t["v_stale"], True), m["heads"], m["patch_idx"], m["N"])
+    e = rel_l2(host(o), ref)
+    say("   rel_l2", e, "max_rel", max_rel(host(o), ref))
+    assert e < TOL_BF16
+
+
+def test_attention_large_logits_are_stable():
+    # scaled-up queries: softmax close to one-hot, needs the running-max rescaling
+    t = _attn_case(22, 1, 512, 64, 2, 1, True)
+    q = round_bf16(t["q"] * 6.0)
+    ref = ops.attn_displaced(q, t["kf"], t["vf"], t["ks"], t["vs"], 1, 1, 2)
+    o = df.attn_displaced(dev(q, True), dev(t["kf"], True), dev(t["vf"], True), dev(t["ks"], True), dev(t["vs"], True),
+                          1, 1, 2)
+    assert np.isfinite(host(o)).all()
+    assert rel_l2(host(o), ref) < TOL_BF16
+
+
+# ------------------------------------------------------------------ configuration 1 block
+
+def test_tiny_block_chain_f32():
+    """GroupNorm -> conv3x3 -> single-head attention on patch 0 of 2, stale buffers left by a
+    full-image pass of the same block over the stale input (all through the oracle)."""
+    t = configs.tiny_block()
+    m = t["meta"]
+    H, W, C, N, G = m["H"], m["W"], m["C"], m["N"], m["G"]
+    x, xs = t["x_full"], t["x_full"] + t["stale_noise"]
+    # full-image pass on the stale input defines the three stale buffers
+    gn_s, _ = ops.groupnorm_stale(xs, ops.group_sums(xs, G)[None], t["gamma"], t["beta"], G, 0, 1, m["eps"])
+    st_stats = ops.patch_group_sums(xs, G, N).astype(np.float32)
+    conv_s = ops.conv3x3_full(gn_s, t["conv_w"], t["conv_b"])
+    kv_s = conv_s.reshape(1, H * W, C)
+    for i in range(N):
+        R = H // N
+        xf = x[:, i * R:(i + 1) * R]
+        r1, _ = ops.groupnorm_stale(xf, st_stats, t["gamma"], t["beta"], G, i, N, m["eps"])
+        r2 = ops.conv3x3_halo(r1, gn_s, t["conv_w"], t["conv_b"], i, N)
+        tok = r2.reshape(1, R * W, C)
+        r3 = ops.attn_displaced(tok, tok, tok, kv_s, kv_s, 1, i, N)
+        g1, _ = df.groupnorm_stale(dev(xf), dev(st_stats), dev(t["gamma"]), dev(t["beta"]), G, i, N, m["eps"])
+        g2 = df.conv3x3_halo(g1, dev(gn_s), dev(t["conv_w"]), dev(t["conv_b"]), i, N)
+        gt = g2.reshape(1, R * W, C)
+        g3 = df.attn_displaced(gt, gt, gt, dev(kv_s), dev(kv_s), 1, i, N)
+        for nm, g, r in (("gn", g1, r1), ("conv", g2, r2), ("attn", g3, r3.reshape(1, R * W, C))):
+            e = rel_l2(host(g), r.reshape(host(g).shape))
+            say("  tiny block patch", i, nm, e)
+            assert e < TOL_F32
