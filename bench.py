@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the displaced-patch UNet step on one MI355X.
+
+A step is one pass of the whole hot path for one patch: df_patch_unet_step in
+DISPLACED mode with refresh (GroupNorm with stale statistics, 3x3 convolutions
+with stale halo rows, self-attention against spliced fresh/stale K/V, all
+per-token layers, and the refresh of the patch's rows of every stale buffer).
+Workload: SDXL-shaped UNet, 1280x1920 image (160x240 latent), N=8 row patches,
+patch 3, batch 1, bf16 with float accumulation, seeded synthetic inputs and
+random-init weights.  The stale state is left by one untimed FULL step.
+
+Prints one JSON line (see README / DESIGN).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def make_weights(df, torch, ccfg, seed):
+    g = torch.Generator(device="cuda:0").manual_seed(seed)
+    out = []
+    for name, shape in df.unet_weight_specs(ccfg):
+        x = torch.randn(shape, generator=g, device="cuda:0", dtype=torch.float32)
+        if name.endswith(".w"):
+            fan_in = 1
+            for d in shape[1:]:
+                fan_in *= d
+            out.append((x * fan_in ** -0.5).to(torch.bfloat16).contiguous())
+        elif name.endswith(".g"):
+            out.append(1.0 + 0.1 * x)
+        elif name.endswith(".beta"):
+            out.append(0.1 * x)
+        else:
+            out.append(0.02 * x)
+    return out
+
+
+def cpu_baseline(cfg, weights_dev, specs, inputs, patch):
+    """Times the CPU oracle (as it stands) on one DISPLACED step of the same configuration."""
+    import numpy as np
+    import torch
+    from df_inputs import unet_table as ut
+    from oracle import unet as ounet
+
+    named = []
+    for (name, _), w in zip(specs, weights_dev):
+        if w.dtype == torch.bfloat16:
+            named.append((name, w.view(torch.int16).cpu().numpy().view(np.uint16)))
+        else:
+            named.append((name, w.cpu().numpy()))
+    P = ounet.Params(named)
+    bl = ut.blocks(cfg)
+    # zero-filled stale buffers of the right shapes (their content does not change the work done)
+    stale = {}
+    G, N = cfg.groups, cfg.N
+    for b in bl:
+        k = b[0]
+        if k == "conv_in":
+            stale[b[1] + ".in"] = np.zeros((1, cfg.H, cfg.W, b[2]))
+        elif k == "res":
+            _, nm, cin, cout, lv, _ = b
+            h, w = cfg.level_hw(lv)
+            stale[nm + ".conv1.in"] = np.zeros((1, h, w, cin))
+            stale[nm + ".conv2.in"] = np.zeros((1, h, w, cout))
+            stale[nm + ".gn1.stats"] = np.ones((N, 1, G, 2))
+            stale[nm + ".gn2.stats"] = np.ones((N, 1, G, 2))
+        elif k == "xf":
+            _, nm, c, depth, lv = b
+            h, w = cfg.level_hw(lv)
+            stale[nm + ".gn.stats"] = np.ones((N, 1, G, 2))
+            for d in range(depth):
+                stale[f"{nm}.b{d}.attn1.k"] = np.zeros((1, h * w, c))
+                stale[f"{nm}.b{d}.attn1.v"] = np.zeros((1, h * w, c))
+        elif k == "down":
+            h, w = cfg.level_hw(b[3])
+            stale[b[1] + ".in"] = np.zeros((1, h, w, b[2]))
+        elif k == "up":
+            h, w = cfg.level_hw(b[3] - 1)
+            stale[b[1] + ".in"] = np.zeros((1, h, w, b[2]))
+        elif k == "out":
+            stale[b[1] + ".gn.stats"] = np.ones((N, 1, G, 2))
+            stale[b[1] + ".conv.in"] = np.zeros((1, cfg.H, cfg.W, b[2]))
+    x, emb, text = inputs
+    t0 = time.perf_counter()
+    ounet.unet_step(cfg, bl, P, x, emb, text, stale, patch, ounet.DISPLACED, refresh=True)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return dict(value=round(dt * 1e3, 1), unit="ms", cores=int(cores), kind="oracle",
+                sample="one DISPLACED step of the same configuration (float64 numpy oracle, zero-filled stale buffers)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--profile-steps", type=int, default=3, help="extra steps with per-launch event timing")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--small", action="store_true", help="reduced-width UNet (plumbing check, not the benchmark)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2402_19481_amd as df
+    from df_inputs import unet_table as ut
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    if args.small:
+        cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
+        patch = 1
+        workload = "reduced-width UNet 32x16 latent, N=4 (plumbing check)"
+    else:
+        cfg = ut.UNetCfg(H=160, W=240, N=8, **ut.SDXL)
+        patch = 3
+        workload = ("SDXL-shaped UNet step for one patch: 1280x1920 image (160x240x4 latent), N=8 row patches "
+                    "(20 latent rows), patch 3, DISPLACED + refresh")
+    ccfg = df.make_cfg(cfg)
+    specs = df.unet_weight_specs(ccfg)
+    weights = make_weights(df, torch, ccfg, seed=4)
+    net = df.PatchUNet(cfg, weights, B=1)
+    g = torch.Generator(device="cuda:0").manual_seed(40)
+    x_prev = torch.randn(1, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
+    R = cfg.H // cfg.N
+    x = (x_prev + 0.02 * torch.randn(x_prev.shape, generator=g, device="cuda:0"))[:, patch * R:(patch + 1) * R].contiguous()
+    emb = torch.randn(1, cfg.emb_dim, generator=g, device="cuda:0")
+    text = torch.randn(1, cfg.text_len, cfg.text_dim, generator=g, device="cuda:0").to(torch.bfloat16)
+    eps = torch.empty_like(x)
+
+    # the synchronous first step fills every stale buffer (untimed)
+    net.step(x_prev, emb, text, mode=df.MODE_FULL)
+    torch.cuda.synchronize()
+
+    def one():
+        net.step(x, emb, text, patch_idx=patch, mode=df.MODE_DISPLACED, refresh=True, out=eps)
+
+    for _ in range(args.warmup):
+        one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert bool(torch.isfinite(eps).all())
+
+    # per-launch event timing over further steps of the same work, on the stream the kernels run on
+    net.profile(True)
+    for _ in range(args.profile_steps):
+        one()
+    prof = net.profile_read()
+    net.profile(False)
+    breakdown = {}
+    for k, v in prof.items():
+        if v["launches"] == 0:
+            continue
+        per_step_ms = v["ms"] / args.profile_steps
+        breakdown[k] = dict(ms_per_step=round(per_step_ms, 4), launches_per_step=v["launches"] // args.profile_steps,
+                            tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else None,
+                            gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1))
+    dom = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
+    d = prof[dom]
+    if d["flops"] > 0:
+        ach = d["flops"] / (d["ms"] * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel=dom, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                        avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
+                        flops_per_launch=d["flops"] / d["launches"])
+    else:
+        ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
+        roofline = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=None,
+                        avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
+                        bytes_per_launch=d["bytes"] / d["launches"])
+
+    macs = ut.count_macs(cfg)
+    tflop = 2.0 * macs["total"] / 1e12
+    out = {
+        "metric": "ms per patch UNet step (1 MI355X)", "value": round(ms, 4), "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": workload, "batch": 1, "patch_idx": patch, "n_patches": cfg.N,
+                   "tflop_per_step": round(tflop, 4)},
+        "tflops": round(tflop / (ms * 1e-3), 2),
+        "mfma_util_frac_of_bf16_peak": round(tflop / (ms * 1e-3) / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        xin = x.cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, specs, (xin, emb.cpu().numpy(), text.float().cpu().numpy()), patch)
+    else:
+        out["cpu_baseline"] = None
+    net.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

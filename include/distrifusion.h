@@ -167,6 +167,20 @@ int df_unet_stale_name(const df_unet* u, int idx, char* name, int name_cap);
 int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* text, void* stale,
                        void* eps_out, int patch_idx, int mode, int refresh, void* stream);
 
+/*
+ * Optional per-launch timing of df_patch_unet_step (measurement support; Section 5.1 times whole runs, this
+ * splits a step by kernel class).  While enabled, every kernel launch of a step is bracketed by two events on
+ * the step's stream, which slows the step down; totals accumulate per class until reset.
+ * df_unet_profile_read synchronises the device, then returns the class totals: elapsed ms, algorithmic flops,
+ * algorithmic bytes and launch count.  Classes: 0 .. df_unet_profile_num_classes()-1, named by
+ * df_unet_profile_class_name.
+ */
+int df_unet_profile_enable(df_unet* u, int on);
+int df_unet_profile_reset(df_unet* u);
+int df_unet_profile_num_classes(void);
+const char* df_unet_profile_class_name(int cls);
+int df_unet_profile_read(df_unet* u, int cls, double* ms, double* flops, double* bytes, long long* launches);
+
 /* Sampler update on the patch's latent rows (Section 3, Eq. 1; Euler step): x += (sigma_next - sigma) * eps. */
 int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream);
 

@@ -67,9 +67,18 @@ def lib():
     L.df_unet_num_stale.argtypes = [vp]
     L.df_unet_stale_name.argtypes = [vp, i, ctypes.c_char_p, i]
     L.df_patch_unet_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
+    L.df_unet_profile_enable.argtypes = [vp, i]
+    L.df_unet_profile_reset.argtypes = [vp]
+    L.df_unet_profile_num_classes.argtypes = []
+    L.df_unet_profile_class_name.argtypes = [i]
+    L.df_unet_profile_class_name.restype = ctypes.c_char_p
+    dp = ctypes.POINTER(ctypes.c_double)
+    L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
                  "df_euler_update", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
-                 "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step"):
+                 "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
+                 "df_unet_profile_enable", "df_unet_profile_reset", "df_unet_profile_num_classes",
+                 "df_unet_profile_read"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -213,6 +222,23 @@ class PatchUNet:
             out = torch.empty_like(x)
         _check(lib().df_patch_unet_step(self.handle, _ptr(x), _ptr(emb), _ptr(text), self.stale.data_ptr(), _ptr(out),
                                         patch_idx, mode, int(refresh), _stream()))
+        return out
+
+    def profile(self, on):
+        """Switches per-launch event timing of the steps on or off (resets the totals)."""
+        _check(lib().df_unet_profile_enable(self.handle, int(on)))
+        _check(lib().df_unet_profile_reset(self.handle))
+
+    def profile_read(self):
+        """{class name: dict(ms, flops, bytes, launches)} accumulated since profiling was switched on."""
+        L = lib()
+        out = {}
+        for k in range(L.df_unet_profile_num_classes()):
+            ms, fl, by, n = ctypes.c_double(), ctypes.c_double(), ctypes.c_double(), ctypes.c_longlong()
+            _check(L.df_unet_profile_read(self.handle, k, ctypes.byref(ms), ctypes.byref(fl), ctypes.byref(by),
+                                          ctypes.byref(n)))
+            out[L.df_unet_profile_class_name(k).decode()] = dict(ms=ms.value, flops=fl.value, bytes=by.value,
+                                                                 launches=n.value)
         return out
 
     def stale_names(self):

@@ -171,8 +171,49 @@ inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 }  // namespace
 
+// Optional per-launch timing: when enabled every kernel launch of a step is bracketed by two
+// events on the step's stream and accounted to its class with its algorithmic flops and bytes.
+enum { PC_GEMM = 0, PC_CONV, PC_SELF_ATTN, PC_CROSS_ATTN, PC_GROUPNORM, PC_REFRESH, PC_LAYERNORM, PC_ELEMENTWISE, PC_COUNT };
+static const char* const kProfNames[PC_COUNT] = {"gemm", "conv3x3", "self_attn", "cross_attn", "groupnorm", "refresh",
+                                                 "layernorm", "elementwise"};
+struct ProfRec { int cls; double flops, bytes; };
+struct Prof {
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  std::vector<ProfRec> recs;       // launch k uses events 2k, 2k+1
+  double ms[PC_COUNT] = {}, flops[PC_COUNT] = {}, bytes[PC_COUNT] = {};
+  long long launches[PC_COUNT] = {};
+  bool begin(int cls, double fl, double by, hipStream_t st) {
+    const size_t k = recs.size();
+    while (pool.size() < 2 * k + 2) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return false;
+      pool.push_back(e);
+    }
+    recs.push_back({cls, fl, by});
+    return hipEventRecord(pool[2 * k], st) == hipSuccess;
+  }
+  bool end(hipStream_t st) { return hipEventRecord(pool[2 * recs.size() - 1], st) == hipSuccess; }
+  bool collect() {  // after the stream has been synchronised
+    for (size_t k = 0; k < recs.size(); ++k) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, pool[2 * k], pool[2 * k + 1]) != hipSuccess) return false;
+      const ProfRec& r = recs[k];
+      ms[r.cls] += t; flops[r.cls] += r.flops; bytes[r.cls] += r.bytes; launches[r.cls] += 1;
+    }
+    recs.clear();
+    return true;
+  }
+  void reset() {
+    for (int i = 0; i < PC_COUNT; ++i) { ms[i] = flops[i] = bytes[i] = 0; launches[i] = 0; }
+    recs.clear();
+  }
+  ~Prof() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
+};
+
 struct df_unet {
   df_unet_cfg cfg;
+  Prof prof;
   std::vector<BlockDesc> blocks;
   std::map<std::string, const void*> w;
   std::vector<StaleEntry> stale;
@@ -202,6 +243,17 @@ struct Exec {
   size_t stale_top = 0;
   size_t scratch_need = 0;
   int err = DF_OK;
+  Prof* prof = nullptr;
+
+  // run a launch, accounted to class `cls` when per-launch timing is on
+  template <typename F>
+  void timed(int cls, double fl, double by, F&& launch) {
+    if (!live()) return;
+    const bool p = prof && prof->on;
+    if (p && !prof->begin(cls, fl, by, st)) { err = DF_EHIP; return; }
+    run(launch());
+    if (p && !prof->end(st)) err = DF_EHIP;
+  }
 
   int B() const { return c.B; }
   int N() const { return c.N; }
@@ -245,7 +297,9 @@ struct Exec {
     GemmArgs g = {};
     g.A = A; g.W = W; g.bias = bp; g.residual = residual; g.out = out;
     g.M = M; g.N = Nn; g.K = K; g.lda = lda; g.ldw = K; g.ldr = ldr; g.ldo = ldo; g.act = 0; g.out_dtype = out_dtype;
-    run(launch_gemm_bf16(g, st));
+    const double osz = out_dtype == DF_BF16 ? 2.0 : 4.0;
+    timed(PC_GEMM, 2.0 * M * Nn * K, 2.0 * ((double)M * K + (double)Nn * K) + osz * M * Nn,
+          [&] { return launch_gemm_bf16(g, st); });
   }
 
   void groupnorm(const std::string& name, const void* x, int in_dtype, int level_rows, int W, int C, float eps, int silu,
@@ -268,7 +322,8 @@ struct Exec {
       a.nseg = 1; a.Rseg = level_rows; a.N = N(); a.patch_idx = patch; a.stale = entry;
       a.sums_out = refresh ? entry + (size_t)patch * B() * G * 2 : nullptr;
     }
-    run(launch_groupnorm(a, st));
+    const double el = (double)B() * level_rows * W * C;
+    timed(PC_GROUPNORM, 0.0, el * (in_dtype == DF_BF16 ? 2.0 : 4.0) + el * 2.0, [&] { return launch_groupnorm(a, st); });
   }
 
   // x: bf16 [B, R, W, Cin] rows of this mode; out: [B, R/stride, W/stride, Cout]
@@ -288,18 +343,28 @@ struct Exec {
       if (patch > 0) a.halo_top = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;           // last row of the patch above
       if (patch + 1 < N() && stride == 1) a.halo_bot = entry + ((size_t)(patch + 1) * 2) * rowe;  // first row of the patch below
     }
-    run(launch_conv3x3(a, st));
+    {
+      const double opx = (double)B() * (R / stride) * (W / stride);
+      const double halo = full() ? 0.0 : 2.0;
+      timed(PC_CONV, 2.0 * 9 * Cin * Cout * opx,
+            2.0 * B() * (R + halo) * rowe + 2.0 * 9 * Cin * Cout + opx * Cout * (out_dtype == DF_BF16 ? 2.0 : 4.0),
+            [&] { return launch_conv3x3(a, st); });
+    }
     if (!live()) return;
     const long long rb = (long long)rowe * sizeof(bf16_t);
     if (full()) {
       const int Rp = R / N();
       for (int which = 0; which < 2; ++which)
-        run(launch_copy_rows(entry + (size_t)which * rowe, x + (size_t)which * (Rp - 1) * rowe, (long long)B() * N(), rb,
-                             2 * rb, (long long)Rp * rb, st));
+        timed(PC_REFRESH, 0.0, 2.0 * B() * N() * rb, [&] {
+          return launch_copy_rows(entry + (size_t)which * rowe, x + (size_t)which * (Rp - 1) * rowe,
+                                  (long long)B() * N(), rb, 2 * rb, (long long)Rp * rb, st);
+        });
     } else if (refresh) {
       for (int which = 0; which < 2; ++which)
-        run(launch_copy_rows(entry + ((size_t)patch * 2 + which) * rowe, x + (size_t)which * (R - 1) * rowe, B(), rb,
-                             (long long)N() * 2 * rb, (long long)R * rb, st));
+        timed(PC_REFRESH, 0.0, 2.0 * B() * rb, [&] {
+          return launch_copy_rows(entry + ((size_t)patch * 2 + which) * rowe, x + (size_t)which * (R - 1) * rowe, B(),
+                                  rb, (long long)N() * 2 * rb, (long long)R * rb, st);
+        });
     }
   }
 
@@ -318,7 +383,7 @@ struct Exec {
     const float* residual = x;
     if (b.cin != b.cout) {
       bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
-      if (live()) run(launch_cast_bf16(x, xb, (long long)px * b.cin, 0, st));
+      timed(PC_ELEMENTWISE, 0.0, 6.0 * px * b.cin, [&] { return launch_cast_bf16(x, xb, (long long)px * b.cin, 0, st); });
       gemm(xb, b.cin, b.name + ".sc", true, nullptr, 0, out, b.cout, (int)px, b.cout, b.cin, DF_F32);
       residual = out;
     }
@@ -347,7 +412,7 @@ struct Exec {
       // --- self-attention: fresh queries against spliced fresh/stale keys and values ---
       const float* g1 = (const float*)weight(p + ".ln1.g");
       const float* b1 = (const float*)weight(p + ".ln1.beta");
-      if (live()) run(launch_layernorm(h, nb, g1, b1, M, C, 1e-5f, st));
+      timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g1, b1, M, C, 1e-5f, st); });
       gemm(nb, C, p + ".attn1.qkv", false, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
       bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
@@ -363,23 +428,28 @@ struct Exec {
         a.ldq = a.ldkf = a.ldvf = 3 * C; a.ldks = a.ldvs = C; a.ldo = C;
         a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C; a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
         a.scale = scale; a.dtype = DF_BF16;
-        run(launch_attention(a, st));
+        timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
+              [&] { return launch_attention(a, st); });
       }
       if (live() && (full() || refresh)) {
         // the patch's projected keys/values replace its rows of the stale buffers (read only by later steps)
         const size_t row0 = full() ? 0 : (size_t)patch * Lq;
         for (int bi = 0; bi < B(); ++bi) {
-          run(launch_copy_rows(ks + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + C, Lq, C * 2LL, C * 2LL,
-                               3LL * C * 2, st));
-          run(launch_copy_rows(vs + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + 2 * C, Lq, C * 2LL,
-                               C * 2LL, 3LL * C * 2, st));
+          timed(PC_REFRESH, 0.0, 4.0 * Lq * C, [&] {
+            return launch_copy_rows(ks + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + C, Lq, C * 2LL,
+                                    C * 2LL, 3LL * C * 2, st);
+          });
+          timed(PC_REFRESH, 0.0, 4.0 * Lq * C, [&] {
+            return launch_copy_rows(vs + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + 2 * C, Lq,
+                                    C * 2LL, C * 2LL, 3LL * C * 2, st);
+          });
         }
       }
       gemm(ao, C, p + ".attn1.o", true, h, C, h, C, M, C, C, DF_F32);
       // --- cross-attention to the text tokens: per token, no cross-patch data ---
       const float* g2 = (const float*)weight(p + ".ln2.g");
       const float* b2 = (const float*)weight(p + ".ln2.beta");
-      if (live()) run(launch_layernorm(h, nb, g2, b2, M, C, 1e-5f, st));
+      timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g2, b2, M, C, 1e-5f, st); });
       gemm(nb, C, p + ".attn2.q", false, nullptr, 0, qkv, C, M, C, C, DF_BF16);
       gemm(text, c.text_dim, p + ".attn2.kv", false, nullptr, 0, kv2, 2 * C, B() * TL, 2 * C, c.text_dim, DF_BF16);
       {
@@ -393,18 +463,19 @@ struct Exec {
         a.ldq = C; a.ldkf = a.ldvf = 2 * C; a.ldks = a.ldvs = 2 * C; a.ldo = C;
         a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * 2 * C; a.bso = (long long)Lq * C;
         a.scale = scale; a.dtype = DF_BF16;
-        run(launch_attention(a, st));
+        timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
+              [&] { return launch_attention(a, st); });
       }
       gemm(ao, C, p + ".attn2.o", true, h, C, h, C, M, C, C, DF_F32);
       // --- GEGLU feed-forward ---
       const float* g3 = (const float*)weight(p + ".ln3.g");
       const float* b3 = (const float*)weight(p + ".ln3.beta");
-      if (live()) run(launch_layernorm(h, nb, g3, b3, M, C, 1e-5f, st));
+      timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g3, b3, M, C, 1e-5f, st); });
       gemm(nb, C, p + ".ff1", true, nullptr, 0, ff, 8 * C, M, 8 * C, C, DF_BF16);
-      if (live()) run(launch_geglu(ff, fg, M, 4 * C, st));
+      timed(PC_ELEMENTWISE, 0.0, 24.0 * M * C, [&] { return launch_geglu(ff, fg, M, 4 * C, st); });
       gemm(fg, 4 * C, p + ".ff2", true, h, C, h, C, M, C, 4 * C, DF_F32);
     }
-    if (live()) run(launch_cast_bf16(h, nb, (long long)M * C, 0, st));
+    timed(PC_ELEMENTWISE, 0.0, 6.0 * M * C, [&] { return launch_cast_bf16(h, nb, (long long)M * C, 0, st); });
     gemm(nb, C, b.name + ".pout", true, x, C, out, C, M, C, C, DF_F32);
     top = mark;
   }
@@ -415,7 +486,7 @@ struct Exec {
     const float* cur = x_in;
     int cur_c = c.in_ch;
     bf16_t* emb_act = (bf16_t*)alloc((size_t)B() * c.emb_dim * 2);
-    if (live()) run(launch_cast_bf16(emb, emb_act, (long long)B() * c.emb_dim, 1, st));
+    timed(PC_ELEMENTWISE, 0.0, 6.0 * B() * c.emb_dim, [&] { return launch_cast_bf16(emb, emb_act, (long long)B() * c.emb_dim, 1, st); });
     for (const BlockDesc& b : blocks) {
       if (err != DF_OK) break;
       const int R = rows(b.level), W = width(b.level);
@@ -425,7 +496,7 @@ struct Exec {
           float* out = (float*)alloc(px * b.cout * 4);
           const size_t mark = top;
           bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
-          if (live()) run(launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st));
+          timed(PC_ELEMENTWISE, 0.0, 6.0 * px * b.cin, [&] { return launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st); });
           conv(b.name, xb, R, W, b.cin, b.cout, 1, out, DF_F32, nullptr, nullptr);
           top = mark;
           cur = out; cur_c = b.cout;
@@ -445,7 +516,7 @@ struct Exec {
             skips.pop_back();
             skip_c.pop_back();
             float* cat = (float*)alloc(px * (size_t)(cur_c + sc) * 4);
-            if (live()) run(launch_concat(cur, cur_c, sk, sc, cat, (long long)px, st));
+            timed(PC_ELEMENTWISE, 0.0, 8.0 * px * (cur_c + sc), [&] { return launch_concat(cur, cur_c, sk, sc, cat, (long long)px, st); });
             xin = cat;
           }
           resblock(b, xin, emb_act, out);
@@ -464,7 +535,7 @@ struct Exec {
           float* out = (float*)alloc(opx * b.cout * 4);
           const size_t mark = top;
           bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
-          if (live()) run(launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st));
+          timed(PC_ELEMENTWISE, 0.0, 6.0 * px * b.cin, [&] { return launch_cast_bf16(cur, xb, (long long)px * b.cin, 0, st); });
           conv(b.name, xb, R, W, b.cin, b.cout, 2, out, DF_F32, nullptr, nullptr);
           top = mark;
           cur = out;
@@ -474,7 +545,7 @@ struct Exec {
           float* out = (float*)alloc(px * 4 * b.cout * 4);
           const size_t mark = top;
           bf16_t* xb = (bf16_t*)alloc(px * 4 * b.cin * 2);
-          if (live()) run(launch_upsample2x_bf16(cur, xb, B(), R, W, b.cin, st));
+          timed(PC_ELEMENTWISE, 0.0, 12.0 * px * b.cin, [&] { return launch_upsample2x_bf16(cur, xb, B(), R, W, b.cin, st); });
           conv(b.name, xb, 2 * R, 2 * W, b.cin, b.cout, 1, out, DF_F32, nullptr, nullptr);
           top = mark;
           cur = out;
@@ -607,7 +678,32 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   e.stale_base = (char*)stale;
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;
+  e.prof = &u->prof;
   return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+}
+
+int df_unet_profile_enable(df_unet* u, int on) {
+  if (!u) return DF_EINVAL;
+  u->prof.on = on != 0;
+  return DF_OK;
+}
+
+int df_unet_profile_reset(df_unet* u) {
+  if (!u) return DF_EINVAL;
+  u->prof.reset();
+  return DF_OK;
+}
+
+int df_unet_profile_num_classes(void) { return PC_COUNT; }
+
+const char* df_unet_profile_class_name(int cls) { return (cls >= 0 && cls < PC_COUNT) ? kProfNames[cls] : ""; }
+
+int df_unet_profile_read(df_unet* u, int cls, double* ms, double* flops, double* bytes, long long* launches) {
+  if (!u || cls < 0 || cls >= PC_COUNT || !ms || !flops || !bytes || !launches) return DF_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  if (!u->prof.collect()) return DF_EHIP;
+  *ms = u->prof.ms[cls]; *flops = u->prof.flops[cls]; *bytes = u->prof.bytes[cls]; *launches = u->prof.launches[cls];
+  return DF_OK;
 }
 
 #pragma GCC visibility pop
