@@ -193,6 +193,184 @@ __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
   }
 }
 
+
+// ---- pipelined variant: global -> LDS direct loads (global_load_lds_dwordx4), multi-stage ring ----
+//
+// BM x BN x 64 tiles.  Every wave instruction moves 64 lanes x 16 B = 8 tile rows of 128 B straight
+// into LDS (no registers), so several k-tiles of loads are in flight per workgroup; the oldest stage
+// is awaited with an explicit vmcnt.  A direct load writes lane l at LDS offset 16*l, so the tile is
+// row-major unpadded; bank conflicts are avoided by fetching, for LDS slot s of row r, the global
+// 16-byte chunk s ^ (r & 7), and reading the MFMA operand for chunk c at slot c ^ (r & 7).
+// Rows beyond M / N are clamped to the last valid row (never stored); zero padding of the
+// convolution is fetched from a page of zeros.
+#define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int VM>
+__device__ __forceinline__ void wait_vm_and_lds() {
+  // s_waitcnt vmcnt(VM) lgkmcnt(0): gfx9 encoding vmcnt[3:0]=imm[3:0], vmcnt[5:4]=imm[15:14], expcnt=imm[6:4], lgkmcnt=imm[11:8]
+  __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (0x7 << 4));
+}
+
+template <int BM, int BN, int STAGES, bool kConv, typename OutT>
+__global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16_t* __restrict__ zeros) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int AJ = BM / 32, BJ = BN / 32;       // direct-load instructions per wave per k-tile
+  constexpr int L = AJ + BJ;
+  static_assert((STAGES - 2) * L < 64, "vmcnt field is 6 bits");
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // workgroups round-robin over the 8 XCDs; give each XCD a contiguous run of tiles, M-tile fastest, so that the
+  // workgroups sharing a weight tile sit behind the same L2
+  const int MT = (p.M + BM - 1) / BM, NT = (p.N + BN - 1) / BN;
+  const int nwg = MT * NT;
+  int t = blockIdx.x;
+  {
+    const int per = (nwg + 7) / 8;
+    const int xcd = t & 7, loc = t >> 3;
+    const int cand = xcd * per + loc;
+    // only a bijection when nwg is a multiple of 8; otherwise keep the plain order
+    if ((nwg & 7) == 0) t = cand;
+  }
+  const int m0 = (t % MT) * BM, n0 = (t / MT) * BN;
+  const int KT = p.K / 64;
+
+  const int lr = lane >> 3;                 // row within the 8-row group a wave instruction covers
+  const int kc = (lane & 7) ^ lr;           // global 16-byte chunk this lane fetches (swizzle)
+  const bf16_t* a_ptr[AJ];
+  int a_b[AJ], a_ro[AJ], a_co[AJ];
+  bool a_ok[AJ];
+#pragma unroll
+  for (int j = 0; j < AJ; ++j) {
+    const int row = wave * (BM / 4) + j * 8 + lr;
+    int m = m0 + row;
+    a_ok[j] = m < p.M;
+    if (m >= p.M) m = p.M - 1;
+    if constexpr (kConv) {
+      const int per = p.Ro * p.Wo;
+      a_b[j] = m / per;
+      const int rem = m - a_b[j] * per;
+      a_ro[j] = rem / p.Wo;
+      a_co[j] = rem - a_ro[j] * p.Wo;
+      a_ptr[j] = nullptr;
+    } else {
+      a_ptr[j] = p.A + (long long)m * p.lda + kc * 8;
+      a_b[j] = a_ro[j] = a_co[j] = 0;
+    }
+  }
+  const bf16_t* b_ptr[BJ];
+#pragma unroll
+  for (int j = 0; j < BJ; ++j) {
+    int n = n0 + wave * (BN / 4) + j * 8 + lr;
+    if (n >= p.N) n = p.N - 1;
+    b_ptr[j] = p.Wt + (long long)n * p.ldw + kc * 8;
+  }
+
+  auto issue = [&](int kt, int stage) {
+    if (kt > KT - 1) kt = KT - 1;           // past the end: reload the last tile into a free stage (keeps vmcnt uniform)
+    const int k0 = kt * 64;
+    char* sa = smem + stage * STAGE + (wave * (BM / 4)) * 128;
+    char* sb = smem + stage * STAGE + A_BYTES + (wave * (BN / 4)) * 128;
+    if constexpr (kConv) {
+      const int tap = k0 / p.Cin;
+      const int cin0 = k0 - tap * p.Cin;
+      const int ky = tap / 3, kx = tap - ky * 3;
+#pragma unroll
+      for (int j = 0; j < AJ; ++j) {
+        const int ri = a_ro[j] * p.stride + ky - 1;
+        const int ci = a_co[j] * p.stride + kx - 1;
+        const bf16_t* src = zeros;
+        if (a_ok[j] && ci >= 0 && ci < p.W) {
+          if (ri < 0) {
+            if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
+          } else if (ri >= p.R) {
+            if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
+          } else {
+            src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin + cin0;
+          }
+        }
+        __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < AJ; ++j)
+        __builtin_amdgcn_global_load_lds(DF_GPTR(a_ptr[j] + k0), DF_LPTR(sa + j * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < BJ; ++j)
+      __builtin_amdgcn_global_load_lds(DF_GPTR(b_ptr[j] + k0), DF_LPTR(sb + j * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
+
+  const int lrow = lane & 31, g = lane >> 5;
+  const int sw = lrow & 7;
+  int stage = 0, nstage = STAGES - 1;
+  for (int kt = 0; kt < KT; ++kt) {
+    // tile kt has landed once at most (STAGES-2)*L younger loads are outstanding; own LDS reads of tile kt-1 are done
+    wait_vm_and_lds<(STAGES - 2) * L>();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(kt + STAGES - 1, nstage);         // into the stage every wave finished reading before the barrier
+    const char* As = smem + stage * STAGE + (wm * (BM / 2) + lrow) * 128;
+    const char* Bs = smem + stage * STAGE + A_BYTES + (wn * (BN / 2) + lrow) * 128;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int slot = ((2 * ks + g) ^ sw) * 16;
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * 128 + slot);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * 128 + slot);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+    nstage = (nstage + 1 == STAGES) ? 0 : nstage + 1;
+  }
+  wait_vm_and_lds<0>();                      // drain the clamped tail loads before the workgroup ends
+
+  OutT* out = reinterpret_cast<OutT*>(p.out);
+  const int per = kConv ? p.Ro * p.Wo : 1;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int col = n0 + wn * (BN / 2) + tn * 32 + (lane & 31);
+    if (col >= p.N) continue;
+    const float bias = p.bias ? p.bias[col] : 0.f;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (row >= p.M) continue;
+        float v = acc[tm][tn][e] + bias;
+        if constexpr (kConv) {
+          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.N + col];
+        }
+        if (p.residual) v += p.residual[(long long)row * p.ldr + col];
+        if (p.act == 1) v = silu_f(v);
+        Elem<OutT>::st(out + (long long)row * p.ldo + col, v);
+      }
+    }
+  }
+}
+
 // ---- direct convolutions for tiny or narrow shapes ----
 
 // One lane per (output pixel, output channel).
@@ -309,10 +487,48 @@ int launch_tile(const TileParams& p, int out_dtype, hipStream_t st) {
   return DF_OK;
 }
 
+template <int BM, int BN, int STAGES, bool kConv>
+int launch_pipe(const TileParams& p, int out_dtype, hipStream_t st) {
+  const bf16_t* zeros = nullptr;
+  if (kConv) {
+    char* scr = (char*)scratch_get(kScratchCounterBytes);
+    if (!scr) return DF_ENOMEM;
+    zeros = (const bf16_t*)(scr + 2048);   // the counter page stays zero; its upper half serves as the zero source
+  }
+  constexpr int smem = STAGES * (BM + BN) * 128;
+  const long long nwg = (long long)cdiv(p.M, BM) * cdiv(p.N, BN);
+  if (nwg > 0x7fffffffLL) return DF_ESHAPE;
+  dim3 grid((unsigned)nwg);
+  if (out_dtype == DF_BF16) {
+    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, bf16_t>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros);
+  } else {
+    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, float>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros);
+  }
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
 template <bool kConv>
 int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
-  // big tiles only when they still give every compute unit work; otherwise 64x64 to expose parallelism
   const long long big = (long long)cdiv(p.M, 128) * cdiv(p.N, 128);
+  const bool pipe = (p.K % 64 == 0) && (!kConv || p.Cin % 64 == 0) && p.K >= 128;
+  if (pipe) {
+    // big tiles only when they still give every compute unit work; otherwise 64x64 to expose parallelism
+    if (big >= 256) return launch_pipe<128, 128, 4, kConv>(p, out_dtype, st);
+    return launch_pipe<64, 64, 4, kConv>(p, out_dtype, st);
+  }
   if (big >= 384) return launch_tile<128, 128, kConv>(p, out_dtype, st);
   return launch_tile<64, 64, kConv>(p, out_dtype, st);
 }
