@@ -114,6 +114,15 @@ int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, c
                       const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
                       float scale, int dtype, void* stream);
 
+/*
+ * Linear layer on the fresh tokens (Section 4, Sparse operations: linear layers run on the fresh region only
+ * and need no data of other patches).  y[M,N] = x[M,K] w[N,K]^T + bias[N] + residual[M,N].
+ *   x, w bf16; bias, residual float or NULL; y bf16 or float (out_dtype); residual may alias y when y is float.
+ * K % 32 == 0.
+ */
+int df_linear(const void* x, const void* w, const float* bias, const float* residual, void* y, int M, int N, int K,
+              int out_dtype, void* stream);
+
 /* ---- whole UNet step --------------------------------------------------------------------- */
 
 typedef struct df_unet_cfg {

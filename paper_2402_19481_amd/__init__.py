@@ -51,6 +51,7 @@ def lib():
     L.df_conv3x3_halo.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]
     L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
+    L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     cfgp = ctypes.POINTER(UNetCfgC)
     if not hasattr(L, "df_patch_unet_step"):
         raise DfError("libdistrifusion.so is stale: rebuild it")
@@ -75,7 +76,7 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
-                 "df_euler_update", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_euler_update", "df_linear", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
                  "df_unet_profile_enable", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
@@ -154,6 +155,16 @@ def attn_displaced(q, k_fresh, v_fresh, k_stale, v_stale, heads, patch_idx, N, s
         out = torch.empty_like(q)
     _check(lib().df_attn_displaced(_ptr(q), _ptr(k_fresh), _ptr(v_fresh), _ptr(k_stale), _ptr(v_stale), _ptr(out), B,
                                    L, heads, d, patch_idx, N, scale, _dt(q), _stream()))
+    return out
+
+
+def linear(x, w, bias=None, residual=None, out_dtype=torch.bfloat16, out=None):
+    """x [M,K] bf16, w [N,K] bf16 -> [M,N] (+ bias + residual)."""
+    M, K = x.shape
+    N = w.shape[0]
+    if out is None:
+        out = torch.empty(M, N, dtype=out_dtype, device=x.device)
+    _check(lib().df_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), M, N, K, _dt(out), _stream()))
     return out
 
 

@@ -136,6 +136,15 @@ int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, c
   return launch_attention(a, (hipStream_t)stream);
 }
 
+int df_linear(const void* x, const void* w, const float* bias, const float* residual, void* y, int M, int N, int K,
+              int out_dtype, void* stream) {
+  if (!x || !w || !y || bad_dtype(out_dtype)) return DF_EINVAL;
+  GemmArgs g = {};
+  g.A = x; g.W = w; g.bias = bias; g.residual = residual; g.out = y;
+  g.M = M; g.N = N; g.K = K; g.lda = K; g.ldw = K; g.ldr = N; g.ldo = N; g.act = 0; g.out_dtype = out_dtype;
+  return launch_gemm_bf16(g, (hipStream_t)stream);
+}
+
 int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream) {
   if (!x || !eps) return DF_EINVAL;
   if (n < 0) return DF_ESHAPE;

@@ -12,6 +12,9 @@
 // (BM/2)x(BN/2) as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  Operands are
 // staged through LDS with an 80-byte row pitch (conflict-free for 16-byte
 // reads), double buffered, next tile prefetched into registers during compute.
+#include <cstdio>
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace df {
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
 // into LDS (no registers), so several k-tiles of loads are in flight per workgroup; the oldest stage
 // is awaited with an explicit vmcnt.  A direct load writes lane l at LDS offset 16*l, so the tile is
 // row-major unpadded; bank conflicts are avoided by fetching, for LDS slot s of row r, the global
-// 16-byte chunk s ^ (r & 7), and reading the MFMA operand for chunk c at slot c ^ (r & 7).
+// 16-byte chunk s ^ ((r >> 1) & 7), and reading the MFMA operand for chunk c at slot c ^ ((r >> 1) & 7).
 // Rows beyond M / N are clamped to the last valid row (never stored); zero padding of the
 // convolution is fetched from a page of zeros.
 #define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -212,8 +215,11 @@ __device__ __forceinline__ void wait_vm_and_lds() {
   __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (0x7 << 4));
 }
 
+// Split-K (gridDim.y > 1): every split accumulates a contiguous range of k-tiles and stores its float
+// partial; splitk_reduce_kernel adds the partials in split order and runs the epilogue.
 template <int BM, int BN, int STAGES, bool kConv, typename OutT>
-__global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16_t* __restrict__ zeros) {
+__global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16_t* __restrict__ zeros,
+                                                        float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
@@ -236,10 +242,17 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     if ((nwg & 7) == 0) t = cand;
   }
   const int m0 = (t % MT) * BM, n0 = (t / MT) * BN;
-  const int KT = p.K / 64;
+  const int nsplit = gridDim.y, split = blockIdx.y;
+  const int KT_all = p.K / 64;
+  const int kt_per = (KT_all + nsplit - 1) / nsplit;
+  const int kt_lo = split * kt_per;
+  const int KT = (kt_lo + kt_per <= KT_all ? kt_per : KT_all - kt_lo);   // >= 1 by construction of nsplit
 
   const int lr = lane >> 3;                 // row within the 8-row group a wave instruction covers
-  const int kc = (lane & 7) ^ lr;           // global 16-byte chunk this lane fetches (swizzle)
+  // LDS row r keeps global chunk c at slot c ^ ((r >> 1) & 7): with 64 banks a 16-byte read is served 16 lanes at a
+  // time, i.e. 16 consecutive rows, which this spreads over all banks (rows r and r+1 differ by 128 B = 32 banks)
+  // tile row of instruction j is 16*a + 8*j + lr, so its key is (lr >> 1) | ((j & 1) << 2)
+  auto kc_of = [&](int j) { return (lane & 7) ^ ((lr >> 1) | ((j & 1) << 2)); };
   const bf16_t* a_ptr[AJ];
   int a_b[AJ], a_ro[AJ], a_co[AJ];
   bool a_ok[AJ];
@@ -257,7 +270,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       a_co[j] = rem - a_ro[j] * p.Wo;
       a_ptr[j] = nullptr;
     } else {
-      a_ptr[j] = p.A + (long long)m * p.lda + kc * 8;
+      a_ptr[j] = p.A + (long long)m * p.lda + kc_of(j) * 8;
       a_b[j] = a_ro[j] = a_co[j] = 0;
     }
   }
@@ -266,12 +279,12 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   for (int j = 0; j < BJ; ++j) {
     int n = n0 + wave * (BN / 4) + j * 8 + lr;
     if (n >= p.N) n = p.N - 1;
-    b_ptr[j] = p.Wt + (long long)n * p.ldw + kc * 8;
+    b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_of(j) * 8;
   }
 
   auto issue = [&](int kt, int stage) {
     if (kt > KT - 1) kt = KT - 1;           // past the end: reload the last tile into a free stage (keeps vmcnt uniform)
-    const int k0 = kt * 64;
+    const int k0 = (kt_lo + kt) * 64;
     char* sa = smem + stage * STAGE + (wave * (BM / 4)) * 128;
     char* sb = smem + stage * STAGE + A_BYTES + (wave * (BN / 4)) * 128;
     if constexpr (kConv) {
@@ -292,7 +305,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
             src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin + cin0;
           }
         }
-        __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc_of(j) * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
       }
     } else {
 #pragma unroll
@@ -316,7 +329,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
 
   const int lrow = lane & 31, g = lane >> 5;
-  const int sw = lrow & 7;
+  const int sw = (lrow >> 1) & 7;
   int stage = 0, nstage = STAGES - 1;
   for (int kt = 0; kt < KT; ++kt) {
     // tile kt has landed once at most (STAGES-2)*L younger loads are outstanding; own LDS reads of tile kt-1 are done
@@ -327,24 +340,50 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     issue(kt + STAGES - 1, nstage);         // into the stage every wave finished reading before the barrier
     const char* As = smem + stage * STAGE + (wm * (BM / 2) + lrow) * 128;
     const char* Bs = smem + stage * STAGE + A_BYTES + (wn * (BN / 2) + lrow) * 128;
+    // software pipeline over the four 16-wide k-steps: the fragments of step ks+1 are requested before the
+    // MFMAs of step ks are issued, so LDS latency overlaps the matrix pipe (sched_barriers pin that order)
+    bf16x8 af[2][TM], bfr[2][TN];
+    auto read_frags = [&](int ks, int buf) {
+      const int slot = ((2 * ks + g) ^ sw) * 16;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * 128 + slot);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[buf][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * 128 + slot);
+    };
+    read_frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const int slot = ((2 * ks + g) ^ sw) * 16;
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * 128 + slot);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * 128 + slot);
+      if (ks < 3) read_frags(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
     nstage = (nstage + 1 == STAGES) ? 0 : nstage + 1;
   }
   wait_vm_and_lds<0>();                      // drain the clamped tail loads before the workgroup ends
+
+  if (nsplit > 1) {
+    // float partial of this split, [split][M][N]; the epilogue runs in splitk_reduce_kernel
+    float* mine = partials + (size_t)split * p.M * p.N;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int col = n0 + wn * (BN / 2) + tn * 32 + (lane & 31);
+      if (col >= p.N) continue;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          if (row < p.M) mine[(size_t)row * p.N + col] = acc[tm][tn][e];
+        }
+    }
+    return;
+  }
 
   OutT* out = reinterpret_cast<OutT*>(p.out);
   const int per = kConv ? p.Ro * p.Wo : 1;
@@ -487,18 +526,48 @@ int launch_tile(const TileParams& p, int out_dtype, hipStream_t st) {
   return DF_OK;
 }
 
-template <int BM, int BN, int STAGES, bool kConv>
-int launch_pipe(const TileParams& p, int out_dtype, hipStream_t st) {
-  const bf16_t* zeros = nullptr;
-  if (kConv) {
-    char* scr = (char*)scratch_get(kScratchCounterBytes);
-    if (!scr) return DF_ENOMEM;
-    zeros = (const bf16_t*)(scr + 2048);   // the counter page stays zero; its upper half serves as the zero source
+// out[m, n] = sum over splits of partial[s][m][n] + bias + per-(batch,channel) add + residual, activation; 4 columns per lane
+template <typename OutT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(TileParams p, const float* __restrict__ partials, int nsplit,
+                                                           int per) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int n4 = p.N / 4;
+  if (idx >= (long long)p.M * n4) return;
+  const int row = (int)(idx / n4), col = (int)(idx % n4) * 4;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < nsplit; ++s)
+    v += *reinterpret_cast<const f32x4*>(partials + ((size_t)s * p.M + row) * p.N + col);
+  if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + col);
+  if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.N + col);
+  if (p.residual) v += *reinterpret_cast<const f32x4*>(p.residual + (long long)row * p.ldr + col);
+  if (p.act == 1) { v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w); }
+  OutT* o = reinterpret_cast<OutT*>(p.out) + (long long)row * p.ldo + col;
+  if constexpr (sizeof(OutT) == 4) {
+    *reinterpret_cast<f32x4*>(o) = v;
+  } else {
+    u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+    *reinterpret_cast<u32x2*>(o) = t;
   }
-  constexpr int smem = STAGES * (BM + BN) * 128;
+}
+
+template <int BM, int BN, int STAGES, bool kConv>
+int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) {
   const long long nwg = (long long)cdiv(p.M, BM) * cdiv(p.N, BN);
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
-  dim3 grid((unsigned)nwg);
+  const int KT = p.K / 64;
+  if (nsplit > KT) nsplit = KT;
+  if (nsplit < 1 || p.N % 4 || p.ldr % 4 || p.ldo % 4) nsplit = 1;
+  if (nsplit > 1) nsplit = cdiv(KT, cdiv(KT, nsplit));   // no empty split
+  const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * p.M * p.N * sizeof(float) : 0;
+  char* scr = nullptr;
+  if (kConv || nsplit > 1) {
+    scr = (char*)scratch_get(kScratchCounterBytes + part_bytes);
+    if (!scr) return DF_ENOMEM;
+  }
+  const bf16_t* zeros = scr ? (const bf16_t*)(scr + kScratchZeroPageOffset) : nullptr;
+  float* partials = scr ? (float*)(scr + kScratchCounterBytes) : nullptr;
+  constexpr int smem = STAGES * (BM + BN) * 128;
+  dim3 grid((unsigned)nwg, (unsigned)nsplit);
   if (out_dtype == DF_BF16) {
     auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, bf16_t>;
     static bool attr_set = false;
@@ -506,7 +575,7 @@ int launch_pipe(const TileParams& p, int out_dtype, hipStream_t st) {
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros);
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros, partials);
   } else {
     auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, float>;
     static bool attr_set = false;
@@ -514,10 +583,42 @@ int launch_pipe(const TileParams& p, int out_dtype, hipStream_t st) {
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros);
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros, partials);
   }
   DF_LAUNCH_CHECK();
+  if (nsplit > 1) {
+    const long long n = (long long)p.M * (p.N / 4);
+    const int per = kConv ? p.Ro * p.Wo : 1;
+    if (out_dtype == DF_BF16)
+      hipLaunchKernelGGL(splitk_reduce_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, partials, nsplit, per);
+    else
+      hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, partials, nsplit, per);
+    DF_LAUNCH_CHECK();
+  }
   return DF_OK;
+}
+
+// Tile choice.  DF_TILE=<BM>x<BN>x<STAGES> in the environment overrides the heuristic (tuning aid).
+int tile_override() {
+  static int v = -1;
+  if (v < 0) {
+    v = 0;
+    const char* e = getenv("DF_TILE");
+    if (e) {
+      int bm = 0, bn = 0, st = 4;
+      if (sscanf(e, "%dx%dx%d", &bm, &bn, &st) >= 2) v = (bm * 1000 + bn) * 10 + st;
+    }
+  }
+  return v;
+}
+
+int split_override() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("DF_SPLITK");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
 }
 
 template <bool kConv>
@@ -525,15 +626,45 @@ int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
   const long long big = (long long)cdiv(p.M, 128) * cdiv(p.N, 128);
   const bool pipe = (p.K % 64 == 0) && (!kConv || p.Cin % 64 == 0) && p.K >= 128;
   if (pipe) {
-    // big tiles only when they still give every compute unit work; otherwise 64x64 to expose parallelism
-    if (big >= 256) return launch_pipe<128, 128, 4, kConv>(p, out_dtype, st);
-    return launch_pipe<64, 64, 4, kConv>(p, out_dtype, st);
+    const int so = split_override() > 0 ? split_override() : 1;
+    switch (tile_override()) {
+      case 1281284: return launch_pipe<128, 128, 4, kConv>(p, out_dtype, so, st);
+      case 1281283: return launch_pipe<128, 128, 3, kConv>(p, out_dtype, so, st);
+      case 1281282: return launch_pipe<128, 128, 2, kConv>(p, out_dtype, so, st);
+      case 1280643: return launch_pipe<128, 64, 3, kConv>(p, out_dtype, so, st);
+      case 640644: return launch_pipe<64, 64, 4, kConv>(p, out_dtype, so, st);
+      case 640642: return launch_pipe<64, 64, 2, kConv>(p, out_dtype, so, st);
+      default: break;
+    }
+    // Fetch throughput of a compute unit grows with the number of resident waves, so the default is the small
+    // 64x64 tile with two stages (32 KB of LDS: five workgroups per unit); problems with few tiles and a deep
+    // K are split along K until about a thousand workgroups exist.
+    const long long nwg = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
+    const int KT = p.K / 64;
+    int ns = 1;
+    if (nwg < 512 && KT >= 32) {             // the extra reduce launch only pays for a deep K
+      ns = (int)((1024 + nwg - 1) / nwg);
+      if (ns > 8) ns = 8;
+      if (ns > KT / 8) ns = KT / 8;          // keep at least eight k-tiles per split
+      if (ns < 1) ns = 1;
+    }
+    if (split_override() > 0) ns = split_override();
+    if (big >= 1024) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
+    if (nwg * ns >= 512) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, ns, st);
+    return launch_pipe<64, 64, 4, kConv>(p, out_dtype, ns, st);
   }
   if (big >= 384) return launch_tile<128, 128, kConv>(p, out_dtype, st);
   return launch_tile<64, 64, kConv>(p, out_dtype, st);
 }
 
 }  // namespace
+
+// bytes of library scratch a tile launch may ask for (plans reserve it up front)
+size_t gemm_scratch_bytes(long long M, long long N) {
+  // split-K is only used below 1024 workgroups of 64x64 and with at most 8 splits
+  const long long nwg = (long long)cdiv(M, 64) * cdiv(N, 64);
+  return kScratchCounterBytes + (size_t)(nwg < 1024 ? 8 * M * N * sizeof(float) : 0);
+}
 
 int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || a.K % BK) return DF_ESHAPE;

@@ -51,6 +51,7 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
   float s[V], q[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) { s[i] = 0.f; q[i] = 0.f; }
+#pragma unroll 4
   for (int p = p_lo + psub; p < p_hi; p += ppb) {
     float v[V];
     ld_vec(x + (seg_base + p) * C + c0, v);
@@ -97,9 +98,11 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
     float a = 0.f, c = 0.f;
     if (part < parts) {
       const float* base = partial + (((long long)b * nseg + sg) * nblk) * G * 2;
+#pragma unroll 4
       for (int k = part; k < nblk; k += parts) {
-        a += __builtin_nontemporal_load(base + ((long long)k * G + g) * 2);
-        c += __builtin_nontemporal_load(base + ((long long)k * G + g) * 2 + 1);
+        const float2 v = *reinterpret_cast<const float2*>(base + ((long long)k * G + g) * 2);
+        a += v.x;
+        c += v.y;
       }
       s_red[0][part][g] = a;
       s_red[1][part][g] = c;
@@ -229,7 +232,8 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   if (a.B > 1024) return DF_ESHAPE;
   const long long pix_seg = (long long)a.Rseg * a.W;
   if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
-  int target = 1024 / a.nseg;
+  // few enough blocks that the last one folds the partials in a handful of trips, enough to fill the chip
+  int target = 256 / a.nseg;
   if (target < 1) target = 1;
   GnLayout L = gn_layout(a.C, vec, pix_seg, target);
   if ((long long)L.nblk * a.nseg > 2048) return DF_ESHAPE;

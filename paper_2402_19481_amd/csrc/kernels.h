@@ -8,9 +8,12 @@ namespace df {
 
 // ---- device scratch owned by the library (one per device, grown on demand) ----
 // Returns a 256-byte aligned device buffer of at least `bytes`, or nullptr.
-// The first 4 KiB are counters that kernels leave at zero.
+// The first 16 KiB are reserved: [0, 8 KiB) counters that every kernel leaves at zero,
+// [8 KiB, 16 KiB) a page of zeros nobody writes (source of the convolution's zero padding).
 void* scratch_get(size_t bytes);
-constexpr size_t kScratchCounterBytes = 4096;
+constexpr size_t kScratchCounterBytes = 16384;
+constexpr size_t kScratchZeroPageOffset = 8192;
+constexpr int kScratchNumCounters = 2048;
 
 // ---- refresh.hip ----
 int launch_copy_rows(void* dst, const void* src, long long rows, long long row_bytes, long long dst_stride_bytes,
@@ -63,6 +66,7 @@ struct GemmArgs {
   int out_dtype;
 };
 int launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
+size_t gemm_scratch_bytes(long long M, long long N);  // also covers a convolution with M output pixels, N = Cout
 
 // ---- attn.hip ----
 struct AttnArgs {

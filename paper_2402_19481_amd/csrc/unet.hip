@@ -293,6 +293,10 @@ struct Exec {
             void* out, long long ldo, int M, int Nn, int K, int out_dtype) {
     const void* W = weight(wn + ".w");
     const float* bp = bias ? (const float*)weight(wn + ".b") : nullptr;
+    {
+      const size_t need = gemm_scratch_bytes(M, Nn);
+      if (need > scratch_need) scratch_need = need;
+    }
     if (!live()) return;
     GemmArgs g = {};
     g.A = A; g.W = W; g.bias = bp; g.residual = residual; g.out = out;
@@ -333,6 +337,10 @@ struct Exec {
     bf16_t* entry = (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * rowe * sizeof(bf16_t));
     const void* wt = weight(name + ".w");
     const float* bias = (const float*)weight(name + ".b");
+    {
+      const size_t need = gemm_scratch_bytes((long long)B() * (R / stride) * (W / stride), Cout);
+      if (need > scratch_need) scratch_need = need;
+    }
     if (!live()) return;
     ConvArgs a = {};
     a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.residual = residual; a.y = out;

@@ -269,3 +269,37 @@ def test_tiny_block_chain_f32():
             e = rel_l2(host(g), r.reshape(host(g).shape))
             say("  tiny block patch", i, nm, e)
             assert e < TOL_F32
+
+
+# ------------------------------------------------------------------ linear layers (per-token, fresh rows only)
+
+@pytest.mark.parametrize("M,N,K,out_f32,res", [
+    (300, 1280, 1280, True, True),     # level-2 projection of the 1280x1920 share: few tiles, split along K
+    (300, 1280, 5120, True, True),     # feed-forward output: deep K
+    (300, 3840, 1280, False, False),   # fused QKV
+    (77, 2560, 2048, False, False),    # text K/V projection: ragged rows
+    (1200, 640, 2560, True, True),
+    (1, 320, 1280, True, False),       # embedding projection: a single row
+    (130, 192, 96, False, False),      # K not a multiple of 64: register-staged kernel
+    (4800, 320, 960, True, False),     # 1x1 shortcut convolution
+])
+def test_linear(M, N, K, out_f32, res):
+    say("linear", M, N, K, out_f32, res)
+    x = round_bf16(normal(31, "x", (M, K)))
+    w = round_bf16(normal(31, "w", (N, K), std=1.0 / math.sqrt(K)))
+    b = normal(31, "b", (N,), std=0.1)
+    r = normal(31, "r", (M, N)) if res else None
+    ref = ops.linear(x, w, b) + (r if res else 0.0)
+    y = df.linear(dev(x, True), dev(w, True), dev(b), dev(r) if res else None,
+                  out_dtype=torch.float32 if out_f32 else torch.bfloat16)
+    e = rel_l2(host(y), ref)
+    say("   rel_l2", e)
+    assert e < (2e-3 if out_f32 else TOL_BF16)
+    if res and out_f32:                 # in-place residual: out aliases the residual
+        rd = dev(r)
+        df.linear(dev(x, True), dev(w, True), dev(b), rd, out=rd)
+        assert rel_l2(host(rd), ref) < 2e-3
+    # run-to-run determinism (split-K partials are added in a fixed order)
+    y2 = df.linear(dev(x, True), dev(w, True), dev(b), dev(r) if res else None,
+                   out_dtype=torch.float32 if out_f32 else torch.bfloat16)
+    np.testing.assert_array_equal(host(y), host(y2))
