@@ -40,6 +40,12 @@ struct TileParams {
   const bf16_t* bot;
   long long halo_bs;
   int R, W, Cin, Ro, Wo, stride;
+  // epilogue variants of the pipelined kernel (see GemmArgs)
+  int geglu;      // F (half of N) or 0
+  int nseg, seg_w;
+  void* seg_out[3];
+  long long seg_ld[3], seg_rows_out[3], seg_row0[3];
+  int seg_rows_in[3];
 };
 
 template <int BM, int BN, bool kConv, typename OutT>
@@ -277,7 +283,14 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   const bf16_t* b_ptr[BJ];
 #pragma unroll
   for (int j = 0; j < BJ; ++j) {
-    int n = n0 + wave * (BN / 4) + j * 8 + lr;
+    const int tr = wave * (BN / 4) + j * 8 + lr;      // tile row of the weight operand
+    int n = n0 + tr;
+    if (p.geglu) {
+      // tile columns come in (value, gate) pairs of 32: columns [64q, 64q+32) are value rows, [64q+32, 64q+64) the
+      // gate rows of the same 32 outputs, so that one wave holds both in its two accumulator blocks
+      const int q = tr >> 6, w32 = tr & 31, gate = (tr >> 5) & 1;
+      n = (n0 >> 1) + q * 32 + w32 + gate * p.geglu;
+    }
     if (n >= p.N) n = p.N - 1;
     b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_of(j) * 8;
   }
@@ -387,11 +400,41 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
 
   OutT* out = reinterpret_cast<OutT*>(p.out);
   const int per = kConv ? p.Ro * p.Wo : 1;
+  if constexpr (!kConv && TN == 2 && sizeof(OutT) == 2) {
+    if (p.geglu) {
+      // accumulator block 0 holds the value columns, block 1 the gate columns of the same outputs
+      const int oc = (n0 >> 1) + wn * 32 + (lane & 31);
+      if (oc < p.geglu) {
+        const float bv = p.bias ? p.bias[oc] : 0.f, bg = p.bias ? p.bias[p.geglu + oc] : 0.f;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            if (row >= p.M) continue;
+            const float gte = acc[tm][1][e] + bg;
+            const float gl = 0.5f * gte * (1.0f + erff(gte * 0.70710678118654752f));
+            Elem<OutT>::st(out + (long long)row * p.ldo + oc, (acc[tm][0][e] + bv) * gl);
+          }
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int tn = 0; tn < TN; ++tn) {
     const int col = n0 + wn * (BN / 2) + tn * 32 + (lane & 31);
     if (col >= p.N) continue;
     const float bias = p.bias ? p.bias[col] : 0.f;
+    // segmented output: the 32 columns of a block never straddle a segment (seg_w % 32 == 0)
+    OutT* obase = out;
+    long long old = p.ldo, orow0 = 0, orows_out = 0;
+    int ocol = col, orows_in = 0x7fffffff;
+    if (p.nseg > 0) {
+      const int sg = col / p.seg_w;
+      obase = reinterpret_cast<OutT*>(p.seg_out[sg]);
+      old = p.seg_ld[sg]; orow0 = p.seg_row0[sg]; orows_out = p.seg_rows_out[sg]; orows_in = p.seg_rows_in[sg];
+      ocol = col - sg * p.seg_w;
+    }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
@@ -404,7 +447,12 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
         }
         if (p.residual) v += p.residual[(long long)row * p.ldr + col];
         if (p.act == 1) v = silu_f(v);
-        Elem<OutT>::st(out + (long long)row * p.ldo + col, v);
+        long long orow = row;
+        if (p.nseg > 0) {
+          const int bi = row / orows_in;
+          orow = (long long)bi * orows_out + orow0 + (row - bi * orows_in);
+        }
+        Elem<OutT>::st(obase + orow * old + ocol, v);
       }
     }
   }
@@ -672,6 +720,22 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
   TileParams p = {};
   p.A = (const bf16_t*)a.A; p.Wt = (const bf16_t*)a.W; p.bias = a.bias; p.residual = a.residual; p.out = a.out;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldw = a.ldw; p.ldr = a.ldr; p.ldo = a.ldo; p.act = a.act;
+  if (a.geglu || a.nseg > 0) {
+    if (a.K % 64 || a.K < 128 || a.out_dtype != DF_BF16 || a.residual || a.act) return DF_ESHAPE;
+    if (a.geglu) {
+      if (a.N % 128 || a.nseg) return DF_ESHAPE;
+      p.geglu = a.N / 2;
+      return launch_pipe<64, 128, 2, false>(p, DF_BF16, 1, st);
+    }
+    if (a.nseg > 3 || a.seg_w % 64 || a.seg_w * a.nseg != a.N) return DF_ESHAPE;
+    p.nseg = a.nseg; p.seg_w = a.seg_w;
+    for (int i = 0; i < a.nseg; ++i) {
+      if (!a.seg_out[i] || a.seg_rows_in[i] <= 0) return DF_EINVAL;
+      p.seg_out[i] = a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
+      p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
+    }
+    return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
+  }
   return pick_tile<false>(p, a.out_dtype, st);
 }
 

@@ -64,6 +64,16 @@ struct GemmArgs {
   long long lda, ldw, ldr, ldo;
   int act;        // 0 none, 1 SiLU
   int out_dtype;
+  // GEGLU epilogue: W holds 2F rows (F value rows, then F gate rows), N = 2F; the output is [M, F] bf16 with
+  // out[m, f] = (x w_f + b_f) * gelu(x w_{F+f} + b_{F+f}).  Requires K % 64 == 0, K >= 128, F % 64 == 0.
+  int geglu;
+  // Segmented bf16 output (fused QKV projection): column segment s = col / seg_w is written to seg_out[s] instead of
+  // `out`; input row m lands on row (m / seg_rows_in[s]) * seg_rows_out[s] + seg_row0[s] + m % seg_rows_in[s] with
+  // row stride seg_ld[s].  nseg = 0: plain output.  Requires K % 64 == 0, K >= 128, no split-K (any K is accepted).
+  int nseg, seg_w;
+  void* seg_out[3];
+  long long seg_ld[3], seg_rows_out[3], seg_row0[3];
+  int seg_rows_in[3];
 };
 int launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
 size_t gemm_scratch_bytes(long long M, long long N);  // also covers a convolution with M output pixels, N = Cout

@@ -221,6 +221,12 @@ struct df_unet {
   size_t stale_bytes = 0;
   char* ws = nullptr;
   size_t ws_bytes = 0;
+  // text K/V projection weights of all transformer blocks of a level, concatenated along the output dimension
+  // ([count * 2C, text_dim] bf16) at the start of the workspace, so that one GEMM per level projects the text
+  // for every block of the step
+  size_t kv_off[4] = {0, 0, 0, 0};
+  int kv_count[4] = {0, 0, 0, 0};
+  size_t packed_bytes = 0;
 };
 
 namespace {
@@ -244,6 +250,10 @@ struct Exec {
   size_t scratch_need = 0;
   int err = DF_OK;
   Prof* prof = nullptr;
+  const bf16_t* kv_packed[4] = {nullptr, nullptr, nullptr, nullptr};
+  int kv_count[4] = {0, 0, 0, 0};
+  int kv_cursor[4] = {0, 0, 0, 0};
+  bf16_t* kv2_all[4] = {nullptr, nullptr, nullptr, nullptr};
 
   // run a launch, accounted to class `cls` when per-launch timing is on
   template <typename F>
@@ -290,15 +300,20 @@ struct Exec {
 
   // ---- layers ----
   void gemm(const void* A, long long lda, const std::string& wn, bool bias, const float* residual, long long ldr,
-            void* out, long long ldo, int M, int Nn, int K, int out_dtype) {
+            void* out, long long ldo, int M, int Nn, int K, int out_dtype, const GemmArgs* extra = nullptr) {
     const void* W = weight(wn + ".w");
     const float* bp = bias ? (const float*)weight(wn + ".b") : nullptr;
+    gemm_w(A, lda, W, bp, residual, ldr, out, ldo, M, Nn, K, out_dtype, extra);
+  }
+  void gemm_w(const void* A, long long lda, const void* W, const float* bp, const float* residual, long long ldr,
+              void* out, long long ldo, int M, int Nn, int K, int out_dtype, const GemmArgs* extra = nullptr) {
     {
       const size_t need = gemm_scratch_bytes(M, Nn);
       if (need > scratch_need) scratch_need = need;
     }
     if (!live()) return;
     GemmArgs g = {};
+    if (extra) g = *extra;   // epilogue variant (GEGLU / segmented output) prepared by the caller
     g.A = A; g.W = W; g.bias = bp; g.residual = residual; g.out = out;
     g.M = M; g.N = Nn; g.K = K; g.lda = lda; g.ldw = K; g.ldr = ldr; g.ldo = ldo; g.act = 0; g.out_dtype = out_dtype;
     const double osz = out_dtype == DF_BF16 ? 2.0 : 4.0;
@@ -409,7 +424,6 @@ struct Exec {
     float* h = (float*)alloc((size_t)M * C * 4);             // hidden state (residual stream)
     bf16_t* qkv = (bf16_t*)alloc((size_t)M * 3 * C * 2);
     bf16_t* ao = (bf16_t*)alloc((size_t)M * C * 2);          // attention output
-    bf16_t* kv2 = (bf16_t*)alloc((size_t)B() * TL * 2 * C * 2);
     bf16_t* ff = (bf16_t*)alloc((size_t)M * 8 * C * 2);
     bf16_t* fg = (bf16_t*)alloc((size_t)M * 4 * C * 2);
     const float scale = 1.0f / sqrtf((float)c.head_dim);
@@ -421,27 +435,47 @@ struct Exec {
       const float* g1 = (const float*)weight(p + ".ln1.g");
       const float* b1 = (const float*)weight(p + ".ln1.beta");
       timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g1, b1, M, C, 1e-5f, st); });
-      gemm(nb, C, p + ".attn1.qkv", false, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
       bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
+      // With refresh the projection writes the patch's keys and values straight into its rows of the stale buffers
+      // (the refresh costs nothing) and attention reads every key from there; without refresh they go to a scratch
+      // tensor and are spliced in by the attention loader.
+      const bool fused_kv = (full() || refresh) && C % 64 == 0 && C >= 128;
+      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      if (fused_kv) {
+        GemmArgs ex = {};
+        ex.nseg = 3; ex.seg_w = C;
+        ex.seg_out[0] = qkv; ex.seg_ld[0] = C; ex.seg_rows_in[0] = 0x7fffffff; ex.seg_rows_out[0] = 0; ex.seg_row0[0] = 0;
+        ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
+        ex.seg_out[2] = vs; ex.seg_ld[2] = C; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = L; ex.seg_row0[2] = (long long)row0;
+        gemm(nb, C, p + ".attn1.qkv", false, nullptr, 0, qkv, C, M, 3 * C, C, DF_BF16, &ex);
+      } else {
+        gemm(nb, C, p + ".attn1.qkv", false, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16);
+      }
       {
         const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
         if (need > scratch_need) scratch_need = need;
       }
       if (live()) {
         AttnArgs a = {};
-        a.q = qkv; a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C; a.k_stale = ks; a.v_stale = vs; a.out = ao;
+        a.k_stale = ks; a.v_stale = vs; a.out = ao; a.q = qkv;
         a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
-        a.own_lo = full() ? 0 : patch * Lq; a.own_n = Lq;
-        a.ldq = a.ldkf = a.ldvf = 3 * C; a.ldks = a.ldvs = C; a.ldo = C;
-        a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C; a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
+        a.ldks = a.ldvs = C; a.ldo = C;
+        a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
+        if (fused_kv) {
+          a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;     // every key row comes from the refreshed buffer
+          a.ldq = C; a.ldkf = a.ldvf = C; a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
+        } else {
+          a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C;
+          a.own_lo = full() ? 0 : patch * Lq; a.own_n = Lq;
+          a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
+        }
         a.scale = scale; a.dtype = DF_BF16;
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
       }
-      if (live() && (full() || refresh)) {
-        // the patch's projected keys/values replace its rows of the stale buffers (read only by later steps)
-        const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      if (live() && !fused_kv && (full() || refresh)) {
+        // narrow layers keep the separate refresh copies of the projected keys and values
         for (int bi = 0; bi < B(); ++bi) {
           timed(PC_REFRESH, 0.0, 4.0 * Lq * C, [&] {
             return launch_copy_rows(ks + ((size_t)bi * L + row0) * C, qkv + (size_t)bi * Lq * 3 * C + C, Lq, C * 2LL,
@@ -459,7 +493,10 @@ struct Exec {
       const float* b2 = (const float*)weight(p + ".ln2.beta");
       timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g2, b2, M, C, 1e-5f, st); });
       gemm(nb, C, p + ".attn2.q", false, nullptr, 0, qkv, C, M, C, C, DF_BF16);
-      gemm(text, c.text_dim, p + ".attn2.kv", false, nullptr, 0, kv2, 2 * C, B() * TL, 2 * C, c.text_dim, DF_BF16);
+      // keys/values of the text tokens: projected for all blocks of the level at the start of the step
+      const long long kvld = (long long)kv_count[b.level] * 2 * C;
+      const bf16_t* kv2 = kv2_all[b.level] + (size_t)kv_cursor[b.level] * 2 * C;
+      kv_cursor[b.level] += 1;
       {
         const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
         if (need > scratch_need) scratch_need = need;
@@ -468,8 +505,8 @@ struct Exec {
         AttnArgs a = {};
         a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = ao;
         a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
-        a.ldq = C; a.ldkf = a.ldvf = 2 * C; a.ldks = a.ldvs = 2 * C; a.ldo = C;
-        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * 2 * C; a.bso = (long long)Lq * C;
+        a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
         a.scale = scale; a.dtype = DF_BF16;
         timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
               [&] { return launch_attention(a, st); });
@@ -479,8 +516,14 @@ struct Exec {
       const float* g3 = (const float*)weight(p + ".ln3.g");
       const float* b3 = (const float*)weight(p + ".ln3.beta");
       timed(PC_LAYERNORM, 0.0, 6.0 * M * C, [&] { return launch_layernorm(h, nb, g3, b3, M, C, 1e-5f, st); });
-      gemm(nb, C, p + ".ff1", true, nullptr, 0, ff, 8 * C, M, 8 * C, C, DF_BF16);
-      timed(PC_ELEMENTWISE, 0.0, 24.0 * M * C, [&] { return launch_geglu(ff, fg, M, 4 * C, st); });
+      if (C % 64 == 0 && C >= 128) {
+        GemmArgs ex = {};
+        ex.geglu = 1;                    // value * gelu(gate) in the epilogue: the [M, 8C] tensor never exists
+        gemm(nb, C, p + ".ff1", true, nullptr, 0, fg, 4 * C, M, 8 * C, C, DF_BF16, &ex);
+      } else {
+        gemm(nb, C, p + ".ff1", true, nullptr, 0, ff, 8 * C, M, 8 * C, C, DF_BF16);
+        timed(PC_ELEMENTWISE, 0.0, 24.0 * M * C, [&] { return launch_geglu(ff, fg, M, 4 * C, st); });
+      }
       gemm(fg, 4 * C, p + ".ff2", true, h, C, h, C, M, C, 4 * C, DF_F32);
     }
     timed(PC_ELEMENTWISE, 0.0, 6.0 * M * C, [&] { return launch_cast_bf16(h, nb, (long long)M * C, 0, st); });
@@ -495,6 +538,14 @@ struct Exec {
     int cur_c = c.in_ch;
     bf16_t* emb_act = (bf16_t*)alloc((size_t)B() * c.emb_dim * 2);
     timed(PC_ELEMENTWISE, 0.0, 6.0 * B() * c.emb_dim, [&] { return launch_cast_bf16(emb, emb_act, (long long)B() * c.emb_dim, 1, st); });
+    for (int lv = 0; lv < c.n_levels; ++lv) {
+      kv_cursor[lv] = 0;
+      if (kv_count[lv] == 0) continue;
+      const int Nkv = kv_count[lv] * 2 * c.levels[lv];
+      kv2_all[lv] = (bf16_t*)alloc((size_t)B() * c.text_len * Nkv * 2);
+      gemm_w(text, c.text_dim, kv_packed[lv], nullptr, nullptr, 0, kv2_all[lv], Nkv, B() * c.text_len, Nkv, c.text_dim,
+             DF_BF16);
+    }
     for (const BlockDesc& b : blocks) {
       if (err != DF_OK) break;
       const int R = rows(b.level), W = width(b.level);
@@ -574,7 +625,9 @@ struct Exec {
 };
 
 struct DryResult {
-  size_t ws_bytes, stale_bytes, scratch;
+  size_t ws_bytes, stale_bytes, scratch, packed_bytes;
+  size_t kv_off[4];
+  int kv_count[4];
   std::vector<StaleEntry> stale;
 };
 
@@ -583,6 +636,8 @@ DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
   for (int mode = 0; mode < 2; ++mode) {
     std::vector<StaleEntry> list;
     Exec e{c, blocks, nullptr, true, mode, 0, 1, nullptr, nullptr, 0};
+    for (const BlockDesc& b : blocks)
+      if (b.kind == BlockDesc::XF) e.kv_count[b.level] += b.depth;
     e.stale_base = nullptr;
     e.stale_list = &list;
     e.stale_idx = nullptr;
@@ -591,7 +646,16 @@ DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
     if (e.scratch_need > r.scratch) r.scratch = e.scratch_need;
     if (mode == 0) { r.stale = list; r.stale_bytes = e.stale_top; }
   }
-  r.ws_bytes += 256;
+  for (int lv = 0; lv < 4; ++lv) { r.kv_off[lv] = 0; r.kv_count[lv] = 0; }
+  for (const BlockDesc& b : blocks)
+    if (b.kind == BlockDesc::XF) r.kv_count[b.level] += b.depth;
+  size_t off = 0;
+  for (int lv = 0; lv < c.n_levels; ++lv) {
+    r.kv_off[lv] = off;
+    off += align256((size_t)r.kv_count[lv] * 2 * c.levels[lv] * c.text_dim * sizeof(bf16_t));
+  }
+  r.packed_bytes = off;
+  r.ws_bytes += off + 256;
   return r;
 }
 
@@ -648,6 +712,22 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
   u->stale_bytes = d.stale_bytes;
   u->ws = (char*)workspace;
   u->ws_bytes = workspace_bytes;
+  u->packed_bytes = d.packed_bytes;
+  {
+    int cursor[4] = {0, 0, 0, 0};
+    for (int lv = 0; lv < 4; ++lv) { u->kv_off[lv] = d.kv_off[lv]; u->kv_count[lv] = d.kv_count[lv]; }
+    for (const BlockDesc& b : u->blocks) {
+      if (b.kind != BlockDesc::XF) continue;
+      const size_t one = (size_t)2 * b.cin * cfg->text_dim * sizeof(bf16_t);
+      for (int dd = 0; dd < b.depth; ++dd) {
+        const void* src = u->w[b.name + ".b" + std::to_string(dd) + ".attn2.kv.w"];
+        char* dst = u->ws + u->kv_off[b.level] + (size_t)cursor[b.level] * one;
+        if (hipMemcpy(dst, src, one, hipMemcpyDeviceToDevice) != hipSuccess) { delete u; return DF_EHIP; }
+        cursor[b.level] += 1;
+      }
+    }
+    if (hipDeviceSynchronize() != hipSuccess) { delete u; return DF_EHIP; }
+  }
   // reserve the library scratch now, so that no step ever has to grow it
   if (!scratch_get(d.scratch > kScratchCounterBytes ? d.scratch : kScratchCounterBytes)) { delete u; return DF_ENOMEM; }
   *out = u;
@@ -682,7 +762,11 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   if (((uintptr_t)x % 16) || ((uintptr_t)text % 16) || ((uintptr_t)stale % 256) || ((uintptr_t)eps_out % 16))
     return DF_EINVAL;
   Exec e{u->cfg, u->blocks, &u->w, false, mode, mode == DF_MODE_FULL ? 0 : patch_idx, refresh ? 1 : 0,
-         (hipStream_t)stream, u->ws, u->ws_bytes};
+         (hipStream_t)stream, u->ws + u->packed_bytes, u->ws_bytes - u->packed_bytes};
+  for (int lv = 0; lv < 4; ++lv) {
+    e.kv_count[lv] = u->kv_count[lv];
+    e.kv_packed[lv] = (const bf16_t*)(u->ws + u->kv_off[lv]);
+  }
   e.stale_base = (char*)stale;
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;

@@ -104,3 +104,33 @@ def test_euler_update():
     want = ounet.euler_update(host(x), host(e), 2.5, 1.75)
     df.euler_update(x, e, 2.5, 1.75)
     np.testing.assert_allclose(host(x), want, rtol=1e-6, atol=1e-6)
+
+
+def test_config4_full_size_against_golden():
+    """SDXL-shaped UNet, 160x240 latent, N=8, patch 3 (the benchmark workload): FULL step on x_prev and
+    DISPLACED step on x = x_prev + 0.02 N(0,1), against oracle outputs stored by
+    tests/golden/make_unet_golden.py (the float64 full-image pass takes minutes on the CPU)."""
+    import os
+    gold = np.load(os.path.join(os.path.dirname(__file__), "golden", "unet_cfg4_eps.npz"))
+    H, W, N, patch, seed = int(gold["H"]), int(gold["W"]), int(gold["N"]), int(gold["patch"]), int(gold["seed"])
+    cfg = ut.UNetCfg(H=H, W=W, N=N, **ut.SDXL)
+    say("config 4: drawing", ut.num_params(cfg) / 1e9, "G parameters")
+    weights = configs.unet_weights(cfg, seed=seed, threads=16)
+    t = configs.unet_inputs(cfg, seed=seed)
+    wd = _upload(weights)
+    del weights
+    net = df.PatchUNet(cfg, wd, B=1, device=DEV)
+    emb_d, text_d = dev(t["emb"]), dev(t["text"], True)
+    g_full = net.step(dev(t["x_prev"]), emb_d, text_d, mode=df.MODE_FULL)
+    e = rel_l2(host(g_full), gold["eps_full"])
+    say("  config 4 FULL eps rel_l2", e)
+    assert np.isfinite(host(g_full)).all() and e < TOL_BF16
+    R = H // N
+    g_disp = net.step(dev(t["x"][:, patch * R:(patch + 1) * R]), emb_d, text_d, patch_idx=patch, mode=df.MODE_DISPLACED)
+    e = rel_l2(host(g_disp), gold["eps_disp"])
+    say("  config 4 DISPLACED patch", patch, "eps rel_l2", e)
+    assert e < TOL_BF16
+    # displaced and synchronous results differ, but only slightly at this staleness
+    d = rel_l2(gold["eps_disp"], gold["eps_full"][:, patch * R:(patch + 1) * R])
+    say("  oracle: displaced vs previous step's rows", d)
+    net.close()
