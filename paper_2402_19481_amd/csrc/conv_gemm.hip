@@ -21,6 +21,8 @@ namespace df {
 
 namespace {
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
 constexpr int BK = 32;
 constexpr int LDS_PITCH = 40;  // bf16 elements per LDS row: 32 + 8 pad
 
@@ -46,6 +48,13 @@ struct TileParams {
   void* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  int packed_w;
+  const float* ln_s;
+  const float* ln_t;
+  float ln_eps;
+  bf16_t* out2;
+  long long ldo2;
+  int vec_epi;    // every epilogue pointer / stride allows 16-byte (float) and 8-byte (bf16) accesses
 };
 
 template <int BM, int BN, bool kConv, typename OutT>
@@ -292,8 +301,12 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       n = (n0 >> 1) + q * 32 + w32 + gate * p.geglu;
     }
     if (n >= p.N) n = p.N - 1;
-    b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_of(j) * 8;
+    if (p.packed_w)   // tile (n/64, kt) is 8 KB contiguous, rows and swizzled 16-byte slots exactly as they sit in LDS
+      b_ptr[j] = p.Wt + ((long long)(n >> 6) * KT_all * 64 + (n & 63)) * 64 + (lane & 7) * 8;
+    else
+      b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_of(j) * 8;
   }
+  const int b_kstep = p.packed_w ? 4096 : 64;   // elements between consecutive k-tiles of the weight operand
 
   auto issue = [&](int kt, int stage) {
     if (kt > KT - 1) kt = KT - 1;           // past the end: reload the last tile into a free stage (keeps vmcnt uniform)
@@ -327,7 +340,8 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     }
 #pragma unroll
     for (int j = 0; j < BJ; ++j)
-      __builtin_amdgcn_global_load_lds(DF_GPTR(b_ptr[j] + k0), DF_LPTR(sb + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(DF_GPTR(b_ptr[j] + (long long)(kt_lo + kt) * b_kstep), DF_LPTR(sb + j * 1024), 16,
+                                       0, 0);
   };
 
   f32x16 acc[TM][TN];
@@ -343,6 +357,10 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
 
   const int lrow = lane & 31, g = lane >> 5;
   const int sw = (lrow >> 1) & 7;
+  const bool ln_fold = !kConv && p.ln_s != nullptr;
+  float ln_sum[TM], ln_sq[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { ln_sum[i] = 0.f; ln_sq[i] = 0.f; }
   int stage = 0, nstage = STAGES - 1;
   for (int kt = 0; kt < KT; ++kt) {
     // tile kt has landed once at most (STAGES-2)*L younger loads are outstanding; own LDS reads of tile kt-1 are done
@@ -373,6 +391,24 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+      if constexpr (!kConv) {
+        // row sums of the A operand for the folded LayerNorm: two v_dot2 per dword, the two waves that share
+        // the rows take alternate k-steps (runs on the vector ALU beside the matrix pipe)
+        if (ln_fold && (ks & 1) == wn) {
+          const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const u32x4 raw = __builtin_bit_cast(u32x4, af[ks & 1][i]);
+            const unsigned int wds[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const bf16x2_t v2 = __builtin_bit_cast(bf16x2_t, wds[q]);
+              ln_sum[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, ones, ln_sum[i], false);
+              ln_sq[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, v2, ln_sq[i], false);
+            }
+          }
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
@@ -380,6 +416,136 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   }
   wait_vm_and_lds<0>();                      // drain the clamped tail loads before the workgroup ends
 
+  // ---- epilogue ----
+  // The accumulators are staged through LDS (the operand ring is free now) so that every lane then handles four
+  // consecutive columns of one row: bias / norm vectors / residual are read and the result is written with 16-byte
+  // (float) or 8-byte (bf16) accesses instead of 4- and 2-byte ones.
+  constexpr int PT = (BM * (BN + 4) * 4 + BM * 24 <= STAGES * STAGE) ? BN + 4 : BN;   // LDS pitch of the staged tile
+  float* tile = reinterpret_cast<float*>(smem);
+  float* s_mr = tile + BM * PT;               // [BM][2] mean, rstd of the tile's rows (folded LayerNorm)
+  if constexpr (!kConv) {
+    if (ln_fold) {
+      float* s_part = s_mr + BM * 2;          // [2][BM][2] partial (sum, sum of squares) of the two waves of a row
+      __syncthreads();                        // every wave is done with the operand stages
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const float sm = ln_sum[i] + __shfl_xor(ln_sum[i], 32, 64);   // the two lane groups hold different k chunks
+        const float sq = ln_sq[i] + __shfl_xor(ln_sq[i], 32, 64);
+        if (g == 0) {
+          const int r = wm * (BM / 2) + i * 32 + lrow;
+          s_part[(wn * BM + r) * 2] = sm;
+          s_part[(wn * BM + r) * 2 + 1] = sq;
+        }
+      }
+      __syncthreads();
+      if (tid < BM) {
+        const float sm = s_part[tid * 2] + s_part[(BM + tid) * 2];
+        const float sq = s_part[tid * 2 + 1] + s_part[(BM + tid) * 2 + 1];
+        const float mean = sm / (float)p.K;
+        const float var = fmaxf(sq / (float)p.K - mean * mean, 0.f);
+        s_mr[tid * 2] = mean;
+        s_mr[tid * 2 + 1] = 1.0f / sqrtf(var + p.ln_eps);
+      }
+    }
+  }
+
+  if (p.vec_epi) {
+    __syncthreads();                          // operand stages no longer read by anyone
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lr_ = wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          tile[lr_ * PT + wn * (BN / 2) + tn * 32 + (lane & 31)] = acc[tm][tn][e];
+        }
+    __syncthreads();
+    const int per = kConv ? p.Ro * p.Wo : 1;
+    if (nsplit > 1) {
+      float* mine = partials + (size_t)split * p.M * p.N;
+      for (int idx = tid; idx < BM * (BN / 4); idx += 256) {
+        const int lr_ = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+        const int row = m0 + lr_, col = n0 + c4;
+        if (row < p.M && col < p.N)
+          *reinterpret_cast<f32x4*>(mine + (size_t)row * p.N + col) = *reinterpret_cast<const f32x4*>(tile + lr_ * PT + c4);
+      }
+      return;
+    }
+    if constexpr (!kConv && TN == 2 && sizeof(OutT) == 2) {
+      if (p.geglu) {
+        // tile columns [64q, 64q+32) are value columns, [64q+32, 64q+64) the gate columns of the same outputs
+        for (int idx = tid; idx < BM * (BN / 8); idx += 256) {
+          const int lr_ = idx / (BN / 8), o = (idx % (BN / 8)) * 4;
+          const int row = m0 + lr_, oc = (n0 >> 1) + o;
+          if (row >= p.M || oc >= p.geglu) continue;
+          const int tc = (o >> 5) * 64 + (o & 31);
+          f32x4 val = *reinterpret_cast<const f32x4*>(tile + lr_ * PT + tc);
+          f32x4 gte = *reinterpret_cast<const f32x4*>(tile + lr_ * PT + tc + 32);
+          if (ln_fold) {
+            const float mean = s_mr[lr_ * 2], rstd = s_mr[lr_ * 2 + 1];
+            val = (val - *reinterpret_cast<const f32x4*>(p.ln_s + oc) * mean) * rstd + *reinterpret_cast<const f32x4*>(p.ln_t + oc);
+            gte = (gte - *reinterpret_cast<const f32x4*>(p.ln_s + p.geglu + oc) * mean) * rstd +
+                  *reinterpret_cast<const f32x4*>(p.ln_t + p.geglu + oc);
+          } else if (p.bias) {
+            val += *reinterpret_cast<const f32x4*>(p.bias + oc);
+            gte += *reinterpret_cast<const f32x4*>(p.bias + p.geglu + oc);
+          }
+          float r4[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) r4[q] = val[q] * (0.5f * gte[q] * (1.0f + erff(gte[q] * 0.70710678118654752f)));
+          u32x2 t = {pack_bf2(r4[0], r4[1]), pack_bf2(r4[2], r4[3])};
+          *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(p.out) + (long long)row * p.ldo + oc) = t;
+        }
+        return;
+      }
+    }
+    for (int idx = tid; idx < BM * (BN / 4); idx += 256) {
+      const int lr_ = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+      const int row = m0 + lr_, col = n0 + c4;
+      if (row >= p.M || col >= p.N) continue;
+      f32x4 v = *reinterpret_cast<const f32x4*>(tile + lr_ * PT + c4);
+      if constexpr (kConv) {
+        if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + col);
+        if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.N + col);
+      } else {
+        if (ln_fold)
+          v = (v - *reinterpret_cast<const f32x4*>(p.ln_s + col) * s_mr[lr_ * 2]) * s_mr[lr_ * 2 + 1] +
+              *reinterpret_cast<const f32x4*>(p.ln_t + col);
+        else if (p.bias)
+          v += *reinterpret_cast<const f32x4*>(p.bias + col);
+      }
+      if (p.residual) v += *reinterpret_cast<const f32x4*>(p.residual + (long long)row * p.ldr + col);
+      if (p.act == 1) { v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w); }
+      OutT* obase = reinterpret_cast<OutT*>(p.out);
+      long long old = p.ldo, orow = row;
+      int ocol = col;
+      if (p.nseg > 0) {                       // a group of four columns never straddles a segment (seg_w % 64 == 0)
+        const int sg = col / p.seg_w;
+        obase = reinterpret_cast<OutT*>(p.seg_out[sg]);
+        old = p.seg_ld[sg];
+        ocol = col - sg * p.seg_w;
+        const int bi = row / p.seg_rows_in[sg];
+        orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (row - bi * p.seg_rows_in[sg]);
+      }
+      if constexpr (sizeof(OutT) == 4) {
+        *reinterpret_cast<f32x4*>(obase + orow * old + ocol) = v;
+      } else {
+        u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+        *reinterpret_cast<u32x2*>(obase + orow * old + ocol) = t;
+      }
+      if constexpr (!kConv) {
+        if (p.out2) {
+          u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+          *reinterpret_cast<u32x2*>(p.out2 + (long long)row * p.ldo2 + col) = t;
+        }
+      }
+    }
+    return;
+  }
+
+  // ---- scalar epilogue: shapes or pointers that do not allow the vector accesses above ----
+  __syncthreads();                            // the folded-norm statistics, if any, are visible
   if (nsplit > 1) {
     // float partial of this split, [split][M][N]; the epilogue runs in splitk_reduce_kernel
     float* mine = partials + (size_t)split * p.M * p.N;
@@ -406,15 +572,23 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       const int oc = (n0 >> 1) + wn * 32 + (lane & 31);
       if (oc < p.geglu) {
         const float bv = p.bias ? p.bias[oc] : 0.f, bg = p.bias ? p.bias[p.geglu + oc] : 0.f;
+        const float sv = ln_fold ? p.ln_s[oc] : 0.f, sg = ln_fold ? p.ln_s[p.geglu + oc] : 0.f;
+        const float tv = ln_fold ? p.ln_t[oc] : 0.f, tg = ln_fold ? p.ln_t[p.geglu + oc] : 0.f;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            const int lr_ = wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            const int row = m0 + lr_;
             if (row >= p.M) continue;
-            const float gte = acc[tm][1][e] + bg;
+            float val = acc[tm][0][e] + bv, gte = acc[tm][1][e] + bg;
+            if (ln_fold) {
+              const float mean = s_mr[lr_ * 2], rstd = s_mr[lr_ * 2 + 1];
+              val = rstd * (acc[tm][0][e] - mean * sv) + tv;
+              gte = rstd * (acc[tm][1][e] - mean * sg) + tg;
+            }
             const float gl = 0.5f * gte * (1.0f + erff(gte * 0.70710678118654752f));
-            Elem<OutT>::st(out + (long long)row * p.ldo + oc, (acc[tm][0][e] + bv) * gl);
+            Elem<OutT>::st(out + (long long)row * p.ldo + oc, val * gl);
           }
       }
       return;
@@ -425,6 +599,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     const int col = n0 + wn * (BN / 2) + tn * 32 + (lane & 31);
     if (col >= p.N) continue;
     const float bias = p.bias ? p.bias[col] : 0.f;
+    const float ln_sc = ln_fold ? p.ln_s[col] : 0.f, ln_tc = ln_fold ? p.ln_t[col] : 0.f;
     // segmented output: the 32 columns of a block never straddle a segment (seg_w % 32 == 0)
     OutT* obase = out;
     long long old = p.ldo, orow0 = 0, orows_out = 0;
@@ -439,11 +614,14 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int lr_ = wm * (BM / 2) + tm * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        const int row = m0 + lr_;
         if (row >= p.M) continue;
         float v = acc[tm][tn][e] + bias;
         if constexpr (kConv) {
           if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.N + col];
+        } else {
+          if (ln_fold) v = s_mr[lr_ * 2 + 1] * (acc[tm][tn][e] - s_mr[lr_ * 2] * ln_sc) + ln_tc;
         }
         if (p.residual) v += p.residual[(long long)row * p.ldr + col];
         if (p.act == 1) v = silu_f(v);
@@ -453,6 +631,9 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
           orow = (long long)bi * orows_out + orow0 + (row - bi * orows_in);
         }
         Elem<OutT>::st(obase + orow * old + ocol, v);
+        if constexpr (!kConv) {
+          if (p.out2) p.out2[(long long)row * p.ldo2 + col] = f2bf(v);
+        }
       }
     }
   }
@@ -562,6 +743,42 @@ __global__ __launch_bounds__(256) void conv3x3_wave(const T* __restrict__ x, con
   }
 }
 
+// ---- one-time weight re-layout for the pipelined kernel ----
+// out tile (n/64, k/64) is 64 rows x 64 k, row r = n % 64 holds global 16-byte chunk c at slot c ^ ((r >> 1) & 7)
+__global__ __launch_bounds__(256) void pack_weight_kernel(const bf16_t* __restrict__ w, const float* __restrict__ gamma,
+                                                          bf16_t* __restrict__ out, int N, int K) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int kch = K / 8;
+  if (idx >= (long long)N * kch) return;
+  const int n = (int)(idx / kch), c = (int)(idx % kch);
+  float v[8];
+  ld_vec(w + (long long)n * K + c * 8, v);
+  if (gamma) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= gamma[c * 8 + i];
+  }
+  const int r = n & 63, kt = c >> 3, slot = (c & 7) ^ ((r >> 1) & 7);
+  st_vec(out + (((long long)(n >> 6) * (K / 64) + kt) * 64 + r) * 64 + slot * 8, v);
+}
+
+// one wave per output row
+__global__ __launch_bounds__(256) void fold_vectors_kernel(const bf16_t* __restrict__ w, const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta, const float* __restrict__ bias,
+                                                           float* __restrict__ s, float* __restrict__ t, int N, int K) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  float a = 0.f, b = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float wv = bf2f(w[(long long)n * K + k]);
+    a += bf2f(f2bf(wv * gamma[k]));
+    b = fmaf(wv, beta[k], b);
+  }
+  a = wave_sum(a);
+  b = wave_sum(b);
+  if (lane == 0) { s[n] = a; t[n] = b + (bias ? bias[n] : 0.f); }
+}
+
 template <int BM, int BN, bool kConv>
 int launch_tile(const TileParams& p, int out_dtype, hipStream_t st) {
   dim3 grid(cdiv(p.N, BN), cdiv(p.M, BM));
@@ -596,6 +813,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(TileParams p, const 
     u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
     *reinterpret_cast<u32x2*>(o) = t;
   }
+  if (p.out2) {
+    u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+    *reinterpret_cast<u32x2*>(p.out2 + (long long)row * p.ldo2 + col) = t;
+  }
 }
 
 template <int BM, int BN, int STAGES, bool kConv>
@@ -604,7 +825,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
   const int KT = p.K / 64;
   if (nsplit > KT) nsplit = KT;
-  if (nsplit < 1 || p.N % 4 || p.ldr % 4 || p.ldo % 4) nsplit = 1;
+  if (nsplit < 1 || p.N % 4 || p.ldr % 4 || p.ldo % 4 || p.ldo2 % 4 || p.ln_s || p.geglu || p.nseg) nsplit = 1;
   if (nsplit > 1) nsplit = cdiv(KT, cdiv(KT, nsplit));   // no empty split
   const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * p.M * p.N * sizeof(float) : 0;
   char* scr = nullptr;
@@ -616,6 +837,16 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   float* partials = scr ? (float*)(scr + kScratchCounterBytes) : nullptr;
   constexpr int smem = STAGES * (BM + BN) * 128;
   dim3 grid((unsigned)nwg, (unsigned)nsplit);
+  TileParams q = p;
+  {
+    auto al = [](const void* ptr, int a) { return ((uintptr_t)ptr % a) == 0; };
+    bool ok = p.N % 4 == 0 && p.ldo % 4 == 0 && al(p.out, 16) && al(p.bias, 16) && al(p.chan_add, 16) &&
+              (!p.residual || (p.ldr % 4 == 0 && al(p.residual, 16))) && (!p.out2 || (p.ldo2 % 4 == 0 && al(p.out2, 8))) &&
+              al(p.ln_s, 16) && al(p.ln_t, 16) && (!p.geglu || p.geglu % 4 == 0);
+    for (int i = 0; i < p.nseg; ++i) ok = ok && p.seg_ld[i] % 4 == 0 && al(p.seg_out[i], 8) && p.seg_w % 4 == 0;
+    if (p.ln_s && BM * (BN + 4) * 4 + BM * 24 > smem) return DF_ESHAPE;   // no room for the row statistics
+    q.vec_epi = ok ? 1 : 0;
+  }
   if (out_dtype == DF_BF16) {
     auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, bf16_t>;
     static bool attr_set = false;
@@ -623,7 +854,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros, partials);
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, q, zeros, partials);
   } else {
     auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, float>;
     static bool attr_set = false;
@@ -631,7 +862,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, p, zeros, partials);
+    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, q, zeros, partials);
   }
   DF_LAUNCH_CHECK();
   if (nsplit > 1) {
@@ -646,27 +877,48 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   return DF_OK;
 }
 
-// Tile choice.  DF_TILE=<BM>x<BN>x<STAGES> in the environment overrides the heuristic (tuning aid).
-int tile_override() {
+// Tile choice.  DF_TILE=<BM>x<BN>x<STAGES> and DF_SPLITK=<n> in the environment override the heuristic (tuning
+// aid); with DF_TUNE set they are re-read on every launch.
+bool tune_mode() {
   static int v = -1;
-  if (v < 0) {
-    v = 0;
-    const char* e = getenv("DF_TILE");
-    if (e) {
-      int bm = 0, bn = 0, st = 4;
-      if (sscanf(e, "%dx%dx%d", &bm, &bn, &st) >= 2) v = (bm * 1000 + bn) * 10 + st;
-    }
-  }
+  if (v < 0) v = getenv("DF_TUNE") ? 1 : 0;
+  return v == 1;
+}
+
+int parse_tile() {
+  const char* e = getenv("DF_TILE");
+  int bm = 0, bn = 0, st = 4;
+  if (e && sscanf(e, "%dx%dx%d", &bm, &bn, &st) >= 2) return (bm * 1000 + bn) * 10 + st;
+  return 0;
+}
+
+int tile_override() {
+  if (tune_mode()) return parse_tile();
+  static int v = -1;
+  if (v < 0) v = parse_tile();
   return v;
 }
 
 int split_override() {
+  if (tune_mode()) { const char* e = getenv("DF_SPLITK"); return e ? atoi(e) : 0; }
   static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("DF_SPLITK");
-    v = e ? atoi(e) : 0;
-  }
+  if (v < 0) { const char* e = getenv("DF_SPLITK"); v = e ? atoi(e) : 0; }
   return v;
+}
+
+// Tile choice measured on the patch step (kernel trace, weights cold): fetch throughput of a compute unit grows with
+// the number of resident waves, so problems with many tiles take the 64x64 tile with two stages (32 KB of LDS, five
+// workgroups per unit) and problems with few tiles a four-stage ring; only very large problems use 128x128.  The
+// deepest reductions on few tiles (feed-forward output, K >= 4096) are split along K.
+template <bool kConv>
+int launch_auto(const TileParams& p, int out_dtype, hipStream_t st) {
+  const long long big = (long long)cdiv(p.M, 128) * cdiv(p.N, 128);
+  const long long nwg = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
+  int ns = (nwg <= 128 && p.K >= 4096) ? 4 : 1;
+  if (split_override() > 0) ns = split_override();
+  if (big >= 1024 && !p.ln_s) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
+  if (nwg * ns >= 512 && ns == 1) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, 1, st);
+  return launch_pipe<64, 64, 4, kConv>(p, out_dtype, ns, st);
 }
 
 template <bool kConv>
@@ -682,30 +934,35 @@ int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
       case 1280643: return launch_pipe<128, 64, 3, kConv>(p, out_dtype, so, st);
       case 640644: return launch_pipe<64, 64, 4, kConv>(p, out_dtype, so, st);
       case 640642: return launch_pipe<64, 64, 2, kConv>(p, out_dtype, so, st);
+      case 640643: return launch_pipe<64, 64, 3, kConv>(p, out_dtype, so, st);
+      case 640646: return launch_pipe<64, 64, 6, kConv>(p, out_dtype, so, st);
+      case 640648: return launch_pipe<64, 64, 8, kConv>(p, out_dtype, so, st);
+      case 641282: return launch_pipe<64, 128, 2, kConv>(p, out_dtype, so, st);
+      case 641284: return launch_pipe<64, 128, 4, kConv>(p, out_dtype, so, st);
       default: break;
     }
-    // Fetch throughput of a compute unit grows with the number of resident waves, so the default is the small
-    // 64x64 tile with two stages (32 KB of LDS: five workgroups per unit); problems with few tiles and a deep
-    // K are split along K until about a thousand workgroups exist.
-    const long long nwg = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
-    const int KT = p.K / 64;
-    int ns = 1;
-    if (nwg < 512 && KT >= 32) {             // the extra reduce launch only pays for a deep K
-      ns = (int)((1024 + nwg - 1) / nwg);
-      if (ns > 8) ns = 8;
-      if (ns > KT / 8) ns = KT / 8;          // keep at least eight k-tiles per split
-      if (ns < 1) ns = 1;
-    }
-    if (split_override() > 0) ns = split_override();
-    if (big >= 1024) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
-    if (nwg * ns >= 512) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, ns, st);
-    return launch_pipe<64, 64, 4, kConv>(p, out_dtype, ns, st);
+    return launch_auto<kConv>(p, out_dtype, st);
   }
   if (big >= 384) return launch_tile<128, 128, kConv>(p, out_dtype, st);
   return launch_tile<64, 64, kConv>(p, out_dtype, st);
 }
 
 }  // namespace
+
+int launch_pack_weight(const bf16_t* w, const float* gamma, bf16_t* out, int N, int K, hipStream_t st) {
+  if (N % 64 || K % 64 || N <= 0 || K <= 0) return DF_ESHAPE;
+  const long long n = (long long)N * (K / 8);
+  hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, gamma, out, N, K);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_fold_vectors(const bf16_t* w, const float* gamma, const float* beta, const float* bias, float* s, float* t,
+                        int N, int K, hipStream_t st) {
+  hipLaunchKernelGGL(fold_vectors_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, st, w, gamma, beta, bias, s, t, N, K);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
 
 // bytes of library scratch a tile launch may ask for (plans reserve it up front)
 size_t gemm_scratch_bytes(long long M, long long N) {
@@ -720,6 +977,15 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
   TileParams p = {};
   p.A = (const bf16_t*)a.A; p.Wt = (const bf16_t*)a.W; p.bias = a.bias; p.residual = a.residual; p.out = a.out;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldw = a.ldw; p.ldr = a.ldr; p.ldo = a.ldo; p.act = a.act;
+  const bool special = a.packed_w || a.ln_s || a.out2;
+  if (special) {
+    if (a.K % 64 || a.K < 128) return DF_ESHAPE;
+    if (a.packed_w && a.N % 64) return DF_ESHAPE;
+    if (a.ln_s && (!a.ln_t || a.bias)) return DF_EINVAL;
+    if (a.out2 && (a.geglu || a.nseg)) return DF_ESHAPE;
+    p.packed_w = a.packed_w; p.ln_s = a.ln_s; p.ln_t = a.ln_t; p.ln_eps = a.ln_eps;
+    p.out2 = (bf16_t*)a.out2; p.ldo2 = a.ldo2;
+  }
   if (a.geglu || a.nseg > 0) {
     if (a.K % 64 || a.K < 128 || a.out_dtype != DF_BF16 || a.residual || a.act) return DF_ESHAPE;
     if (a.geglu) {
@@ -734,8 +1000,10 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
       p.seg_out[i] = a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
     }
-    return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
+    if ((long long)cdiv(a.M, 64) * cdiv(a.N, 64) >= 512) return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
+    return launch_pipe<64, 64, 4, false>(p, DF_BF16, 1, st);
   }
+  if (special) return launch_auto<false>(p, a.out_dtype, st);   // these epilogues exist in the pipelined kernel only
   return pick_tile<false>(p, a.out_dtype, st);
 }
 

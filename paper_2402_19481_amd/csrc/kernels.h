@@ -74,8 +74,26 @@ struct GemmArgs {
   void* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  // W is in the tiled layout written by launch_pack_weight (requires N % 64 == 0, K % 64 == 0, K >= 128).
+  int packed_w;
+  // LayerNorm folded into the GEMM: A holds the un-normalised rows (bf16), W was packed with the norm scale
+  // multiplied in, ln_s[n] = sum_k W'[n,k], ln_t[n] = sum_k W[n,k] beta[k] + bias[n] (bias must then be null).
+  // The kernel derives each row's mean and rstd from the A tiles it streams and applies
+  // out = rstd * (acc - mean * ln_s[n]) + ln_t[n].  Requires the pipelined kernel (K % 64 == 0, K >= 128).
+  const float* ln_s;
+  const float* ln_t;
+  float ln_eps;
+  // optional second output: the same values rounded to bf16, [M, N] with row stride ldo2 (plain outputs only)
+  void* out2;
+  long long ldo2;
 };
 int launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
+// Weight re-layout for the pipelined kernel: 64x64 tiles [N/64][K/64][64][64] with the LDS swizzle baked in, optionally
+// scaled per input channel by gamma[K] before rounding.  N % 64 == 0, K % 64 == 0.
+int launch_pack_weight(const bf16_t* w, const float* gamma, bf16_t* out, int N, int K, hipStream_t st);
+// s[n] = sum_k bf16(w[n,k] * gamma[k]); t[n] = sum_k w[n,k] * beta[k] + bias[n] (bias may be null)
+int launch_fold_vectors(const bf16_t* w, const float* gamma, const float* beta, const float* bias, float* s, float* t,
+                        int N, int K, hipStream_t st);
 size_t gemm_scratch_bytes(long long M, long long N);  // also covers a convolution with M output pixels, N = Cout
 
 // ---- attn.hip ----

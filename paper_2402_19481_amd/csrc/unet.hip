@@ -20,6 +20,7 @@
 // Precision: matrix operands bf16, accumulation float; the residual stream
 // (block outputs, transformer hidden state) stays float so that rounding does
 // not accumulate over the 70 transformer blocks.
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <string>
@@ -167,6 +168,18 @@ struct StaleEntry {
   size_t off, bytes;
 };
 
+// A linear weight the plan keeps in the tiled layout of the pipelined GEMM, optionally with the preceding
+// LayerNorm folded in (scale multiplied into the weight, shift and bias collected in `t`, column sums in `s`).
+struct PackSpec {
+  std::string name;   // parameter name without ".w"
+  int N, K;
+  std::string norm;   // name of the folded norm ("" = none)
+  bool has_bias;
+  size_t w_off, s_off, t_off;   // byte offsets inside the packed region (s/t only with a folded norm)
+};
+
+inline bool fold_ok(int C) { return C % 64 == 0 && C >= 128; }
+
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 }  // namespace
@@ -211,9 +224,16 @@ struct Prof {
   ~Prof() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
 };
 
+struct PackedW {
+  const bf16_t* w = nullptr;
+  const float* s = nullptr;
+  const float* t = nullptr;
+};
+
 struct df_unet {
   df_unet_cfg cfg;
   Prof prof;
+  std::map<std::string, PackedW> packed;
   std::vector<BlockDesc> blocks;
   std::map<std::string, const void*> w;
   std::vector<StaleEntry> stale;
@@ -250,6 +270,7 @@ struct Exec {
   size_t scratch_need = 0;
   int err = DF_OK;
   Prof* prof = nullptr;
+  const std::map<std::string, PackedW>* packed = nullptr;
   const bf16_t* kv_packed[4] = {nullptr, nullptr, nullptr, nullptr};
   int kv_count[4] = {0, 0, 0, 0};
   int kv_cursor[4] = {0, 0, 0, 0};
@@ -304,6 +325,27 @@ struct Exec {
     const void* W = weight(wn + ".w");
     const float* bp = bias ? (const float*)weight(wn + ".b") : nullptr;
     gemm_w(A, lda, W, bp, residual, ldr, out, ldo, M, Nn, K, out_dtype, extra);
+  }
+  // GEMM on a plan-packed weight; `ln` applies the folded LayerNorm of that weight (A then holds raw rows)
+  void gemm_packed(const void* A, long long lda, const std::string& wn, bool bias, bool ln, const float* residual,
+                   long long ldr, void* out, long long ldo, int M, int Nn, int K, int out_dtype, void* out2,
+                   const GemmArgs* extra = nullptr) {
+    GemmArgs g = {};
+    if (extra) g = *extra;
+    const float* bp = nullptr;
+    const void* W = nullptr;
+    if (!dry) {
+      auto it = packed->find(wn);
+      if (it == packed->end()) { err = DF_EINVAL; return; }
+      W = it->second.w;
+      g.packed_w = 1;
+      if (ln) { g.ln_s = it->second.s; g.ln_t = it->second.t; g.ln_eps = 1e-5f; }
+      else if (bias) bp = (const float*)weight(wn + ".b");
+      static const bool no_pack = getenv("DF_NO_PACK") != nullptr;   // tuning aid: canonical layout where no norm is folded
+      if (no_pack && !ln) { W = weight(wn + ".w"); g.packed_w = 0; }
+    }
+    g.out2 = out2; g.ldo2 = Nn;
+    gemm_w(A, lda, W, bp, residual, ldr, out, ldo, M, Nn, K, out_dtype, &g);
   }
   void gemm_w(const void* A, long long lda, const void* W, const float* bp, const float* residual, long long ldr,
               void* out, long long ldo, int M, int Nn, int K, int out_dtype, const GemmArgs* extra = nullptr) {
@@ -414,6 +456,87 @@ struct Exec {
     top = mark;
   }
 
+
+  // Transformer with every LayerNorm folded into the GEMM that consumes it: the residual GEMMs also emit a bf16 copy
+  // of the hidden state, which is the A operand of the next projection; no LayerNorm, cast or GEGLU kernel is launched.
+  void transformer_folded(const BlockDesc& b, const float* x, float* out, bf16_t* nb, float* h, bf16_t* qkv, bf16_t* ao,
+                          bf16_t* fg, int R, int W) {
+    const int C = b.cin;
+    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int M = B() * Lq, TL = c.text_len;
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    bf16_t* hb = (bf16_t*)alloc((size_t)M * C * 2);      // bf16 copy of the hidden state
+    gemm_packed(nb, C, b.name + ".pin", true, false, nullptr, 0, h, C, M, C, C, DF_F32, hb);
+    for (int d = 0; d < b.depth; ++d) {
+      const std::string p = b.name + ".b" + std::to_string(d);
+      bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
+      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
+      const bool fused_kv = full() || refresh;
+      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      if (fused_kv) {
+        GemmArgs ex = {};
+        ex.nseg = 3; ex.seg_w = C;
+        ex.seg_out[0] = qkv; ex.seg_ld[0] = C; ex.seg_rows_in[0] = 0x7fffffff; ex.seg_rows_out[0] = 0; ex.seg_row0[0] = 0;
+        ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
+        ex.seg_out[2] = vs; ex.seg_ld[2] = C; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = L; ex.seg_row0[2] = (long long)row0;
+        gemm_packed(hb, C, p + ".attn1.qkv", false, true, nullptr, 0, qkv, C, M, 3 * C, C, DF_BF16, nullptr, &ex);
+      } else {
+        gemm_packed(hb, C, p + ".attn1.qkv", false, true, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16, nullptr);
+      }
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.k_stale = ks; a.v_stale = vs; a.out = ao; a.q = qkv;
+        a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
+        a.ldks = a.ldvs = C; a.ldo = C;
+        a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
+        if (fused_kv) {
+          a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
+          a.ldq = C; a.ldkf = a.ldvf = C; a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
+        } else {
+          a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C;
+          a.own_lo = patch * Lq; a.own_n = Lq;
+          a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
+        }
+        a.scale = scale; a.dtype = DF_BF16;
+        timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
+              [&] { return launch_attention(a, st); });
+      }
+      gemm_packed(ao, C, p + ".attn1.o", true, false, h, C, h, C, M, C, C, DF_F32, hb);
+      // cross-attention to the text tokens
+      gemm_packed(hb, C, p + ".attn2.q", false, true, nullptr, 0, qkv, C, M, C, C, DF_BF16, nullptr);
+      const long long kvld = (long long)kv_count[b.level] * 2 * C;
+      const bf16_t* kv2 = kv2_all[b.level] + (size_t)kv_cursor[b.level] * 2 * C;
+      kv_cursor[b.level] += 1;
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = ao;
+        a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
+        a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
+        a.scale = scale; a.dtype = DF_BF16;
+        timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
+              [&] { return launch_attention(a, st); });
+      }
+      gemm_packed(ao, C, p + ".attn2.o", true, false, h, C, h, C, M, C, C, DF_F32, hb);
+      // GEGLU feed-forward
+      {
+        GemmArgs ex = {};
+        ex.geglu = 1;
+        gemm_packed(hb, C, p + ".ff1", false, true, nullptr, 0, fg, 4 * C, M, 8 * C, C, DF_BF16, nullptr, &ex);
+      }
+      gemm_packed(fg, 4 * C, p + ".ff2", true, false, h, C, h, C, M, C, 4 * C, DF_F32, hb);
+    }
+    gemm_packed(hb, C, b.name + ".pout", true, false, x, C, out, C, M, C, C, DF_F32, nullptr);
+  }
+
   void transformer(const BlockDesc& b, const float* x, const bf16_t* text, float* out) {
     const int R = rows(b.level), W = width(b.level), C = b.cin;
     const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
@@ -428,6 +551,11 @@ struct Exec {
     bf16_t* fg = (bf16_t*)alloc((size_t)M * 4 * C * 2);
     const float scale = 1.0f / sqrtf((float)c.head_dim);
     groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nb);
+    if (fold_ok(C)) {
+      transformer_folded(b, x, out, nb, h, qkv, ao, fg, R, W);
+      top = mark;
+      return;
+    }
     gemm(nb, C, b.name + ".pin", true, nullptr, 0, h, C, M, C, C, DF_F32);
     for (int d = 0; d < b.depth; ++d) {
       const std::string p = b.name + ".b" + std::to_string(d);
@@ -543,8 +671,10 @@ struct Exec {
       if (kv_count[lv] == 0) continue;
       const int Nkv = kv_count[lv] * 2 * c.levels[lv];
       kv2_all[lv] = (bf16_t*)alloc((size_t)B() * c.text_len * Nkv * 2);
+      GemmArgs ex = {};
+      ex.packed_w = (c.text_dim % 64 == 0 && c.text_dim >= 128) ? 1 : 0;
       gemm_w(text, c.text_dim, kv_packed[lv], nullptr, nullptr, 0, kv2_all[lv], Nkv, B() * c.text_len, Nkv, c.text_dim,
-             DF_BF16);
+             DF_BF16, &ex);
     }
     for (const BlockDesc& b : blocks) {
       if (err != DF_OK) break;
@@ -624,6 +754,38 @@ struct Exec {
   }
 };
 
+std::vector<PackSpec> build_pack_specs(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks, size_t base,
+                                       size_t* end) {
+  std::vector<PackSpec> v;
+  size_t off = base;
+  auto add = [&](const std::string& name, int N, int K, const std::string& norm, bool has_bias) {
+    PackSpec sp{name, N, K, norm, has_bias, 0, 0, 0};
+    sp.w_off = off; off += align256((size_t)N * K * sizeof(bf16_t));
+    if (!norm.empty()) {
+      sp.s_off = off; off += align256((size_t)N * sizeof(float));
+      sp.t_off = off; off += align256((size_t)N * sizeof(float));
+    }
+    v.push_back(sp);
+  };
+  for (const BlockDesc& b : blocks) {
+    if (b.kind != BlockDesc::XF || !fold_ok(b.cin)) continue;
+    const int C = b.cin;
+    add(b.name + ".pin", C, C, "", true);
+    for (int d = 0; d < b.depth; ++d) {
+      const std::string p = b.name + ".b" + std::to_string(d);
+      add(p + ".attn1.qkv", 3 * C, C, p + ".ln1", false);
+      add(p + ".attn1.o", C, C, "", true);
+      add(p + ".attn2.q", C, C, p + ".ln2", false);
+      add(p + ".attn2.o", C, C, "", true);
+      add(p + ".ff1", 8 * C, C, p + ".ln3", true);
+      add(p + ".ff2", C, 4 * C, "", true);
+    }
+    add(b.name + ".pout", C, C, "", true);
+  }
+  *end = off;
+  return v;
+}
+
 struct DryResult {
   size_t ws_bytes, stale_bytes, scratch, packed_bytes;
   size_t kv_off[4];
@@ -654,8 +816,10 @@ DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
     r.kv_off[lv] = off;
     off += align256((size_t)r.kv_count[lv] * 2 * c.levels[lv] * c.text_dim * sizeof(bf16_t));
   }
-  r.packed_bytes = off;
-  r.ws_bytes += off + 256;
+  size_t end = off;
+  build_pack_specs(c, blocks, off, &end);
+  r.packed_bytes = end;
+  r.ws_bytes += end + 256;
   return r;
 }
 
@@ -726,6 +890,43 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
         cursor[b.level] += 1;
       }
     }
+    const bool pack_kv = cfg->text_dim % 64 == 0 && cfg->text_dim >= 128;
+    if (pack_kv) {
+      // re-tile the concatenated text K/V weights in place of the plain copies made above: pack each block's
+      // weight from its original tensor (its rows are whole 64-row tiles of the concatenation)
+      int cur2[4] = {0, 0, 0, 0};
+      for (const BlockDesc& b : u->blocks) {
+        if (b.kind != BlockDesc::XF) continue;
+        const size_t one = (size_t)2 * b.cin * cfg->text_dim;
+        for (int dd = 0; dd < b.depth; ++dd) {
+          const bf16_t* src = (const bf16_t*)u->w[b.name + ".b" + std::to_string(dd) + ".attn2.kv.w"];
+          bf16_t* dst = (bf16_t*)(u->ws + u->kv_off[b.level]) + (size_t)cur2[b.level] * one;
+          if (launch_pack_weight(src, nullptr, dst, 2 * b.cin, cfg->text_dim, 0) != DF_OK) { delete u; return DF_EHIP; }
+          cur2[b.level] += 1;
+        }
+      }
+    }
+    size_t end = 0;
+    size_t base = 0;
+    for (int lv = 0; lv < cfg->n_levels; ++lv)
+      base = u->kv_off[lv] + align256((size_t)u->kv_count[lv] * 2 * cfg->levels[lv] * cfg->text_dim * sizeof(bf16_t));
+    for (const PackSpec& sp : build_pack_specs(u->cfg, u->blocks, base, &end)) {
+      PackedW pw;
+      bf16_t* dst = (bf16_t*)(u->ws + sp.w_off);
+      const bf16_t* src = (const bf16_t*)u->w[sp.name + ".w"];
+      const float* gamma = sp.norm.empty() ? nullptr : (const float*)u->w[sp.norm + ".g"];
+      if (launch_pack_weight(src, gamma, dst, sp.N, sp.K, 0) != DF_OK) { delete u; return DF_EHIP; }
+      pw.w = dst;
+      if (!sp.norm.empty()) {
+        float* sv = (float*)(u->ws + sp.s_off);
+        float* tv = (float*)(u->ws + sp.t_off);
+        const float* beta = (const float*)u->w[sp.norm + ".beta"];
+        const float* bias = sp.has_bias ? (const float*)u->w[sp.name + ".b"] : nullptr;
+        if (launch_fold_vectors(src, gamma, beta, bias, sv, tv, sp.N, sp.K, 0) != DF_OK) { delete u; return DF_EHIP; }
+        pw.s = sv; pw.t = tv;
+      }
+      u->packed[sp.name] = pw;
+    }
     if (hipDeviceSynchronize() != hipSuccess) { delete u; return DF_EHIP; }
   }
   // reserve the library scratch now, so that no step ever has to grow it
@@ -767,6 +968,7 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
     e.kv_count[lv] = u->kv_count[lv];
     e.kv_packed[lv] = (const bf16_t*)(u->ws + u->kv_off[lv]);
   }
+  e.packed = &u->packed;
   e.stale_base = (char*)stale;
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;

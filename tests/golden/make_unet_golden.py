@@ -24,7 +24,48 @@ from oracle import unet as ounet  # noqa: E402
 
 RECIPES = {
     "cfg4": dict(H=160, W=240, N=8, patch=3, seed=4, arch="SDXL"),
+    # multi-step loop of configuration 5 at a latent size the oracle finishes in minutes: SDXL architecture,
+    # 64x64 latent, N=4 (16 latent rows per patch), patch 1, 6 Euler steps (1 FULL + 5 DISPLACED with refresh)
+    "loop": dict(H=64, W=64, N=4, patch=1, seed=5, arch="SDXL", steps=6),
 }
+
+# sigma ladder of the multi-step loop: geometric from 14.6 to 0.03 (the range of SDXL's Euler schedule)
+def sigma_ladder(steps):
+    return [14.6 * (0.03 / 14.6) ** (k / steps) for k in range(steps + 1)]
+
+
+def main_loop(which):
+    """Euler loop (Section 3, Eq. 1): x <- x + (sigma_{k+1} - sigma_k) * eps on the patch's latent rows; step 0
+    computes the full image and fills the stale state, later steps compute the patch only and refresh its rows."""
+    r = RECIPES[which]
+    cfg = ut.UNetCfg(H=r["H"], W=r["W"], N=r["N"], **getattr(ut, r["arch"]))
+    weights = configs.unet_weights(cfg, seed=r["seed"], threads=8)
+    t = configs.unet_inputs(cfg, seed=r["seed"])
+    bl = ut.blocks(cfg)
+    P = ounet.Params(weights)
+    sig = sigma_ladder(r["steps"])
+    R = cfg.H // cfg.N
+    i = r["patch"]
+    stale = {}
+    x_full = t["x_prev"].astype(np.float64) * sig[0]                      # noisy latent at sigma_0
+    t0 = time.time()
+    eps = ounet.unet_step(cfg, bl, P, x_full / np.sqrt(sig[0] ** 2 + 1), t["emb"], t["text"], stale, mode=ounet.FULL)
+    print("step 0 FULL", round(time.time() - t0, 1), "s", flush=True)
+    x = ounet.euler_update(x_full, eps, sig[0], sig[1])[:, i * R:(i + 1) * R]
+    eps_list = [eps[:, i * R:(i + 1) * R]]
+    x_list = [x]
+    for k in range(1, r["steps"]):
+        t0 = time.time()
+        e = ounet.unet_step(cfg, bl, P, x / np.sqrt(sig[k] ** 2 + 1), t["emb"], t["text"], stale, i, ounet.DISPLACED)
+        x = ounet.euler_update(x, e, sig[k], sig[k + 1])
+        eps_list.append(e)
+        x_list.append(x)
+        print("step", k, "DISPLACED", round(time.time() - t0, 1), "s", flush=True)
+    out = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"unet_{which}_eps.npz")
+    np.savez_compressed(out, eps=np.stack(eps_list).astype(np.float32), x=np.stack(x_list).astype(np.float32),
+                        sigmas=np.array(sig), H=r["H"], W=r["W"], N=r["N"], patch=i, seed=r["seed"], steps=r["steps"])
+    print("wrote", out, os.path.getsize(out), "bytes")
+
 
 
 def main(which):
@@ -52,4 +93,5 @@ def main(which):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1] if len(sys.argv) > 1 else "cfg4")
+    which = sys.argv[1] if len(sys.argv) > 1 else "cfg4"
+    (main_loop if "steps" in RECIPES[which] else main)(which)

@@ -134,3 +134,39 @@ def test_config4_full_size_against_golden():
     d = rel_l2(gold["eps_disp"], gold["eps_full"][:, patch * R:(patch + 1) * R])
     say("  oracle: displaced vs previous step's rows", d)
     net.close()
+
+
+def test_multi_step_euler_loop_against_golden():
+    """Configuration 5's loop at a latent size the oracle finishes in minutes (SDXL architecture, 64x64 latent,
+    N=4, patch 1): step 0 FULL on the whole image, then DISPLACED + refresh steps with the Euler update on the
+    patch's rows.  Reports the drift of eps from the oracle per step."""
+    import math
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "unet_loop_eps.npz")
+    if not os.path.exists(path):
+        pytest.skip("golden file of the loop not generated (tests/golden/make_unet_golden.py loop)")
+    gold = np.load(path)
+    H, W, N, patch, seed, steps = (int(gold[k]) for k in ("H", "W", "N", "patch", "seed", "steps"))
+    sig = [float(v) for v in gold["sigmas"]]
+    cfg = ut.UNetCfg(H=H, W=W, N=N, **ut.SDXL)
+    weights = configs.unet_weights(cfg, seed=seed, threads=16)
+    t = configs.unet_inputs(cfg, seed=seed)
+    wd = _upload(weights)
+    del weights
+    net = df.PatchUNet(cfg, wd, B=1, device=DEV)
+    emb_d, text_d = dev(t["emb"]), dev(t["text"], True)
+    R = H // N
+    x_full = dev(t["x_prev"].astype(np.float64) * sig[0])
+    eps = net.step((x_full / math.sqrt(sig[0] ** 2 + 1)).contiguous(), emb_d, text_d, mode=df.MODE_FULL)
+    df.euler_update(x_full, eps, sig[0], sig[1])
+    x = x_full[:, patch * R:(patch + 1) * R].contiguous()
+    drift = [rel_l2(host(eps)[:, patch * R:(patch + 1) * R], gold["eps"][0])]
+    for k in range(1, steps):
+        e = net.step((x / math.sqrt(sig[k] ** 2 + 1)).contiguous(), emb_d, text_d, patch_idx=patch,
+                     mode=df.MODE_DISPLACED, refresh=True)
+        df.euler_update(x, e, sig[k], sig[k + 1])
+        drift.append(rel_l2(host(e), gold["eps"][k]))
+        assert rel_l2(host(x), gold["x"][k]) < TOL_BF16
+    say("  loop drift of eps per step (rel_l2):", ["%.4f" % d for d in drift])
+    assert max(drift) < TOL_BF16
+    net.close()
