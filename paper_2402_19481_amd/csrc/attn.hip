@@ -16,6 +16,9 @@
 //
 // f32 kernel: one wave per query, lanes stride over keys; for the small
 // full-precision configuration only.
+#include <cstdlib>
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace df {
@@ -84,32 +87,37 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
 
   // cooperative tile loads: K: lane -> (key = tid/8 (+32), chunk = tid%8); V: keys 2*kap, 2*kap+1, chunk = tid%8
   const int ld_key = tid >> 3, ld_ch = tid & 7;
-  u32x4 kreg[2], vreg[2];
+  // The K/V rows come from HBM or the Infinity Cache with microseconds of latency and a tile's compute is a fraction
+  // of that, so three tiles of loads are kept in flight in a register ring (slot = tile % 3, loop unrolled by 3).
+  constexpr int PF = 3;
+  u32x4 kreg[PF][2], vreg[PF][2];
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  auto load_tile = [&](int t) {
+  auto load_tile = [&](int t, auto slot) {
+    constexpr int S = decltype(slot)::value;
     const int base = kv_lo + t * TK;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int jk = base + ld_key + 32 * i;
-      kreg[i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, jk) + ld_ch * 8)
-                           : zero4;
+      kreg[S][i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, jk) + ld_ch * 8)
+                              : zero4;
       const int jv = base + 2 * ld_key + i;
-      vreg[i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, jv) + ld_ch * 8)
-                           : zero4;
+      vreg[S][i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, jv) + ld_ch * 8)
+                              : zero4;
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf, auto slot) {
+    constexpr int S = decltype(slot)::value;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = ld_key + 32 * i;
       const int f = (row & 3) | (((row >> 3) & 1) << 2);
-      *reinterpret_cast<u32x4*>(&Ks[buf][row * D + ((ld_ch ^ f) * 8)]) = kreg[i];
+      *reinterpret_cast<u32x4*>(&Ks[buf][row * D + ((ld_ch ^ f) * 8)]) = kreg[S][i];
     }
     // V transposed: dword (keys 2*kap, 2*kap+1) of row d goes to chunk (kap/4) ^ (d%8) ^ (d/8), dword kap%4
     const int kap = ld_key;
     unsigned int* vt = reinterpret_cast<unsigned int*>(&Vt[buf][0]);
-    const unsigned int a[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
-    const unsigned int bq[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
+    const unsigned int a[4] = {vreg[S][0].x, vreg[S][0].y, vreg[S][0].z, vreg[S][0].w};
+    const unsigned int bq[4] = {vreg[S][1].x, vreg[S][1].y, vreg[S][1].z, vreg[S][1].w};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int d = ld_ch * 8 + e;
@@ -128,15 +136,20 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale * kLog2e;
 
-  if (ntiles > 0) {
-    load_tile(0);
-    store_tile(0);
-  }
-  __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  if (ntiles > 0) load_tile(0, I0{});
+  if (ntiles > 1) load_tile(1, I1{});
+  if (ntiles > 2) load_tile(2, I2{});
+  // one tile: ring slot -> LDS buffer t&1, barrier, refill the slot with tile t+3, compute from LDS.  A buffer is
+  // rewritten two tiles later, after the barrier of the tile in between, which every wave reaches only after it has
+  // finished reading it.
+  auto do_tile = [&](int t, auto slot) {
     const int buf = t & 1;
-    if (t + 1 < ntiles) load_tile(t + 1);
-
+    store_tile(buf, slot);
+    __syncthreads();
+    if (t + PF < ntiles) load_tile(t + PF, slot);
     // ---- S^T = K Q^T for two 32-key blocks ----
     f32x16 s_acc[2];
 #pragma unroll
@@ -154,26 +167,29 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
     // accumulator e = 4*j + r of block kb is key  base + 32*kb + 16*(j/2) + 8*g + 4*(j%2) + r  for query c
     const int tile_base = kv_lo + t * TK;
     float mx = -INFINITY;
+    if (tile_base + TK > kv_hi) {   // ragged last tile: keys beyond the range get no weight
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = e >> 2, r = e & 3;
+          const int key = tile_base + 32 * kb + 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
+          if (key >= kv_hi) s_acc[kb][e] = -INFINITY;
+        }
+    }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int j = e >> 2, r = e & 3;
-        const int key = tile_base + 32 * kb + 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
-        float v = s_acc[kb][e] * sc;
-        if (key >= kv_hi) v = -INFINITY;
-        s_acc[kb][e] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_acc[kb][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;    // scale > 0, so the maximum commutes with the scaling
     const float m_new = fmaxf(m_run, mx);           // finite: every tile holds at least one valid key
-    const float alpha = exp2f(m_run - m_new);       // exp2(-inf) = 0 on the first tile
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // exp2(-inf) = 0 on the first tile
     float rs = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float pv = exp2f(s_acc[kb][e] - m_new);
+        const float pv = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][e], sc, -m_new));   // raw v_exp_f32: arguments are <= 0
         s_acc[kb][e] = pv;
         rs += pv;
       }
@@ -204,8 +220,11 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
         o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pfrag, o_acc[db], 0, 0, 0);
       }
     }
-    if (t + 1 < ntiles) store_tile(buf ^ 1);
-    __syncthreads();
+  };
+  for (int t = 0; t < ntiles; t += PF) {
+    do_tile(t, I0{});
+    if (t + 1 < ntiles) do_tile(t + 1, I1{});
+    if (t + 2 < ntiles) do_tile(t + 2, I2{});
   }
 
   // ---- write: lane (g, c) holds O[q0 + c][32*db + 8*j + 4*g + r] ----
@@ -315,6 +334,8 @@ __global__ __launch_bounds__(256) void attn_f32(AttnParams p) {
 }
 
 int pick_splits(int B, int Lq, int L, int heads) {
+  static const int forced = getenv("DF_ATTN_SPLITS") ? atoi(getenv("DF_ATTN_SPLITS")) : 0;   // tuning aid
+  if (forced > 0) return (L / forced >= 64) ? forced : 1;
   const long long blocks = (long long)cdiv(Lq, 128) * heads * B;
   int ns = 1;
   // aim at >= 512 workgroups (two per compute unit) while keeping >= 4 key tiles per split
