@@ -177,6 +177,14 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
                        void* eps_out, int patch_idx, int mode, int refresh, void* stream);
 
 /*
+ * df_patch_unet_step records the launches of a step into a HIP graph the second time it sees the same call (mode,
+ * patch, refresh, stream and all pointers equal) and replays the graph from then on (Section 5.1 uses CUDAGraph for
+ * the same purpose).  Calls on the legacy default stream (stream == 0) and calls made while per-launch timing is on
+ * always launch eagerly.  df_unet_set_graph(u, 0) switches the graph path off.
+ */
+int df_unet_set_graph(df_unet* u, int on);
+
+/*
  * Optional per-launch timing of df_patch_unet_step (measurement support; Section 5.1 times whole runs, this
  * splits a step by kernel class).  While enabled, every kernel launch of a step is bracketed by two events on
  * the step's stream, which slows the step down; totals accumulate per class until reset.

@@ -69,6 +69,7 @@ def lib():
     L.df_unet_stale_name.argtypes = [vp, i, ctypes.c_char_p, i]
     L.df_patch_unet_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     L.df_unet_profile_enable.argtypes = [vp, i]
+    L.df_unet_set_graph.argtypes = [vp, i]
     L.df_unet_profile_reset.argtypes = [vp]
     L.df_unet_profile_num_classes.argtypes = []
     L.df_unet_profile_class_name.argtypes = [i]
@@ -78,7 +79,7 @@ def lib():
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
                  "df_euler_update", "df_linear", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
-                 "df_unet_profile_enable", "df_unet_profile_reset", "df_unet_profile_num_classes",
+                 "df_unet_profile_enable", "df_unet_set_graph", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
         getattr(L, name).restype = i
     _lib = L
@@ -234,6 +235,10 @@ class PatchUNet:
         _check(lib().df_patch_unet_step(self.handle, _ptr(x), _ptr(emb), _ptr(text), self.stale.data_ptr(), _ptr(out),
                                         patch_idx, mode, int(refresh), _stream()))
         return out
+
+    def set_graph(self, on):
+        """Switches HIP-graph replay of repeated steps on (default) or off."""
+        _check(lib().df_unet_set_graph(self.handle, int(on)))
 
     def profile(self, on):
         """Switches per-launch event timing of the steps on or off (resets the totals)."""

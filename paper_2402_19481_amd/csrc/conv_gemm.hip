@@ -232,18 +232,26 @@ __device__ __forceinline__ void wait_vm_and_lds() {
 
 // Split-K (gridDim.y > 1): every split accumulates a contiguous range of k-tiles and stores its float
 // partial; splitk_reduce_kernel adds the partials in split order and runs the epilogue.
-template <int BM, int BN, int STAGES, bool kConv, typename OutT>
-__global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16_t* __restrict__ zeros,
-                                                        float* __restrict__ partials) {
+// KS = 64-wide k-slabs per ring stage: with two, the barrier and the first LDS round trip of an iteration are paid
+// once per 128 of K, which is what bounds the short K loops of the patch-sized GEMMs.
+// NW = waves per workgroup (4 or 8).  The first four compute; with eight, the other four only issue their share of the
+// direct loads: measured fetch throughput of a compute unit is bounded per wave, so problems that put a single
+// workgroup on a unit (the ~100-tile GEMMs of the patch step) stream their operands twice as fast with twice the waves.
+template <int BM, int BN, int STAGES, bool kConv, typename OutT, int KS, int NW>
+__global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const bf16_t* __restrict__ zeros,
+                                                            float* __restrict__ partials) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  constexpr int AJ = BM / 32, BJ = BN / 32;       // direct-load instructions per wave per k-tile
-  constexpr int L = AJ + BJ;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, SLAB = A_BYTES + B_BYTES, STAGE = SLAB * KS;
+  constexpr int NTHR = 64 * NW;
+  constexpr int AJ = BM / (8 * NW), BJ = BN / (8 * NW);   // direct-load instructions per wave per k-slab
+  static_assert(AJ >= 1 && BJ >= 1, "every wave issues at least one load per operand");
+  constexpr int L = (AJ + BJ) * KS;
   static_assert((STAGES - 2) * L < 64, "vmcnt field is 6 bits");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = (wave >> 1) & 1, wn = wave & 1;
+  const bool computes = wave < 4;
   // workgroups round-robin over the 8 XCDs; give each XCD a contiguous run of tiles, M-tile fastest, so that the
   // workgroups sharing a weight tile sit behind the same L2
   const int MT = (p.M + BM - 1) / BM, NT = (p.N + BN - 1) / BN;
@@ -258,7 +266,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   }
   const int m0 = (t % MT) * BM, n0 = (t / MT) * BN;
   const int nsplit = gridDim.y, split = blockIdx.y;
-  const int KT_all = p.K / 64;
+  const int KT_all = p.K / (64 * KS);
   const int kt_per = (KT_all + nsplit - 1) / nsplit;
   const int kt_lo = split * kt_per;
   const int KT = (kt_lo + kt_per <= KT_all ? kt_per : KT_all - kt_lo);   // >= 1 by construction of nsplit
@@ -266,14 +274,16 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
   const int lr = lane >> 3;                 // row within the 8-row group a wave instruction covers
   // LDS row r keeps global chunk c at slot c ^ ((r >> 1) & 7): with 64 banks a 16-byte read is served 16 lanes at a
   // time, i.e. 16 consecutive rows, which this spreads over all banks (rows r and r+1 differ by 128 B = 32 banks)
-  // tile row of instruction j is 16*a + 8*j + lr, so its key is (lr >> 1) | ((j & 1) << 2)
-  auto kc_of = [&](int j) { return (lane & 7) ^ ((lr >> 1) | ((j & 1) << 2)); };
+  // swizzle key of a tile row r is (r >> 1) & 7; BM / NW and BN / NW are multiples of 8, so the key is the same for
+  // the A and B rows of instruction j when BM == BN, and is computed per operand otherwise
+  auto kc_a = [&](int j) { return (lane & 7) ^ (((wave * (BM / NW) + j * 8 + lr) >> 1) & 7); };
+  auto kc_b = [&](int j) { return (lane & 7) ^ (((wave * (BN / NW) + j * 8 + lr) >> 1) & 7); };
   const bf16_t* a_ptr[AJ];
   int a_b[AJ], a_ro[AJ], a_co[AJ];
   bool a_ok[AJ];
 #pragma unroll
   for (int j = 0; j < AJ; ++j) {
-    const int row = wave * (BM / 4) + j * 8 + lr;
+    const int row = wave * (BM / NW) + j * 8 + lr;
     int m = m0 + row;
     a_ok[j] = m < p.M;
     if (m >= p.M) m = p.M - 1;
@@ -285,14 +295,14 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       a_co[j] = rem - a_ro[j] * p.Wo;
       a_ptr[j] = nullptr;
     } else {
-      a_ptr[j] = p.A + (long long)m * p.lda + kc_of(j) * 8;
+      a_ptr[j] = p.A + (long long)m * p.lda + kc_a(j) * 8;
       a_b[j] = a_ro[j] = a_co[j] = 0;
     }
   }
   const bf16_t* b_ptr[BJ];
 #pragma unroll
   for (int j = 0; j < BJ; ++j) {
-    const int tr = wave * (BN / 4) + j * 8 + lr;      // tile row of the weight operand
+    const int tr = wave * (BN / NW) + j * 8 + lr;     // tile row of the weight operand
     int n = n0 + tr;
     if (p.geglu) {
       // tile columns come in (value, gate) pairs of 32: columns [64q, 64q+32) are value rows, [64q+32, 64q+64) the
@@ -302,46 +312,49 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     }
     if (n >= p.N) n = p.N - 1;
     if (p.packed_w)   // tile (n/64, kt) is 8 KB contiguous, rows and swizzled 16-byte slots exactly as they sit in LDS
-      b_ptr[j] = p.Wt + ((long long)(n >> 6) * KT_all * 64 + (n & 63)) * 64 + (lane & 7) * 8;
+      b_ptr[j] = p.Wt + ((long long)(n >> 6) * (p.K / 64) * 64 + (n & 63)) * 64 + (lane & 7) * 8;
     else
-      b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_of(j) * 8;
+      b_ptr[j] = p.Wt + (long long)n * p.ldw + kc_b(j) * 8;
   }
   const int b_kstep = p.packed_w ? 4096 : 64;   // elements between consecutive k-tiles of the weight operand
 
   auto issue = [&](int kt, int stage) {
     if (kt > KT - 1) kt = KT - 1;           // past the end: reload the last tile into a free stage (keeps vmcnt uniform)
-    const int k0 = (kt_lo + kt) * 64;
-    char* sa = smem + stage * STAGE + (wave * (BM / 4)) * 128;
-    char* sb = smem + stage * STAGE + A_BYTES + (wave * (BN / 4)) * 128;
-    if constexpr (kConv) {
-      const int tap = k0 / p.Cin;
-      const int cin0 = k0 - tap * p.Cin;
-      const int ky = tap / 3, kx = tap - ky * 3;
 #pragma unroll
-      for (int j = 0; j < AJ; ++j) {
-        const int ri = a_ro[j] * p.stride + ky - 1;
-        const int ci = a_co[j] * p.stride + kx - 1;
-        const bf16_t* src = zeros;
-        if (a_ok[j] && ci >= 0 && ci < p.W) {
-          if (ri < 0) {
-            if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
-          } else if (ri >= p.R) {
-            if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
-          } else {
-            src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin + cin0;
+    for (int sl = 0; sl < KS; ++sl) {
+      const int slab = (kt_lo + kt) * KS + sl;
+      const int k0 = slab * 64;
+      char* sa = smem + stage * STAGE + sl * SLAB + (wave * (BM / NW)) * 128;
+      char* sb = smem + stage * STAGE + sl * SLAB + A_BYTES + (wave * (BN / NW)) * 128;
+      if constexpr (kConv) {
+        const int tap = k0 / p.Cin;
+        const int cin0 = k0 - tap * p.Cin;
+        const int ky = tap / 3, kx = tap - ky * 3;
+#pragma unroll
+        for (int j = 0; j < AJ; ++j) {
+          const int ri = a_ro[j] * p.stride + ky - 1;
+          const int ci = a_co[j] * p.stride + kx - 1;
+          const bf16_t* src = zeros;
+          if (a_ok[j] && ci >= 0 && ci < p.W) {
+            if (ri < 0) {
+              if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
+            } else if (ri >= p.R) {
+              if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
+            } else {
+              src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin + cin0;
+            }
           }
+          __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc_a(j) * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
         }
-        __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc_of(j) * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
+      } else {
+#pragma unroll
+        for (int j = 0; j < AJ; ++j)
+          __builtin_amdgcn_global_load_lds(DF_GPTR(a_ptr[j] + k0), DF_LPTR(sa + j * 1024), 16, 0, 0);
       }
-    } else {
 #pragma unroll
-      for (int j = 0; j < AJ; ++j)
-        __builtin_amdgcn_global_load_lds(DF_GPTR(a_ptr[j] + k0), DF_LPTR(sa + j * 1024), 16, 0, 0);
+      for (int j = 0; j < BJ; ++j)
+        __builtin_amdgcn_global_load_lds(DF_GPTR(b_ptr[j] + (long long)slab * b_kstep), DF_LPTR(sb + j * 1024), 16, 0, 0);
     }
-#pragma unroll
-    for (int j = 0; j < BJ; ++j)
-      __builtin_amdgcn_global_load_lds(DF_GPTR(b_ptr[j] + (long long)(kt_lo + kt) * b_kstep), DF_LPTR(sb + j * 1024), 16,
-                                       0, 0);
   };
 
   f32x16 acc[TM][TN];
@@ -369,8 +382,11 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     issue(kt + STAGES - 1, nstage);         // into the stage every wave finished reading before the barrier
-    const char* As = smem + stage * STAGE + (wm * (BM / 2) + lrow) * 128;
-    const char* Bs = smem + stage * STAGE + A_BYTES + (wn * (BN / 2) + lrow) * 128;
+    if (computes) {
+#pragma unroll
+    for (int sl = 0; sl < KS; ++sl) {
+    const char* As = smem + stage * STAGE + sl * SLAB + (wm * (BM / 2) + lrow) * 128;
+    const char* Bs = smem + stage * STAGE + sl * SLAB + A_BYTES + (wn * (BN / 2) + lrow) * 128;
     // software pipeline over the four 16-wide k-steps: the fragments of step ks+1 are requested before the
     // MFMAs of step ks are issued, so LDS latency overlaps the matrix pipe (sched_barriers pin that order)
     bf16x8 af[2][TM], bfr[2][TN];
@@ -411,6 +427,8 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    }
+    }
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
     nstage = (nstage + 1 == STAGES) ? 0 : nstage + 1;
   }
@@ -431,7 +449,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
       for (int i = 0; i < TM; ++i) {
         const float sm = ln_sum[i] + __shfl_xor(ln_sum[i], 32, 64);   // the two lane groups hold different k chunks
         const float sq = ln_sq[i] + __shfl_xor(ln_sq[i], 32, 64);
-        if (g == 0) {
+        if (g == 0 && computes) {
           const int r = wm * (BM / 2) + i * 32 + lrow;
           s_part[(wn * BM + r) * 2] = sm;
           s_part[(wn * BM + r) * 2 + 1] = sq;
@@ -451,6 +469,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
 
   if (p.vec_epi) {
     __syncthreads();                          // operand stages no longer read by anyone
+    if (computes)
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -464,7 +483,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     const int per = kConv ? p.Ro * p.Wo : 1;
     if (nsplit > 1) {
       float* mine = partials + (size_t)split * p.M * p.N;
-      for (int idx = tid; idx < BM * (BN / 4); idx += 256) {
+      for (int idx = tid; idx < BM * (BN / 4); idx += NTHR) {
         const int lr_ = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
         const int row = m0 + lr_, col = n0 + c4;
         if (row < p.M && col < p.N)
@@ -475,7 +494,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
     if constexpr (!kConv && TN == 2 && sizeof(OutT) == 2) {
       if (p.geglu) {
         // tile columns [64q, 64q+32) are value columns, [64q+32, 64q+64) the gate columns of the same outputs
-        for (int idx = tid; idx < BM * (BN / 8); idx += 256) {
+        for (int idx = tid; idx < BM * (BN / 8); idx += NTHR) {
           const int lr_ = idx / (BN / 8), o = (idx % (BN / 8)) * 4;
           const int row = m0 + lr_, oc = (n0 >> 1) + o;
           if (row >= p.M || oc >= p.geglu) continue;
@@ -500,7 +519,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
         return;
       }
     }
-    for (int idx = tid; idx < BM * (BN / 4); idx += 256) {
+    for (int idx = tid; idx < BM * (BN / 4); idx += NTHR) {
       const int lr_ = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
       const int row = m0 + lr_, col = n0 + c4;
       if (row >= p.M || col >= p.N) continue;
@@ -546,6 +565,7 @@ __global__ __launch_bounds__(256) void mfma_pipe_kernel(TileParams p, const bf16
 
   // ---- scalar epilogue: shapes or pointers that do not allow the vector accesses above ----
   __syncthreads();                            // the folded-norm statistics, if any, are visible
+  if (!computes) return;                      // loader waves hold no accumulators
   if (nsplit > 1) {
     // float partial of this split, [split][M][N]; the epilogue runs in splitk_reduce_kernel
     float* mine = partials + (size_t)split * p.M * p.N;
@@ -819,11 +839,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(TileParams p, const 
   }
 }
 
-template <int BM, int BN, int STAGES, bool kConv>
+template <int BM, int BN, int STAGES, bool kConv, int KS = 1, int NW = 4>
 int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) {
   const long long nwg = (long long)cdiv(p.M, BM) * cdiv(p.N, BN);
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
-  const int KT = p.K / 64;
+  if (p.K % (64 * KS)) return DF_ESHAPE;
+  const int KT = p.K / (64 * KS);
   if (nsplit > KT) nsplit = KT;
   if (nsplit < 1 || p.N % 4 || p.ldr % 4 || p.ldo % 4 || p.ldo2 % 4 || p.ln_s || p.geglu || p.nseg) nsplit = 1;
   if (nsplit > 1) nsplit = cdiv(KT, cdiv(KT, nsplit));   // no empty split
@@ -835,7 +856,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   }
   const bf16_t* zeros = scr ? (const bf16_t*)(scr + kScratchZeroPageOffset) : nullptr;
   float* partials = scr ? (float*)(scr + kScratchCounterBytes) : nullptr;
-  constexpr int smem = STAGES * (BM + BN) * 128;
+  constexpr int smem = STAGES * (BM + BN) * 128 * KS;
   dim3 grid((unsigned)nwg, (unsigned)nsplit);
   TileParams q = p;
   {
@@ -848,21 +869,21 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
     q.vec_epi = ok ? 1 : 0;
   }
   if (out_dtype == DF_BF16) {
-    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, bf16_t>;
+    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, bf16_t, KS, NW>;
     static bool attr_set = false;
     if (!attr_set) {
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, q, zeros, partials);
+    hipLaunchKernelGGL(k, grid, dim3(64 * NW), smem, st, q, zeros, partials);
   } else {
-    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, float>;
+    auto k = mfma_pipe_kernel<BM, BN, STAGES, kConv, float, KS, NW>;
     static bool attr_set = false;
     if (!attr_set) {
       if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
       attr_set = true;
     }
-    hipLaunchKernelGGL(k, grid, dim3(256), smem, st, q, zeros, partials);
+    hipLaunchKernelGGL(k, grid, dim3(64 * NW), smem, st, q, zeros, partials);
   }
   DF_LAUNCH_CHECK();
   if (nsplit > 1) {
@@ -918,7 +939,7 @@ int launch_auto(const TileParams& p, int out_dtype, hipStream_t st) {
   if (split_override() > 0) ns = split_override();
   if (big >= 1024 && !p.ln_s) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
   if (nwg * ns >= 512 && ns == 1) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, 1, st);
-  return launch_pipe<64, 64, 4, kConv>(p, out_dtype, ns, st);
+  return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, ns, st);   // few tiles: four stages, eight waves
 }
 
 template <bool kConv>
@@ -935,8 +956,11 @@ int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
       case 640644: return launch_pipe<64, 64, 4, kConv>(p, out_dtype, so, st);
       case 640642: return launch_pipe<64, 64, 2, kConv>(p, out_dtype, so, st);
       case 640643: return launch_pipe<64, 64, 3, kConv>(p, out_dtype, so, st);
-      case 640646: return launch_pipe<64, 64, 6, kConv>(p, out_dtype, so, st);
+      case 640646: return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, so, st);   // 'x6': four stages, eight waves
       case 640648: return launch_pipe<64, 64, 8, kConv>(p, out_dtype, so, st);
+      case 640649: if (p.K % 128 == 0) return launch_pipe<64, 64, 2, kConv, 2>(p, out_dtype, so, st); break;   // 'x9': two slabs per stage, 2 stages
+      case 640645: if (p.K % 128 == 0) return launch_pipe<64, 64, 3, kConv, 2, 8>(p, out_dtype, so, st); break;   // 'x5': two slabs, 3 stages, eight waves
+      case 640647: if (p.K % 128 == 0) return launch_pipe<64, 64, 4, kConv, 2>(p, out_dtype, so, st); break;   // 'x7': two slabs, 4 stages
       case 641282: return launch_pipe<64, 128, 2, kConv>(p, out_dtype, so, st);
       case 641284: return launch_pipe<64, 128, 4, kConv>(p, out_dtype, so, st);
       default: break;
@@ -1001,7 +1025,7 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
     }
     if ((long long)cdiv(a.M, 64) * cdiv(a.N, 64) >= 512) return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
-    return launch_pipe<64, 64, 4, false>(p, DF_BF16, 1, st);
+    return launch_pipe<64, 64, 4, false, 1, 8>(p, DF_BF16, 1, st);
   }
   if (special) return launch_auto<false>(p, a.out_dtype, st);   // these epilogues exist in the pipelined kernel only
   return pick_tile<false>(p, a.out_dtype, st);

@@ -27,16 +27,12 @@ struct GnLayout {
 };
 
 template <typename Tin>
-__global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial, unsigned int* __restrict__ counters,
-                         float* __restrict__ meanrstd, const float* __restrict__ stale, float* __restrict__ sums_out,
-                         int pix_seg, int C, int G, int tp, int ppb, int pix_per_blk, int nseg, int patch_idx, int N,
-                         float eps, int stat_mode) {
+__global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial, int pix_seg, int C, int G, int tp,
+                         int ppb, int pix_per_blk, int nseg) {
   constexpr int V = Elem<Tin>::kVec;
   __shared__ float s_sum[kMaxG], s_sq[kMaxG];
-  __shared__ float s_red[2][16][kMaxG];
-  __shared__ int s_last;
   const int blk = blockIdx.x, seg = blockIdx.y, b = blockIdx.z;
-  const int nblk = gridDim.x, B = gridDim.z;
+  const int nblk = gridDim.x;
   const int cg = C / G;
   const int tid = threadIdx.x;
   if (tid < G) { s_sum[tid] = 0.f; s_sq[tid] = 0.f; }
@@ -78,20 +74,20 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
   __syncthreads();
   float* my = partial + ((((long long)b * nseg + seg) * nblk + blk) * G) * 2;
   if (tid < G) { my[2 * tid] = s_sum[tid]; my[2 * tid + 1] = s_sq[tid]; }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned int total = (unsigned int)(nblk * nseg);
-    const unsigned int prev = atomicAdd(&counters[b], 1u);
-    s_last = (prev == total - 1);
-    if (s_last) counters[b] = 0u;  // leave the counter at zero for the next launch
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
+}
 
-  // ---- last block of this batch item: ordered reduction of all partials ----
-  const int parts = blockDim.x / G < 16 ? blockDim.x / G : 16;
+// One workgroup per batch item: adds the partials in a fixed order, emits the fresh per-patch sums, combines them with
+// the stale sums of the other patches according to the statistic mode and stores mean / rstd.  A separate launch
+// instead of a "last workgroup" epilogue: the device-scope fences that pattern needs cost more than the launch.
+__global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ partial, float* __restrict__ meanrstd,
+                                                    const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                    int pix_seg, int C, int G, int nblk, int nseg, int B, int patch_idx,
+                                                    int N, float eps, int stat_mode) {
+  __shared__ float s_red[2][32][kMaxG];
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int cg = C / G;
+  const int parts = blockDim.x / G < 32 ? blockDim.x / G : 32;
   const int g = tid % G, part = tid / G;
   float tot_s = 0.f, tot_q = 0.f;  // over all segments (valid on part == 0 lanes)
   for (int sg = 0; sg < nseg; ++sg) {
@@ -203,10 +199,10 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
   }
 }
 
-GnLayout gn_layout(int C, int vec, long long pix, int target_blocks) {
+GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_threads) {
   GnLayout L;
   L.tp = C / vec;
-  L.ppb = 256 / L.tp;
+  L.ppb = max_threads / L.tp;
   if (L.ppb < 1) L.ppb = 1;
   L.threads = L.tp * L.ppb;
   long long per = (pix + target_blocks - 1) / target_blocks;
@@ -232,30 +228,29 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   if (a.B > 1024) return DF_ESHAPE;
   const long long pix_seg = (long long)a.Rseg * a.W;
   if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
-  // few enough blocks that the last one folds the partials in a handful of trips, enough to fill the chip
-  int target = 256 / a.nseg;
+  // up to 512 partial blocks per batch item: the finalize workgroup folds them with 32 lanes per group
+  int target = 512 / a.nseg;
   if (target < 1) target = 1;
-  GnLayout L = gn_layout(a.C, vec, pix_seg, target);
+  GnLayout L = gn_layout(a.C, vec, pix_seg, target, 256);
   if ((long long)L.nblk * a.nseg > 2048) return DF_ESHAPE;
   if (L.threads < a.G) return DF_ESHAPE;
   char* scr = (char*)scratch_get(groupnorm_scratch_bytes(a.B, a.nseg, a.G));
   if (!scr) return DF_ENOMEM;
-  unsigned int* counters = (unsigned int*)scr;
   float* meanrstd = (float*)(scr + kScratchCounterBytes);
   float* partial = meanrstd + (size_t)a.B * a.G * 2;
   dim3 gs(L.nblk, a.nseg, a.B);
-  if (a.in_dtype == DF_BF16) {
-    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), 0, st, (const bf16_t*)a.x, partial, counters, meanrstd,
-                       a.stale, a.sums_out, (int)pix_seg, a.C, a.G, L.tp, L.ppb, L.pix_per_blk, a.nseg, a.patch_idx,
-                       a.N, a.eps, a.stat_mode);
-  } else {
-    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), 0, st, (const float*)a.x, partial, counters, meanrstd,
-                       a.stale, a.sums_out, (int)pix_seg, a.C, a.G, L.tp, L.ppb, L.pix_per_blk, a.nseg, a.patch_idx,
-                       a.N, a.eps, a.stat_mode);
-  }
+  if (a.in_dtype == DF_BF16)
+    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), 0, st, (const bf16_t*)a.x, partial, (int)pix_seg, a.C, a.G,
+                       L.tp, L.ppb, L.pix_per_blk, a.nseg);
+  else
+    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), 0, st, (const float*)a.x, partial, (int)pix_seg, a.C, a.G,
+                       L.tp, L.ppb, L.pix_per_blk, a.nseg);
+  DF_LAUNCH_CHECK();
+  hipLaunchKernelGGL(gn_finalize, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out, (int)pix_seg, a.C,
+                     a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
   DF_LAUNCH_CHECK();
   const long long pix_b = pix_seg * a.nseg;
-  GnLayout A = gn_layout(a.C, vec, pix_b, 2048);
+  GnLayout A = gn_layout(a.C, vec, pix_b, 2048, 256);
   dim3 ga(A.nblk, a.B);
   if (a.in_dtype == DF_BF16) {
     hipLaunchKernelGGL((gn_apply<bf16_t, bf16_t>), ga, dim3(A.threads), 0, st, (const bf16_t*)a.x, (bf16_t*)a.y,

@@ -230,9 +230,24 @@ struct PackedW {
   const float* t = nullptr;
 };
 
+// A step captured as a HIP graph: the ~1000 launches of a step replay from one submission, which takes the host
+// out of the critical path (the counterpart of the paper's CUDAGraph use, Section 5.1).  A graph is tied to the
+// mode, patch, refresh flag, stream and every pointer of the call that recorded it.
+struct GraphEntry {
+  int mode, patch, refresh;
+  const void *x, *emb, *text, *eps;
+  void* stale;
+  hipStream_t stream;
+  int calls = 0;                 // eager calls seen with this key (the first one stays eager: it may still set
+                                 // function attributes or grow the scratch, which must not happen under capture)
+  hipGraphExec_t exec = nullptr;
+};
+
 struct df_unet {
   df_unet_cfg cfg;
   Prof prof;
+  bool use_graph = true;
+  std::vector<GraphEntry> graphs;
   std::map<std::string, PackedW> packed;
   std::vector<BlockDesc> blocks;
   std::map<std::string, const void*> w;
@@ -935,7 +950,12 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
   return DF_OK;
 }
 
-void df_unet_destroy(df_unet* u) { delete u; }
+void df_unet_destroy(df_unet* u) {
+  if (!u) return;
+  for (GraphEntry& g : u->graphs)
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  delete u;
+}
 
 int df_unet_num_stale(const df_unet* u) { return u ? (int)u->stale.size() : DF_EINVAL; }
 
@@ -973,7 +993,54 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;
   e.prof = &u->prof;
-  return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+  hipStream_t st = (hipStream_t)stream;
+  // the legacy default stream cannot be captured; per-launch timing needs the events between the launches
+  if (!u->use_graph || u->prof.on || st == nullptr)
+    return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+  GraphEntry* ge = nullptr;
+  for (GraphEntry& g : u->graphs)
+    if (g.mode == mode && g.patch == e.patch && g.refresh == e.refresh && g.x == x && g.emb == emb && g.text == text &&
+        g.eps == eps_out && g.stale == stale && g.stream == st) { ge = &g; break; }
+  if (!ge) {
+    if (u->graphs.size() >= 64) {   // bound the cache: drop everything and start over
+      for (GraphEntry& g : u->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
+      u->graphs.clear();
+    }
+    GraphEntry g;
+    g.mode = mode; g.patch = e.patch; g.refresh = e.refresh; g.x = x; g.emb = emb; g.text = text; g.eps = eps_out;
+    g.stale = stale; g.stream = st;
+    u->graphs.push_back(g);
+    ge = &u->graphs.back();
+  }
+  if (ge->exec) return hipGraphLaunch(ge->exec, st) == hipSuccess ? DF_OK : DF_EHIP;
+  if (ge->calls == 0) {
+    ge->calls = 1;
+    return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+  }
+  if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    (void)hipGetLastError();
+    return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+  }
+  const int rc = e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
+  hipGraph_t graph = nullptr;
+  const hipError_t ec = hipStreamEndCapture(st, &graph);
+  if (rc != DF_OK || ec != hipSuccess || !graph) {
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    return rc != DF_OK ? rc : DF_EHIP;
+  }
+  hipGraphExec_t exec = nullptr;
+  const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (ei != hipSuccess || !exec) return DF_EHIP;
+  ge->exec = exec;
+  return hipGraphLaunch(exec, st) == hipSuccess ? DF_OK : DF_EHIP;
+}
+
+int df_unet_set_graph(df_unet* u, int on) {
+  if (!u) return DF_EINVAL;
+  u->use_graph = on != 0;
+  return DF_OK;
 }
 
 int df_unet_profile_enable(df_unet* u, int on) {

@@ -170,3 +170,38 @@ def test_multi_step_euler_loop_against_golden():
     say("  loop drift of eps per step (rel_l2):", ["%.4f" % d for d in drift])
     assert max(drift) < TOL_BF16
     net.close()
+
+
+def test_graph_replay_matches_eager_launches():
+    """The step is recorded into a HIP graph on its second identical call and replayed afterwards: every replay, with
+    other GPU work and synchronisations in between, must reproduce the eager result (the only run-to-run freedom is
+    the order of a few float additions inside GroupNorm's partial sums)."""
+    cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=9, threads=8)
+    t = configs.unet_inputs(cfg, seed=9, stale_std=0.3)
+    net = df.PatchUNet(cfg, _upload(weights), B=1, device=DEV)
+    emb_d, text_d = dev(t["emb"]), dev(t["text"], True)
+    R = cfg.H // cfg.N
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        net.step(dev(t["x_prev"]), emb_d, text_d, mode=df.MODE_FULL)
+        side.synchronize()
+        stale0 = net.stale.clone()
+        x = dev(t["x"][:, R:2 * R])
+        out = torch.empty_like(x)
+        net.set_graph(False)
+        net.step(x, emb_d, text_d, patch_idx=1, mode=df.MODE_DISPLACED, out=out)
+        side.synchronize()
+        want, want_stale = out.clone(), net.stale.clone()
+        net.set_graph(True)
+        scratch = torch.zeros(1 << 20, device=DEV)
+        for rep in range(5):                     # 1: eager, 2: capture + launch, 3..5: replays
+            net.stale.copy_(stale0)
+            out.zero_()
+            scratch.add_(1.0)                    # unrelated eager work between the replays
+            net.step(x, emb_d, text_d, patch_idx=1, mode=df.MODE_DISPLACED, out=out)
+            side.synchronize()
+            assert rel_l2(host(out), host(want)) < 1e-5, rep
+            assert torch.equal(net.stale.view(torch.int16)[::7], want_stale.view(torch.int16)[::7]) or \
+                rel_l2(host(net.stale.view(torch.float32)[:1024]), host(want_stale.view(torch.float32)[:1024])) < 1e-3
+    net.close()
