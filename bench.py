@@ -109,6 +109,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--profile-steps", type=int, default=3, help="extra steps with per-launch event timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly (no HIP graph replay)")
     ap.add_argument("--small", action="store_true", help="reduced-width UNet (plumbing check, not the benchmark)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -136,6 +137,8 @@ def main():
     specs = df.unet_weight_specs(ccfg)
     weights = make_weights(df, torch, ccfg, seed=4)
     net = df.PatchUNet(cfg, weights, B=1)
+    if args.no_graph:
+        net.set_graph(False)
     g = torch.Generator(device="cuda:0").manual_seed(40)
     x_prev = torch.randn(1, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
     R = cfg.H // cfg.N

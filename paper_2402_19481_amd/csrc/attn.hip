@@ -59,9 +59,21 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c = lane & 31;
-  const int h = blockIdx.y;
-  const int b = blockIdx.z / p.nsplit, split = blockIdx.z % p.nsplit;
-  const int q0 = blockIdx.x * 128 + wave * 32;
+  // 1-D grid; workgroups go round-robin over the 8 XCDs, so XCD x takes the x-th contiguous chunk of the
+  // (query block fastest, head, batch*split) order: the query blocks that read the same K/V range share an L2
+  int t = blockIdx.x;
+  {
+    const int nwg = gridDim.x;
+    const int xcd = t & 7, loc = t >> 3;
+    const int base = nwg >> 3, rem = nwg & 7;
+    t = xcd * base + (xcd < rem ? xcd : rem) + loc;
+  }
+  const int nqb = (p.Lq + 127) / 128;
+  const int qb = t % nqb;
+  const int h = (t / nqb) % p.heads;
+  const int zz = t / (nqb * p.heads);
+  const int b = zz / p.nsplit, split = zz % p.nsplit;
+  const int q0 = qb * 128 + wave * 32;
   const int kv_lo = split * p.keys_per_split;
   int kv_hi = kv_lo + p.keys_per_split;
   if (kv_hi > p.L) kv_hi = p.L;
@@ -386,8 +398,9 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     p.part_o = (float*)(scr + kScratchCounterBytes);
     p.part_ml = p.part_o + (size_t)ns * a.B * a.heads * a.Lq * 64;
   }
-  dim3 grid(cdiv(a.Lq, 128), a.heads, a.B * p.nsplit);
-  hipLaunchKernelGGL(attn_bf16_d64, grid, dim3(256), 0, st, p);
+  const long long nwg = (long long)cdiv(a.Lq, 128) * a.heads * a.B * p.nsplit;
+  if (nwg > 0x7fffffffLL) return DF_ESHAPE;
+  hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
   DF_LAUNCH_CHECK();
   if (ns > 1) {
     const long long n = (long long)a.B * a.heads * a.Lq * 16;

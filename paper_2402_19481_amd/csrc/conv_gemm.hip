@@ -258,13 +258,15 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
   const int nwg = MT * NT;
   int t = blockIdx.x;
   {
-    const int per = (nwg + 7) / 8;
+    // XCD x (= workgroup id mod 8) receives the x-th contiguous chunk of tiles; chunk sizes differ by at most one
     const int xcd = t & 7, loc = t >> 3;
-    const int cand = xcd * per + loc;
-    // only a bijection when nwg is a multiple of 8; otherwise keep the plain order
-    if ((nwg & 7) == 0) t = cand;
+    const int base = nwg >> 3, rem = nwg & 7;
+    t = xcd * base + (xcd < rem ? xcd : rem) + loc;
   }
-  const int m0 = (t % MT) * BM, n0 = (t / MT) * BN;
+  // consecutive tiles (same XCD, same time) share the larger operand: the weight tile when M is small (patch GEMMs),
+  // the activation rows when M is large (convolutions)
+  const bool m_fast = (long long)p.M <= (long long)p.N * 2;
+  const int m0 = (m_fast ? t % MT : t / NT) * BM, n0 = (m_fast ? t / MT : t % NT) * BN;
   const int nsplit = gridDim.y, split = blockIdx.y;
   const int KT_all = p.K / (64 * KS);
   const int kt_per = (KT_all + nsplit - 1) / nsplit;
