@@ -25,6 +25,19 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic(cls):
+    """HBM bytes per step of a kernel class from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
+    calibrated against the copy kernel), or None."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "unet_step_cfg4_hbm_traffic.md")):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_per_step_bytes" and f[1] == cls:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def make_weights(df, torch, ccfg, seed):
     g = torch.Generator(device="cuda:0").manual_seed(seed)
     out = []
@@ -185,16 +198,20 @@ def main():
                             gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1))
     dom = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
     d = prof[dom]
+    traffic = None if args.small else measured_traffic(dom)
+    if traffic is not None:
+        traffic = round(traffic / (d["launches"] / args.profile_steps))      # per launch, like `achieved`
     if d["flops"] > 0:
         ach = d["flops"] / (d["ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=traffic,
+                        algorithmic_bytes_per_launch=round(d["bytes"] / d["launches"]),
                         avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
                         flops_per_launch=d["flops"] / d["launches"])
     else:
         ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=None,
+                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic,
                         avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
                         bytes_per_launch=d["bytes"] / d["launches"])
 
@@ -209,6 +226,11 @@ def main():
         "tflops": round(tflop / (ms * 1e-3), 2),
         "mfma_util_frac_of_bf16_peak": round(tflop / (ms * 1e-3) / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
+        # the other parts of the headline metric: MFMA utilisation of attention and convolution, GroupNorm / refresh GB/s
+        "attn_mfma_util_frac": round((breakdown.get("self_attn", {}).get("tflops") or 0.0) / PEAK_BF16_TFLOPS, 4),
+        "conv_mfma_util_frac": round((breakdown.get("conv3x3", {}).get("tflops") or 0.0) / PEAK_BF16_TFLOPS, 4),
+        "groupnorm_hbm_gbs": breakdown.get("groupnorm", {}).get("gbs"),
+        "refresh_hbm_gbs": breakdown.get("refresh", {}).get("gbs"),
         "breakdown": breakdown,
     }
     if not args.no_cpu_baseline:

@@ -3,15 +3,16 @@
 //
 // Sparse convolution of one patch (Section 4, Sparse operations): an implicit
 // GEMM over M = B*Ro*Wo output pixels of the patch, N = Cout, K = 9*Cin.  The
-// A-operand loader gathers each 32-channel slice of a tap straight from the
+// A-operand loader gathers each 32- or 64-channel slice of a tap straight from the
 // fresh patch, or - for the row above / below the patch - from the stale halo
 // row (Section 5.3: only boundary rows come from other patches), or zero at the
 // image border.  The scatter is never materialised.
 //
-// Tile: BM x BN x 32, 256 lanes = 4 waves in a 2x2 grid, each wave owns
-// (BM/2)x(BN/2) as 32x32 blocks of v_mfma_f32_32x32x16_bf16.  Operands are
-// staged through LDS with an 80-byte row pitch (conflict-free for 16-byte
-// reads), double buffered, next tile prefetched into registers during compute.
+// Two tile kernels: mfma_pipe_kernel (BM x BN x 64 slabs, operands loaded
+// global -> LDS directly into a multi-stage ring, used whenever K % 64 == 0)
+// and mfma_tile_kernel (BM x BN x 32, register-staged, any K % 32 == 0).  Both
+// run 4 compute waves in a 2x2 grid, each owning (BM/2)x(BN/2) as 32x32 blocks
+// of v_mfma_f32_32x32x16_bf16.
 #include <cstdio>
 #include <cstdlib>
 

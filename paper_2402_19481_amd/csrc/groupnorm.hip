@@ -1,13 +1,14 @@
 // Corrected asynchronous GroupNorm (Section 4, Eq. 2) for channels-last patches.
 //
-// Two launches, both HBM-bound streaming passes with 16-byte accesses:
-//   gn_stats  every block sums a strip of pixels into per-group (sum, sum of
-//             squares) partials; the last block to finish (per batch item)
-//             adds the partials in a fixed order, emits the fresh per-patch
-//             sums, combines them with the stale sums of the other patches
-//             according to the statistic mode and stores mean / rstd.
-//   gn_apply  y = (x - mean) * rstd * gamma + beta (+ SiLU), second read of x
-//             comes from L2 / Infinity Cache at the sizes of one patch.
+// Three launches, the two big ones HBM-bound streaming passes with 16-byte accesses:
+//   gn_stats     every block sums a strip of pixels into per-group (sum, sum of
+//                squares) partials.
+//   gn_finalize  one workgroup per batch item adds the partials in a fixed order,
+//                emits the fresh per-patch sums, combines them with the stale sums
+//                of the other patches according to the statistic mode and stores
+//                mean / rstd (and refreshes the patch's slot of the cache).
+//   gn_apply     y = (x - mean) * rstd * gamma + beta (+ SiLU); the second read of
+//                x comes from L2 / Infinity Cache at the sizes of one patch.
 // A lane keeps a fixed channel offset for its whole strip, so gamma/beta and
 // the statistics are fetched once per lane.
 #include "kernels.h"
@@ -54,22 +55,27 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
 #pragma unroll
     for (int i = 0; i < V; ++i) { s[i] += v[i]; q[i] = fmaf(v[i], v[i], q[i]); }
   }
-  // fold the lane's channels into their groups (neighbouring channels mostly share one)
-  {
-    int g_prev = c0 / cg;
-    float ss = 0.f, qq = 0.f;
+  // Ordered fold of the lanes' per-channel sums into groups (no atomics: the result must not depend on timing -
+  // the UNet amplifies even one-ulp differences of a statistic to the level of its bf16 rounding noise).
+  extern __shared__ float s_lane[];            // [2][V][blockDim.x]: per-channel-slot sums of every lane
+  const int nthr = blockDim.x;
 #pragma unroll
-    for (int i = 0; i < V; ++i) {
-      const int g = (c0 + i) / cg;
-      if (g != g_prev) {
-        atomicAdd(&s_sum[g_prev], ss);
-        atomicAdd(&s_sq[g_prev], qq);
-        ss = 0.f; qq = 0.f; g_prev = g;
+  for (int i = 0; i < V; ++i) {
+    s_lane[i * nthr + tid] = s[i];
+    s_lane[(V + i) * nthr + tid] = q[i];
+  }
+  __syncthreads();
+  if (tid < G) {
+    float ss = 0.f, qq = 0.f;
+    for (int ch = tid * cg; ch < (tid + 1) * cg; ++ch) {
+      const int tcol = ch / V, i = ch % V;
+      for (int ps = 0; ps < ppb; ++ps) {
+        ss += s_lane[i * nthr + ps * tp + tcol];
+        qq += s_lane[(V + i) * nthr + ps * tp + tcol];
       }
-      ss += s[i]; qq += q[i];
     }
-    atomicAdd(&s_sum[g_prev], ss);
-    atomicAdd(&s_sq[g_prev], qq);
+    s_sum[tid] = ss;
+    s_sq[tid] = qq;
   }
   __syncthreads();
   float* my = partial + ((((long long)b * nseg + seg) * nblk + blk) * G) * 2;
@@ -240,10 +246,10 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   float* partial = meanrstd + (size_t)a.B * a.G * 2;
   dim3 gs(L.nblk, a.nseg, a.B);
   if (a.in_dtype == DF_BF16)
-    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), 0, st, (const bf16_t*)a.x, partial, (int)pix_seg, a.C, a.G,
+    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), (size_t)2 * 8 * L.threads * sizeof(float), st, (const bf16_t*)a.x, partial, (int)pix_seg, a.C, a.G,
                        L.tp, L.ppb, L.pix_per_blk, a.nseg);
   else
-    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), 0, st, (const float*)a.x, partial, (int)pix_seg, a.C, a.G,
+    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), (size_t)2 * 4 * L.threads * sizeof(float), st, (const float*)a.x, partial, (int)pix_seg, a.C, a.G,
                        L.tp, L.ppb, L.pix_per_blk, a.nseg);
   DF_LAUNCH_CHECK();
   hipLaunchKernelGGL(gn_finalize, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out, (int)pix_seg, a.C,

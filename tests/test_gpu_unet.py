@@ -174,8 +174,9 @@ def test_multi_step_euler_loop_against_golden():
 
 def test_graph_replay_matches_eager_launches():
     """The step is recorded into a HIP graph on its second identical call and replayed afterwards: every replay, with
-    other GPU work and synchronisations in between, must reproduce the eager result (the only run-to-run freedom is
-    the order of a few float additions inside GroupNorm's partial sums)."""
+    other GPU work and synchronisations in between, must reproduce the eager result bit for bit (every kernel of the
+    step adds in a fixed order; a random-weight UNet amplifies even one-ulp differences to its bf16 noise level, so
+    anything weaker than exact equality would hide a race)."""
     cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
     weights = configs.unet_weights(cfg, seed=9, threads=8)
     t = configs.unet_inputs(cfg, seed=9, stale_std=0.3)
@@ -201,7 +202,6 @@ def test_graph_replay_matches_eager_launches():
             scratch.add_(1.0)                    # unrelated eager work between the replays
             net.step(x, emb_d, text_d, patch_idx=1, mode=df.MODE_DISPLACED, out=out)
             side.synchronize()
-            assert rel_l2(host(out), host(want)) < 1e-5, rep
-            assert torch.equal(net.stale.view(torch.int16)[::7], want_stale.view(torch.int16)[::7]) or \
-                rel_l2(host(net.stale.view(torch.float32)[:1024]), host(want_stale.view(torch.float32)[:1024])) < 1e-3
+            assert torch.equal(out.view(torch.int32), want.view(torch.int32)), rep
+            assert torch.equal(net.stale, want_stale), rep
     net.close()
