@@ -123,6 +123,30 @@ int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, c
 int df_linear(const void* x, const void* w, const float* bias, const float* residual, void* y, int M, int N, int K,
               int out_dtype, void* stream);
 
+/*
+ * The same linear layer on operands stored in the order the matrix instructions consume them (the layout the UNet
+ * step uses internally between the layers of a transformer block; Section 4, Sparse operations).
+ * Packed layout of a [R, K] bf16 matrix, K % 16 == 0: fragments [ceil(R/32)][K/16][64][8]; slot l of fragment
+ * (rt, kf) holds row rt*32 + l%32, columns kf*16 + 8*(l/32) .. +7; rows beyond R are zero.  df_packed_bytes gives
+ * the size.  Packed weights use the same layout with in-fragment row i holding matrix row rt*32 + sigma(i), sigma
+ * swapping bits 2 and 3 of i, and may be scaled per column by gamma[K] (LayerNorm scale folded in) before rounding.
+ *   df_pack_rows           x [M, K] bf16 row-major -> packed
+ *   df_pack_linear_weight  w [N, K] bf16 row-major (N % 32 == 0) -> packed; gamma may be NULL
+ *   df_linear_packed       y = x w^T + bias (+ residual), K % 64 == 0, N % 32 == 0.
+ *     ln_s, ln_t non-NULL (then bias must be NULL): LayerNorm folded into the layer, y = rstd*(acc - mean*ln_s) +
+ *     ln_t with mean / rstd of each row of x over K computed by the kernel, ln_s[n] = sum_k w'[n,k] (w' the scaled,
+ *     rounded weights), ln_t[n] = sum_k w[n,k] beta[k] + bias[n].
+ *     geglu != 0: w holds N/2 value rows then N/2 gate rows; y [M, N/2] = value * gelu(gate).
+ *     Outputs (any subset, at least one): y_f32 row-major float (residual may alias it), y_packed packed bf16 (all
+ *     ceil(M/32)*32 rows are written), y_rows row-major bf16.
+ */
+size_t df_packed_bytes(long long rows, long long K);
+int df_pack_rows(const void* x, void* packed, int M, int K, void* stream);
+int df_pack_linear_weight(const void* w, const float* gamma, void* packed, int N, int K, void* stream);
+int df_linear_packed(const void* xp, const void* wp, const float* bias, const float* ln_s, const float* ln_t,
+                     float ln_eps, const float* residual, float* y_f32, void* y_packed, void* y_rows, int M, int N,
+                     int K, int geglu, void* stream);
+
 /* ---- whole UNet step --------------------------------------------------------------------- */
 
 typedef struct df_unet_cfg {

@@ -52,6 +52,11 @@ def lib():
     L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.df_packed_bytes.restype = sz
+    L.df_packed_bytes.argtypes = [ll, ll]
+    L.df_pack_rows.argtypes = [vp, vp, i, i, vp]
+    L.df_pack_linear_weight.argtypes = [vp, vp, vp, i, i, vp]
+    L.df_linear_packed.argtypes = [vp, vp, vp, vp, vp, f, vp, vp, vp, vp, i, i, i, i, vp]
     cfgp = ctypes.POINTER(UNetCfgC)
     if not hasattr(L, "df_patch_unet_step"):
         raise DfError("libdistrifusion.so is stale: rebuild it")
@@ -77,7 +82,7 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
-                 "df_euler_update", "df_linear", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_euler_update", "df_linear", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
                  "df_unet_profile_enable", "df_unet_set_graph", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
@@ -167,6 +172,41 @@ def linear(x, w, bias=None, residual=None, out_dtype=torch.bfloat16, out=None):
         out = torch.empty(M, N, dtype=out_dtype, device=x.device)
     _check(lib().df_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), M, N, K, _dt(out), _stream()))
     return out
+
+
+def pack_rows(x):
+    """x [M,K] bf16 row-major -> fragment-packed copy (int16 tensor of df_packed_bytes/2 elements)."""
+    M, K = x.shape
+    out = torch.empty(lib().df_packed_bytes(M, K) // 2, dtype=torch.bfloat16, device=x.device)
+    _check(lib().df_pack_rows(_ptr(x), _ptr(out), M, K, _stream()))
+    return out
+
+
+def pack_linear_weight(w, gamma=None):
+    """w [N,K] bf16 -> fragment-packed weights (rows permuted inside each 32-row fragment, optional column scale)."""
+    N, K = w.shape
+    out = torch.empty(N * K, dtype=torch.bfloat16, device=w.device)
+    _check(lib().df_pack_linear_weight(_ptr(w), _ptr(gamma), _ptr(out), N, K, _stream()))
+    return out
+
+
+def linear_packed(xp, wp, M, N, K, bias=None, ln_s=None, ln_t=None, ln_eps=1e-5, residual=None, geglu=False,
+                  want=("f32",)):
+    """Linear layer on packed operands; returns a dict of the requested outputs: "f32" [M,N'] float row-major,
+    "packed" packed bf16, "rows" [M,N'] bf16 row-major (N' = N/2 with geglu)."""
+    No = N // 2 if geglu else N
+    dev = xp.device
+    outs = {}
+    if "f32" in want:
+        outs["f32"] = torch.empty(M, No, dtype=torch.float32, device=dev)
+    if "packed" in want:
+        outs["packed"] = torch.empty(lib().df_packed_bytes(M, No) // 2, dtype=torch.bfloat16, device=dev)
+    if "rows" in want:
+        outs["rows"] = torch.empty(M, No, dtype=torch.bfloat16, device=dev)
+    _check(lib().df_linear_packed(_ptr(xp), _ptr(wp), _ptr(bias), _ptr(ln_s), _ptr(ln_t), ln_eps, _ptr(residual),
+                                  _ptr(outs.get("f32")), _ptr(outs.get("packed")), _ptr(outs.get("rows")), M, N, K,
+                                  1 if geglu else 0, _stream()))
+    return outs
 
 
 def euler_update(x, eps, sigma, sigma_next):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdistrifusion.so")
-SOURCES = ["api.hip", "refresh.hip", "groupnorm.hip", "conv_gemm.hip", "attn.hip", "elementwise.hip", "unet.hip"]
+SOURCES = ["api.hip", "refresh.hip", "groupnorm.hip", "conv_gemm.hip", "wgemm.hip", "attn.hip", "elementwise.hip", "unet.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -145,6 +145,31 @@ int df_linear(const void* x, const void* w, const float* bias, const float* resi
   return launch_gemm_bf16(g, (hipStream_t)stream);
 }
 
+size_t df_packed_bytes(long long rows, long long K) { return rows > 0 && K > 0 ? packed_rows_bytes(rows, K) : 0; }
+
+int df_pack_rows(const void* x, void* packed, int M, int K, void* stream) {
+  if (!x || !packed) return DF_EINVAL;
+  return launch_pack_rows((const bf16_t*)x, K, (bf16_t*)packed, M, K, (hipStream_t)stream);
+}
+
+int df_pack_linear_weight(const void* w, const float* gamma, void* packed, int N, int K, void* stream) {
+  if (!w || !packed) return DF_EINVAL;
+  return launch_pack_wfrag((const bf16_t*)w, gamma, (bf16_t*)packed, N, K, (hipStream_t)stream);
+}
+
+int df_linear_packed(const void* xp, const void* wp, const float* bias, const float* ln_s, const float* ln_t,
+                     float ln_eps, const float* residual, float* y_f32, void* y_packed, void* y_rows, int M, int N,
+                     int K, int geglu, void* stream) {
+  if (!xp || !wp || (!y_f32 && !y_packed && !y_rows)) return DF_EINVAL;
+  if (geglu && N % 2) return DF_ESHAPE;
+  const int Nout = geglu ? N / 2 : N;
+  WGemmArgs a = {};
+  a.Xp = xp; a.Wp = wp; a.M = M; a.N = N; a.K = K; a.bias = bias; a.ln_s = ln_s; a.ln_t = ln_t; a.ln_eps = ln_eps;
+  a.residual = residual; a.ldr = Nout; a.out_f32 = y_f32; a.ldo = Nout; a.out_packed = y_packed; a.out_rows = y_rows;
+  a.ld_rows = Nout; a.geglu = geglu ? Nout : 0;
+  return launch_wgemm(a, (hipStream_t)stream);
+}
+
 int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream) {
   if (!x || !eps) return DF_EINVAL;
   if (n < 0) return DF_ESHAPE;

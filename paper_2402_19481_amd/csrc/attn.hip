@@ -38,6 +38,7 @@ struct AttnParams {
   long long bsq, bskf, bsvf, bsks, bsvs, bso;
   float scale;
   int nsplit, keys_per_split;
+  int out_packed;
 };
 
 __device__ __forceinline__ const bf16_t* key_row(const bf16_t* fresh, const bf16_t* stale, long long ldf, long long lds,
@@ -59,6 +60,7 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c = lane & 31;
+  const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);   // c with bits 2 and 3 swapped
   // 1-D grid; workgroups go round-robin over the 8 XCDs, so XCD x takes the x-th contiguous chunk of the
   // (query block fastest, head, batch*split) order: the query blocks that read the same K/V range share an L2
   int t = blockIdx.x;
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
       const int kchunk = 4 * kb + 2 * half + g;     // keys 32*kb + 16*half + 8*g .. +7
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
-        const int d = 32 * db + c;
+        const int d = 32 * db + csig;                 // MFMA row c computes feature row sigma(c) (see the write below)
         const int chunk = kchunk ^ (d & 7) ^ (d >> 3);
         const bf16x8 vfrag = *reinterpret_cast<const bf16x8*>(&Vt[buf][d * TK + chunk * 8]);
         o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pfrag, o_acc[db], 0, 0, 0);
@@ -239,19 +241,26 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
     if (t + 2 < ntiles) do_tile(t + 2, I2{});
   }
 
-  // ---- write: lane (g, c) holds O[q0 + c][32*db + 8*j + 4*g + r] ----
+  // ---- write: V^T rows were taken in the order sigma (bits 2 and 3 of the row index swapped), so accumulator
+  // elements 8f .. 8f+7 of lane (g, c) are O[q0 + c][32*db + 16*f + 8*g .. +7]: eight consecutive features ----
   const int qi = q0 + c;
   if (qi >= p.Lq) return;
   if (p.nsplit == 1) {
     const float inv = 1.0f / l_run;
     bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D;
+    const long long m = (long long)b * p.Lq + qi;     // token row of the packed operand
+    bf16_t* pp = (bf16_t*)p.out + (((m >> 5) * (long long)(p.heads * D / 16) + h * (D / 16)) * 64 + (m & 31) + 32 * g) * 8;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x2 t = {pack_bf2(o_acc[db][4 * j] * inv, o_acc[db][4 * j + 1] * inv),
-                   pack_bf2(o_acc[db][4 * j + 2] * inv, o_acc[db][4 * j + 3] * inv)};
-        *reinterpret_cast<u32x2*>(op + 32 * db + 8 * j + 4 * g) = t;
+      for (int f = 0; f < 2; ++f) {
+        u32x4 t;
+        t.x = pack_bf2(o_acc[db][8 * f + 0] * inv, o_acc[db][8 * f + 1] * inv);
+        t.y = pack_bf2(o_acc[db][8 * f + 2] * inv, o_acc[db][8 * f + 3] * inv);
+        t.z = pack_bf2(o_acc[db][8 * f + 4] * inv, o_acc[db][8 * f + 5] * inv);
+        t.w = pack_bf2(o_acc[db][8 * f + 6] * inv, o_acc[db][8 * f + 7] * inv);
+        if (p.out_packed) *reinterpret_cast<u32x4*>(pp + (2 * db + f) * 512) = t;
+        else *reinterpret_cast<u32x4*>(op + 32 * db + 16 * f + 8 * g) = t;
       }
   } else {
     const long long row = (((long long)split * p.B + b) * p.heads + h) * p.Lq + qi;
@@ -259,9 +268,11 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4 t = {o_acc[db][4 * j], o_acc[db][4 * j + 1], o_acc[db][4 * j + 2], o_acc[db][4 * j + 3]};
-        *reinterpret_cast<f32x4*>(po + 32 * db + 8 * j + 4 * g) = t;
+      for (int f = 0; f < 2; ++f) {
+        f32x4 t0 = {o_acc[db][8 * f], o_acc[db][8 * f + 1], o_acc[db][8 * f + 2], o_acc[db][8 * f + 3]};
+        f32x4 t1 = {o_acc[db][8 * f + 4], o_acc[db][8 * f + 5], o_acc[db][8 * f + 6], o_acc[db][8 * f + 7]};
+        *reinterpret_cast<f32x4*>(po + 32 * db + 16 * f + 8 * g) = t0;
+        *reinterpret_cast<f32x4*>(po + 32 * db + 16 * f + 8 * g + 4) = t1;
       }
     if (g == 0) {
       p.part_ml[row * 2] = m_run;      // in log2 units
@@ -293,6 +304,11 @@ __global__ __launch_bounds__(256) void attn_combine_d64(AttnParams p) {
   const int h = (int)((row / p.Lq) % p.heads);
   const int b = (int)(row / ((long long)p.Lq * p.heads));
   bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D + d4;
+  if (p.out_packed) {
+    const long long m = (long long)b * p.Lq + qi;
+    const int col = h * D + d4;
+    op = (bf16_t*)p.out + (((m >> 5) * (long long)(p.heads * D / 16) + (col >> 4)) * 64 + (m & 31) + 32 * ((col >> 3) & 1)) * 8 + (col & 7);
+  }
   u32x2 t = {pack_bf2(o.x * inv, o.y * inv), pack_bf2(o.z * inv, o.w * inv)};
   *reinterpret_cast<u32x2*>(op) = t;
 }
@@ -374,6 +390,8 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   p.bsq = a.bsq; p.bskf = a.bskf; p.bsvf = a.bsvf; p.bsks = a.bsks; p.bsvs = a.bsvs; p.bso = a.bso;
   p.scale = a.scale;
   p.nsplit = 1; p.keys_per_split = a.L;
+  p.out_packed = a.out_packed;
+  if (a.out_packed && (a.dtype != DF_BF16 || ((uintptr_t)a.out % 16))) return DF_EINVAL;
   if (a.dtype == DF_F32) {
     const long long waves = (long long)a.B * a.heads * a.Lq;
     dim3 grid((unsigned)((waves + 3) / 4));

@@ -15,6 +15,7 @@
 // of v_mfma_f32_32x32x16_bf16.
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -248,7 +249,8 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
   constexpr int AJ = BM / (8 * NW), BJ = BN / (8 * NW);   // direct-load instructions per wave per k-slab
   static_assert(AJ >= 1 && BJ >= 1, "every wave issues at least one load per operand");
   constexpr int L = (AJ + BJ) * KS;
-  static_assert((STAGES - 2) * L < 64, "vmcnt field is 6 bits");
+  static_assert(KS == 1, "one k-slab per ring stage");
+  static_assert((STAGES - 1) * L < 64, "vmcnt field is 6 bits");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) & 1, wn = wave & 1;
@@ -369,7 +371,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
+  for (int s = 0; s < STAGES; ++s) issue(s, s);
 
   const int lrow = lane & 31, g = lane >> 5;
   const int sw = (lrow >> 1) & 7;
@@ -377,63 +379,105 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
   float ln_sum[TM], ln_sq[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) { ln_sum[i] = 0.f; ln_sq[i] = 0.f; }
-  int stage = 0, nstage = STAGES - 1;
-  for (int kt = 0; kt < KT; ++kt) {
-    // tile kt has landed once at most (STAGES-2)*L younger loads are outstanding; own LDS reads of tile kt-1 are done
+
+  // The MFMA operands of a whole k-slab (four 16-wide k-steps) are held in registers, double-buffered over slabs:
+  // the fragments of slab kt+1 are requested from LDS before the MFMAs of slab kt are issued, so neither the LDS
+  // round trip nor the barrier sits between dependent matrix instructions.  (One fragment read per MFMA made the
+  // K loop a chain of LDS latencies: 0.4 us per slab whatever the depth of the ring.)  A ring stage is free again
+  // once every wave holds its fragments, so STAGES slabs of loads are in flight, not STAGES-1.
+  bf16x8 af[2][4][TM], bfr[2][4][TN];
+  auto read_frags = [&](int stage, auto bufc) {
+    constexpr int buf = decltype(bufc)::value;
+    const char* As = smem + stage * STAGE + (wm * (BM / 2) + lrow) * 128;
+    const char* Bs = smem + stage * STAGE + A_BYTES + (wn * (BN / 2) + lrow) * 128;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int slot = ((2 * ks + g) ^ sw) * 16;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[buf][ks][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * 128 + slot);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[buf][ks][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * 128 + slot);
+    }
+  };
+  // with fewer than four accumulator blocks per wave, even and odd k-steps go to separate accumulators so that
+  // consecutive MFMAs do not wait for each other's result
+  constexpr int NACC = (TM * TN >= 4) ? 1 : 2;
+  f32x16 acc2[NACC - 1 ? TM : 1][NACC - 1 ? TN : 1];
+  if constexpr (NACC == 2) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc2[i][j][e] = 0.f;
+  }
+  auto slab_step = [&](int kt, int stage, auto curc, auto nxtc) {
+    constexpr int cur = decltype(curc)::value;
+    // own loads of slab kt+1 have landed (at most STAGES-2 younger slabs outstanding); own fragment reads of slab kt
+    // are complete
     wait_vm_and_lds<(STAGES - 2) * L>();
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(kt + STAGES - 1, nstage);         // into the stage every wave finished reading before the barrier
+    issue(kt + STAGES, stage);                // stage of slab kt: every wave holds its fragments in registers
     if (computes) {
-#pragma unroll
-    for (int sl = 0; sl < KS; ++sl) {
-    const char* As = smem + stage * STAGE + sl * SLAB + (wm * (BM / 2) + lrow) * 128;
-    const char* Bs = smem + stage * STAGE + sl * SLAB + A_BYTES + (wn * (BN / 2) + lrow) * 128;
-    // software pipeline over the four 16-wide k-steps: the fragments of step ks+1 are requested before the
-    // MFMAs of step ks are issued, so LDS latency overlaps the matrix pipe (sched_barriers pin that order)
-    bf16x8 af[2][TM], bfr[2][TN];
-    auto read_frags = [&](int ks, int buf) {
-      const int slot = ((2 * ks + g) ^ sw) * 16;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(As + i * 32 * 128 + slot);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[buf][j] = *reinterpret_cast<const bf16x8*>(Bs + j * 32 * 128 + slot);
-    };
-    read_frags(0, 0);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks < 3) read_frags(ks + 1, (ks + 1) & 1);
+      if (kt + 1 < KT) read_frags(stage + 1 == STAGES ? 0 : stage + 1, nxtc);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-      if constexpr (!kConv) {
-        // row sums of the A operand for the folded LayerNorm: two v_dot2 per dword, the two waves that share
-        // the rows take alternate k-steps (runs on the vector ALU beside the matrix pipe)
-        if (ln_fold && (ks & 1) == wn) {
-          const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int i = 0; i < TM; ++i) {
-            const u32x4 raw = __builtin_bit_cast(u32x4, af[ks & 1][i]);
-            const unsigned int wds[4] = {raw.x, raw.y, raw.z, raw.w};
+          for (int j = 0; j < TN; ++j) {
+            if (NACC == 2 && (ks & 1))
+              acc2[NACC - 1 ? i : 0][NACC - 1 ? j : 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  af[cur][ks][i], bfr[cur][ks][j], acc2[NACC - 1 ? i : 0][NACC - 1 ? j : 0], 0, 0, 0);
+            else
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][ks][i], bfr[cur][ks][j], acc[i][j], 0, 0, 0);
+          }
+        if constexpr (!kConv) {
+          // row sums of the A operand for the folded LayerNorm: two v_dot2 per dword, the two waves that share
+          // the rows take alternate k-steps (runs on the vector ALU beside the matrix pipe)
+          if (ln_fold && (ks & 1) == wn) {
+            const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const bf16x2_t v2 = __builtin_bit_cast(bf16x2_t, wds[q]);
-              ln_sum[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, ones, ln_sum[i], false);
-              ln_sq[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, v2, ln_sq[i], false);
+            for (int i = 0; i < TM; ++i) {
+              const u32x4 raw = __builtin_bit_cast(u32x4, af[cur][ks][i]);
+              const unsigned int wds[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const bf16x2_t v2 = __builtin_bit_cast(bf16x2_t, wds[q]);
+                ln_sum[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, ones, ln_sum[i], false);
+                ln_sq[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, v2, ln_sq[i], false);
+              }
             }
           }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    }
-    }
+  };
+
+  // slab 0 has landed once at most STAGES-1 younger slabs are outstanding
+  wait_vm_and_lds<(STAGES - 1) * L>();
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  if (computes) read_frags(0, std::integral_constant<int, 0>());
+  int stage = 0;
+  for (int kt = 0; kt < KT; kt += 2) {
+    slab_step(kt, stage, std::integral_constant<int, 0>(), std::integral_constant<int, 1>());
     stage = (stage + 1 == STAGES) ? 0 : stage + 1;
-    nstage = (nstage + 1 == STAGES) ? 0 : nstage + 1;
+    if (kt + 1 < KT) {
+      slab_step(kt + 1, stage, std::integral_constant<int, 1>(), std::integral_constant<int, 0>());
+      stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+    }
+  }
+  if constexpr (NACC == 2) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] += acc2[i][j];
   }
   wait_vm_and_lds<0>();                      // drain the clamped tail loads before the workgroup ends
 
@@ -961,9 +1005,6 @@ int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
       case 640643: return launch_pipe<64, 64, 3, kConv>(p, out_dtype, so, st);
       case 640646: return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, so, st);   // 'x6': four stages, eight waves
       case 640648: return launch_pipe<64, 64, 8, kConv>(p, out_dtype, so, st);
-      case 640649: if (p.K % 128 == 0) return launch_pipe<64, 64, 2, kConv, 2>(p, out_dtype, so, st); break;   // 'x9': two slabs per stage, 2 stages
-      case 640645: if (p.K % 128 == 0) return launch_pipe<64, 64, 3, kConv, 2, 8>(p, out_dtype, so, st); break;   // 'x5': two slabs, 3 stages, eight waves
-      case 640647: if (p.K % 128 == 0) return launch_pipe<64, 64, 4, kConv, 2>(p, out_dtype, so, st); break;   // 'x7': two slabs, 4 stages
       case 641282: return launch_pipe<64, 128, 2, kConv>(p, out_dtype, so, st);
       case 641284: return launch_pipe<64, 128, 4, kConv>(p, out_dtype, so, st);
       default: break;

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
 template <typename Tin, typename Tout>
 __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const float* __restrict__ meanrstd,
                          const float* __restrict__ gamma, const float* __restrict__ beta, int pix_b, int C, int G,
-                         int tp, int ppb, int pix_per_blk, int silu) {
+                         int tp, int ppb, int pix_per_blk, int silu, int packed) {
   constexpr int V = Elem<Tin>::kVec;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
@@ -196,6 +196,12 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
       v[i] = silu ? silu_f(t) : t;
     }
     Tout* o = y + (base + p) * C + c0;
+    if (packed) {
+      // fragment-packed bf16 operand of the linear layers: pixel m = base + p is row m%32 of fragment row m/32, the
+      // 8 channels from c0 & ~7 sit in slot (m%32) + 32*((c0/8)%2) of fragment column c0/16
+      const long long m = base + p;
+      o = y + (((m >> 5) * (C >> 4) + (c0 >> 4)) * 64 + (m & 31) + 32 * ((c0 >> 3) & 1)) * 8 + (c0 & 7);
+    }
     if constexpr (sizeof(Tout) == sizeof(Tin)) {
       st_vec(o, v);
     } else {  // float in, bf16 out: 4 values = 8 bytes
@@ -232,6 +238,7 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   if (a.C % a.G || a.C % vec || a.G > kMaxG || a.C / vec > 1024) return DF_ESHAPE;
   if (a.in_dtype == DF_BF16 && a.out_dtype != DF_BF16) return DF_ESHAPE;
   if (a.B > 1024) return DF_ESHAPE;
+  if (a.y_packed && (a.out_dtype != DF_BF16 || a.C % 16)) return DF_ESHAPE;
   const long long pix_seg = (long long)a.Rseg * a.W;
   if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
   // up to 512 partial blocks per batch item: the finalize workgroup folds them with 32 lanes per group
@@ -260,13 +267,13 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   dim3 ga(A.nblk, a.B);
   if (a.in_dtype == DF_BF16) {
     hipLaunchKernelGGL((gn_apply<bf16_t, bf16_t>), ga, dim3(A.threads), 0, st, (const bf16_t*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
   } else if (a.out_dtype == DF_BF16) {
     hipLaunchKernelGGL((gn_apply<float, bf16_t>), ga, dim3(A.threads), 0, st, (const float*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
   } else {
     hipLaunchKernelGGL((gn_apply<float, float>), ga, dim3(A.threads), 0, st, (const float*)a.x, (float*)a.y, meanrstd,
-                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu);
+                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
   }
   DF_LAUNCH_CHECK();
   return DF_OK;

@@ -33,6 +33,7 @@ struct GnArgs {
   float eps;
   int stat_mode, silu;
   int in_dtype, out_dtype;
+  int y_packed;         // bf16 output in the fragment-packed layout of wgemm.hip (rows = B*rows*W pixels, K = C)
 };
 int launch_groupnorm(const GnArgs& a, hipStream_t st);
 size_t groupnorm_scratch_bytes(int B, int nseg, int G);
@@ -96,6 +97,36 @@ int launch_fold_vectors(const bf16_t* w, const float* gamma, const float* beta, 
                         int N, int K, hipStream_t st);
 size_t gemm_scratch_bytes(long long M, long long N);  // also covers a convolution with M output pixels, N = Cout
 
+// ---- wgemm.hip: linear layers on fragment-packed operands ----
+// Packed layout of a [R, K] bf16 matrix: fragments [ceil(R/32)][K/16][64 lanes][8], lane l of fragment (rt, kf)
+// holding row rt*32 + l%32, columns kf*16 + 8*(l/32) .. +7 (rows beyond R are zero).  Weights use the same layout with
+// the in-fragment row i holding matrix row rt*32 + (i with bits 2 and 3 swapped).
+struct WGemmArgs {
+  const void* Xp;         // packed activations [M, K]
+  const void* Wp;         // packed weights [N, K]
+  int M, N, K;            // K % 64 == 0, N % 32 == 0
+  const float* bias;      // [N] or nullptr
+  const float* ln_s;      // folded LayerNorm vectors (see GemmArgs), or nullptr
+  const float* ln_t;
+  float ln_eps;
+  const float* residual;  // row-major [M, N'] float, row stride ldr, or nullptr (may alias out_f32)
+  long long ldr;
+  float* out_f32;         // row-major [M, N'] float, row stride ldo, or nullptr
+  long long ldo;
+  void* out_packed;       // packed bf16 [M, N'] (the next layer's activation operand), or nullptr
+  void* out_rows;         // row-major bf16 [M, N'], row stride ld_rows, or nullptr
+  long long ld_rows;
+  int geglu;              // F: W holds F value rows then F gate rows (N == 2F), N' = F; 0: N' = N
+  int nseg, seg_w;        // segmented row-major bf16 output as in GemmArgs (replaces out_rows)
+  void* seg_out[3];
+  long long seg_ld[3], seg_rows_out[3], seg_row0[3];
+  int seg_rows_in[3];
+};
+int launch_wgemm(const WGemmArgs& a, hipStream_t st);
+size_t packed_rows_bytes(long long M, long long K);
+int launch_pack_rows(const bf16_t* x, long long ldx, bf16_t* out, int M, int K, hipStream_t st);
+int launch_pack_wfrag(const bf16_t* w, const float* gamma, bf16_t* out, int N, int K, hipStream_t st);
+
 // ---- attn.hip ----
 struct AttnArgs {
   const void* q;        // [B, Lq, heads*d], row stride ldq, batch stride bsq
@@ -110,6 +141,7 @@ struct AttnArgs {
   long long bsq, bskf, bsvf, bsks, bsvs, bso;  // batch strides in elements
   float scale;
   int dtype;
+  int out_packed;       // bf16 output in the fragment-packed layout of wgemm.hip: rows = B*Lq tokens, K = heads*d
 };
 int launch_attention(const AttnArgs& a, hipStream_t st);
 size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d);

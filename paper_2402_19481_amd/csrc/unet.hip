@@ -176,9 +176,18 @@ struct PackSpec {
   std::string norm;   // name of the folded norm ("" = none)
   bool has_bias;
   size_t w_off, s_off, t_off;   // byte offsets inside the packed region (s/t only with a folded norm)
+  size_t f_off;                 // the same weight in the fragment layout of the wave-level GEMM
 };
 
 inline bool fold_ok(int C) { return C % 64 == 0 && C >= 128; }
+
+// Token counts up to this use the fragment-packed transformer (wave-level GEMMs); larger ones (the synchronous first
+// step on the whole image) the workgroup-tiled kernels, whose operand traffic per flop is lower.
+constexpr int kFragMaxRows = 2048;
+inline bool frag_path() {
+  static const bool off = getenv("DF_NO_FRAG") != nullptr;   // tuning aid
+  return !off;
+}
 
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
@@ -226,6 +235,7 @@ struct Prof {
 
 struct PackedW {
   const bf16_t* w = nullptr;
+  const bf16_t* f = nullptr;    // fragment layout (wgemm.hip)
   const float* s = nullptr;
   const float* t = nullptr;
 };
@@ -379,7 +389,7 @@ struct Exec {
   }
 
   void groupnorm(const std::string& name, const void* x, int in_dtype, int level_rows, int W, int C, float eps, int silu,
-                 bf16_t* y) {
+                 bf16_t* y, int y_packed = 0) {
     // level_rows: rows of x in this mode
     const int G = c.groups;
     float* entry = (float*)stale_buf(name + ".stats", (size_t)N() * B() * G * 2 * sizeof(float));
@@ -392,6 +402,7 @@ struct Exec {
     a.x = x; a.y = y; a.gamma = gamma; a.beta = beta;
     a.B = B(); a.W = W; a.C = C; a.G = G; a.eps = eps; a.silu = silu; a.in_dtype = in_dtype; a.out_dtype = DF_BF16;
     a.stat_mode = DF_GN_SUMS;
+    a.y_packed = y_packed;
     if (full()) {
       a.nseg = N(); a.Rseg = level_rows / N(); a.N = 1; a.patch_idx = 0; a.stale = nullptr; a.sums_out = entry;
     } else {
@@ -471,6 +482,113 @@ struct Exec {
     top = mark;
   }
 
+
+  // Linear layer on fragment-packed operands (wgemm.hip); `ln` applies the folded LayerNorm of that weight.
+  void wg(const bf16_t* Xp, const std::string& wn, bool bias, bool ln, const float* residual, float* out_f32,
+          bf16_t* out_packed, bf16_t* out_rows, long long ld_rows, int M, int Nn, int K, const WGemmArgs* extra = nullptr) {
+    if (!live()) return;
+    WGemmArgs g = {};
+    if (extra) g = *extra;
+    auto it = packed->find(wn);
+    if (it == packed->end()) { err = DF_EINVAL; return; }
+    g.Xp = Xp; g.Wp = it->second.f; g.M = M; g.N = Nn; g.K = K;
+    if (ln) { g.ln_s = it->second.s; g.ln_t = it->second.t; g.ln_eps = 1e-5f; }
+    else if (bias) g.bias = (const float*)weight(wn + ".b");
+    const int No = g.geglu ? g.geglu : Nn;
+    g.residual = residual; g.ldr = No; g.out_f32 = out_f32; g.ldo = No; g.out_packed = out_packed;
+    g.out_rows = out_rows; g.ld_rows = ld_rows;
+    const double ob = (out_f32 ? 4.0 : 0.0) + (out_packed ? 2.0 : 0.0) + ((out_rows || g.nseg) ? 2.0 : 0.0);
+    timed(PC_GEMM, 2.0 * M * Nn * K, 2.0 * ((double)M * K + (double)Nn * K) + ob * M * No,
+          [&] { return launch_wgemm(g, st); });
+  }
+
+  // Transformer on fragment-packed activations (patch-sized token counts): every linear layer reads its operands in
+  // MFMA order straight into registers and writes the next layer's operand in that order; LayerNorms are folded into
+  // the consuming layers; attention reads row-major Q/K/V and writes its output packed.
+  void transformer_frag(const BlockDesc& b, const float* x, float* out, int R, int W) {
+    const int C = b.cin;
+    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int M = B() * Lq, TL = c.text_len;
+    const float scale = 1.0f / sqrtf((float)c.head_dim);
+    const size_t pC = packed_rows_bytes(M, C);
+    bf16_t* nbp = (bf16_t*)alloc(pC);                       // GroupNorm output
+    float* h = (float*)alloc((size_t)M * C * 4);            // hidden state (residual stream), row-major
+    bf16_t* hp = (bf16_t*)alloc(pC);                        // its bf16 copy, packed
+    bf16_t* qkv = (bf16_t*)alloc((size_t)M * 3 * C * 2);    // row-major queries (and fresh K/V without refresh)
+    bf16_t* aop = (bf16_t*)alloc(pC);                       // attention output, packed
+    bf16_t* fgp = (bf16_t*)alloc(packed_rows_bytes(M, 4 * C));
+    groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nbp, 1);
+    wg(nbp, b.name + ".pin", true, false, nullptr, h, hp, nullptr, 0, M, C, C);
+    for (int d = 0; d < b.depth; ++d) {
+      const std::string p = b.name + ".b" + std::to_string(d);
+      bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
+      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
+      const bool fused_kv = full() || refresh;
+      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      if (fused_kv) {
+        // queries to a scratch tensor, keys and values straight into the patch's rows of the stale buffers
+        WGemmArgs ex = {};
+        ex.nseg = 3; ex.seg_w = C;
+        ex.seg_out[0] = qkv; ex.seg_ld[0] = C; ex.seg_rows_in[0] = 0x7fffffff; ex.seg_rows_out[0] = 0; ex.seg_row0[0] = 0;
+        ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
+        ex.seg_out[2] = vs; ex.seg_ld[2] = C; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = L; ex.seg_row0[2] = (long long)row0;
+        wg(hp, p + ".attn1.qkv", false, true, nullptr, nullptr, nullptr, nullptr, 0, M, 3 * C, C, &ex);
+      } else {
+        wg(hp, p + ".attn1.qkv", false, true, nullptr, nullptr, nullptr, qkv, 3 * C, M, 3 * C, C);
+      }
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.k_stale = ks; a.v_stale = vs; a.out = aop; a.q = qkv; a.out_packed = 1;
+        a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
+        a.ldks = a.ldvs = C; a.ldo = C;
+        a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
+        if (fused_kv) {
+          a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
+          a.ldq = C; a.ldkf = a.ldvf = C; a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
+        } else {
+          a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C;
+          a.own_lo = patch * Lq; a.own_n = Lq;
+          a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
+        }
+        a.scale = scale; a.dtype = DF_BF16;
+        timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
+              [&] { return launch_attention(a, st); });
+      }
+      wg(aop, p + ".attn1.o", true, false, h, h, hp, nullptr, 0, M, C, C);
+      // cross-attention to the text tokens
+      wg(hp, p + ".attn2.q", false, true, nullptr, nullptr, nullptr, qkv, C, M, C, C);
+      const long long kvld = (long long)kv_count[b.level] * 2 * C;
+      const bf16_t* kv2 = kv2_all[b.level] + (size_t)kv_cursor[b.level] * 2 * C;
+      kv_cursor[b.level] += 1;
+      {
+        const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
+        if (need > scratch_need) scratch_need = need;
+      }
+      if (live()) {
+        AttnArgs a = {};
+        a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = aop; a.out_packed = 1;
+        a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
+        a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
+        a.scale = scale; a.dtype = DF_BF16;
+        timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
+              [&] { return launch_attention(a, st); });
+      }
+      wg(aop, p + ".attn2.o", true, false, h, h, hp, nullptr, 0, M, C, C);
+      // GEGLU feed-forward
+      {
+        WGemmArgs ex = {};
+        ex.geglu = 4 * C;
+        wg(hp, p + ".ff1", false, true, nullptr, nullptr, fgp, nullptr, 0, M, 8 * C, C, &ex);
+      }
+      wg(fgp, p + ".ff2", true, false, h, h, hp, nullptr, 0, M, C, 4 * C);
+    }
+    wg(hp, b.name + ".pout", true, false, x, out, nullptr, nullptr, 0, M, C, C);
+  }
 
   // Transformer with every LayerNorm folded into the GEMM that consumes it: the residual GEMMs also emit a bf16 copy
   // of the hidden state, which is the A operand of the next projection; no LayerNorm, cast or GEGLU kernel is launched.
@@ -565,6 +683,12 @@ struct Exec {
     bf16_t* ff = (bf16_t*)alloc((size_t)M * 8 * C * 2);
     bf16_t* fg = (bf16_t*)alloc((size_t)M * 4 * C * 2);
     const float scale = 1.0f / sqrtf((float)c.head_dim);
+    if (fold_ok(C) && M <= kFragMaxRows && frag_path()) {
+      top = mark;
+      transformer_frag(b, x, out, R, W);
+      top = mark;
+      return;
+    }
     groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nb);
     if (fold_ok(C)) {
       transformer_folded(b, x, out, nb, h, qkv, ao, fg, R, W);
@@ -774,8 +898,9 @@ std::vector<PackSpec> build_pack_specs(const df_unet_cfg& c, const std::vector<B
   std::vector<PackSpec> v;
   size_t off = base;
   auto add = [&](const std::string& name, int N, int K, const std::string& norm, bool has_bias) {
-    PackSpec sp{name, N, K, norm, has_bias, 0, 0, 0};
+    PackSpec sp{name, N, K, norm, has_bias, 0, 0, 0, 0};
     sp.w_off = off; off += align256((size_t)N * K * sizeof(bf16_t));
+    sp.f_off = off; off += align256((size_t)N * K * sizeof(bf16_t));
     if (!norm.empty()) {
       sp.s_off = off; off += align256((size_t)N * sizeof(float));
       sp.t_off = off; off += align256((size_t)N * sizeof(float));
@@ -932,6 +1057,11 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
       const float* gamma = sp.norm.empty() ? nullptr : (const float*)u->w[sp.norm + ".g"];
       if (launch_pack_weight(src, gamma, dst, sp.N, sp.K, 0) != DF_OK) { delete u; return DF_EHIP; }
       pw.w = dst;
+      {
+        bf16_t* fdst = (bf16_t*)(u->ws + sp.f_off);
+        if (launch_pack_wfrag(src, gamma, fdst, sp.N, sp.K, 0) != DF_OK) { delete u; return DF_EHIP; }
+        pw.f = fdst;
+      }
       if (!sp.norm.empty()) {
         float* sv = (float*)(u->ws + sp.s_off);
         float* tv = (float*)(u->ws + sp.t_off);

@@ -1,0 +1,454 @@
+// Linear layers of the patch on MFMA-fragment-packed operands (Section 4, Sparse operations: linear layers act on
+// the fresh tokens only).
+//
+// The patch's linear layers have few rows (300-1200 tokens) and short reductions, so a workgroup-tiled GEMM spends
+// its time on barriers and LDS round trips, not on the matrix pipe.  Here neither operand touches LDS in the K loop:
+//   - activations and weights are stored in the order the MFMA consumes them: a fragment is 32 rows x 16 k
+//     = 64 lanes x 16 bytes = 1 KB contiguous, lane l holding row l%32, k = 8*(l/32) .. +7, so one
+//     global_load_dwordx4 per lane fetches an operand, perfectly coalesced, straight into registers;
+//   - a wave owns a (TM*32 tokens) x (TN*32 features) output tile and a 1/KSPLIT share of K; the KSPLIT waves of a
+//     workgroup add their partial tiles through LDS in wave order at the end (fixed order: results are
+//     reproducible), so even a 300 x 1280 output puts ~800 waves on the chip;
+//   - loads run PF k-steps ahead in a register ring; there is no barrier inside the K loop.
+// The product is computed transposed (weights as the A operand, tokens as the B operand), so a lane ends up with
+// one token and 16 features.  Weight rows are stored with bits 2 and 3 of the in-fragment row index swapped, which
+// makes those 16 features two runs of 8 consecutive ones: exactly the 16 bytes that the same lane of the *next*
+// layer's activation fragment holds.  The epilogue therefore writes the next layer's packed operand with one
+// 16-byte store per lane and no data exchange.
+#include "kernels.h"
+
+namespace df {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_w;
+
+struct WParams {
+  const bf16x8* Xp;
+  const bf16x8* Wp;
+  int M, N, K;          // N: rows of W that produce outputs (geglu: F value rows; the gate rows follow at row F)
+  const float* bias;
+  const float* ln_s;
+  const float* ln_t;
+  float ln_eps;
+  const float* residual;
+  long long ldr;
+  float* out_f32;
+  long long ldo;
+  bf16_t* out_packed;
+  bf16_t* out_rows;
+  long long ld_rows;
+  int geglu;
+  int nseg, seg_w;
+  bf16_t* seg_out[3];
+  long long seg_ld[3], seg_rows_out[3], seg_row0[3];
+  int seg_rows_in[3];
+};
+
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+template <int TM, int TN, int KSPLIT, int PF, bool LN>
+__global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  constexpr int U = TM * TN * 4;            // float4 units of a wave's tile: (tm, tn, jj)
+  f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64]
+  float* stat = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024);  // [KSPLIT][TM][32][2]
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tok = lane & 31, g = lane >> 5;
+  const int MT = (p.M + 31) >> 5;                      // 32-token fragments rows
+  const int MG = (MT + TM - 1) / TM;                   // tile groups along M
+  const int NTo = p.N >> 5;                            // 32-feature output fragments
+  const int NG = p.geglu ? NTo : NTo / TN;             // geglu: TN == 2 is (value, gate) of the same 32 outputs
+  const int nwg = MG * NG;
+  int t = blockIdx.x;
+  {
+    // workgroups go round-robin over the 8 XCDs; give each XCD a contiguous run of tiles, token tiles fastest, so
+    // that the workgroups that share a weight fragment sit behind the same L2
+    const int xcd = t & 7, loc = t >> 3;
+    const int base = nwg >> 3, rem = nwg & 7;
+    t = xcd * base + (xcd < rem ? xcd : rem) + loc;
+  }
+  const int mg = t % MG, ng = t / MG;
+  const int KF = p.K >> 4, KFw = KF / KSPLIT;
+  const int kf0 = wave * KFw;
+
+  const bf16x8* xb[TM];
+  const bf16x8* wb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    int mt = mg * TM + i;
+    if (mt > MT - 1) mt = MT - 1;                     // ragged last group: recompute the last fragment row, never stored
+    xb[i] = p.Xp + ((size_t)mt * KF + kf0) * 64 + lane;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int nt = p.geglu ? ng + j * NTo : ng * TN + j;
+    wb[j] = p.Wp + ((size_t)nt * KF + kf0) * 64 + lane;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  float ln_sum[TM], ln_sq[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { ln_sum[i] = 0.f; ln_sq[i] = 0.f; }
+  constexpr bool ln = LN;
+
+  // Epilogue operands of this wave's first pair unit (norm / bias vectors, residual) are requested before the K
+  // loop: their latency would otherwise sit, un-overlapped, at the end of every one of these short kernels.
+  // A pair unit = (token fragment i, output fragment j, half f): 8 consecutive features per lane; pair units go
+  // round-robin over the waves, which run the epilogue for them.
+  const int npu = TM * (p.geglu ? 1 : TN) * 2;
+  struct Epi { float a[8], b[8], ga[8], gb[8], r[8]; };
+  auto pu_decode = [&](int pu, int& i, int& j, int& f) {
+    f = pu & 1;
+    j = p.geglu ? 0 : (pu >> 1) % TN;
+    i = p.geglu ? (pu >> 1) : (pu >> 1) / TN;
+  };
+  auto load_epi = [&](int pu, Epi& e) {
+    int i, j, f;
+    pu_decode(pu, i, j, f);
+    const int mt = mg * TM + i;
+    const int m = mt * 32 + tok;
+    const int n = (p.geglu ? ng : ng * TN + j) * 32 + 16 * f + 8 * g;
+    if (ln) {
+      ld_vec(p.ln_s + n, e.a); ld_vec(p.ln_s + n + 4, e.a + 4);
+      ld_vec(p.ln_t + n, e.b); ld_vec(p.ln_t + n + 4, e.b + 4);
+      if (TN >= 2 && p.geglu) {
+        ld_vec(p.ln_s + p.N + n, e.ga); ld_vec(p.ln_s + p.N + n + 4, e.ga + 4);
+        ld_vec(p.ln_t + p.N + n, e.gb); ld_vec(p.ln_t + p.N + n + 4, e.gb + 4);
+      }
+    } else if (p.bias) {
+      ld_vec(p.bias + n, e.a); ld_vec(p.bias + n + 4, e.a + 4);
+      if (TN >= 2 && p.geglu) { ld_vec(p.bias + p.N + n, e.ga); ld_vec(p.bias + p.N + n + 4, e.ga + 4); }
+    }
+    if (p.residual && m < p.M) {
+      ld_vec(p.residual + (long long)m * p.ldr + n, e.r); ld_vec(p.residual + (long long)m * p.ldr + n + 4, e.r + 4);
+    }
+  };
+  Epi epi0;
+  if (wave < npu) load_epi(wave, epi0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  bf16x8 xr[PF][TM], wr[PF][TN];
+  // The loop body is straight-line code (no branches): KFw % PF == 0 (launcher), refills past the end re-read the
+  // wave's last fragment.  Every wave walks its k-range from a different starting fragment (wrapping around): the
+  // streams of all waves are otherwise aligned modulo the fragment-row pitch and hit the same few L2 / memory
+  // channels at any moment.  The order is a fixed function of the tile, so results stay reproducible.
+  const int rot = (int)((unsigned)(mg * 7 + ng * 3 + wave * 5) % (unsigned)KFw);
+  auto pos = [&](int step) {
+    if (step > KFw - 1) step = KFw - 1;
+    const int k = step + rot;
+    return (size_t)(k < KFw ? k : k - KFw) * 64;
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s) {
+    const size_t o = pos(s);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) xr[s][i] = xb[i][o];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) wr[s][j] = wb[j][o];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  for (int kf = 0; kf < KFw; kf += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[s][j], xr[s][i], acc[i][j], 0, 0, 0);
+      if constexpr (ln) {
+        // row sums of the tokens for the folded LayerNorm (vector ALU, beside the matrix pipe)
+        const bf16x2_w ones = __builtin_bit_cast(bf16x2_w, 0x3f803f80u);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const u32x4 raw = __builtin_bit_cast(u32x4, xr[s][i]);
+          const unsigned int wds[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const bf16x2_w v2 = __builtin_bit_cast(bf16x2_w, wds[q]);
+            ln_sum[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, ones, ln_sum[i], false);
+            ln_sq[i] = __builtin_amdgcn_fdot2_f32_bf16(v2, v2, ln_sq[i], false);
+          }
+        }
+      }
+      const size_t o = pos(kf + s + PF);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xr[s][i] = xb[i][o];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) wr[s][j] = wb[j][o];
+      __builtin_amdgcn_sched_barrier(0);               // keep the refill here, PF steps ahead of its use
+    }
+  }
+
+  // ---- add the KSPLIT partial tiles in wave order ----
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const f32x4 v = {acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]};
+        red[(wave * U + (i * TN + j) * 4 + jj) * 64 + lane] = v;
+      }
+  if (ln) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const float sm = ln_sum[i] + __shfl_xor(ln_sum[i], 32, 64);   // the two lane groups hold different k
+      const float sq = ln_sq[i] + __shfl_xor(ln_sq[i], 32, 64);
+      if (g == 0) {
+        stat[((wave * TM + i) * 32 + tok) * 2] = sm;
+        stat[((wave * TM + i) * 32 + tok) * 2 + 1] = sq;
+      }
+    }
+  }
+  __syncthreads();
+
+  for (int pu = wave; pu < npu; pu += KSPLIT) {
+    int i, j, f;
+    pu_decode(pu, i, j, f);
+    const int mt = mg * TM + i;
+    if (mt >= MT) continue;
+    Epi e = epi0;
+    if (pu != wave) load_epi(pu, e);
+    float v[8], gt[8];
+    {
+      f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+#pragma unroll
+      for (int w = 0; w < KSPLIT; ++w) {
+        a += red[(w * U + (i * TN + j) * 4 + 2 * f) * 64 + lane];
+        b += red[(w * U + (i * TN + j) * 4 + 2 * f + 1) * 64 + lane];
+      }
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    if (TN >= 2 && p.geglu) {
+      f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+#pragma unroll
+      for (int w = 0; w < KSPLIT; ++w) {
+        a += red[(w * U + (i * TN + 1) * 4 + 2 * f) * 64 + lane];
+        b += red[(w * U + (i * TN + 1) * 4 + 2 * f + 1) * 64 + lane];
+      }
+      gt[0] = a.x; gt[1] = a.y; gt[2] = a.z; gt[3] = a.w; gt[4] = b.x; gt[5] = b.y; gt[6] = b.z; gt[7] = b.w;
+    }
+    const int m = mt * 32 + tok;
+    const int nfrag = p.geglu ? ng : ng * TN + j;      // output fragment along the feature axis
+    const int n = nfrag * 32 + 16 * f + 8 * g;         // first of this lane's 8 consecutive features
+    if (ln) {
+      float sm = 0.f, sq = 0.f;
+#pragma unroll
+      for (int w = 0; w < KSPLIT; ++w) {
+        sm += stat[((w * TM + i) * 32 + tok) * 2];
+        sq += stat[((w * TM + i) * 32 + tok) * 2 + 1];
+      }
+      const float mean = sm / (float)p.K;
+      const float var = fmaxf(sq / (float)p.K - mean * mean, 0.f);
+      const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = rstd * (v[q] - mean * e.a[q]) + e.b[q];
+      if (TN >= 2 && p.geglu) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) gt[q] = rstd * (gt[q] - mean * e.ga[q]) + e.gb[q];
+      }
+    } else if (p.bias) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] += e.a[q];
+      if (TN >= 2 && p.geglu) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) gt[q] += e.ga[q];
+      }
+    }
+    if (TN >= 2 && p.geglu) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] *= gelu_erf(gt[q]);
+    }
+    const bool row_ok = m < p.M;
+    if (p.residual && row_ok) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] += e.r[q];
+    }
+    if (p.out_f32 && row_ok) {
+      st_vec(p.out_f32 + (long long)m * p.ldo + n, v);
+      st_vec(p.out_f32 + (long long)m * p.ldo + n + 4, v + 4);
+    }
+    if (p.out_packed) {
+      // fragment (mt, n/16) of the [M, N] result as the next layer's activation operand; padded token rows are
+      // written too (they only ever feed padded rows)
+      const int KFo = p.N >> 4;
+      st_vec(p.out_packed + (((size_t)mt * KFo + (n >> 4)) * 64 + lane) * 8, v);
+    }
+    if (row_ok) {
+      if (p.nseg > 0) {
+        const int sg = n / p.seg_w;                     // 8 features never straddle a segment (seg_w % 32 == 0)
+        const int bi = m / p.seg_rows_in[sg];
+        const long long orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (m - bi * p.seg_rows_in[sg]);
+        st_vec(p.seg_out[sg] + orow * p.seg_ld[sg] + (n - sg * p.seg_w), v);
+      } else if (p.out_rows) {
+        st_vec(p.out_rows + (long long)m * p.ld_rows + n, v);
+      }
+    }
+  }
+}
+
+// row-major [M, K] bf16 -> fragments [ceil(M/32)][K/16][64][8]; rows beyond M are zero
+__global__ void pack_rows_kernel(const bf16_t* __restrict__ x, long long ldx, u32x4* __restrict__ out, int M, int K,
+                                 long long total) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte lane slot
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const long long frag = idx >> 6;
+  const int KF = K >> 4;
+  const int kf = (int)(frag % KF);
+  const long long mt = frag / KF;
+  const long long m = mt * 32 + (lane & 31);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (m < M) v = *reinterpret_cast<const u32x4*>(x + m * ldx + kf * 16 + 8 * (lane >> 5));
+  out[idx] = v;
+}
+
+// [N, K] bf16 weights -> fragments [N/32][K/16][64][8] with in-fragment row i holding weight row
+// (i with bits 2 and 3 swapped), optionally scaled per input channel by gamma before rounding
+__global__ void pack_wfrag_kernel(const bf16_t* __restrict__ w, const float* __restrict__ gamma,
+                                  u32x4* __restrict__ out, int N, int K, long long total) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const long long frag = idx >> 6;
+  const int KF = K >> 4;
+  const int kf = (int)(frag % KF);
+  const long long nt = frag / KF;
+  const int i = lane & 31;
+  const int row = (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1);
+  const long long n = nt * 32 + row;
+  const int k0 = kf * 16 + 8 * (lane >> 5);
+  u32x4 v = *reinterpret_cast<const u32x4*>(w + n * K + k0);
+  if (gamma) {
+    const unsigned int wd[4] = {v.x, v.y, v.z, v.w};
+    unsigned int o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float lo = __uint_as_float(wd[q] << 16) * gamma[k0 + 2 * q];
+      const float hi = __uint_as_float(wd[q] & 0xffff0000u) * gamma[k0 + 2 * q + 1];
+      o[q] = pack_bf2(lo, hi);
+    }
+    v.x = o[0]; v.y = o[1]; v.z = o[2]; v.w = o[3];
+  }
+  out[idx] = v;
+}
+
+template <int TM, int TN, int KSPLIT, int PFMAX>
+int launch_cfg(const WParams& p, hipStream_t st);
+
+int tune_cfg() {
+  static const int v = [] { const char* e = getenv("DF_WGEMM_CFG"); return e ? atoi(e) : 0; }();
+  return v;
+}
+
+template <int TM, int TN, int KSPLIT, int PF, bool LN>
+int launch_one(const WParams& p, hipStream_t st) {
+  const int MT = (p.M + 31) / 32, MG = (MT + TM - 1) / TM;
+  const int NTo = p.N / 32;
+  if (!p.geglu && NTo % TN) return DF_ESHAPE;
+  if (p.geglu && TN != 2) return DF_ESHAPE;
+  const int NG = p.geglu ? NTo : NTo / TN;
+  const int KF = p.K / 16;
+  if (KF % KSPLIT) return DF_ESHAPE;
+  constexpr int smem = KSPLIT * TM * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4;
+  auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(k, dim3((unsigned)(MG * NG)), dim3(64 * KSPLIT), smem, st, p);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+// prefetch depth: the largest of PFMAX (5 or 10), 4, 2, 1 that divides the k-steps of a wave
+template <int TM, int TN, int KSPLIT, int PFMAX>
+int launch_cfg(const WParams& p, hipStream_t st) {
+  const int KF = p.K / 16;
+  if (KF % KSPLIT) return DF_ESHAPE;
+  const int KFw = KF / KSPLIT;
+  const bool ln = p.ln_s != nullptr;
+#define DF_WG(PFV)                                                                     \
+  return ln ? launch_one<TM, TN, KSPLIT, PFV, true>(p, st) : launch_one<TM, TN, KSPLIT, PFV, false>(p, st)
+  if (KFw % PFMAX == 0) { DF_WG(PFMAX); }
+  if (KFw % 4 == 0) { DF_WG(4); }
+  if (KFw % 2 == 0) { DF_WG(2); }
+  DF_WG(1);
+#undef DF_WG
+}
+
+}  // namespace
+
+size_t packed_rows_bytes(long long M, long long K) { return (size_t)((M + 31) / 32) * 32 * K * 2; }
+
+int launch_pack_rows(const bf16_t* x, long long ldx, bf16_t* out, int M, int K, hipStream_t st) {
+  if (M <= 0 || K <= 0 || K % 16 || ldx % 8 || ((uintptr_t)x % 16) || ((uintptr_t)out % 16)) return DF_ESHAPE;
+  const long long total = (long long)((M + 31) / 32) * (K / 16) * 64;
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, x, ldx, (u32x4*)out, M, K,
+                     total);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_pack_wfrag(const bf16_t* w, const float* gamma, bf16_t* out, int N, int K, hipStream_t st) {
+  if (N <= 0 || K <= 0 || N % 32 || K % 16 || ((uintptr_t)w % 16) || ((uintptr_t)out % 16)) return DF_ESHAPE;
+  const long long total = (long long)(N / 32) * (K / 16) * 64;
+  hipLaunchKernelGGL(pack_wfrag_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w, gamma, (u32x4*)out, N,
+                     K, total);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+int launch_wgemm(const WGemmArgs& a, hipStream_t st) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0 || a.K % 64) return DF_ESHAPE;
+  const int Nout = a.geglu ? a.geglu : a.N;
+  if (a.geglu && a.N != 2 * a.geglu) return DF_ESHAPE;
+  if (Nout % 32) return DF_ESHAPE;
+  if (!a.Xp || !a.Wp) return DF_EINVAL;
+  if (a.ln_s && (!a.ln_t || a.bias)) return DF_EINVAL;
+  auto al = [](const void* ptr, int b) { return ((uintptr_t)ptr % b) == 0; };
+  if (!al(a.Xp, 16) || !al(a.Wp, 16) || !al(a.bias, 16) || !al(a.ln_s, 16) || !al(a.ln_t, 16) || !al(a.residual, 16) ||
+      !al(a.out_f32, 16) || !al(a.out_packed, 16) || !al(a.out_rows, 16))
+    return DF_EINVAL;
+  if ((a.residual && a.ldr % 4) || (a.out_f32 && a.ldo % 4) || (a.out_rows && a.ld_rows % 8)) return DF_EINVAL;
+  WParams p = {};
+  p.Xp = (const bf16x8*)a.Xp; p.Wp = (const bf16x8*)a.Wp; p.M = a.M; p.N = Nout; p.K = a.K;
+  p.bias = a.bias; p.ln_s = a.ln_s; p.ln_t = a.ln_t; p.ln_eps = a.ln_eps; p.residual = a.residual; p.ldr = a.ldr;
+  p.out_f32 = a.out_f32; p.ldo = a.ldo; p.out_packed = (bf16_t*)a.out_packed; p.out_rows = (bf16_t*)a.out_rows;
+  p.ld_rows = a.ld_rows; p.geglu = a.geglu ? 1 : 0;
+  if (a.nseg > 0) {
+    if (a.nseg > 3 || a.seg_w % 32 || a.seg_w * a.nseg != a.N || a.geglu) return DF_ESHAPE;
+    p.nseg = a.nseg; p.seg_w = a.seg_w;
+    for (int i = 0; i < a.nseg; ++i) {
+      if (!a.seg_out[i] || a.seg_rows_in[i] <= 0 || a.seg_ld[i] % 8 || !al(a.seg_out[i], 16)) return DF_EINVAL;
+      p.seg_out[i] = (bf16_t*)a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
+      p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
+    }
+  }
+  switch (tune_cfg()) {                                  // DF_WGEMM_CFG: tuning aid
+    case 1: return launch_cfg<1, 2, 4, 5>(p, st);
+    case 2: return launch_cfg<2, 2, 4, 5>(p, st);
+    case 3: return launch_cfg<1, 2, 4, 10>(p, st);
+    case 5: return launch_cfg<1, 2, 8, 5>(p, st);
+    default: break;
+  }
+  const int nfrag = Nout / 32;
+  if (!p.geglu && nfrag % 2) return launch_cfg<1, 1, 4, 5>(p, st);
+  // Measured on the patch step (kernel trace, cold weights): a wave tile of 32 tokens x 64 features keeps the most
+  // waves in flight and wins while the problem has few tiles; from ~320 workgroups on, the 64 x 64 tile's lower
+  // operand traffic per flop wins.
+  const long long wg12 = (long long)((a.M + 31) / 32) * (p.geglu ? nfrag : nfrag / 2);
+  if (wg12 >= 320) return launch_cfg<2, 2, 4, 5>(p, st);
+  return launch_cfg<1, 2, 4, 5>(p, st);
+}
+
+}  // namespace df

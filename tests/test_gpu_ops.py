@@ -303,3 +303,75 @@ def test_linear(M, N, K, out_f32, res):
     y2 = df.linear(dev(x, True), dev(w, True), dev(b), dev(r) if res else None,
                    out_dtype=torch.float32 if out_f32 else torch.bfloat16)
     np.testing.assert_array_equal(host(y), host(y2))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# linear layers on fragment-packed operands
+# ---------------------------------------------------------------------------------------------------------------
+
+def unpack_rows(packed, M, K):
+    """Decodes the packed layout documented in include/distrifusion.h: fragments [ceil(M/32)][K/16][64][8]; slot l of
+    fragment (rt, kf) holds row rt*32 + l%32, columns kf*16 + 8*(l/32) .. +7."""
+    MT, KF = (M + 31) // 32, K // 16
+    a = packed.reshape(MT, KF, 2, 32, 8)                 # [rt, kf, l/32, l%32, e]
+    full = a.transpose(0, 3, 1, 2, 4).reshape(MT * 32, K)
+    return full[:M], full[M:]
+
+
+def test_pack_rows_layout():
+    M, K = 77, 96
+    say("pack_rows", M, K)
+    x = round_bf16(normal(40, "x", (M, K)))
+    p = host(df.pack_rows(dev(x, True)))
+    got, pad = unpack_rows(p, M, K)
+    np.testing.assert_array_equal(got, x)
+    assert not pad.any()                                 # rows beyond M are zero
+
+
+@pytest.mark.parametrize("M,N,K,variant", [
+    (300, 1280, 1280, "plain"),        # level-2 projection of the patch step, 10 ragged token fragments
+    (300, 1280, 5120, "plain"),        # feed-forward output (deep K)
+    (77, 64, 128, "plain"),            # fewer k-steps per wave than the prefetch depth
+    (33, 96, 192, "plain"),            # odd number of 32-feature fragments
+    (300, 384, 256, "ln"),             # LayerNorm folded into the layer
+    (300, 2560, 320, "geglu"),         # value * gelu(gate)
+    (130, 512, 128, "ln_geglu"),
+    (1200, 640, 640, "plain"),
+])
+def test_linear_packed(M, N, K, variant):
+    say("linear_packed", M, N, K, variant)
+    x = round_bf16(normal(41, "x", (M, K)) + 0.3)
+    w = round_bf16(normal(41, "w", (N, K), std=1.0 / math.sqrt(K)))
+    b = normal(41, "b", (N,), std=0.1)
+    geglu = "geglu" in variant
+    No = N // 2 if geglu else N
+    r = normal(41, "r", (M, No))
+    xp = df.pack_rows(dev(x, True))
+    if "ln" in variant:
+        gamma = 1.0 + 0.2 * normal(41, "g", (K,))
+        beta = 0.1 * normal(41, "be", (K,))
+        pre = ops.linear(ops.layernorm(x, gamma, beta, 1e-5), w, b)
+        # host-side fold in float64 from the bf16-rounded scaled weights, as the header defines it
+        wg = round_bf16(w * gamma[None, :].astype(np.float32))
+        ln_s = wg.astype(np.float64).sum(1)
+        ln_t = w.astype(np.float64) @ beta.astype(np.float64) + b
+        wp = df.pack_linear_weight(dev(w, True), dev(gamma.astype(np.float32)))
+        kw = dict(ln_s=dev(ln_s.astype(np.float32)), ln_t=dev(ln_t.astype(np.float32)), ln_eps=1e-5)
+    else:
+        pre = ops.linear(x, w, b)
+        wp = df.pack_linear_weight(dev(w, True))
+        kw = dict(bias=dev(b))
+    ref = ops.geglu(pre) if geglu else pre
+    ref = ref + r
+    rd = dev(r)
+    outs = df.linear_packed(xp, wp, M, N, K, residual=rd, geglu=geglu, want=("f32", "packed", "rows"), **kw)
+    tol32 = 1e-2 if "ln" in variant else 2e-3           # folded norm: weights rounded after scaling by gamma
+    e = rel_l2(host(outs["f32"]), ref)
+    say("   rel_l2 f32", e)
+    assert e < tol32
+    assert rel_l2(host(outs["rows"]), ref) < TOL_BF16
+    got, _ = unpack_rows(host(outs["packed"]), M, No)
+    np.testing.assert_array_equal(got, host(outs["rows"]))       # both bf16 outputs round the same float
+    # determinism and in-place residual
+    outs2 = df.linear_packed(xp, wp, M, N, K, residual=rd, geglu=geglu, want=("f32",), **kw)
+    np.testing.assert_array_equal(host(outs["f32"]), host(outs2["f32"]))

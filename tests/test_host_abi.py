@@ -41,7 +41,7 @@ def test_plan_sizes_and_validation():
     # stale state: K and V of 70 self-attention layers dominate
     kv = 2 * 2 * (10 * 9600 * 640 + 60 * 2400 * 1280)
     assert kv < ss < kv * 1.2
-    assert 100e6 < ws < 8e9
+    assert 100e6 < ws < 12e9     # arena + two packings (tiled, fragment) of the transformer weights
     bad = df.make_cfg(ut.UNetCfg(H=160, W=240, N=7, **ut.SDXL))       # rows not divisible by the patch count
     assert L.df_unet_num_weights(ctypes.byref(bad)) == -2
     assert L.df_unet_workspace_bytes(ctypes.byref(bad)) == 0
