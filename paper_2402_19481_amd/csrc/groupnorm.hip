@@ -11,6 +11,7 @@
 //                x comes from L2 / Infinity Cache at the sizes of one patch.
 // A lane keeps a fixed channel offset for its whole strip, so gamma/beta and
 // the statistics are fetched once per lane.
+#include <cstdlib>
 #include "kernels.h"
 
 namespace df {
@@ -18,6 +19,31 @@ namespace df {
 namespace {
 
 constexpr int kMaxG = 64;
+constexpr long long kGnGroupMaxElems = 80 * 1024;   // per (group, batch item): above this the three-kernel path
+
+struct GnHalo {
+  bf16_t* out;      // nullptr: no boundary-row copy
+  int W, rpp, patch0, npatch;
+};
+
+// stores 4 or 8 bf16 values of pixel p (within its batch item), channels c0.., into the boundary-row state if the
+// pixel lies on the first or last row of its patch
+template <int V>
+__device__ __forceinline__ void halo_store(const GnHalo& h, int b, long long p, int C, int c0, const float* v) {
+  const int row = (int)(p / h.W), col = (int)(p - (long long)row * h.W);
+  const int pr = row % h.rpp, patch = h.patch0 + row / h.rpp;
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    if (pr != (which ? h.rpp - 1 : 0)) continue;
+    bf16_t* o = h.out + ((((long long)b * h.npatch + patch) * 2 + which) * h.W + col) * C + c0;
+    if constexpr (V == 8) {
+      st_vec(o, v);
+    } else {
+      u32x2 t = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])};
+      *reinterpret_cast<u32x2*>(o) = t;
+    }
+  }
+}
 
 struct GnLayout {
   int tp;        // lanes per pixel (C / vec)
@@ -82,6 +108,43 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
   if (tid < G) { my[2 * tid] = s_sum[tid]; my[2 * tid + 1] = s_sq[tid]; }
 }
 
+// Mean and variance of one (batch item, group) from the fresh sums of this launch and the cached per-patch sums,
+// according to the statistic mode (Section 4, Eq. 2; Section 5.3).
+__device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
+                                           const float* __restrict__ stale, int b, int g, int B, int G, int patch_idx,
+                                           float& mean, float& var) {
+  if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
+    // the whole image is fresh: exact statistics
+    const float n = n_loc * (float)nseg;
+    mean = tot_s / n;
+    var = fmaxf(tot_q / n - mean * mean, 0.f);
+    return;
+  }
+  const float n_glob = n_loc * (float)N;
+  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  for (int j = 0; j < N; ++j) {
+    const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
+    const float a = sp[0], c = sp[1];
+    if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
+  }
+  const float loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
+  if (stat_mode == DF_GN_SUMS) {
+    mean = (tot_s + st_s) / n_glob;
+    var = fmaxf((tot_q + st_q) / n_glob - mean * mean, 0.f);
+  } else if (stat_mode == DF_GN_EQ2) {
+    mean = (st_s + own_s) / n_glob + (loc_m - own_s / n_loc);
+    const float m2 = (st_q + own_q) / n_glob + (loc_m2 - own_q / n_loc);
+    var = m2 - mean * mean;
+    if (var < 0.f) var = loc_m2 - loc_m * loc_m;
+  } else if (stat_mode == DF_GN_SEPARATE) {
+    mean = loc_m;
+    var = fmaxf(loc_m2 - loc_m * loc_m, 0.f);
+  } else {
+    mean = (st_s + own_s) / n_glob;
+    var = fmaxf((st_q + own_q) / n_glob - mean * mean, 0.f);
+  }
+}
+
 // One workgroup per batch item: adds the partials in a fixed order, emits the fresh per-patch sums, combines them with
 // the stale sums of the other patches according to the statistic mode and stores mean / rstd.  A separate launch
 // instead of a "last workgroup" epilogue: the device-scope fences that pattern needs cost more than the launch.
@@ -122,38 +185,8 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
     __syncthreads();
   }
   if (part != 0) return;
-  const float n_loc = (float)pix_seg * (float)cg;
   float mean, var;
-  if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
-    // the whole image is fresh: exact statistics
-    const float n = n_loc * (float)nseg;
-    mean = tot_s / n;
-    var = fmaxf(tot_q / n - mean * mean, 0.f);
-  } else {
-    const float n_glob = n_loc * (float)N;
-    float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
-    for (int j = 0; j < N; ++j) {
-      const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
-      const float a = sp[0], c = sp[1];
-      if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
-    }
-    const float loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
-    if (stat_mode == DF_GN_SUMS) {
-      mean = (tot_s + st_s) / n_glob;
-      var = fmaxf((tot_q + st_q) / n_glob - mean * mean, 0.f);
-    } else if (stat_mode == DF_GN_EQ2) {
-      mean = (st_s + own_s) / n_glob + (loc_m - own_s / n_loc);
-      const float m2 = (st_q + own_q) / n_glob + (loc_m2 - own_q / n_loc);
-      var = m2 - mean * mean;
-      if (var < 0.f) var = loc_m2 - loc_m * loc_m;
-    } else if (stat_mode == DF_GN_SEPARATE) {
-      mean = loc_m;
-      var = fmaxf(loc_m2 - loc_m * loc_m, 0.f);
-    } else {
-      mean = (st_s + own_s) / n_glob;
-      var = fmaxf((st_q + own_q) / n_glob - mean * mean, 0.f);
-    }
-  }
+  gn_combine(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, stale, b, g, B, G, patch_idx, mean, var);
   if (nseg == 1 && sums_out != nullptr) {  // written after the stale sums were read: may alias the own slot
     float* o = sums_out + ((long long)b * G + g) * 2;
     o[0] = tot_s; o[1] = tot_q;
@@ -166,7 +199,7 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
 template <typename Tin, typename Tout>
 __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const float* __restrict__ meanrstd,
                          const float* __restrict__ gamma, const float* __restrict__ beta, int pix_b, int C, int G,
-                         int tp, int ppb, int pix_per_blk, int silu, int packed) {
+                         int tp, int ppb, int pix_per_blk, int silu, int packed, GnHalo halo) {
   constexpr int V = Elem<Tin>::kVec;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
@@ -208,6 +241,108 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
       u32x2 t = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])};
       *reinterpret_cast<u32x2*>(o) = t;
     }
+    if constexpr (sizeof(Tout) == 2) {
+      if (halo.out) halo_store<V>(halo, b, p, C, c0, v);
+    }
+  }
+}
+
+// Small tensors (the patch at the deeper levels): one workgroup per (group, batch item) does the whole GroupNorm in
+// one launch - sums over the group's channels of every pixel, ordered fold, statistic combination, then the
+// normalisation on a second read that hits L2.  Groups are independent, so no workgroup waits for another.
+template <typename Tin, typename Tout>
+__global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ x, Tout* __restrict__ y,
+                                                        const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                        int pix_seg, int C, int G, int nseg, int B, int patch_idx, int N,
+                                                        float eps, int stat_mode, int silu, int packed, GnHalo halo) {
+  __shared__ float s_s[1024], s_q[1024];
+  __shared__ float s_mr[2];
+  const int g = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int cg = C / G, cgv = cg >> 2;              // channel vectors of 4 per group
+  const int ppass = blockDim.x / cgv;               // pixels per pass
+  const int cv = tid % cgv, psub = tid / cgv;
+  const bool active = psub < ppass;
+  const int c0 = g * cg + cv * 4;
+  float tot_s = 0.f, tot_q = 0.f;
+  for (int sg = 0; sg < nseg; ++sg) {
+    const long long base = ((long long)b * nseg + sg) * pix_seg;
+    float a = 0.f, q = 0.f;
+    if (active)
+      for (int p = psub; p < pix_seg; p += ppass) {
+        float v[4];
+        const Tin* src = x + (base + p) * C + c0;
+        if constexpr (sizeof(Tin) == 4) {
+          ld_vec(src, v);
+        } else {
+          const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+          v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+          v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a += v[i]; q = fmaf(v[i], v[i], q); }
+      }
+    s_s[tid] = a; s_q[tid] = q;
+    __syncthreads();
+    if (tid < 64) {                                  // ordered fold: strided serial sums, then a fixed butterfly
+      float fs = 0.f, fq = 0.f;
+      for (int k = lane; k < (int)blockDim.x; k += 64) { fs += s_s[k]; fq += s_q[k]; }
+      fs = wave_sum(fs); fq = wave_sum(fq);
+      tot_s += fs; tot_q += fq;
+      if (nseg > 1 && lane == 0) {
+        float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
+        o[0] = fs; o[1] = fq;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    float mean, var;
+    gn_combine(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, stale, b, g, B, G, patch_idx, mean, var);
+    if (nseg == 1 && sums_out != nullptr) {          // after the stale sums were read: may alias the own slot
+      float* o = sums_out + ((long long)b * G + g) * 2;
+      o[0] = tot_s; o[1] = tot_q;
+    }
+    s_mr[0] = mean;
+    s_mr[1] = 1.0f / sqrtf(var + eps);
+  }
+  __syncthreads();
+  if (!active) return;
+  const float mean = s_mr[0], rstd = s_mr[1];
+  float sc[4], sh[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sc[i] = rstd * gamma[c0 + i];
+    sh[i] = beta[c0 + i] - mean * sc[i];
+  }
+  const long long pix_b = (long long)pix_seg * nseg;
+  const long long base = (long long)b * pix_b;
+  for (long long p = psub; p < pix_b; p += ppass) {
+    float v[4];
+    const Tin* src = x + (base + p) * C + c0;
+    if constexpr (sizeof(Tin) == 4) {
+      ld_vec(src, v);
+    } else {
+      const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+      v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+      v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float t = fmaf(v[i], sc[i], sh[i]);
+      v[i] = silu ? silu_f(t) : t;
+    }
+    const long long m = base + p;
+    Tout* o = y + m * C + c0;
+    if (packed) o = y + (((m >> 5) * (C >> 4) + (c0 >> 4)) * 64 + (m & 31) + 32 * ((c0 >> 3) & 1)) * 8 + (c0 & 7);
+    if constexpr (sizeof(Tout) == 4) {
+      st_vec(o, v);
+    } else {
+      u32x2 t = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])};
+      *reinterpret_cast<u32x2*>(o) = t;
+      if (halo.out) halo_store<4>(halo, b, p, C, c0, v);
+    }
   }
 }
 
@@ -240,7 +375,34 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   if (a.B > 1024) return DF_ESHAPE;
   if (a.y_packed && (a.out_dtype != DF_BF16 || a.C % 16)) return DF_ESHAPE;
   const long long pix_seg = (long long)a.Rseg * a.W;
+  GnHalo halo = {};
+  if (a.halo_out) {
+    if (a.out_dtype != DF_BF16 || a.y_packed || a.halo_rpp <= 0 || ((long long)a.Rseg * a.nseg) % a.halo_rpp ||
+        a.halo_patch0 < 0 || a.halo_patch0 + (a.Rseg * a.nseg) / a.halo_rpp > a.halo_npatch || ((uintptr_t)a.halo_out % 16))
+      return DF_EINVAL;
+    halo.out = (bf16_t*)a.halo_out; halo.W = a.W; halo.rpp = a.halo_rpp; halo.patch0 = a.halo_patch0;
+    halo.npatch = a.halo_npatch;
+  }
   if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
+  // small tensors: the whole GroupNorm in one launch, one workgroup per (group, batch item)
+  {
+    const int cg = a.C / a.G;
+    const long long per_group = pix_seg * a.nseg * cg;
+    static const bool no_fused = getenv("DF_GN_3K") != nullptr;   // tuning aid
+    if (!no_fused && cg % 4 == 0 && cg / 4 <= 1024 && per_group <= kGnGroupMaxElems) {
+      dim3 grid(a.G, a.B);
+#define DF_GN_GROUP(TI, TO)                                                                                         \
+  hipLaunchKernelGGL((gn_group_kernel<TI, TO>), grid, dim3(1024), 0, st, (const TI*)a.x, (TO*)a.y, a.stale, a.sums_out, \
+                     a.gamma, a.beta, (int)pix_seg, a.C, a.G, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode, a.silu, \
+                     a.y_packed, halo)
+      if (a.in_dtype == DF_BF16) DF_GN_GROUP(bf16_t, bf16_t);
+      else if (a.out_dtype == DF_BF16) DF_GN_GROUP(float, bf16_t);
+      else DF_GN_GROUP(float, float);
+#undef DF_GN_GROUP
+      DF_LAUNCH_CHECK();
+      return DF_OK;
+    }
+  }
   // up to 512 partial blocks per batch item: the finalize workgroup folds them with 32 lanes per group
   int target = 512 / a.nseg;
   if (target < 1) target = 1;
@@ -267,13 +429,13 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   dim3 ga(A.nblk, a.B);
   if (a.in_dtype == DF_BF16) {
     hipLaunchKernelGGL((gn_apply<bf16_t, bf16_t>), ga, dim3(A.threads), 0, st, (const bf16_t*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
   } else if (a.out_dtype == DF_BF16) {
     hipLaunchKernelGGL((gn_apply<float, bf16_t>), ga, dim3(A.threads), 0, st, (const float*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
+                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
   } else {
     hipLaunchKernelGGL((gn_apply<float, float>), ga, dim3(A.threads), 0, st, (const float*)a.x, (float*)a.y, meanrstd,
-                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed);
+                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
   }
   DF_LAUNCH_CHECK();
   return DF_OK;

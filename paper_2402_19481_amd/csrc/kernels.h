@@ -33,6 +33,11 @@ struct GnArgs {
   float eps;
   int stat_mode, silu;
   int in_dtype, out_dtype;
+  // optional copy of the boundary rows of y (bf16 output, row-major y only) into the stale state of the convolution
+  // that consumes y: [B, halo_npatch, 2, W, C]; pixel row r belongs to patch halo_patch0 + r / halo_rpp and is stored
+  // as that patch's first (r % halo_rpp == 0) and / or last (== halo_rpp - 1) row
+  void* halo_out;
+  int halo_rpp, halo_patch0, halo_npatch;
   int y_packed;         // bf16 output in the fragment-packed layout of wgemm.hip (rows = B*rows*W pixels, K = C)
 };
 int launch_groupnorm(const GnArgs& a, hipStream_t st);

@@ -389,7 +389,7 @@ struct Exec {
   }
 
   void groupnorm(const std::string& name, const void* x, int in_dtype, int level_rows, int W, int C, float eps, int silu,
-                 bf16_t* y, int y_packed = 0) {
+                 bf16_t* y, int y_packed = 0, bf16_t* halo_entry = nullptr) {
     // level_rows: rows of x in this mode
     const int G = c.groups;
     float* entry = (float*)stale_buf(name + ".stats", (size_t)N() * B() * G * 2 * sizeof(float));
@@ -403,6 +403,12 @@ struct Exec {
     a.B = B(); a.W = W; a.C = C; a.G = G; a.eps = eps; a.silu = silu; a.in_dtype = in_dtype; a.out_dtype = DF_BF16;
     a.stat_mode = DF_GN_SUMS;
     a.y_packed = y_packed;
+    if (halo_entry && (full() || refresh)) {
+      // the consumer convolution's boundary-row state is refreshed by this kernel's store loop
+      a.halo_out = halo_entry; a.halo_npatch = N();
+      a.halo_rpp = full() ? level_rows / N() : level_rows;
+      a.halo_patch0 = full() ? 0 : patch;
+    }
     if (full()) {
       a.nseg = N(); a.Rseg = level_rows / N(); a.N = 1; a.patch_idx = 0; a.stale = nullptr; a.sums_out = entry;
     } else {
@@ -414,10 +420,15 @@ struct Exec {
   }
 
   // x: bf16 [B, R, W, Cin] rows of this mode; out: [B, R/stride, W/stride, Cout]
+  bf16_t* conv_entry(const std::string& name, int W, int Cin) {
+    return (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * (size_t)W * Cin * sizeof(bf16_t));
+  }
+  // `entry_in` non-null: the stale entry was looked up by the caller and the producer of x has already refreshed it
   void conv(const std::string& name, const bf16_t* x, int R, int W, int Cin, int Cout, int stride, void* out,
-            int out_dtype, const float* chan_add, const float* residual) {
+            int out_dtype, const float* chan_add, const float* residual, bf16_t* entry_in = nullptr,
+            bool halo_done = false) {
     const size_t rowe = (size_t)W * Cin;
-    bf16_t* entry = (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * rowe * sizeof(bf16_t));
+    bf16_t* entry = halo_done ? entry_in : conv_entry(name, W, Cin);
     const void* wt = weight(name + ".w");
     const float* bias = (const float*)weight(name + ".b");
     {
@@ -441,7 +452,7 @@ struct Exec {
             2.0 * B() * (R + halo) * rowe + 2.0 * 9 * Cin * Cout + opx * Cout * (out_dtype == DF_BF16 ? 2.0 : 4.0),
             [&] { return launch_conv3x3(a, st); });
     }
-    if (!live()) return;
+    if (!live() || halo_done) return;
     const long long rb = (long long)rowe * sizeof(bf16_t);
     if (full()) {
       const int Rp = R / N();
@@ -467,10 +478,13 @@ struct Exec {
     bf16_t* h1 = (bf16_t*)alloc(px * b.cout * 2);
     bf16_t* a2 = (bf16_t*)alloc(px * b.cout * 2);
     float* embp = (float*)alloc((size_t)B() * b.cout * 4);
-    groupnorm(b.name + ".gn1", x, DF_F32, R, W, b.cin, 1e-5f, 1, a1);
+    bf16_t* e1 = conv_entry(b.name + ".conv1", W, b.cin);
+    bf16_t* e2 = conv_entry(b.name + ".conv2", W, b.cout);
+    const bool hd = dry || e1 != nullptr;      // the GroupNorm kernels refresh the boundary rows of the convolutions
+    groupnorm(b.name + ".gn1", x, DF_F32, R, W, b.cin, 1e-5f, 1, a1, 0, e1);
     gemm(emb_act, c.emb_dim, b.name + ".emb", true, nullptr, 0, embp, b.cout, B(), b.cout, c.emb_dim, DF_F32);
-    conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr);
-    groupnorm(b.name + ".gn2", h1, DF_BF16, R, W, b.cout, 1e-5f, 1, a2);
+    conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr, e1, hd);
+    groupnorm(b.name + ".gn2", h1, DF_BF16, R, W, b.cout, 1e-5f, 1, a2, 0, e2);
     const float* residual = x;
     if (b.cin != b.cout) {
       bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
@@ -478,7 +492,7 @@ struct Exec {
       gemm(xb, b.cin, b.name + ".sc", true, nullptr, 0, out, b.cout, (int)px, b.cout, b.cin, DF_F32);
       residual = out;
     }
-    conv(b.name + ".conv2", a2, R, W, b.cout, b.cout, 1, out, DF_F32, nullptr, residual);
+    conv(b.name + ".conv2", a2, R, W, b.cout, b.cout, 1, out, DF_F32, nullptr, residual, e2, hd);
     top = mark;
   }
 
