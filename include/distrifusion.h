@@ -201,6 +201,14 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
                        void* eps_out, int patch_idx, int mode, int refresh, void* stream);
 
 /*
+ * GroupNorm statistic mode of the DISPLACED steps (Section 4, Eq. 2; Section 5.3 compares the corrected
+ * asynchronous GroupNorm with "Separate GN" and "Stale GN"): one of DF_GN_*, default DF_GN_SUMS.  FULL steps always
+ * use the exact statistics of the whole image.  Warm-up steps (Section 4: a few synchronous steps before the
+ * displaced ones) need no entry point of their own: the caller runs DF_MODE_FULL for them.
+ */
+int df_unet_set_gn_mode(df_unet* u, int stat_mode);
+
+/*
  * df_patch_unet_step records the launches of a step into a HIP graph the second time it sees the same call (mode,
  * patch, refresh, stream and all pointers equal) and replays the graph from then on (Section 5.1 uses CUDAGraph for
  * the same purpose).  Calls on the legacy default stream (stream == 0) and calls made while per-launch timing is on
@@ -224,6 +232,10 @@ int df_unet_profile_read(df_unet* u, int cls, double* ms, double* flops, double*
 
 /* Sampler update on the patch's latent rows (Section 3, Eq. 1; Euler step): x += (sigma_next - sigma) * eps. */
 int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream);
+
+/* Input scaling of the noise predictor on the sigma ladder of the Euler sampler (Section 3, Eq. 1: the model is
+ * evaluated on the current noisy latent): y = x / sqrt(sigma^2 + 1).  y may alias x. */
+int df_scale_input(float* y, const float* x, float sigma, long long n, void* stream);
 
 /* Plain device-to-device copy of `bytes` bytes with the refresh kernel (bandwidth calibration). */
 int df_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);

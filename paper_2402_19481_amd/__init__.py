@@ -52,6 +52,7 @@ def lib():
     L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.df_scale_input.argtypes = [vp, vp, f, ll, vp]
     L.df_packed_bytes.restype = sz
     L.df_packed_bytes.argtypes = [ll, ll]
     L.df_pack_rows.argtypes = [vp, vp, i, i, vp]
@@ -75,6 +76,7 @@ def lib():
     L.df_patch_unet_step.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp]
     L.df_unet_profile_enable.argtypes = [vp, i]
     L.df_unet_set_graph.argtypes = [vp, i]
+    L.df_unet_set_gn_mode.argtypes = [vp, i]
     L.df_unet_profile_reset.argtypes = [vp]
     L.df_unet_profile_num_classes.argtypes = []
     L.df_unet_profile_class_name.argtypes = [i]
@@ -82,7 +84,7 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
-                 "df_euler_update", "df_linear", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
                  "df_unet_profile_enable", "df_unet_set_graph", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
@@ -171,6 +173,14 @@ def linear(x, w, bias=None, residual=None, out_dtype=torch.bfloat16, out=None):
     if out is None:
         out = torch.empty(M, N, dtype=out_dtype, device=x.device)
     _check(lib().df_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), M, N, K, _dt(out), _stream()))
+    return out
+
+
+def scale_input(x, sigma, out=None):
+    """x / sqrt(sigma^2 + 1): the sampler's scaling of the model input."""
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().df_scale_input(_ptr(out), _ptr(x), float(sigma), x.numel(), _stream()))
     return out
 
 
@@ -275,6 +285,34 @@ class PatchUNet:
         _check(lib().df_patch_unet_step(self.handle, _ptr(x), _ptr(emb), _ptr(text), self.stale.data_ptr(), _ptr(out),
                                         patch_idx, mode, int(refresh), _stream()))
         return out
+
+    def set_gn_mode(self, stat_mode):
+        """GroupNorm statistic mode of the displaced steps (GN_SUMS default, GN_EQ2, GN_SEPARATE, GN_STALE)."""
+        _check(lib().df_unet_set_gn_mode(self.handle, int(stat_mode)))
+
+    def sample_patch(self, x_full, emb, text, sigmas, patch_idx, n_warmup=1):
+        """Euler sampling loop of one device: `n_warmup` synchronous steps on the whole latent (they fill the stale
+        state; the paper runs the first steps this way), then displaced steps that advance the rows of patch
+        `patch_idx` only and refresh its slots of the stale state.  x_full [B,H,W,4] float is updated in place (all rows
+        during warm-up, then the patch's rows); every arithmetic step runs in the library.  Returns the list of the
+        per-step eps tensors (full image for warm-up steps, patch rows afterwards)."""
+        B, H, W, C = x_full.shape
+        R = H // self.cfg.N
+        rows = slice(patch_idx * R, (patch_idx + 1) * R)
+        eps_all = []
+        for k in range(len(sigmas) - 1):
+            s0, s1 = float(sigmas[k]), float(sigmas[k + 1])
+            if k < n_warmup:
+                eps = self.step(scale_input(x_full, s0), emb, text, 0, MODE_FULL, True)
+                euler_update(x_full, eps, s0, s1)
+            else:
+                xp = x_full[:, rows].contiguous()          # the patch's rows (a view when B == 1)
+                eps = self.step(scale_input(xp, s0), emb, text, patch_idx, MODE_DISPLACED, True)
+                euler_update(xp, eps, s0, s1)
+                if xp.data_ptr() != x_full[:, rows].data_ptr():
+                    buffer_refresh(x_full, xp, patch_idx, self.cfg.N)
+            eps_all.append(eps)
+        return eps_all
 
     def set_graph(self, on):
         """Switches HIP-graph replay of repeated steps on (default) or off."""

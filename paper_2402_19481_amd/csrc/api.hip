@@ -145,6 +145,12 @@ int df_linear(const void* x, const void* w, const float* bias, const float* resi
   return launch_gemm_bf16(g, (hipStream_t)stream);
 }
 
+int df_scale_input(float* y, const float* x, float sigma, long long n, void* stream) {
+  if (!x || !y) return DF_EINVAL;
+  if (n < 0) return DF_ESHAPE;
+  return launch_scale(y, x, 1.0f / sqrtf(sigma * sigma + 1.0f), n, (hipStream_t)stream);
+}
+
 size_t df_packed_bytes(long long rows, long long K) { return rows > 0 && K > 0 ? packed_rows_bytes(rows, K) : 0; }
 
 int df_pack_rows(const void* x, void* packed, int M, int K, void* stream) {

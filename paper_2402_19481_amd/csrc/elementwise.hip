@@ -175,6 +175,18 @@ int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C
   return DF_OK;
 }
 
+__global__ void scale_kernel(float* __restrict__ y, const float* __restrict__ x, float alpha, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) y[i] = alpha * x[i];
+}
+
+int launch_scale(float* y, const float* x, float alpha, long long n, hipStream_t st) {
+  if (n <= 0) return DF_OK;
+  hipLaunchKernelGGL(scale_kernel, dim3(blocks_for(n)), dim3(256), 0, st, y, x, alpha, n);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
 int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st) {
   if (n <= 0) return DF_OK;
   hipLaunchKernelGGL(axpy_kernel, dim3(blocks_for(n)), dim3(256), 0, st, x, e, alpha, n);

@@ -244,7 +244,7 @@ struct PackedW {
 // out of the critical path (the counterpart of the paper's CUDAGraph use, Section 5.1).  A graph is tied to the
 // mode, patch, refresh flag, stream and every pointer of the call that recorded it.
 struct GraphEntry {
-  int mode, patch, refresh;
+  int mode, patch, refresh, gn_mode;
   const void *x, *emb, *text, *eps;
   void* stale;
   hipStream_t stream;
@@ -257,6 +257,7 @@ struct df_unet {
   df_unet_cfg cfg;
   Prof prof;
   bool use_graph = true;
+  int gn_mode = DF_GN_SUMS;      // statistic mode of the DISPLACED steps (df_unet_set_gn_mode)
   std::vector<GraphEntry> graphs;
   std::map<std::string, PackedW> packed;
   std::vector<BlockDesc> blocks;
@@ -296,6 +297,7 @@ struct Exec {
   int err = DF_OK;
   Prof* prof = nullptr;
   const std::map<std::string, PackedW>* packed = nullptr;
+  int gn_mode = DF_GN_SUMS;      // GroupNorm statistic mode of a DISPLACED step
   const bf16_t* kv_packed[4] = {nullptr, nullptr, nullptr, nullptr};
   int kv_count[4] = {0, 0, 0, 0};
   int kv_cursor[4] = {0, 0, 0, 0};
@@ -401,7 +403,7 @@ struct Exec {
     GnArgs a = {};
     a.x = x; a.y = y; a.gamma = gamma; a.beta = beta;
     a.B = B(); a.W = W; a.C = C; a.G = G; a.eps = eps; a.silu = silu; a.in_dtype = in_dtype; a.out_dtype = DF_BF16;
-    a.stat_mode = DF_GN_SUMS;
+    a.stat_mode = gn_mode;
     a.y_packed = y_packed;
     if (halo_entry && (full() || refresh)) {
       // the consumer convolution's boundary-row state is refreshed by this kernel's store loop
@@ -1133,6 +1135,7 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
     e.kv_packed[lv] = (const bf16_t*)(u->ws + u->kv_off[lv]);
   }
   e.packed = &u->packed;
+  e.gn_mode = u->gn_mode;
   e.stale_base = (char*)stale;
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;
@@ -1143,7 +1146,7 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
     return e.step((const float*)x, (const float*)emb, (const bf16_t*)text, (float*)eps_out);
   GraphEntry* ge = nullptr;
   for (GraphEntry& g : u->graphs)
-    if (g.mode == mode && g.patch == e.patch && g.refresh == e.refresh && g.x == x && g.emb == emb && g.text == text &&
+    if (g.mode == mode && g.patch == e.patch && g.refresh == e.refresh && g.gn_mode == e.gn_mode && g.x == x && g.emb == emb && g.text == text &&
         g.eps == eps_out && g.stale == stale && g.stream == st) { ge = &g; break; }
   if (!ge) {
     if (u->graphs.size() >= 64) {   // bound the cache: drop everything and start over
@@ -1151,7 +1154,7 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
       u->graphs.clear();
     }
     GraphEntry g;
-    g.mode = mode; g.patch = e.patch; g.refresh = e.refresh; g.x = x; g.emb = emb; g.text = text; g.eps = eps_out;
+    g.mode = mode; g.patch = e.patch; g.refresh = e.refresh; g.gn_mode = e.gn_mode; g.x = x; g.emb = emb; g.text = text; g.eps = eps_out;
     g.stale = stale; g.stream = st;
     u->graphs.push_back(g);
     ge = &u->graphs.back();
@@ -1179,6 +1182,12 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   if (ei != hipSuccess || !exec) return DF_EHIP;
   ge->exec = exec;
   return hipGraphLaunch(exec, st) == hipSuccess ? DF_OK : DF_EHIP;
+}
+
+int df_unet_set_gn_mode(df_unet* u, int stat_mode) {
+  if (!u || stat_mode < DF_GN_SUMS || stat_mode > DF_GN_STALE) return DF_EINVAL;
+  u->gn_mode = stat_mode;
+  return DF_OK;
 }
 
 int df_unet_set_graph(df_unet* u, int on) {

@@ -205,3 +205,69 @@ def test_graph_replay_matches_eager_launches():
             assert torch.equal(out.view(torch.int32), want.view(torch.int32)), rep
             assert torch.equal(net.stale, want_stale), rep
     net.close()
+
+
+@pytest.mark.parametrize("stat_mode", [df.GN_EQ2, df.GN_SEPARATE, df.GN_STALE])
+def test_small_unet_groupnorm_modes(stat_mode):
+    """The displaced step under the other GroupNorm statistic modes (the printed Eq. 2 and the two ablation variants of
+    Section 5.3) against the oracle run with the same mode, fresh input far from the stale one."""
+    H, W, N = 32, 16, 4
+    cfg = ut.UNetCfg(H=H, W=W, N=N, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=11, threads=8)
+    t = configs.unet_inputs(cfg, seed=11, stale_std=0.5)
+    bl = ut.blocks(cfg)
+    P = ounet.Params(weights)
+    ostale = {}
+    ounet.unet_step(cfg, bl, P, t["x_prev"], t["emb"], t["text"], ostale, mode=ounet.FULL)
+    net = df.PatchUNet(cfg, _upload(weights), B=1, device=DEV)
+    emb_d, text_d = dev(t["emb"]), dev(t["text"], True)
+    net.step(dev(t["x_prev"]), emb_d, text_d, mode=df.MODE_FULL)
+    net.set_gn_mode(stat_mode)
+    R, i = H // N, 2
+    xs = t["x"][:, i * R:(i + 1) * R]
+    o_mode = ounet.unet_step(cfg, bl, P, xs, t["emb"], t["text"], {k: v.copy() for k, v in ostale.items()}, i,
+                             ounet.DISPLACED, stat_mode=stat_mode)
+    o_sums = ounet.unet_step(cfg, bl, P, xs, t["emb"], t["text"], {k: v.copy() for k, v in ostale.items()}, i,
+                             ounet.DISPLACED, stat_mode=df.GN_SUMS)
+    g = net.step(dev(xs), emb_d, text_d, patch_idx=i, mode=df.MODE_DISPLACED, refresh=False)
+    e, far = rel_l2(host(g), o_mode), rel_l2(o_sums, o_mode)
+    say("  GroupNorm mode", stat_mode, "rel_l2", e, "(distance to the default mode's eps:", far, ")")
+    assert e < TOL_BF16 and far > 2 * TOL_BF16     # the modes differ by much more than the tolerance
+    with pytest.raises(df.DfError):
+        net.set_gn_mode(7)
+    net.close()
+
+
+def test_small_unet_sampling_loop_with_warmup():
+    """PatchUNet.sample_patch: two synchronous warm-up steps, then displaced steps on one patch, against the same loop
+    written with oracle calls (Section 4: warm-up steps precede the displaced ones)."""
+    import math
+    H, W, N, patch, n_warm = 16, 8, 2, 1, 2
+    cfg = ut.UNetCfg(H=H, W=W, N=N, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=13, threads=8)
+    t = configs.unet_inputs(cfg, seed=13)
+    bl = ut.blocks(cfg)
+    P = ounet.Params(weights)
+    sig = [3.0, 2.0, 1.2, 0.6, 0.2]
+    R = H // N
+    rows = slice(patch * R, (patch + 1) * R)
+    # oracle loop
+    xo = t["x_prev"].astype(np.float64) * sig[0]
+    ostale, eps_o = {}, []
+    for k in range(len(sig) - 1):
+        sc = 1.0 / math.sqrt(sig[k] ** 2 + 1)
+        if k < n_warm:
+            e = ounet.unet_step(cfg, bl, P, xo * sc, t["emb"], t["text"], ostale, mode=ounet.FULL)
+            xo = ounet.euler_update(xo, e, sig[k], sig[k + 1])
+        else:
+            e = ounet.unet_step(cfg, bl, P, xo[:, rows] * sc, t["emb"], t["text"], ostale, patch, ounet.DISPLACED)
+            xo[:, rows] = ounet.euler_update(xo[:, rows], e, sig[k], sig[k + 1])
+        eps_o.append(e)
+    net = df.PatchUNet(cfg, _upload(weights), B=1, device=DEV)
+    xg = dev(t["x_prev"].astype(np.float64) * sig[0])
+    eps_g = net.sample_patch(xg, dev(t["emb"]), dev(t["text"], True), sig, patch, n_warmup=n_warm)
+    drift = [rel_l2(host(a), b) for a, b in zip(eps_g, eps_o)]
+    say("  warm-up loop drift of eps per step:", ["%.4f" % d for d in drift])
+    assert max(drift) < TOL_BF16
+    assert rel_l2(host(xg)[:, rows], xo[:, rows]) < TOL_BF16
+    net.close()

@@ -111,3 +111,24 @@ def test_displaced_uses_stale_context_and_refresh_touches_own_rows_only():
 def test_euler_update():
     x = np.array([1.0, 2.0])
     np.testing.assert_allclose(unet.euler_update(x, np.array([0.5, -1.0]), 2.0, 1.5), [0.75, 2.5])
+
+
+def test_ablation_emulation_invariants():
+    """oracle/ablation.py emulates all N devices with the oracle.  Warm-up on every step is the synchronous run itself;
+    with stale == fresh state and unchanged input a displaced step of all patches reproduces the synchronous eps, so
+    one displaced step after an Euler step of size zero changes nothing."""
+    import numpy as np
+    from df_inputs import configs, unet_table as ut
+    from oracle import ablation, ops
+    cfg = ut.UNetCfg(H=16, W=8, N=2, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=5, threads=4)
+    t = configs.unet_inputs(cfg, seed=5)
+    sig = [2.0, 1.0, 0.5]
+    ref = ablation.run(cfg, weights, t, sig, 2, ops.STAT_SUMS)
+    assert np.array_equal(ablation.run(cfg, weights, t, sig, 5, ops.STAT_EQ2), ref)
+    # sigma ladder with a zero-size first step: the displaced second step sees exactly the state it was built from
+    flat = [2.0, 2.0, 1.0]
+    a = ablation.run(cfg, weights, t, flat, 2, ops.STAT_SUMS)
+    for mode in (ops.STAT_SUMS, ops.STAT_EQ2, ops.STAT_STALE):
+        b = ablation.run(cfg, weights, t, flat, 1, mode)
+        assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-9, mode
