@@ -115,6 +115,116 @@ def cpu_baseline(cfg, weights_dev, specs, inputs, patch):
                 sample="one DISPLACED step of the same configuration (float64 numpy oracle, zero-filled stale buffers)")
 
 
+def measured_mfma_peak(df, torch):
+    """TFLOP/s of the library's register-resident bf16 MFMA loop, timed with events on a side stream."""
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        df.mfma_probe(2048, 2048)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        fl = df.mfma_probe(2048, 8192)
+        e1.record(st)
+        e1.synchronize()
+    return round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+
+
+def run_ops(df, torch):
+    """Single operations at the shapes of configurations 2, 3 and 5 plus the two ceilings (register-resident MFMA
+    loop, plain copy).  Every case runs REP times back to back on a side stream; the time is the HIP-event span divided
+    by REP, so cases shorter than ~10 us are bounded by the host's launch rate - the committed rocprofv3 kernel trace
+    of this command has the per-kernel durations.  One JSON line per case."""
+    import math
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(2)
+    rn = lambda *sh, std=1.0: torch.randn(*sh, generator=g, device=dev) * std
+    bf = lambda t: t.to(torch.bfloat16).contiguous()
+    stream = torch.cuda.Stream()
+    REP = 20
+
+    def timed(name, fn, flops=None, nbytes=None, note=None):
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            e0.record(stream)
+            for _ in range(REP):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / REP
+        rec = {"op": name, "us": round(us, 2)}
+        if flops:
+            rec["tflops"] = round(flops / us / 1e6, 2)
+            rec["frac_of_bf16_mfma_peak"] = round(flops / us / 1e6 / 2500.0, 4)
+        if nbytes:
+            rec["gbs"] = round(nbytes / us / 1e3, 1)
+            rec["frac_of_hbm_peak"] = round(nbytes / us / 1e3 / 8000.0, 4)
+        if note:
+            rec["note"] = note
+        print(json.dumps(rec), flush=True)
+
+    # ceilings
+    fl = [0.0]
+    def probe():
+        fl[0] = df.mfma_probe(2048, 8192)
+    probe()
+    timed("mfma_probe_register_resident", probe, flops=fl[0])
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    big2 = torch.empty_like(big)
+    timed("copy_1GiB", lambda: df.copy_bytes(big2, big), nbytes=2.0 * big.numel())
+    del big, big2
+
+    # configuration 2: displaced self-attention layer, N=4, 1024 fresh of 4096 tokens, 10 heads x 64
+    Lq, L, C, heads = 1024, 4096, 640, 10
+    hid = bf(rn(1, Lq, C))
+    wq, wk, wv, wo = (bf(rn(C, C, std=1 / math.sqrt(C))) for _ in range(4))
+    ks, vs = bf(rn(1, L, C)), bf(rn(1, L, C))
+    q, kf, vf = bf(rn(1, Lq, C)), bf(rn(1, Lq, C)), bf(rn(1, Lq, C))
+    timed("cfg2_attention_core", lambda: df.attn_displaced(q, kf, vf, ks, vs, heads, 1, 4),
+          flops=4.0 * Lq * L * C, nbytes=2.0 * (2 * Lq * C + 2 * L * C))
+    def layer():
+        h2 = hid.view(Lq, C)
+        qq = df.linear(h2, wq).view(1, Lq, C)
+        kk = df.linear(h2, wk).view(1, Lq, C)
+        vv = df.linear(h2, wv).view(1, Lq, C)
+        o = df.attn_displaced(qq, kk, vv, ks, vs, heads, 1, 4)
+        return df.linear(o.view(Lq, C), wo)
+    timed("cfg2_self_attention_layer", layer, flops=4.0 * Lq * L * C + 2.0 * Lq * C * C * 4,
+          note="Q, K, V, out projections + attention core: 5 launches through the per-op entry points")
+
+    # configuration 3: GroupNorm -> conv3x3 -> SiLU on a 32-row patch of 128x128x320, N=4
+    R, H, W, Cc, G = 32, 128, 128, 320, 32
+    xg = bf(rn(1, R, W, Cc))
+    stats = rn(4, 1, G, 2).abs() * 1000
+    gam, bet = 1 + 0.1 * rn(Cc), 0.1 * rn(Cc)
+    wc = bf(rn(Cc, 3, 3, Cc, std=math.sqrt(2.0 / (9 * Cc))))
+    bc = 0.02 * rn(Cc)
+    stale_full = bf(rn(1, H, W, Cc))
+    timed("cfg3_groupnorm", lambda: df.groupnorm_stale(xg, stats, gam, bet, G, 1, 4), nbytes=2.0 * xg.numel() * 2)
+    timed("cfg3_conv3x3", lambda: df.conv3x3_halo(xg, stale_full, wc, bc, 1, 4, act=1),
+          flops=2.0 * 9 * Cc * Cc * R * W, nbytes=2.0 * ((R + 2) * W * Cc + 9 * Cc * Cc + R * W * Cc))
+    timed("cfg3_gn_conv_silu_chain",
+          lambda: df.conv3x3_halo(df.groupnorm_stale(xg, stats, gam, bet, G, 1, 4)[0], stale_full, wc, bc, 1, 4, act=1),
+          flops=2.0 * 9 * Cc * Cc * R * W)
+
+    # configuration 5: the largest GroupNorm (64 x 256 x 960 bf16 = 31.5 MB) and one step's K/V refresh volume
+    x5 = bf(rn(1, 64, 256, 960))
+    st5 = rn(4, 1, G, 2).abs() * 1000
+    g5, b5 = 1 + 0.1 * rn(960), 0.1 * rn(960)
+    timed("cfg5_groupnorm_31MB", lambda: df.groupnorm_stale(x5, st5, g5, b5, G, 1, 4), nbytes=2.0 * x5.numel() * 2)
+    full = torch.empty(1, 4 * 52_428_800, dtype=torch.bfloat16, device=dev)     # 0.42 GB: K/V of one step, one patch of 4
+    part = torch.empty(1, 52_428_800, dtype=torch.bfloat16, device=dev)
+    timed("cfg5_refresh_105MB_slice", lambda: df.buffer_refresh(full, part, 1, 4), nbytes=2.0 * part.numel() * 2)
+    # level-2 patch GEMMs of configuration 4 on packed operands
+    for (M, N, K, gg) in [(300, 1280, 1280, False), (300, 3840, 1280, False), (300, 1280, 5120, False), (300, 10240, 1280, True)]:
+        wp = df.pack_linear_weight(bf(rn(N, K, std=1 / math.sqrt(K))))
+        xp = df.pack_rows(bf(rn(M, K)))
+        timed("cfg4_linear_packed_%dx%dx%d%s" % (M, N, K, "_geglu" if gg else ""),
+              lambda: df.linear_packed(xp, wp, M, N, K, geglu=gg, want=("packed",)), flops=2.0 * M * N * K,
+              nbytes=2.0 * (M * K + N * K + M * (N // 2 if gg else N)), note="weights stay hot in L2 / Infinity Cache")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +234,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly (no HIP graph replay)")
     ap.add_argument("--small", action="store_true", help="reduced-width UNet (plumbing check, not the benchmark)")
+    ap.add_argument("--ops", action="store_true",
+                    help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -137,6 +249,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.ops:
+        run_ops(df, torch)
+        return
     if args.small:
         cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
         patch = 1
@@ -226,6 +341,8 @@ def main():
         "tflops": round(tflop / (ms * 1e-3), 2),
         "mfma_util_frac_of_bf16_peak": round(tflop / (ms * 1e-3) / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
+        # ceiling measured in this run: register-resident MFMA loop (nominal dense bf16 peak is 2500 TFLOP/s)
+        "mfma_peak_measured_tflops": measured_mfma_peak(df, torch),
         # the other parts of the headline metric: MFMA utilisation of attention and convolution, GroupNorm / refresh GB/s
         "attn_mfma_util_frac": round((breakdown.get("self_attn", {}).get("tflops") or 0.0) / PEAK_BF16_TFLOPS, 4),
         "conv_mfma_util_frac": round((breakdown.get("conv3x3", {}).get("tflops") or 0.0) / PEAK_BF16_TFLOPS, 4),

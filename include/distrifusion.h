@@ -237,6 +237,11 @@ int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, l
  * evaluated on the current noisy latent): y = x / sqrt(sigma^2 + 1).  y may alias x. */
 int df_scale_input(float* y, const float* x, float sigma, long long n, void* stream);
 
+/* Measurement support: `blocks` workgroups of four waves each issue `iters` x 4 register-resident bf16 MFMAs
+ * (32x32x16, four independent accumulators); *flops receives the operation count.  `out` needs `blocks` floats and
+ * is not written.  The achieved rate is the matrix-pipe ceiling the kernels are compared with besides the nominal one. */
+int df_mfma_probe(float* out, int blocks, int iters, double* flops, void* stream);
+
 /* Plain device-to-device copy of `bytes` bytes with the refresh kernel (bandwidth calibration). */
 int df_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
 

@@ -53,6 +53,7 @@ def lib():
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.df_scale_input.argtypes = [vp, vp, f, ll, vp]
+    L.df_mfma_probe.argtypes = [vp, i, i, ctypes.POINTER(ctypes.c_double), vp]
     L.df_packed_bytes.restype = sz
     L.df_packed_bytes.argtypes = [ll, ll]
     L.df_pack_rows.argtypes = [vp, vp, i, i, vp]
@@ -84,7 +85,7 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
-                 "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_mfma_probe", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
                  "df_unet_profile_enable", "df_unet_set_graph", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
@@ -174,6 +175,14 @@ def linear(x, w, bias=None, residual=None, out_dtype=torch.bfloat16, out=None):
         out = torch.empty(M, N, dtype=out_dtype, device=x.device)
     _check(lib().df_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), M, N, K, _dt(out), _stream()))
     return out
+
+
+def mfma_probe(blocks=2048, iters=4096):
+    """Launches the register-resident MFMA loop; returns its flop count (time it with events)."""
+    out = torch.empty(blocks, dtype=torch.float32, device="cuda")
+    fl = ctypes.c_double()
+    _check(lib().df_mfma_probe(_ptr(out), blocks, iters, ctypes.byref(fl), _stream()))
+    return fl.value
 
 
 def scale_input(x, sigma, out=None):

@@ -145,6 +145,12 @@ int df_linear(const void* x, const void* w, const float* bias, const float* resi
   return launch_gemm_bf16(g, (hipStream_t)stream);
 }
 
+int df_mfma_probe(float* out, int blocks, int iters, double* flops, void* stream) {
+  if (!out) return DF_EINVAL;
+  if (flops) *flops = (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16);
+  return launch_mfma_probe(out, blocks, iters, (hipStream_t)stream);
+}
+
 int df_scale_input(float* y, const float* x, float sigma, long long n, void* stream) {
   if (!x || !y) return DF_EINVAL;
   if (n < 0) return DF_ESHAPE;

@@ -175,6 +175,29 @@ int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C
   return DF_OK;
 }
 
+// Register-resident MFMA loop: what the matrix pipes deliver when nothing else is in the way (measurement support).
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ out, int iters) {
+  bf16x8 a, b;
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(1.0f + 0.001f * (threadIdx.x & 7)); b[i] = (__bf16)(0.5f); }
+  f32x16 acc[4];
+  for (int k = 0; k < 4; ++k)
+    for (int e = 0; e < 16; ++e) acc[k][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+  }
+  float s = 0.f;
+  for (int k = 0; k < 4; ++k) s += acc[k][0];
+  if (s == 12345.678f) out[blockIdx.x] = s;      // keeps the loop alive; never true
+}
+
+int launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st) {
+  if (blocks <= 0 || iters <= 0) return DF_ESHAPE;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, out, iters);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
 __global__ void scale_kernel(float* __restrict__ y, const float* __restrict__ x, float alpha, long long n) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) y[i] = alpha * x[i];

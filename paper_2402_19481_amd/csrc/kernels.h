@@ -158,6 +158,7 @@ int launch_cast_bf16(const float* x, bf16_t* y, long long n, int silu, hipStream
 int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, long long pixels, hipStream_t st);
 int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C, hipStream_t st);
 int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st);
+int launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st);
 int launch_scale(float* y, const float* x, float alpha, long long n, hipStream_t st);
 
 }  // namespace df
