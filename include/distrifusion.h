@@ -182,8 +182,11 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
 void df_unet_destroy(df_unet* u);
 
 /* Location of one named stale buffer inside the blob (tests and tools).  Names: "<conv>.in" (boundary
- * rows [B, N, 2, W, Cin] bf16: first and last input row of every patch), "<attn>.k", "<attn>.v"
- * ([B, L, C] bf16), "<gn>.stats" ([N, B, G, 2] float). */
+ * rows [B, N, 2, W, Cin] bf16: first and last input row of every patch), "<attn>.k" ([B, L, C] bf16),
+ * "<attn>.v" (values stored transposed, [B, C, Lp] bf16 with Lp = L rounded up to a multiple of 64 - the key index
+ * is contiguous so that the attention kernel streams V^T tiles; columns L .. Lp-1 are never written and never
+ * contribute; layers whose width is not a multiple of 64 or is below 128 keep [B, L, C]),
+ * "<gn>.stats" ([N, B, G, 2] float). */
 int df_unet_stale_lookup(const df_unet* u, const char* name, size_t* offset, size_t* bytes);
 int df_unet_num_stale(const df_unet* u);
 int df_unet_stale_name(const df_unet* u, int idx, char* name, int name_cap);

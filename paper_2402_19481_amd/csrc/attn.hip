@@ -39,6 +39,8 @@ struct AttnParams {
   float scale;
   int nsplit, keys_per_split;
   int out_packed;
+  // transposed-V variant: vs is V^T [B][heads*64][vt_ld] (keys contiguous), every key comes from ks / vs
+  long long vt_ld;
 };
 
 __device__ __forceinline__ const bf16_t* key_row(const bf16_t* fresh, const bf16_t* stale, long long ldf, long long lds,
@@ -53,7 +55,7 @@ __device__ __forceinline__ int key_of_mfma_row(int rho) {
   return 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
 }
 
-__global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
+__global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
   constexpr int D = 64, TK = 64;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][TK * D];   // [key][d], 16-byte chunks XOR-swizzled by row
   __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * TK];   // [d][key], swizzled
@@ -281,6 +283,236 @@ __global__ __launch_bounds__(256) void attn_bf16_d64(AttnParams p) {
   }
 }
 
+// ---- variant for the UNet step: every key row comes from the (already refreshed) stale buffers, V is stored
+// transposed ([feature][key], written that way by the projection), so K and V^T tiles go global -> LDS with direct
+// loads (no registers, no transposing stores) through a 3-stage ring awaited with an explicit vmcnt.  The swizzles
+// of the LDS tiles are applied on the source side: LDS slot s of row r receives global chunk s ^ key(r). ----
+#define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+__global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
+  constexpr int D = 64, TK = 64, NST = 3;
+  constexpr int KB = TK * D * 2, STAGE = 2 * KB;           // bytes: K tile, V^T tile
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, c = lane & 31;
+  const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
+  int t = blockIdx.x;
+  {
+    const int nwg = gridDim.x;
+    const int xcd = t & 7, loc = t >> 3;
+    const int base = nwg >> 3, rem = nwg & 7;
+    t = xcd * base + (xcd < rem ? xcd : rem) + loc;
+  }
+  const int nqb = (p.Lq + 127) / 128;
+  const int qb = t % nqb;
+  const int h = (t / nqb) % p.heads;
+  const int zz = t / (nqb * p.heads);
+  const int b = zz / p.nsplit, split = zz % p.nsplit;
+  const int q0 = qb * 128 + wave * 32;
+  const int kv_lo = split * p.keys_per_split;              // multiple of 64
+  int kv_hi = kv_lo + p.keys_per_split;
+  if (kv_hi > p.L) kv_hi = p.L;
+  const int ntiles = (kv_hi - kv_lo + TK - 1) / TK;
+
+  const bf16_t* kg = (const bf16_t*)p.ks + (long long)b * p.bsks + h * D;
+  const bf16_t* vg = (const bf16_t*)p.vs + (long long)b * p.bsvs + (long long)h * D * p.vt_ld;
+
+  bf16x8 qreg[4];
+  {
+    const int qi = q0 + c;
+    const bf16_t* qp = (const bf16_t*)p.q + (long long)b * p.bsq + (long long)qi * p.ldq + h * D;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 tq = {0u, 0u, 0u, 0u};
+      if (qi < p.Lq) tq = *reinterpret_cast<const u32x4*>(qp + 16 * s + 8 * g);
+      qreg[s] = __builtin_bit_cast(bf16x8, tq);
+    }
+  }
+
+  // direct loads: instruction j of a wave covers tile rows (2*wave + j)*8 + lane/8, 16-byte slot lane%8
+  const int lr = lane >> 3, slot = lane & 7;
+  auto issue = [&](int tl, int stage) {
+    if (tl > ntiles - 1) tl = ntiles - 1;                  // past the end: re-read the last tile (keeps vmcnt uniform)
+    const int key0 = kv_lo + tl * TK;
+    char* sk = smem + stage * STAGE;
+    char* sv = sk + KB;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = (2 * wave + j) * 8 + lr;             // key within the tile
+      int key = key0 + row;
+      if (key > p.L - 1) key = p.L - 1;                    // rows beyond the last key are masked below
+      const int f = (row >> 1) & 7;                        // swizzle key: conflict-free 16-byte reads on 64 banks
+      __builtin_amdgcn_global_load_lds(DF_GPTR(kg + (long long)key * p.ldks + ((slot ^ f) * 8)),
+                                       DF_LPTR(sk + (2 * wave + j) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int d = (2 * wave + j) * 8 + lr;               // feature row of the V^T tile
+      const int ch = slot ^ (d & 7) ^ (d >> 3);            // 8-key chunk; the buffer is padded to whole tiles
+      __builtin_amdgcn_global_load_lds(DF_GPTR(vg + (long long)d * p.vt_ld + key0 + ch * 8),
+                                       DF_LPTR(sv + (2 * wave + j) * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16 o_acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = p.scale * kLog2e;
+
+  issue(0, 0);
+  issue(1, 1);
+  int stage = 0, nstage = 2;
+  for (int tl = 0; tl < ntiles; ++tl) {
+    // tile tl has landed once at most the 4 loads of tile tl+1 are outstanding
+    __builtin_amdgcn_s_waitcnt((4 & 0xF) | (0x7 << 4) | (0 << 8));   // vmcnt(4) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    issue(tl + 2, nstage);                                 // the stage every wave finished reading before the barrier
+    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE);
+    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB);
+    // All LDS fragment reads of a phase are issued before its MFMAs (one read per MFMA would put an LDS round trip
+    // between every pair of matrix instructions), and the V^T fragments are requested before the softmax so that
+    // they arrive while the vector ALU works.
+    bf16x8 kfr[2][4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int row = 32 * kb + key_of_mfma_row(c);
+      const int f = (row >> 1) & 7;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kfr[kb][s] = *reinterpret_cast<const bf16x8*>(&Ks[row * D + (((2 * s + g) ^ f) * 8)]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kb][s], qreg[s], s_acc[kb], 0, 0, 0);
+    u32x4 vfr[4][2];
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      const int kchunk = 4 * (ts >> 1) + 2 * (ts & 1) + g;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const int d = 32 * db + csig;
+        vfr[ts][db] = *reinterpret_cast<const u32x4*>(&Vt[d * TK + (kchunk ^ (d & 7) ^ (d >> 3)) * 8]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const int tile_base = kv_lo + tl * TK;
+    const bool ragged = tile_base + TK > kv_hi;
+    if (ragged) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = e >> 2, r = e & 3;
+          const int key = tile_base + 32 * kb + 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
+          if (key >= kv_hi) s_acc[kb][e] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_acc[kb][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][e], sc, -m_new));
+        s_acc[kb][e] = pv;
+        rs += pv;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * alpha + rs;
+    m_run = m_new;
+    // the running maximum rarely moves after the first tiles: rescale only when some query of the wave needs it
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+    }
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      const int kb = ts >> 1, half = ts & 1;
+      u32x4 pk;
+      pk.x = pack_bf2(s_acc[kb][8 * half + 0], s_acc[kb][8 * half + 1]);
+      pk.y = pack_bf2(s_acc[kb][8 * half + 2], s_acc[kb][8 * half + 3]);
+      pk.z = pack_bf2(s_acc[kb][8 * half + 4], s_acc[kb][8 * half + 5]);
+      pk.w = pack_bf2(s_acc[kb][8 * half + 6], s_acc[kb][8 * half + 7]);
+      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
+      const int kchunk = 4 * kb + 2 * half + g;            // keys 32*kb + 16*half + 8*g .. +7
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        u32x4 vraw = vfr[ts][db];
+        if (ragged) {                                      // keys beyond the range: P is 0, V must be finite
+          const int key = tile_base + kchunk * 8;
+          if (key + 0 >= kv_hi) vraw.x = 0u; else if (key + 1 >= kv_hi) vraw.x &= 0xffffu;
+          if (key + 2 >= kv_hi) vraw.y = 0u; else if (key + 3 >= kv_hi) vraw.y &= 0xffffu;
+          if (key + 4 >= kv_hi) vraw.z = 0u; else if (key + 5 >= kv_hi) vraw.z &= 0xffffu;
+          if (key + 6 >= kv_hi) vraw.w = 0u; else if (key + 7 >= kv_hi) vraw.w &= 0xffffu;
+        }
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pfrag, o_acc[db], 0, 0, 0);
+      }
+    }
+    stage = (stage + 1 == NST) ? 0 : stage + 1;
+    nstage = (nstage + 1 == NST) ? 0 : nstage + 1;
+  }
+  __builtin_amdgcn_s_waitcnt((0 & 0xF) | (0x7 << 4) | (0 << 8));     // drain the clamped tail loads
+
+  const int qi = q0 + c;
+  if (qi >= p.Lq) return;
+  if (p.nsplit == 1) {
+    const float inv = 1.0f / l_run;
+    bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D;
+    const long long m = (long long)b * p.Lq + qi;
+    bf16_t* pp = (bf16_t*)p.out + (((m >> 5) * (long long)(p.heads * D / 16) + h * (D / 16)) * 64 + (m & 31) + 32 * g) * 8;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        u32x4 tq;
+        tq.x = pack_bf2(o_acc[db][8 * f + 0] * inv, o_acc[db][8 * f + 1] * inv);
+        tq.y = pack_bf2(o_acc[db][8 * f + 2] * inv, o_acc[db][8 * f + 3] * inv);
+        tq.z = pack_bf2(o_acc[db][8 * f + 4] * inv, o_acc[db][8 * f + 5] * inv);
+        tq.w = pack_bf2(o_acc[db][8 * f + 6] * inv, o_acc[db][8 * f + 7] * inv);
+        if (p.out_packed) *reinterpret_cast<u32x4*>(pp + (2 * db + f) * 512) = tq;
+        else *reinterpret_cast<u32x4*>(op + 32 * db + 16 * f + 8 * g) = tq;
+      }
+  } else {
+    const long long row = (((long long)split * p.B + b) * p.heads + h) * p.Lq + qi;
+    float* po = p.part_o + row * D;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        f32x4 t0 = {o_acc[db][8 * f], o_acc[db][8 * f + 1], o_acc[db][8 * f + 2], o_acc[db][8 * f + 3]};
+        f32x4 t1 = {o_acc[db][8 * f + 4], o_acc[db][8 * f + 5], o_acc[db][8 * f + 6], o_acc[db][8 * f + 7]};
+        *reinterpret_cast<f32x4*>(po + 32 * db + 16 * f + 8 * g) = t0;
+        *reinterpret_cast<f32x4*>(po + 32 * db + 16 * f + 8 * g + 4) = t1;
+      }
+    if (g == 0) {
+      p.part_ml[row * 2] = m_run;
+      p.part_ml[row * 2 + 1] = l_run;
+    }
+  }
+}
+
 // merges the per-split partials: one lane per (query, 4 consecutive d)
 __global__ __launch_bounds__(256) void attn_combine_d64(AttnParams p) {
   constexpr int D = 64;
@@ -361,14 +593,25 @@ __global__ __launch_bounds__(256) void attn_f32(AttnParams p) {
   }
 }
 
+// Number of key-range splits.  Cost model from the kernel traces of the patch step: a compute unit works through its
+// workgroups' 64-key tiles at a roughly constant rate whether one or three of them are resident, so the time follows
+// the most loaded unit, ceil(workgroups / 256) x (tiles per workgroup + a fixed part); the merge kernel grows with the
+// number of partials.  (Plain "at least 512 workgroups" picked 800 for the 1200-query level: 768 run at once and
+// the last 32 had the chip to themselves for a full workgroup lifetime, +35 %.)
 int pick_splits(int B, int Lq, int L, int heads) {
   static const int forced = getenv("DF_ATTN_SPLITS") ? atoi(getenv("DF_ATTN_SPLITS")) : 0;   // tuning aid
   if (forced > 0) return (L / forced >= 64) ? forced : 1;
   const long long blocks = (long long)cdiv(Lq, 128) * heads * B;
-  int ns = 1;
-  // aim at >= 512 workgroups (two per compute unit) while keeping >= 4 key tiles per split
-  while (blocks * ns < 512 && L / (ns * 2) >= 256 && ns < 16) ns *= 2;
-  return ns;
+  int best = 1;
+  double best_cost = 1e30;
+  for (int ns = 1; ns <= 16; ++ns) {
+    if (ns > 1 && L / ns < 128) break;
+    const int tiles = cdiv(cdiv(L, ns), 64);
+    const long long per_cu = (blocks * ns + 255) / 256;
+    const double cost = (double)per_cu * (tiles + 2) + (ns > 1 ? 1.0 + 0.5 * ns : 0.0);
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = ns; }
+  }
+  return best;
 }
 
 }  // namespace
@@ -418,7 +661,21 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   }
   const long long nwg = (long long)cdiv(a.Lq, 128) * a.heads * a.B * p.nsplit;
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
-  hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
+  if (a.v_transposed) {
+    // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
+    if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
+    p.vt_ld = a.vt_ld;
+    constexpr int smem = 3 * 2 * 64 * 64 * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute((const void*)attn_vt_d64, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+        return DF_EHIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(attn_vt_d64, dim3((unsigned)nwg), dim3(256), smem, st, p);
+  } else {
+    hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
+  }
   DF_LAUNCH_CHECK();
   if (ns > 1) {
     const long long n = (long long)a.B * a.heads * a.Lq * 16;

@@ -50,6 +50,7 @@ struct TileParams {
   void* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  int seg_tr[3];
   int packed_w;
   const float* ln_s;
   const float* ln_t;
@@ -566,6 +567,26 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
         return;
       }
     }
+    if constexpr (!kConv && sizeof(OutT) == 2) {
+      if (p.nseg > 0 && p.seg_tr[n0 / p.seg_w]) {
+        // transposed segment (V^T for the attention kernel): feature-major output, rows contiguous.  Threads walk the
+        // tile row-fastest so that neighbouring threads write neighbouring rows of one feature.
+        const int sg = n0 / p.seg_w;
+        bf16_t* obase = reinterpret_cast<bf16_t*>(p.seg_out[sg]);
+        for (int idx = tid; idx < BM * BN; idx += NTHR) {
+          const int lr_ = idx % BM, lc = idx / BM;
+          const int row = m0 + lr_, col = n0 + lc;
+          if (row >= p.M || col >= p.N) continue;
+          float v = tile[lr_ * PT + lc];
+          if (ln_fold) v = (v - p.ln_s[col] * s_mr[lr_ * 2]) * s_mr[lr_ * 2 + 1] + p.ln_t[col];
+          else if (p.bias) v += p.bias[col];
+          const int bi = row / p.seg_rows_in[sg];
+          obase[((long long)bi * p.seg_w + (col - sg * p.seg_w)) * p.seg_ld[sg] + p.seg_row0[sg] +
+                (row - bi * p.seg_rows_in[sg])] = f2bf(v);
+        }
+        return;
+      }
+    }
     for (int idx = tid; idx < BM * (BN / 4); idx += NTHR) {
       const int lr_ = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
       const int row = m0 + lr_, col = n0 + c4;
@@ -671,11 +692,13 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
     OutT* obase = out;
     long long old = p.ldo, orow0 = 0, orows_out = 0;
     int ocol = col, orows_in = 0x7fffffff;
+    bool otr = false;
     if (p.nseg > 0) {
       const int sg = col / p.seg_w;
       obase = reinterpret_cast<OutT*>(p.seg_out[sg]);
       old = p.seg_ld[sg]; orow0 = p.seg_row0[sg]; orows_out = p.seg_rows_out[sg]; orows_in = p.seg_rows_in[sg];
       ocol = col - sg * p.seg_w;
+      otr = p.seg_tr[sg] != 0;
     }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -696,6 +719,10 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
         if (p.nseg > 0) {
           const int bi = row / orows_in;
           orow = (long long)bi * orows_out + orow0 + (row - bi * orows_in);
+          if (otr) {   // feature-major segment
+            Elem<OutT>::st(obase + ((long long)bi * p.seg_w + ocol) * old + orow0 + (row - bi * orows_in), v);
+            continue;
+          }
         }
         Elem<OutT>::st(obase + orow * old + ocol, v);
         if constexpr (!kConv) {
@@ -911,7 +938,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
     bool ok = p.N % 4 == 0 && p.ldo % 4 == 0 && al(p.out, 16) && al(p.bias, 16) && al(p.chan_add, 16) &&
               (!p.residual || (p.ldr % 4 == 0 && al(p.residual, 16))) && (!p.out2 || (p.ldo2 % 4 == 0 && al(p.out2, 8))) &&
               al(p.ln_s, 16) && al(p.ln_t, 16) && (!p.geglu || p.geglu % 4 == 0);
-    for (int i = 0; i < p.nseg; ++i) ok = ok && p.seg_ld[i] % 4 == 0 && al(p.seg_out[i], 8) && p.seg_w % 4 == 0;
+    for (int i = 0; i < p.nseg; ++i) ok = ok && (p.seg_tr[i] || (p.seg_ld[i] % 4 == 0 && al(p.seg_out[i], 8))) && p.seg_w % 4 == 0;
     if (p.ln_s && BM * (BN + 4) * 4 + BM * 24 > smem) return DF_ESHAPE;   // no room for the row statistics
     q.vec_epi = ok ? 1 : 0;
   }
@@ -1066,7 +1093,7 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
     for (int i = 0; i < a.nseg; ++i) {
       if (!a.seg_out[i] || a.seg_rows_in[i] <= 0) return DF_EINVAL;
       p.seg_out[i] = a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
-      p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
+      p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i]; p.seg_tr[i] = a.seg_tr[i];
     }
     if ((long long)cdiv(a.M, 64) * cdiv(a.N, 64) >= 512) return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
     return launch_pipe<64, 64, 4, false, 1, 8>(p, DF_BF16, 1, st);

@@ -80,6 +80,9 @@ struct GemmArgs {
   void* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  // seg_tr[s] != 0: segment s is written transposed, out[(b * seg_w + col) * seg_ld[s] + seg_row0[s] + row_in_batch]
+  // (feature-major, rows contiguous: the V^T layout of the attention kernel); seg_rows_out is ignored for it
+  int seg_tr[3];
   // W is in the tiled layout written by launch_pack_weight (requires N % 64 == 0, K % 64 == 0, K >= 128).
   int packed_w;
   // LayerNorm folded into the GEMM: A holds the un-normalised rows (bf16), W was packed with the norm scale
@@ -126,6 +129,7 @@ struct WGemmArgs {
   void* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  int seg_tr[3];          // transposed segments, as in GemmArgs
 };
 int launch_wgemm(const WGemmArgs& a, hipStream_t st);
 size_t packed_rows_bytes(long long M, long long K);
@@ -147,6 +151,10 @@ struct AttnArgs {
   float scale;
   int dtype;
   int out_packed;       // bf16 output in the fragment-packed layout of wgemm.hip: rows = B*Lq tokens, K = heads*d
+  // v_transposed: v_stale is V^T [B][heads*d][vt_ld] (key index contiguous, vt_ld >= L rounded up to 64, batch stride
+  // bsvs) and every key is read from k_stale / v_stale (own_n must be 0; k_fresh / v_fresh are ignored); bf16, d = 64
+  int v_transposed;
+  long long vt_ld;
 };
 int launch_attention(const AttnArgs& a, hipStream_t st);
 size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d);

@@ -533,24 +533,37 @@ struct Exec {
     bf16_t* qkv = (bf16_t*)alloc((size_t)M * 3 * C * 2);    // row-major queries (and fresh K/V without refresh)
     bf16_t* aop = (bf16_t*)alloc(pC);                       // attention output, packed
     bf16_t* fgp = (bf16_t*)alloc(packed_rows_bytes(M, 4 * C));
+    const long long Lpad = (long long)((L + 63) / 64) * 64;   // key pitch of the V^T buffers: whole 64-key tiles
+    bf16_t* ks_tmp = nullptr; bf16_t* vs_tmp = nullptr;
+    if (!(full() || refresh)) {
+      ks_tmp = (bf16_t*)alloc((size_t)B() * L * C * 2);
+      vs_tmp = (bf16_t*)alloc((size_t)B() * C * Lpad * 2);
+    }
     groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nbp, 1);
     wg(nbp, b.name + ".pin", true, false, nullptr, h, hp, nullptr, 0, M, C, C);
     for (int d = 0; d < b.depth; ++d) {
       const std::string p = b.name + ".b" + std::to_string(d);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
-      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
-      const bool fused_kv = full() || refresh;
+      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * C * Lpad * 2);   // V^T: [B, C, Lpad]
       const size_t row0 = full() ? 0 : (size_t)patch * Lq;
-      if (fused_kv) {
-        // queries to a scratch tensor, keys and values straight into the patch's rows of the stale buffers
+      if (!(full() || refresh)) {
+        // no refresh: the patch's keys and values go into private copies of the two buffers
+        if (live()) {
+          timed(PC_REFRESH, 0.0, 4.0 * B() * L * C, [&] { return launch_copy_rows(ks_tmp, ks, 1, (long long)B() * L * C * 2, 0, 0, st); });
+          timed(PC_REFRESH, 0.0, 4.0 * B() * C * Lpad, [&] { return launch_copy_rows(vs_tmp, vs, 1, (long long)B() * C * Lpad * 2, 0, 0, st); });
+        }
+        ks = ks_tmp; vs = vs_tmp;
+      }
+      {
+        // queries to a scratch tensor, keys straight into the patch's rows of the key buffer, values transposed into
+        // the patch's columns of the V^T buffer (the refresh costs nothing)
         WGemmArgs ex = {};
         ex.nseg = 3; ex.seg_w = C;
         ex.seg_out[0] = qkv; ex.seg_ld[0] = C; ex.seg_rows_in[0] = 0x7fffffff; ex.seg_rows_out[0] = 0; ex.seg_row0[0] = 0;
         ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
-        ex.seg_out[2] = vs; ex.seg_ld[2] = C; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = L; ex.seg_row0[2] = (long long)row0;
+        ex.seg_out[2] = vs; ex.seg_ld[2] = Lpad; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = 0; ex.seg_row0[2] = (long long)row0;
+        ex.seg_tr[2] = 1;
         wg(hp, p + ".attn1.qkv", false, true, nullptr, nullptr, nullptr, nullptr, 0, M, 3 * C, C, &ex);
-      } else {
-        wg(hp, p + ".attn1.qkv", false, true, nullptr, nullptr, nullptr, qkv, 3 * C, M, 3 * C, C);
       }
       {
         const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
@@ -559,17 +572,12 @@ struct Exec {
       if (live()) {
         AttnArgs a = {};
         a.k_stale = ks; a.v_stale = vs; a.out = aop; a.q = qkv; a.out_packed = 1;
+        a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
+        a.v_transposed = 1; a.vt_ld = Lpad;
         a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
-        a.ldks = a.ldvs = C; a.ldo = C;
-        a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
-        if (fused_kv) {
-          a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
-          a.ldq = C; a.ldkf = a.ldvf = C; a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
-        } else {
-          a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C;
-          a.own_lo = patch * Lq; a.own_n = Lq;
-          a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
-        }
+        a.ldq = C; a.ldkf = a.ldvf = C; a.ldks = C; a.ldvs = C; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
+        a.bsks = (long long)L * C; a.bsvs = (long long)C * Lpad; a.bso = (long long)Lq * C;
         a.scale = scale; a.dtype = DF_BF16;
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
@@ -615,22 +623,33 @@ struct Exec {
     const int M = B() * Lq, TL = c.text_len;
     const float scale = 1.0f / sqrtf((float)c.head_dim);
     bf16_t* hb = (bf16_t*)alloc((size_t)M * C * 2);      // bf16 copy of the hidden state
+    const long long Lpad = (long long)((L + 63) / 64) * 64;   // key pitch of the V^T buffers: whole 64-key tiles
+    bf16_t* ks_tmp = nullptr; bf16_t* vs_tmp = nullptr;
+    if (!(full() || refresh)) {
+      ks_tmp = (bf16_t*)alloc((size_t)B() * L * C * 2);
+      vs_tmp = (bf16_t*)alloc((size_t)B() * C * Lpad * 2);
+    }
     gemm_packed(nb, C, b.name + ".pin", true, false, nullptr, 0, h, C, M, C, C, DF_F32, hb);
     for (int d = 0; d < b.depth; ++d) {
       const std::string p = b.name + ".b" + std::to_string(d);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
-      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * L * C * 2);
-      const bool fused_kv = full() || refresh;
+      bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * C * Lpad * 2);   // V^T: [B, C, Lpad]
       const size_t row0 = full() ? 0 : (size_t)patch * Lq;
-      if (fused_kv) {
+      if (!(full() || refresh)) {
+        if (live()) {
+          timed(PC_REFRESH, 0.0, 4.0 * B() * L * C, [&] { return launch_copy_rows(ks_tmp, ks, 1, (long long)B() * L * C * 2, 0, 0, st); });
+          timed(PC_REFRESH, 0.0, 4.0 * B() * C * Lpad, [&] { return launch_copy_rows(vs_tmp, vs, 1, (long long)B() * C * Lpad * 2, 0, 0, st); });
+        }
+        ks = ks_tmp; vs = vs_tmp;
+      }
+      {
         GemmArgs ex = {};
         ex.nseg = 3; ex.seg_w = C;
         ex.seg_out[0] = qkv; ex.seg_ld[0] = C; ex.seg_rows_in[0] = 0x7fffffff; ex.seg_rows_out[0] = 0; ex.seg_row0[0] = 0;
         ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
-        ex.seg_out[2] = vs; ex.seg_ld[2] = C; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = L; ex.seg_row0[2] = (long long)row0;
+        ex.seg_out[2] = vs; ex.seg_ld[2] = Lpad; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = 0; ex.seg_row0[2] = (long long)row0;
+        ex.seg_tr[2] = 1;
         gemm_packed(hb, C, p + ".attn1.qkv", false, true, nullptr, 0, qkv, C, M, 3 * C, C, DF_BF16, nullptr, &ex);
-      } else {
-        gemm_packed(hb, C, p + ".attn1.qkv", false, true, nullptr, 0, qkv, 3 * C, M, 3 * C, C, DF_BF16, nullptr);
       }
       {
         const size_t need = attention_scratch_bytes(B(), Lq, L, heads, c.head_dim);
@@ -639,17 +658,12 @@ struct Exec {
       if (live()) {
         AttnArgs a = {};
         a.k_stale = ks; a.v_stale = vs; a.out = ao; a.q = qkv;
+        a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
+        a.v_transposed = 1; a.vt_ld = Lpad;
         a.B = B(); a.Lq = Lq; a.L = L; a.heads = heads; a.d = c.head_dim;
-        a.ldks = a.ldvs = C; a.ldo = C;
-        a.bsks = a.bsvs = (long long)L * C; a.bso = (long long)Lq * C;
-        if (fused_kv) {
-          a.k_fresh = ks; a.v_fresh = vs; a.own_lo = 0; a.own_n = 0;
-          a.ldq = C; a.ldkf = a.ldvf = C; a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
-        } else {
-          a.k_fresh = qkv + C; a.v_fresh = qkv + 2 * C;
-          a.own_lo = patch * Lq; a.own_n = Lq;
-          a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
-        }
+        a.ldq = C; a.ldkf = a.ldvf = C; a.ldks = C; a.ldvs = C; a.ldo = C;
+        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
+        a.bsks = (long long)L * C; a.bsvs = (long long)C * Lpad; a.bso = (long long)Lq * C;
         a.scale = scale; a.dtype = DF_BF16;
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
@@ -951,9 +965,10 @@ struct DryResult {
 
 DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
   DryResult r = {};
-  for (int mode = 0; mode < 2; ++mode) {
+  for (int pass = 0; pass < 3; ++pass) {   // FULL; DISPLACED with refresh; DISPLACED without (private K / V^T copies)
+    const int mode = pass == 0 ? 0 : 1;
     std::vector<StaleEntry> list;
-    Exec e{c, blocks, nullptr, true, mode, 0, 1, nullptr, nullptr, 0};
+    Exec e{c, blocks, nullptr, true, mode, 0, pass == 2 ? 0 : 1, nullptr, nullptr, 0};
     for (const BlockDesc& b : blocks)
       if (b.kind == BlockDesc::XF) e.kv_count[b.level] += b.depth;
     e.stale_base = nullptr;

@@ -43,6 +43,7 @@ struct WParams {
   bf16_t* seg_out[3];
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
+  int seg_tr[3];
 };
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
@@ -286,8 +287,16 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       if (p.nseg > 0) {
         const int sg = n / p.seg_w;                     // 8 features never straddle a segment (seg_w % 32 == 0)
         const int bi = m / p.seg_rows_in[sg];
-        const long long orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (m - bi * p.seg_rows_in[sg]);
-        st_vec(p.seg_out[sg] + orow * p.seg_ld[sg] + (n - sg * p.seg_w), v);
+        if (p.seg_tr[sg]) {
+          // feature-major output: the 32 tokens of a half wave are consecutive in memory for each feature
+          bf16_t* o = p.seg_out[sg] + ((long long)bi * p.seg_w + (n - sg * p.seg_w)) * p.seg_ld[sg] + p.seg_row0[sg] +
+                      (m - bi * p.seg_rows_in[sg]);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) o[q * p.seg_ld[sg]] = f2bf(v[q]);
+        } else {
+          const long long orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (m - bi * p.seg_rows_in[sg]);
+          st_vec(p.seg_out[sg] + orow * p.seg_ld[sg] + (n - sg * p.seg_w), v);
+        }
       } else if (p.out_rows) {
         st_vec(p.out_rows + (long long)m * p.ld_rows + n, v);
       }
@@ -429,7 +438,9 @@ int launch_wgemm(const WGemmArgs& a, hipStream_t st) {
     if (a.nseg > 3 || a.seg_w % 32 || a.seg_w * a.nseg != a.N || a.geglu) return DF_ESHAPE;
     p.nseg = a.nseg; p.seg_w = a.seg_w;
     for (int i = 0; i < a.nseg; ++i) {
-      if (!a.seg_out[i] || a.seg_rows_in[i] <= 0 || a.seg_ld[i] % 8 || !al(a.seg_out[i], 16)) return DF_EINVAL;
+      if (!a.seg_out[i] || a.seg_rows_in[i] <= 0 || (!a.seg_tr[i] && (a.seg_ld[i] % 8 || !al(a.seg_out[i], 16))))
+        return DF_EINVAL;
+      p.seg_tr[i] = a.seg_tr[i];
       p.seg_out[i] = (bf16_t*)a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
     }

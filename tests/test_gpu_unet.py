@@ -39,6 +39,12 @@ def _stale_as_oracle(net, name, cfg, B, ostale):
         g = host(raw.view(torch.bfloat16).reshape(B, cfg.N, 2, W, C))
         want = np.stack([np.stack([o[:, j * Rp], o[:, (j + 1) * Rp - 1]], axis=1) for j in range(cfg.N)], axis=1)
         return g, want
+    if name.endswith(".v"):
+        Bn, L, C = o.shape
+        Lp = (L + 63) // 64 * 64
+        if raw.numel() == Bn * C * Lp * 2:      # values are stored transposed, key pitch padded to whole 64-key tiles
+            g = host(raw.view(torch.bfloat16).reshape(Bn, C, Lp))
+            return g[:, :, :L].transpose(0, 2, 1), o
     return host(raw.view(torch.bfloat16).reshape(o.shape)), o
 
 
