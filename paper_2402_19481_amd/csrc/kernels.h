@@ -130,11 +130,24 @@ struct WGemmArgs {
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
   int seg_tr[3];          // transposed segments, as in GemmArgs
+  // Fused cross-attention: the layer is a query projection with N = heads * 64 and a folded LayerNorm; instead of
+  // the projection the kernel writes out_packed = softmax(q k^T * xa_scale) v per head, against xa_keys text tokens
+  // whose keys / values were packed by launch_pack_text_kv (xa_kv: this block's fragments, batch stride
+  // xa_bstride elements; xa_rows token rows per batch item, a multiple of 32 unless there is one batch item).
+  const void* xa_kv;
+  int xa_keys, xa_rows;
+  long long xa_bstride;
+  float xa_scale;
 };
 int launch_wgemm(const WGemmArgs& a, hipStream_t st);
 size_t packed_rows_bytes(long long M, long long K);
 int launch_pack_rows(const bf16_t* x, long long ldx, bf16_t* out, int M, int K, hipStream_t st);
 int launch_pack_wfrag(const bf16_t* w, const float* gamma, bf16_t* out, int N, int K, hipStream_t st);
+// Text keys / values of `count` transformer blocks (kv [B*TL, count*2C] row-major: per block C key then C value
+// columns) -> MFMA fragments [B][count][heads][12*XA][64][8], XA = ceil(TL/32): per head 4*XA key fragments (32 keys x
+// 16 d, key rows in the bit-2/3-swapped order, zero beyond TL) then 4*XA value fragments (V^T: 32 d x 16 keys).
+size_t packed_text_kv_bytes(int B, int TL, int count, int C);
+int launch_pack_text_kv(const bf16_t* kv, long long ld, bf16_t* out, int B, int TL, int count, int C, hipStream_t st);
 
 // ---- attn.hip ----
 struct AttnArgs {

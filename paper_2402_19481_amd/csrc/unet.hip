@@ -302,6 +302,7 @@ struct Exec {
   int kv_count[4] = {0, 0, 0, 0};
   int kv_cursor[4] = {0, 0, 0, 0};
   bf16_t* kv2_all[4] = {nullptr, nullptr, nullptr, nullptr};
+  bf16_t* xkv_all[4] = {nullptr, nullptr, nullptr, nullptr};   // text keys / values as per-head MFMA fragments
 
   // run a launch, accounted to class `cls` when per-launch timing is on
   template <typename F>
@@ -584,23 +585,44 @@ struct Exec {
       }
       wg(aop, p + ".attn1.o", true, false, h, h, hp, nullptr, 0, M, C, C);
       // cross-attention to the text tokens
-      wg(hp, p + ".attn2.q", false, true, nullptr, nullptr, nullptr, qkv, C, M, C, C);
       const long long kvld = (long long)kv_count[b.level] * 2 * C;
-      const bf16_t* kv2 = kv2_all[b.level] + (size_t)kv_cursor[b.level] * 2 * C;
+      const int kvi = kv_cursor[b.level];
+      const bf16_t* kv2 = kv2_all[b.level] + (size_t)kvi * 2 * C;
       kv_cursor[b.level] += 1;
-      {
-        const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
-        if (need > scratch_need) scratch_need = need;
-      }
-      if (live()) {
-        AttnArgs a = {};
-        a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = aop; a.out_packed = 1;
-        a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
-        a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
-        a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
-        a.scale = scale; a.dtype = DF_BF16;
-        timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
-              [&] { return launch_attention(a, st); });
+      const bool fuse_x = xkv_all[b.level] != nullptr && (B() == 1 || Lq % 32 == 0);
+      if (fuse_x) {
+        // a head is one 64-feature tile of the query projection: attention against the packed text keys / values
+        // runs in that layer's epilogue and writes the packed attention output
+        if (live()) {
+          const int XA = (TL + 31) / 32;
+          WGemmArgs ex = {};
+          ex.xa_kv = xkv_all[b.level] + (size_t)kvi * heads * 12 * XA * 512;
+          ex.xa_keys = TL; ex.xa_rows = Lq; ex.xa_scale = scale;
+          ex.xa_bstride = (long long)kv_count[b.level] * heads * 12 * XA * 512;
+          auto it = packed->find(p + ".attn2.q");
+          if (it == packed->end()) { err = DF_EINVAL; return; }
+          WGemmArgs g2 = ex;
+          g2.Xp = hp; g2.Wp = it->second.f; g2.M = M; g2.N = C; g2.K = C;
+          g2.ln_s = it->second.s; g2.ln_t = it->second.t; g2.ln_eps = 1e-5f; g2.out_packed = aop;
+          timed(PC_CROSS_ATTN, 2.0 * M * C * C + 4.0 * M * TL * C, 2.0 * ((double)M * C + (double)C * C) + 2.0 * M * C,
+                [&] { return launch_wgemm(g2, st); });
+        }
+      } else {
+        wg(hp, p + ".attn2.q", false, true, nullptr, nullptr, nullptr, qkv, C, M, C, C);
+        {
+          const size_t need = attention_scratch_bytes(B(), Lq, TL, heads, c.head_dim);
+          if (need > scratch_need) scratch_need = need;
+        }
+        if (live()) {
+          AttnArgs a = {};
+          a.q = qkv; a.k_fresh = kv2; a.v_fresh = kv2 + C; a.out = aop; a.out_packed = 1;
+          a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
+          a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
+          a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
+          a.scale = scale; a.dtype = DF_BF16;
+          timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
+                [&] { return launch_attention(a, st); });
+        }
       }
       wg(aop, p + ".attn2.o", true, false, h, h, hp, nullptr, 0, M, C, C);
       // GEGLU feed-forward
@@ -844,6 +866,18 @@ struct Exec {
       ex.packed_w = (c.text_dim % 64 == 0 && c.text_dim >= 128) ? 1 : 0;
       gemm_w(text, c.text_dim, kv_packed[lv], nullptr, nullptr, 0, kv2_all[lv], Nkv, B() * c.text_len, Nkv, c.text_dim,
              DF_BF16, &ex);
+      // the same keys / values as MFMA fragments per head, for the cross-attention fused into the query projection
+      xkv_all[lv] = nullptr;
+      if (fold_ok(c.levels[lv]) && c.text_len <= 128 && c.head_dim == 64) {
+        xkv_all[lv] = (bf16_t*)alloc(packed_text_kv_bytes(B(), c.text_len, kv_count[lv], c.levels[lv]));
+        if (live()) {
+          bf16_t* dst = xkv_all[lv];
+          const bf16_t* src = kv2_all[lv];
+          const int cnt = kv_count[lv], Cl = c.levels[lv];
+          timed(PC_ELEMENTWISE, 0.0, 4.0 * B() * c.text_len * Nkv,
+                [&] { return launch_pack_text_kv(src, Nkv, dst, B(), c.text_len, cnt, Cl, st); });
+        }
+      }
     }
     for (const BlockDesc& b : blocks) {
       if (err != DF_OK) break;

@@ -44,16 +44,26 @@ struct WParams {
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
   int seg_tr[3];
+  // fused cross-attention (XA > 0): per (batch item, head) 8*XA key fragments then 4*XA value fragments
+  const bf16x8* xkv;
+  int xa_keys;          // valid text tokens
+  long long xa_bstride; // fragments between batch items
+  int xa_rows;          // token rows per batch item
+  float xa_scale;
 };
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-template <int TM, int TN, int KSPLIT, int PF, bool LN>
+// XA > 0 (TM = 1, TN = 2, KSPLIT = 4, N = one head per workgroup): the 64 output features are the query of one
+// attention head; cross-attention against XA 32-key tiles of packed text keys / values runs in the epilogue and the
+// kernel writes the attention output (packed) instead of the projection.
+template <int TM, int TN, int KSPLIT, int PF, bool LN, int XA>
 __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   constexpr int U = TM * TN * 4;            // float4 units of a wave's tile: (tm, tn, jj)
   f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64]
   float* stat = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024);  // [KSPLIT][TM][32][2]
+  u32x4* qlds = reinterpret_cast<u32x4*>(smem_raw + KSPLIT * U * 1024 + KSPLIT * TM * 32 * 2 * 4);   // [4][64] (XA)
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tok = lane & 31, g = lane >> 5;
@@ -268,6 +278,12 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) v[q] *= gelu_erf(gt[q]);
     }
+    if constexpr (XA > 0) {
+      // this wave's 8 features x 32 tokens are the d-step 2*j + f of the head's Q^T operand
+      u32x4 qv = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7])};
+      qlds[(2 * j + f) * 64 + lane] = qv;
+      continue;
+    }
     const bool row_ok = m < p.M;
     if (p.residual && row_ok) {
 #pragma unroll
@@ -301,6 +317,88 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
         st_vec(p.out_rows + (long long)m * p.ld_rows + n, v);
       }
     }
+  }
+  if constexpr (XA > 0) {
+    __syncthreads();
+    if (wave != 0) return;
+    // one wave: S^T = K Q^T over XA key tiles (lane = token, 16 keys per tile in natural order thanks to the row
+    // permutation of the packed keys), softmax over the valid keys, O^T = V^T P^T, packed output
+    const int mt = mg;                                   // TM == 1
+    const long long m0 = (long long)mt * 32;
+    const int bi = (int)(m0 / p.xa_rows);                // a fragment row never straddles batch items when rows % 32 == 0;
+                                                         // otherwise the launcher requires a single batch item
+    const bf16x8* kv = p.xkv + (size_t)bi * p.xa_bstride + (size_t)ng * (12 * XA) * 64 + lane;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int ds = 0; ds < 4; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, qlds[ds * 64 + lane]);
+    bf16x8 kf[XA][4];
+#pragma unroll
+    for (int kt = 0; kt < XA; ++kt)
+#pragma unroll
+      for (int ds = 0; ds < 4; ++ds) kf[kt][ds] = kv[(size_t)(kt * 4 + ds) * 64];
+    f32x16 sa[XA];
+#pragma unroll
+    for (int kt = 0; kt < XA; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sa[kt][e] = 0.f;
+#pragma unroll
+      for (int ds = 0; ds < 4; ++ds) sa[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ds], qf[ds], sa[kt], 0, 0, 0);
+    }
+    bf16x8 vf[2][2 * XA];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int ks = 0; ks < 2 * XA; ++ks) vf[dt][ks] = kv[(size_t)(4 * XA + dt * 2 * XA + ks) * 64];
+    const float sc = p.xa_scale * 1.4426950408889634f;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < XA; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = kt * 32 + 16 * (e >> 3) + 8 * g + (e & 7);
+        if (key >= p.xa_keys) sa[kt][e] = -INFINITY;
+        mx = fmaxf(mx, sa[kt][e]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;
+    float l = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < XA; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = __builtin_amdgcn_exp2f(fmaf(sa[kt][e], sc, -mx));
+        sa[kt][e] = pv;
+        l += pv;
+      }
+    l += __shfl_xor(l, 32, 64);
+    f32x16 oa[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oa[dt][e] = 0.f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2 * XA; ++ks) {
+      const int kt = ks >> 1, hf = ks & 1;
+      u32x4 pk;
+      pk.x = pack_bf2(sa[kt][8 * hf + 0], sa[kt][8 * hf + 1]);
+      pk.y = pack_bf2(sa[kt][8 * hf + 2], sa[kt][8 * hf + 3]);
+      pk.z = pack_bf2(sa[kt][8 * hf + 4], sa[kt][8 * hf + 5]);
+      pk.w = pack_bf2(sa[kt][8 * hf + 6], sa[kt][8 * hf + 7]);
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) oa[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][ks], pf, oa[dt], 0, 0, 0);
+    }
+    const float inv = 1.0f / l;
+    const int KFo = p.N >> 4;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2) {
+        float o8[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) o8[q] = oa[dt][8 * f2 + q] * inv;
+        st_vec(p.out_packed + (((size_t)mt * KFo + ng * 4 + dt * 2 + f2) * 64 + lane) * 8, o8);
+      }
   }
 }
 
@@ -353,12 +451,46 @@ __global__ void pack_wfrag_kernel(const bf16_t* __restrict__ w, const float* __r
 template <int TM, int TN, int KSPLIT, int PFMAX>
 int launch_cfg(const WParams& p, hipStream_t st);
 
+__global__ void pack_text_kv_kernel(const bf16_t* __restrict__ kv, long long ld, u32x4* __restrict__ out, int B, int TL,
+                                    int count, int C, int XA, long long total) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  long long frag = idx >> 6;
+  const int heads = C / 64, per_head = 12 * XA;
+  const int fr = (int)(frag % per_head); frag /= per_head;
+  const int hh = (int)(frag % heads); frag /= heads;
+  const int j = (int)(frag % count);
+  const int b = (int)(frag / count);
+  const int i = lane & 31, g = lane >> 5;
+  const int sig = (i & 0x13) | ((i & 4) << 1) | ((i & 8) >> 1);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (fr < 4 * XA) {
+    const int kt = fr >> 2, ds = fr & 3;
+    const int key = kt * 32 + sig;
+    if (key < TL)
+      v = *reinterpret_cast<const u32x4*>(kv + ((long long)b * TL + key) * ld + (long long)j * 2 * C + hh * 64 + ds * 16 + 8 * g);
+  } else {
+    const int fv = fr - 4 * XA;
+    const int dt = fv / (2 * XA), ks = fv % (2 * XA);
+    const int d = dt * 32 + sig;
+    unsigned int e[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int key = ks * 16 + 8 * g + q;
+      e[q] = key < TL ? kv[((long long)b * TL + key) * ld + (long long)j * 2 * C + C + hh * 64 + d] : 0u;
+    }
+    v.x = e[0] | (e[1] << 16); v.y = e[2] | (e[3] << 16); v.z = e[4] | (e[5] << 16); v.w = e[6] | (e[7] << 16);
+  }
+  out[idx] = v;
+}
+
 int tune_cfg() {
   static const int v = [] { const char* e = getenv("DF_WGEMM_CFG"); return e ? atoi(e) : 0; }();
   return v;
 }
 
-template <int TM, int TN, int KSPLIT, int PF, bool LN>
+template <int TM, int TN, int KSPLIT, int PF, bool LN, int XA = 0>
 int launch_one(const WParams& p, hipStream_t st) {
   const int MT = (p.M + 31) / 32, MG = (MT + TM - 1) / TM;
   const int NTo = p.N / 32;
@@ -367,8 +499,8 @@ int launch_one(const WParams& p, hipStream_t st) {
   const int NG = p.geglu ? NTo : NTo / TN;
   const int KF = p.K / 16;
   if (KF % KSPLIT) return DF_ESHAPE;
-  constexpr int smem = KSPLIT * TM * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4;
-  auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN>;
+  constexpr int smem = KSPLIT * TM * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0);
+  auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN, XA>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return DF_EHIP;
@@ -396,6 +528,21 @@ int launch_cfg(const WParams& p, hipStream_t st) {
 }
 
 }  // namespace
+
+size_t packed_text_kv_bytes(int B, int TL, int count, int C) {
+  const int XA = (TL + 31) / 32;
+  return (size_t)B * count * (C / 64) * 12 * XA * 1024;
+}
+
+int launch_pack_text_kv(const bf16_t* kv, long long ld, bf16_t* out, int B, int TL, int count, int C, hipStream_t st) {
+  if (B <= 0 || TL <= 0 || count <= 0 || C % 64 || ld % 8 || ((uintptr_t)kv % 16) || ((uintptr_t)out % 16)) return DF_ESHAPE;
+  const int XA = (TL + 31) / 32;
+  const long long total = (long long)B * count * (C / 64) * 12 * XA * 64;
+  hipLaunchKernelGGL(pack_text_kv_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, kv, ld, (u32x4*)out, B, TL,
+                     count, C, XA, total);
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
 
 size_t packed_rows_bytes(long long M, long long K) { return (size_t)((M + 31) / 32) * 32 * K * 2; }
 
@@ -444,6 +591,27 @@ int launch_wgemm(const WGemmArgs& a, hipStream_t st) {
       p.seg_out[i] = (bf16_t*)a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
     }
+  }
+  if (a.xa_kv) {
+    const int XA = (a.xa_keys + 31) / 32;
+    if (a.geglu || a.nseg || !a.ln_s || !a.out_packed || a.N % 64 || XA < 1 || XA > 4 || a.xa_rows <= 0 ||
+        (a.M != a.xa_rows && a.xa_rows % 32) || !al(a.xa_kv, 16))
+      return DF_ESHAPE;
+    p.xkv = (const bf16x8*)a.xa_kv; p.xa_keys = a.xa_keys; p.xa_rows = a.xa_rows; p.xa_scale = a.xa_scale;
+    p.xa_bstride = a.xa_bstride / 8;
+    const int KFw = a.K / 16 / 4;
+#define DF_XA(PFV)                                                             \
+  switch (XA) {                                                                \
+    case 1: return launch_one<1, 2, 4, PFV, true, 1>(p, st);                   \
+    case 2: return launch_one<1, 2, 4, PFV, true, 2>(p, st);                   \
+    case 3: return launch_one<1, 2, 4, PFV, true, 3>(p, st);                   \
+    default: return launch_one<1, 2, 4, PFV, true, 4>(p, st);                  \
+  }
+    if (KFw % 5 == 0) { DF_XA(5) }
+    if (KFw % 4 == 0) { DF_XA(4) }
+    if (KFw % 2 == 0) { DF_XA(2) }
+    DF_XA(1)
+#undef DF_XA
   }
   switch (tune_cfg()) {                                  // DF_WGEMM_CFG: tuning aid
     case 1: return launch_cfg<1, 2, 4, 5>(p, st);
