@@ -35,6 +35,7 @@ struct TileParams {
   const float* bias;
   const float* residual;
   const float* chan_add;
+  long long chan_ld;
   void* out;
   int M, N, K;
   long long lda, ldw, ldr, ldo;
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
         if (row >= p.M) continue;
         float v = acc[tm][tn][e] + bias;
         if constexpr (kConv) {
-          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.N + col];
+          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.chan_ld + col];
         }
         if (p.residual) v += p.residual[(long long)row * p.ldr + col];
         if (p.act == 1) v = silu_f(v);
@@ -594,7 +595,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
       f32x4 v = *reinterpret_cast<const f32x4*>(tile + lr_ * PT + c4);
       if constexpr (kConv) {
         if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + col);
-        if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.N + col);
+        if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.chan_ld + col);
       } else {
         if (ln_fold)
           v = (v - *reinterpret_cast<const f32x4*>(p.ln_s + col) * s_mr[lr_ * 2]) * s_mr[lr_ * 2 + 1] +
@@ -709,7 +710,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
         if (row >= p.M) continue;
         float v = acc[tm][tn][e] + bias;
         if constexpr (kConv) {
-          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.N + col];
+          if (p.chan_add) v += p.chan_add[(long long)(row / per) * p.chan_ld + col];
         } else {
           if (ln_fold) v = s_mr[lr_ * 2 + 1] * (acc[tm][tn][e] - s_mr[lr_ * 2] * ln_sc) + ln_tc;
         }
@@ -897,7 +898,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(TileParams p, const 
   for (int s = 0; s < nsplit; ++s)
     v += *reinterpret_cast<const f32x4*>(partials + ((size_t)s * p.M + row) * p.N + col);
   if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + col);
-  if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.N + col);
+  if (p.chan_add) v += *reinterpret_cast<const f32x4*>(p.chan_add + (long long)(row / per) * p.chan_ld + col);
   if (p.residual) v += *reinterpret_cast<const f32x4*>(p.residual + (long long)row * p.ldr + col);
   if (p.act == 1) { v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w); }
   OutT* o = reinterpret_cast<OutT*>(p.out) + (long long)row * p.ldo + col;
@@ -935,7 +936,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   TileParams q = p;
   {
     auto al = [](const void* ptr, int a) { return ((uintptr_t)ptr % a) == 0; };
-    bool ok = p.N % 4 == 0 && p.ldo % 4 == 0 && al(p.out, 16) && al(p.bias, 16) && al(p.chan_add, 16) &&
+    bool ok = p.N % 4 == 0 && p.ldo % 4 == 0 && al(p.out, 16) && al(p.bias, 16) && al(p.chan_add, 16) && p.chan_ld % 4 == 0 &&
               (!p.residual || (p.ldr % 4 == 0 && al(p.residual, 16))) && (!p.out2 || (p.ldo2 % 4 == 0 && al(p.out2, 8))) &&
               al(p.ln_s, 16) && al(p.ln_t, 16) && (!p.geglu || p.geglu % 4 == 0);
     for (int i = 0; i < p.nseg; ++i) ok = ok && (p.seg_tr[i] || (p.seg_ld[i] % 4 == 0 && al(p.seg_out[i], 8))) && p.seg_w % 4 == 0;
@@ -1114,13 +1115,14 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
   if (mfma) {
     TileParams p = {};
     p.A = (const bf16_t*)a.x; p.Wt = (const bf16_t*)a.w; p.bias = a.bias; p.residual = a.residual;
-    p.chan_add = a.chan_add; p.out = a.y;
+    p.chan_add = a.chan_add; p.chan_ld = a.chan_ld ? a.chan_ld : a.Cout; p.out = a.y;
     p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin; p.lda = 0; p.ldw = 9LL * a.Cin; p.ldr = a.Cout; p.ldo = a.Cout;
     p.act = a.act;
     p.top = (const bf16_t*)a.halo_top; p.bot = (const bf16_t*)a.halo_bot; p.halo_bs = a.halo_bstride;
     p.R = a.R; p.W = a.W; p.Cin = a.Cin; p.Ro = Ro; p.Wo = Wo; p.stride = a.stride;
     return pick_tile<true>(p, a.out_dtype, st);
   }
+  if (a.chan_add && a.chan_ld && a.chan_ld != a.Cout) return DF_ESHAPE;   // the direct kernels assume a dense [B, Cout]
   const long long total = M * a.Cout;
 #define DF_DIRECT(T, OT)                                                                                              \
   hipLaunchKernelGGL((conv3x3_direct<T, OT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a.x, \

@@ -51,7 +51,8 @@ struct ConvArgs {
   long long halo_bstride;
   const void* w;         // [Cout, 3, 3, Cin]
   const float* bias;     // [Cout] or nullptr
-  const float* chan_add; // [B, Cout] added per batch item and channel, or nullptr
+  const float* chan_add; // [B, Cout] added per batch item and channel (row stride chan_ld), or nullptr
+  long long chan_ld;
   const float* residual; // [B, Ro, Wo, Cout] float added before the activation, or nullptr
   void* y;               // [B, Ro, Wo, Cout]
   int B, R, W, Cin, Cout, stride, act;

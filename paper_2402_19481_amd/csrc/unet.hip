@@ -191,6 +191,16 @@ inline bool frag_path() {
 
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
+// Output channels of the conditioning projections of all residual blocks, in block order: one GEMM at the start of
+// the step computes them all (they depend on the embedding vector only).
+inline int emb_total(const std::vector<BlockDesc>& blocks) {
+  int t = 0;
+  for (const BlockDesc& b : blocks)
+    if (b.kind == BlockDesc::RES) t += b.cout;
+  return t;
+}
+
+
 }  // namespace
 
 // Optional per-launch timing: when enabled every kernel launch of a step is bracketed by two
@@ -273,6 +283,7 @@ struct df_unet {
   size_t kv_off[4] = {0, 0, 0, 0};
   int kv_count[4] = {0, 0, 0, 0};
   size_t packed_bytes = 0;
+  size_t emb_w_off = 0, emb_b_off = 0;   // concatenated conditioning-projection weights / biases
 };
 
 namespace {
@@ -303,6 +314,10 @@ struct Exec {
   int kv_cursor[4] = {0, 0, 0, 0};
   bf16_t* kv2_all[4] = {nullptr, nullptr, nullptr, nullptr};
   bf16_t* xkv_all[4] = {nullptr, nullptr, nullptr, nullptr};   // text keys / values as per-head MFMA fragments
+  const bf16_t* emb_w_all = nullptr;     // [sum of cout, emb_dim] conditioning projections of all residual blocks
+  const float* emb_b_all = nullptr;
+  float* emb_all = nullptr;              // their outputs for this step, [B, emb_n]
+  int emb_n = 0, emb_cursor = 0;
 
   // run a launch, accounted to class `cls` when per-launch timing is on
   template <typename F>
@@ -429,7 +444,7 @@ struct Exec {
   // `entry_in` non-null: the stale entry was looked up by the caller and the producer of x has already refreshed it
   void conv(const std::string& name, const bf16_t* x, int R, int W, int Cin, int Cout, int stride, void* out,
             int out_dtype, const float* chan_add, const float* residual, bf16_t* entry_in = nullptr,
-            bool halo_done = false) {
+            bool halo_done = false, long long chan_ld = 0) {
     const size_t rowe = (size_t)W * Cin;
     bf16_t* entry = halo_done ? entry_in : conv_entry(name, W, Cin);
     const void* wt = weight(name + ".w");
@@ -440,7 +455,7 @@ struct Exec {
     }
     if (!live()) return;
     ConvArgs a = {};
-    a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.residual = residual; a.y = out;
+    a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.chan_ld = chan_ld ? chan_ld : Cout; a.residual = residual; a.y = out;
     a.B = B(); a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = 0;
     a.dtype = DF_BF16; a.out_dtype = out_dtype;
     a.halo_bstride = (long long)N() * 2 * rowe;
@@ -480,13 +495,13 @@ struct Exec {
     bf16_t* a1 = (bf16_t*)alloc(px * b.cin * 2);
     bf16_t* h1 = (bf16_t*)alloc(px * b.cout * 2);
     bf16_t* a2 = (bf16_t*)alloc(px * b.cout * 2);
-    float* embp = (float*)alloc((size_t)B() * b.cout * 4);
+    const float* embp = emb_all ? emb_all + emb_cursor : nullptr;     // this block's columns of the hoisted projection
+    emb_cursor += b.cout;
     bf16_t* e1 = conv_entry(b.name + ".conv1", W, b.cin);
     bf16_t* e2 = conv_entry(b.name + ".conv2", W, b.cout);
     const bool hd = dry || e1 != nullptr;      // the GroupNorm kernels refresh the boundary rows of the convolutions
     groupnorm(b.name + ".gn1", x, DF_F32, R, W, b.cin, 1e-5f, 1, a1, 0, e1);
-    gemm(emb_act, c.emb_dim, b.name + ".emb", true, nullptr, 0, embp, b.cout, B(), b.cout, c.emb_dim, DF_F32);
-    conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr, e1, hd);
+    conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr, e1, hd, emb_n);
     groupnorm(b.name + ".gn2", h1, DF_BF16, R, W, b.cout, 1e-5f, 1, a2, 0, e2);
     const float* residual = x;
     if (b.cin != b.cout) {
@@ -857,6 +872,10 @@ struct Exec {
     int cur_c = c.in_ch;
     bf16_t* emb_act = (bf16_t*)alloc((size_t)B() * c.emb_dim * 2);
     timed(PC_ELEMENTWISE, 0.0, 6.0 * B() * c.emb_dim, [&] { return launch_cast_bf16(emb, emb_act, (long long)B() * c.emb_dim, 1, st); });
+    emb_n = emb_total(blocks);
+    emb_cursor = 0;
+    emb_all = (float*)alloc((size_t)B() * emb_n * 4);
+    gemm_w(emb_act, c.emb_dim, emb_w_all, emb_b_all, nullptr, 0, emb_all, emb_n, B(), emb_n, c.emb_dim, DF_F32);
     for (int lv = 0; lv < c.n_levels; ++lv) {
       kv_cursor[lv] = 0;
       if (kv_count[lv] == 0) continue;
@@ -992,6 +1011,7 @@ std::vector<PackSpec> build_pack_specs(const df_unet_cfg& c, const std::vector<B
 
 struct DryResult {
   size_t ws_bytes, stale_bytes, scratch, packed_bytes;
+  size_t emb_w_off, emb_b_off;
   size_t kv_off[4];
   int kv_count[4];
   std::vector<StaleEntry> stale;
@@ -1023,6 +1043,10 @@ DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
   }
   size_t end = off;
   build_pack_specs(c, blocks, off, &end);
+  r.emb_w_off = end;
+  end += align256((size_t)emb_total(blocks) * c.emb_dim * sizeof(bf16_t));
+  r.emb_b_off = end;
+  end += align256((size_t)emb_total(blocks) * sizeof(float));
   r.packed_bytes = end;
   r.ws_bytes += end + 256;
   return r;
@@ -1137,6 +1161,20 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
       }
       u->packed[sp.name] = pw;
     }
+    {
+      u->emb_w_off = d.emb_w_off; u->emb_b_off = d.emb_b_off;
+      size_t row = 0;
+      for (const BlockDesc& b : u->blocks) {
+        if (b.kind != BlockDesc::RES) continue;
+        const void* wsrc = u->w[b.name + ".emb.w"];
+        const void* bsrc = u->w[b.name + ".emb.b"];
+        if (hipMemcpy(u->ws + u->emb_w_off + row * cfg->emb_dim * sizeof(bf16_t), wsrc,
+                      (size_t)b.cout * cfg->emb_dim * sizeof(bf16_t), hipMemcpyDeviceToDevice) != hipSuccess ||
+            hipMemcpy(u->ws + u->emb_b_off + row * sizeof(float), bsrc, (size_t)b.cout * sizeof(float),
+                      hipMemcpyDeviceToDevice) != hipSuccess) { delete u; return DF_EHIP; }
+        row += b.cout;
+      }
+    }
     if (hipDeviceSynchronize() != hipSuccess) { delete u; return DF_EHIP; }
   }
   // reserve the library scratch now, so that no step ever has to grow it
@@ -1185,6 +1223,8 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   }
   e.packed = &u->packed;
   e.gn_mode = u->gn_mode;
+  e.emb_w_all = (const bf16_t*)(u->ws + u->emb_w_off);
+  e.emb_b_all = (const float*)(u->ws + u->emb_b_off);
   e.stale_base = (char*)stale;
   e.stale_list = &u->stale;
   e.stale_idx = &u->stale_idx;
