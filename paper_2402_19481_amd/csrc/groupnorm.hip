@@ -110,9 +110,10 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
 
 // Mean and variance of one (batch item, group) from the fresh sums of this launch and the cached per-patch sums,
 // according to the statistic mode (Section 4, Eq. 2; Section 5.3).
-__device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
-                                           const float* __restrict__ stale, int b, int g, int B, int G, int patch_idx,
-                                           float& mean, float& var) {
+// `st_*`: sums of the cached entries of the other patches, `own_*`: the cached entry of this patch.
+__device__ __forceinline__ void gn_combine_pre(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
+                                               float st_s, float st_q, float own_s, float own_q, float& mean,
+                                               float& var) {
   if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
     // the whole image is fresh: exact statistics
     const float n = n_loc * (float)nseg;
@@ -121,12 +122,6 @@ __device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc
     return;
   }
   const float n_glob = n_loc * (float)N;
-  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
-  for (int j = 0; j < N; ++j) {
-    const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
-    const float a = sp[0], c = sp[1];
-    if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
-  }
   const float loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
   if (stat_mode == DF_GN_SUMS) {
     mean = (tot_s + st_s) / n_glob;
@@ -142,6 +137,41 @@ __device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc
   } else {
     mean = (st_s + own_s) / n_glob;
     var = fmaxf((st_q + own_q) / n_glob - mean * mean, 0.f);
+  }
+}
+
+__device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
+                                           const float* __restrict__ stale, int b, int g, int B, int G, int patch_idx,
+                                           float& mean, float& var) {
+  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  if (!(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE))) {
+    for (int j = 0; j < N; ++j) {
+      const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
+      const float a = sp[0], c = sp[1];
+      if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
+    }
+  }
+  gn_combine_pre(tot_s, tot_q, n_loc, nseg, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
+}
+
+// The cached sums of one (batch item, group) gathered by a whole wave: lane j fetches patch j's entry (one memory
+// round trip for all patches instead of a chain of N), lane order fixes the order of the additions.
+__device__ __forceinline__ void gn_stale_wave(const float* __restrict__ stale, int b, int g, int B, int G, int N,
+                                              int patch_idx, int lane, float& st_s, float& st_q, float& own_s,
+                                              float& own_q) {
+  st_s = st_q = own_s = own_q = 0.f;
+  if (stale == nullptr) return;
+  for (int j0 = 0; j0 < N; j0 += 64) {
+    float a = 0.f, c = 0.f;
+    if (j0 + lane < N) {
+      const float* sp = stale + (((long long)(j0 + lane) * B + b) * G + g) * 2;
+      a = sp[0]; c = sp[1];
+    }
+    const int n = N - j0 < 64 ? N - j0 : 64;
+    for (int j = 0; j < n; ++j) {
+      const float aj = __shfl(a, j, 64), cj = __shfl(c, j, 64);
+      if (j0 + j == patch_idx) { own_s = aj; own_q = cj; } else { st_s += aj; st_q += cj; }
+    }
   }
 }
 
@@ -346,6 +376,99 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
   }
 }
 
+// The same for one segment whose share per lane is at most NV pixels: every lane requests all its pixels at once
+// (one memory round trip instead of one per pass) and keeps them in registers for the normalisation, so x is read
+// once.
+template <typename Tin, typename Tout, int NV>
+__global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restrict__ x, Tout* __restrict__ y,
+                                                            const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                            const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                            int pix, int C, int G, int B, int patch_idx, int N, float eps,
+                                                            int stat_mode, int silu, int packed, GnHalo halo) {
+  __shared__ float s_s[1024], s_q[1024];
+  __shared__ float s_mr[2];
+  const int g = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int cg = C / G, cgv = cg >> 2;
+  const int ppass = blockDim.x / cgv;
+  const int cv = tid % cgv, psub = tid / cgv;
+  const bool active = psub < ppass;
+  const int c0 = g * cg + cv * 4;
+  const long long base = (long long)b * pix;
+  float v[NV][4];
+  float a = 0.f, q = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int p = psub + k * ppass;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[k][i] = 0.f;
+    if (active && p < pix) {
+      const Tin* src = x + (base + p) * C + c0;
+      if constexpr (sizeof(Tin) == 4) {
+        ld_vec(src, v[k]);
+      } else {
+        const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+        v[k][0] = __uint_as_float(t.x << 16); v[k][1] = __uint_as_float(t.x & 0xffff0000u);
+        v[k][2] = __uint_as_float(t.y << 16); v[k][3] = __uint_as_float(t.y & 0xffff0000u);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a += v[k][i]; q = fmaf(v[k][i], v[k][i], q); }
+  s_s[tid] = a; s_q[tid] = q;
+  __syncthreads();
+  if (tid < 64) {
+    float fs = 0.f, fq = 0.f;
+    for (int k = lane; k < (int)blockDim.x; k += 64) { fs += s_s[k]; fq += s_q[k]; }
+    fs = wave_sum(fs); fq = wave_sum(fq);
+    float st_s, st_q, own_s, own_q;
+    gn_stale_wave((N == 1 && stat_mode != DF_GN_STALE) ? nullptr : stale, b, g, B, G, N, patch_idx, lane, st_s, st_q,
+                  own_s, own_q);
+    if (tid == 0) {
+      float mean, var;
+      gn_combine_pre(fs, fq, (float)pix * (float)cg, 1, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
+      if (sums_out != nullptr) {                     // after the stale sums were read: may alias the own slot
+        float* o = sums_out + ((long long)b * G + g) * 2;
+        o[0] = fs; o[1] = fq;
+      }
+      s_mr[0] = mean;
+      s_mr[1] = 1.0f / sqrtf(var + eps);
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+  const float mean = s_mr[0], rstd = s_mr[1];
+  float sc[4], sh[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sc[i] = rstd * gamma[c0 + i];
+    sh[i] = beta[c0 + i] - mean * sc[i];
+  }
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int p = psub + k * ppass;
+    if (p >= pix) continue;
+    float o4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float t = fmaf(v[k][i], sc[i], sh[i]);
+      o4[i] = silu ? silu_f(t) : t;
+    }
+    const long long m = base + p;
+    Tout* o = y + m * C + c0;
+    if (packed) o = y + (((m >> 5) * (C >> 4) + (c0 >> 4)) * 64 + (m & 31) + 32 * ((c0 >> 3) & 1)) * 8 + (c0 & 7);
+    if constexpr (sizeof(Tout) == 4) {
+      st_vec(o, o4);
+    } else {
+      u32x2 t = {pack_bf2(o4[0], o4[1]), pack_bf2(o4[2], o4[3])};
+      *reinterpret_cast<u32x2*>(o) = t;
+      if (halo.out) halo_store<4>(halo, b, p, C, c0, o4);
+    }
+  }
+}
+
 GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_threads) {
   GnLayout L;
   L.tp = C / vec;
@@ -391,6 +514,20 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
     static const bool no_fused = getenv("DF_GN_3K") != nullptr;   // tuning aid
     if (!no_fused && cg % 4 == 0 && cg / 4 <= 1024 && per_group <= kGnGroupMaxElems) {
       dim3 grid(a.G, a.B);
+      const int ppass = 1024 / (cg / 4);
+      if (a.nseg == 1 && pix_seg <= (long long)ppass * 8) {
+        // one patch, at most 8 pixels per lane: single read of x
+#define DF_GN_REG(TI, TO)                                                                                             \
+  hipLaunchKernelGGL((gn_group_reg_kernel<TI, TO, 8>), grid, dim3(1024), 0, st, (const TI*)a.x, (TO*)a.y, a.stale,     \
+                     a.sums_out, a.gamma, a.beta, (int)pix_seg, a.C, a.G, a.B, a.patch_idx, a.N, a.eps, a.stat_mode,  \
+                     a.silu, a.y_packed, halo)
+        if (a.in_dtype == DF_BF16) DF_GN_REG(bf16_t, bf16_t);
+        else if (a.out_dtype == DF_BF16) DF_GN_REG(float, bf16_t);
+        else DF_GN_REG(float, float);
+#undef DF_GN_REG
+        DF_LAUNCH_CHECK();
+        return DF_OK;
+      }
 #define DF_GN_GROUP(TI, TO)                                                                                         \
   hipLaunchKernelGGL((gn_group_kernel<TI, TO>), grid, dim3(1024), 0, st, (const TI*)a.x, (TO*)a.y, a.stale, a.sums_out, \
                      a.gamma, a.beta, (int)pix_seg, a.C, a.G, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode, a.silu, \
