@@ -234,6 +234,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly (no HIP graph replay)")
     ap.add_argument("--small", action="store_true", help="reduced-width UNet (plumbing check, not the benchmark)")
+    ap.add_argument("--workload", choices=["cfg4", "3840"], default="cfg4",
+                    help="cfg4: the headline workload (1280x1920, N=8); 3840: one of 8 row patches of a 3840x3840 image "
+                         "(480x480 latent), the paper's best-scaling resolution - a second workload, not the headline")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -256,6 +259,11 @@ def main():
         cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
         patch = 1
         workload = "reduced-width UNet 32x16 latent, N=4 (plumbing check)"
+    elif args.workload == "3840":
+        cfg = ut.UNetCfg(H=480, W=480, N=8, **ut.SDXL)
+        patch = 3
+        workload = ("SDXL-shaped UNet step for one patch: 3840x3840 image (480x480x4 latent), N=8 row patches "
+                    "(60 latent rows), patch 3, DISPLACED + refresh")
     else:
         cfg = ut.UNetCfg(H=160, W=240, N=8, **ut.SDXL)
         patch = 3
@@ -324,7 +332,7 @@ def main():
                             event_ms_per_step=round(v["event_ms"] / args.profile_steps, 4))
     dom = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
     d = prof[dom]
-    traffic = None if args.small else measured_traffic(dom)
+    traffic = None if (args.small or args.workload != "cfg4") else measured_traffic(dom)
     if traffic is not None:
         traffic = round(traffic / (d["launches"] / args.profile_steps))      # per launch, like `achieved`
     if d["flops"] > 0:
@@ -362,7 +370,7 @@ def main():
         "breakdown": breakdown,
         "event_overhead_us_per_launch": round(ev_over_ms * 1e3, 2),
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "cfg4":
         xin = x.cpu().numpy()
         out["cpu_baseline"] = cpu_baseline(cfg, weights, specs, (xin, emb.cpu().numpy(), text.float().cpu().numpy()), patch)
     else:
