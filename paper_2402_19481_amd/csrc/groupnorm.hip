@@ -395,6 +395,13 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
   const bool active = psub < ppass;
   const int c0 = g * cg + cv * 4;
   const long long base = (long long)b * pix;
+  // everything that does not depend on x is requested first: affine parameters and the cached sums
+  float gm[4] = {0.f, 0.f, 0.f, 0.f}, bt[4] = {0.f, 0.f, 0.f, 0.f};
+  if (active) { ld_vec(gamma + c0, gm); ld_vec(beta + c0, bt); }
+  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  if (tid < 64)
+    gn_stale_wave((N == 1 && stat_mode != DF_GN_STALE) ? nullptr : stale, b, g, B, G, N, patch_idx, lane, st_s, st_q,
+                  own_s, own_q);
   float v[NV][4];
   float a = 0.f, q = 0.f;
 #pragma unroll
@@ -423,9 +430,6 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
     float fs = 0.f, fq = 0.f;
     for (int k = lane; k < (int)blockDim.x; k += 64) { fs += s_s[k]; fq += s_q[k]; }
     fs = wave_sum(fs); fq = wave_sum(fq);
-    float st_s, st_q, own_s, own_q;
-    gn_stale_wave((N == 1 && stat_mode != DF_GN_STALE) ? nullptr : stale, b, g, B, G, N, patch_idx, lane, st_s, st_q,
-                  own_s, own_q);
     if (tid == 0) {
       float mean, var;
       gn_combine_pre(fs, fq, (float)pix * (float)cg, 1, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
@@ -443,8 +447,8 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
   float sc[4], sh[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    sc[i] = rstd * gamma[c0 + i];
-    sh[i] = beta[c0 + i] - mean * sc[i];
+    sc[i] = rstd * gm[i];
+    sh[i] = bt[i] - mean * sc[i];
   }
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
