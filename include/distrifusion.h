@@ -147,6 +147,30 @@ int df_linear_packed(const void* xp, const void* wp, const float* bias, const fl
                      float ln_eps, const float* residual, float* y_f32, void* y_packed, void* y_rows, int M, int N,
                      int K, int geglu, void* stream);
 
+/*
+ * The two attention forms the UNet step runs internally, exposed for tests and measurements.
+ *
+ * df_attn_stale_vt: self-attention of Lq query rows against L key rows when every key already sits in the (refreshed)
+ * stale buffers and the values are stored transposed (Section 4: the patch's own K / V rows are written into the
+ * buffers by the projection, so no splice is left for the attention kernel).  q [B, Lq, heads*64], k [B, L, heads*64],
+ * vt [B, heads*64, vt_ld] with vt[b][c][j] = v[b][j][c], vt_ld >= L rounded up to a multiple of 64 (columns beyond L
+ * are never used); out [B, Lq, heads*64] row-major, or fragment-packed (rows = B*Lq) if out_packed.  bf16, d = 64.
+ *
+ * df_cross_attn_packed: cross-attention to the text tokens fused into its query projection (Section 4: per-token
+ * layers need no data of other patches).  out = softmax(q k^T * scale) v per head with q = LayerNorm(x) wq^T, the
+ * norm folded as in df_linear_packed (ln_s, ln_t).  x and out are fragment-packed [B*rows_per_batch, C]; wq_packed
+ * from df_pack_linear_weight; text_kv_packed from df_pack_text_kv, which re-lays the projected text keys / values
+ * kv [B*text_len, count*2C] (per block C key columns then C value columns, row-major bf16) of `count` blocks as MFMA
+ * fragments; `block` selects one.  text_len <= 128; rows_per_batch % 32 == 0 unless B == 1; C % 64 == 0.
+ */
+int df_attn_stale_vt(const void* q, const void* k, const void* vt, void* out, int B, int Lq, int L, int heads,
+                     long long vt_ld, float scale, int out_packed, void* stream);
+size_t df_packed_text_kv_bytes(int B, int text_len, int count, int C);
+int df_pack_text_kv(const void* kv, void* packed, int B, int text_len, int count, int C, void* stream);
+int df_cross_attn_packed(const void* xp, const void* wq_packed, const float* ln_s, const float* ln_t, float ln_eps,
+                         const void* text_kv_packed, void* out_packed, int B, int rows_per_batch, int C, int text_len,
+                         int count, int block, float scale, void* stream);
+
 /* ---- whole UNet step --------------------------------------------------------------------- */
 
 typedef struct df_unet_cfg {

@@ -54,6 +54,11 @@ def lib():
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.df_scale_input.argtypes = [vp, vp, f, ll, vp]
     L.df_mfma_probe.argtypes = [vp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    L.df_attn_stale_vt.argtypes = [vp, vp, vp, vp, i, i, i, i, ll, f, i, vp]
+    L.df_packed_text_kv_bytes.restype = sz
+    L.df_packed_text_kv_bytes.argtypes = [i, i, i, i]
+    L.df_pack_text_kv.argtypes = [vp, vp, i, i, i, i, vp]
+    L.df_cross_attn_packed.argtypes = [vp, vp, vp, vp, f, vp, vp, i, i, i, i, i, i, f, vp]
     L.df_packed_bytes.restype = sz
     L.df_packed_bytes.argtypes = [ll, ll]
     L.df_pack_rows.argtypes = [vp, vp, i, i, vp]
@@ -85,7 +90,8 @@ def lib():
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
-                 "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_mfma_probe", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
+                 "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_mfma_probe", "df_attn_stale_vt", "df_packed_text_kv_bytes", "df_pack_text_kv",
+                 "df_cross_attn_packed", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
                  "df_unet_stale_lookup", "df_unet_num_stale", "df_unet_stale_name", "df_patch_unet_step",
                  "df_unet_profile_enable", "df_unet_set_graph", "df_unet_profile_reset", "df_unet_profile_num_classes",
                  "df_unet_profile_read"):
@@ -174,6 +180,38 @@ def linear(x, w, bias=None, residual=None, out_dtype=torch.bfloat16, out=None):
     if out is None:
         out = torch.empty(M, N, dtype=out_dtype, device=x.device)
     _check(lib().df_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), M, N, K, _dt(out), _stream()))
+    return out
+
+
+def attn_stale_vt(q, k, vt, heads, L, scale=None, packed=False):
+    """q [B,Lq,C], k [B,L,C], vt [B,C,vt_ld] (values transposed) -> attention output, row-major [B,Lq,C] or packed."""
+    B, Lq, C = q.shape
+    if scale is None:
+        scale = 64 ** -0.5
+    if packed:
+        out = torch.empty(lib().df_packed_bytes(B * Lq, C) // 2, dtype=torch.bfloat16, device=q.device)
+    else:
+        out = torch.empty_like(q)
+    _check(lib().df_attn_stale_vt(_ptr(q), _ptr(k), _ptr(vt), _ptr(out), B, Lq, L, heads, vt.shape[2], scale,
+                                  1 if packed else 0, _stream()))
+    return out
+
+
+def pack_text_kv(kv, B, text_len, count, C):
+    """kv [B*text_len, count*2C] bf16 (projected text keys / values of `count` blocks) -> per-head MFMA fragments."""
+    out = torch.empty(lib().df_packed_text_kv_bytes(B, text_len, count, C) // 2, dtype=torch.bfloat16, device=kv.device)
+    _check(lib().df_pack_text_kv(_ptr(kv), _ptr(out), B, text_len, count, C, _stream()))
+    return out
+
+
+def cross_attn_packed(xp, wq_packed, ln_s, ln_t, text_kv_packed, B, rows_per_batch, C, text_len, count, block,
+                      ln_eps=1e-5, scale=None):
+    """Cross-attention fused into its LayerNorm-folded query projection; returns the packed output [B*rows, C]."""
+    if scale is None:
+        scale = 64 ** -0.5
+    out = torch.empty(lib().df_packed_bytes(B * rows_per_batch, C) // 2, dtype=torch.bfloat16, device=xp.device)
+    _check(lib().df_cross_attn_packed(_ptr(xp), _ptr(wq_packed), _ptr(ln_s), _ptr(ln_t), ln_eps, _ptr(text_kv_packed),
+                                      _ptr(out), B, rows_per_batch, C, text_len, count, block, scale, _stream()))
     return out
 
 

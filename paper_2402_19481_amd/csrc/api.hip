@@ -136,6 +136,48 @@ int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, c
   return launch_attention(a, (hipStream_t)stream);
 }
 
+int df_attn_stale_vt(const void* q, const void* k, const void* vt, void* out, int B, int Lq, int L, int heads,
+                     long long vt_ld, float scale, int out_packed, void* stream) {
+  if (!q || !k || !vt || !out) return DF_EINVAL;
+  if (B <= 0 || Lq <= 0 || L <= 0 || heads <= 0) return DF_ESHAPE;
+  const long long C = (long long)heads * 64;
+  AttnArgs a = {};
+  a.q = q; a.k_fresh = k; a.v_fresh = vt; a.k_stale = k; a.v_stale = vt; a.out = out;
+  a.B = B; a.Lq = Lq; a.L = L; a.heads = heads; a.d = 64; a.own_lo = 0; a.own_n = 0;
+  a.ldq = a.ldkf = a.ldvf = a.ldks = a.ldvs = a.ldo = C;
+  a.bsq = a.bso = (long long)Lq * C; a.bskf = a.bsvf = a.bsks = (long long)L * C; a.bsvs = C * vt_ld;
+  a.v_transposed = 1; a.vt_ld = vt_ld; a.out_packed = out_packed ? 1 : 0;
+  a.scale = scale; a.dtype = DF_BF16;
+  return launch_attention(a, (hipStream_t)stream);
+}
+
+size_t df_packed_text_kv_bytes(int B, int text_len, int count, int C) {
+  return (B > 0 && text_len > 0 && count > 0 && C > 0 && C % 64 == 0) ? packed_text_kv_bytes(B, text_len, count, C) : 0;
+}
+
+int df_pack_text_kv(const void* kv, void* packed, int B, int text_len, int count, int C, void* stream) {
+  if (!kv || !packed) return DF_EINVAL;
+  if (text_len > 128) return DF_ESHAPE;
+  return launch_pack_text_kv((const bf16_t*)kv, (long long)count * 2 * C, (bf16_t*)packed, B, text_len, count, C,
+                             (hipStream_t)stream);
+}
+
+int df_cross_attn_packed(const void* xp, const void* wq_packed, const float* ln_s, const float* ln_t, float ln_eps,
+                         const void* text_kv_packed, void* out_packed, int B, int rows_per_batch, int C, int text_len,
+                         int count, int block, float scale, void* stream) {
+  if (!xp || !wq_packed || !ln_s || !ln_t || !text_kv_packed || !out_packed) return DF_EINVAL;
+  if (B <= 0 || rows_per_batch <= 0 || C <= 0 || C % 64 || text_len <= 0 || text_len > 128 || block < 0 || block >= count)
+    return DF_ESHAPE;
+  const int XA = (text_len + 31) / 32, heads = C / 64;
+  WGemmArgs a = {};
+  a.Xp = xp; a.Wp = wq_packed; a.M = B * rows_per_batch; a.N = C; a.K = C;
+  a.ln_s = ln_s; a.ln_t = ln_t; a.ln_eps = ln_eps; a.out_packed = out_packed;
+  a.xa_kv = (const bf16_t*)text_kv_packed + (size_t)block * heads * 12 * XA * 512;
+  a.xa_keys = text_len; a.xa_rows = rows_per_batch; a.xa_scale = scale;
+  a.xa_bstride = (long long)count * heads * 12 * XA * 512;
+  return launch_wgemm(a, (hipStream_t)stream);
+}
+
 int df_linear(const void* x, const void* w, const float* bias, const float* residual, void* y, int M, int N, int K,
               int out_dtype, void* stream) {
   if (!x || !w || !y || bad_dtype(out_dtype)) return DF_EINVAL;

@@ -375,3 +375,69 @@ def test_linear_packed(M, N, K, variant):
     # determinism and in-place residual
     outs2 = df.linear_packed(xp, wp, M, N, K, residual=rd, geglu=geglu, want=("f32",), **kw)
     np.testing.assert_array_equal(host(outs["f32"]), host(outs2["f32"]))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# the attention forms of the UNet step: transposed values in the stale buffer; cross-attention fused into its
+# query projection
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,Lq,L,heads,packed", [
+    (1, 300, 2400, 20, True),       # level 2 of the benchmark step: ragged last key tile, 2.3 query blocks
+    (1, 1200, 9600, 10, False),     # level 1
+    (2, 96, 200, 2, True),          # two batch items, key count not a multiple of 8
+    (1, 33, 64, 1, False),          # a single full tile, ragged queries
+])
+def test_attn_stale_vt(B, Lq, L, heads, packed):
+    say("attn_stale_vt", B, Lq, L, heads, packed)
+    C = heads * 64
+    q = round_bf16(normal(51, "q", (B, Lq, C)))
+    k = round_bf16(normal(51, "k", (B, L, C)))
+    v = round_bf16(normal(51, "v", (B, L, C)))
+    ref = ops.attention_dense(q, k, v, heads)
+    Lp = (L + 63) // 64 * 64
+    vt = np.full((B, C, Lp), np.nan, dtype=np.float32)      # pad columns hold NaN: they must never contribute
+    vt[:, :, :L] = v.transpose(0, 2, 1)
+    vt_d = dev(np.nan_to_num(vt, nan=0.0), True)
+    if Lp > L:
+        vt_d[:, :, L:] = float("nan")
+    out = df.attn_stale_vt(dev(q, True), dev(k, True), vt_d, heads, L, packed=packed)
+    got = unpack_rows(host(out), B * Lq, C)[0].reshape(B, Lq, C) if packed else host(out)
+    e = rel_l2(got, ref)
+    say("   rel_l2", e)
+    assert np.isfinite(got).all() and e < TOL_BF16
+    out2 = df.attn_stale_vt(dev(q, True), dev(k, True), vt_d, heads, L, packed=packed)
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+@pytest.mark.parametrize("B,rows,C,TL,count,block", [
+    (1, 300, 1280, 77, 3, 1),       # level 2 of the benchmark step
+    (1, 1200, 640, 77, 2, 0),       # level 1
+    (2, 64, 128, 13, 2, 1),         # two batch items, one key tile
+    (1, 40, 256, 128, 1, 0),        # the longest supported text
+])
+def test_cross_attn_packed(B, rows, C, TL, count, block):
+    say("cross_attn_packed", B, rows, C, TL, count, block)
+    heads = C // 64
+    M = B * rows
+    x = round_bf16(normal(52, "x", (M, C)) + 0.2)
+    wq = round_bf16(normal(52, "wq", (C, C), std=1.0 / math.sqrt(C)))
+    gamma = (1.0 + 0.2 * normal(52, "g", (C,))).astype(np.float32)
+    beta = (0.1 * normal(52, "be", (C,))).astype(np.float32)
+    kv = round_bf16(normal(52, "kv", (B * TL, count * 2 * C)))
+    qref = ops.linear(ops.layernorm(x, gamma, beta, 1e-5), wq).reshape(B, rows, C)
+    kref = kv[:, block * 2 * C:block * 2 * C + C].reshape(B, TL, C)
+    vref = kv[:, block * 2 * C + C:(block + 1) * 2 * C].reshape(B, TL, C)
+    ref = ops.attention_dense(qref, kref, vref, heads).reshape(M, C)
+    wg = round_bf16(wq * gamma[None, :])
+    ln_s = wg.astype(np.float64).sum(1)
+    ln_t = wq.astype(np.float64) @ beta.astype(np.float64)
+    xp = df.pack_rows(dev(x, True))
+    wp = df.pack_linear_weight(dev(wq, True), dev(gamma))
+    kvp = df.pack_text_kv(dev(kv, True), B, TL, count, C)
+    out = df.cross_attn_packed(xp, wp, dev(ln_s.astype(np.float32)), dev(ln_t.astype(np.float32)), kvp, B, rows, C, TL,
+                               count, block)
+    got = unpack_rows(host(out), M, C)[0]
+    e = rel_l2(got, ref)
+    say("   rel_l2", e)
+    assert np.isfinite(got).all() and e < TOL_BF16
