@@ -237,6 +237,8 @@ def main():
     ap.add_argument("--workload", choices=["cfg4", "3840"], default="cfg4",
                     help="cfg4: the headline workload (1280x1920, N=8); 3840: one of 8 row patches of a 3840x3840 image "
                          "(480x480 latent), the paper's best-scaling resolution - a second workload, not the headline")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="batch items through the same step (2 = both classifier-free-guidance branches); the headline is 1")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -272,15 +274,16 @@ def main():
     ccfg = df.make_cfg(cfg)
     specs = df.unet_weight_specs(ccfg)
     weights = make_weights(df, torch, ccfg, seed=4)
-    net = df.PatchUNet(cfg, weights, B=1)
+    Bn = args.batch
+    net = df.PatchUNet(cfg, weights, B=Bn)
     if args.no_graph:
         net.set_graph(False)
     g = torch.Generator(device="cuda:0").manual_seed(40)
-    x_prev = torch.randn(1, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
+    x_prev = torch.randn(Bn, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
     R = cfg.H // cfg.N
     x = (x_prev + 0.02 * torch.randn(x_prev.shape, generator=g, device="cuda:0"))[:, patch * R:(patch + 1) * R].contiguous()
-    emb = torch.randn(1, cfg.emb_dim, generator=g, device="cuda:0")
-    text = torch.randn(1, cfg.text_len, cfg.text_dim, generator=g, device="cuda:0").to(torch.bfloat16)
+    emb = torch.randn(Bn, cfg.emb_dim, generator=g, device="cuda:0")
+    text = torch.randn(Bn, cfg.text_len, cfg.text_dim, generator=g, device="cuda:0").to(torch.bfloat16)
     eps = torch.empty_like(x)
 
     # everything runs on one side stream (the library replays repeated steps as a HIP graph, which the legacy default
@@ -332,7 +335,7 @@ def main():
                             event_ms_per_step=round(v["event_ms"] / args.profile_steps, 4))
     dom = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
     d = prof[dom]
-    traffic = None if (args.small or args.workload != "cfg4") else measured_traffic(dom)
+    traffic = None if (args.small or args.workload != "cfg4" or args.batch != 1) else measured_traffic(dom)
     if traffic is not None:
         traffic = round(traffic / (d["launches"] / args.profile_steps))      # per launch, like `achieved`
     if d["flops"] > 0:
@@ -350,12 +353,12 @@ def main():
                         bytes_per_launch=d["bytes"] / d["launches"])
 
     macs = ut.count_macs(cfg)
-    tflop = 2.0 * macs["total"] / 1e12
+    tflop = 2.0 * macs["total"] / 1e12 * Bn
     out = {
         "metric": "ms per patch UNet step (1 MI355X)", "value": round(ms, 4), "unit": "ms", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": workload, "batch": 1, "patch_idx": patch, "n_patches": cfg.N,
+        "config": {"workload": workload, "batch": Bn, "patch_idx": patch, "n_patches": cfg.N,
                    "tflop_per_step": round(tflop, 4)},
         "tflops": round(tflop / (ms * 1e-3), 2),
         "mfma_util_frac_of_bf16_peak": round(tflop / (ms * 1e-3) / PEAK_BF16_TFLOPS, 4),
@@ -370,7 +373,7 @@ def main():
         "breakdown": breakdown,
         "event_overhead_us_per_launch": round(ev_over_ms * 1e3, 2),
     }
-    if not args.no_cpu_baseline and args.workload == "cfg4":
+    if not args.no_cpu_baseline and args.workload == "cfg4" and Bn == 1:
         xin = x.cpu().numpy()
         out["cpu_baseline"] = cpu_baseline(cfg, weights, specs, (xin, emb.cpu().numpy(), text.float().cpu().numpy()), patch)
     else:
