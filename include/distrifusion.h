@@ -154,7 +154,8 @@ int df_linear_packed(const void* xp, const void* wp, const float* bias, const fl
  * stale buffers and the values are stored transposed (Section 4: the patch's own K / V rows are written into the
  * buffers by the projection, so no splice is left for the attention kernel).  q [B, Lq, heads*64], k [B, L, heads*64],
  * vt [B, heads*64, vt_ld] with vt[b][c][j] = v[b][j][c], vt_ld >= L rounded up to a multiple of 64 (columns beyond L
- * are never used); out [B, Lq, heads*64] row-major, or fragment-packed (rows = B*Lq) if out_packed.  bf16, d = 64.
+ * are never used); out [B, Lq, heads*64] row-major, or fragment-packed (rows = B*Lq; the padding rows of the last
+ * fragment row are left untouched) if out_packed.  bf16, d = 64.
  *
  * df_cross_attn_packed: cross-attention to the text tokens fused into its query projection (Section 4: per-token
  * layers need no data of other patches).  out = softmax(q k^T * scale) v per head with q = LayerNorm(x) wq^T, the

@@ -290,8 +290,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
 #define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+template <int NST>
 __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
-  constexpr int D = 64, TK = 64, NST = 3;
+  constexpr int D = 64, TK = 64;
   constexpr int KB = TK * D * 2, STAGE = 2 * KB;           // bytes: K tile, V^T tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -363,16 +364,19 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = p.scale * kLog2e;
 
-  issue(0, 0);
-  issue(1, 1);
-  int stage = 0, nstage = 2;
+#pragma unroll
+  for (int i = 0; i < NST - 1; ++i) issue(i, i);
+  int stage = 0, nstage = NST - 1;
   for (int tl = 0; tl < ntiles; ++tl) {
-    // tile tl has landed once at most the 4 loads of tile tl+1 are outstanding
-    __builtin_amdgcn_s_waitcnt((4 & 0xF) | (0x7 << 4) | (0 << 8));   // vmcnt(4) lgkmcnt(0)
+    // tile tl has landed once at most the loads of the NST-2 younger tiles (4 each) are outstanding
+    {
+      constexpr int VM = 4 * (NST - 2);
+      __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (0x7 << 4) | (0 << 8));   // vmcnt(VM) lgkmcnt(0)
+    }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    issue(tl + 2, nstage);                                 // the stage every wave finished reading before the barrier
+    issue(tl + NST - 1, nstage);                           // the stage every wave finished reading before the barrier
     const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE);
     const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB);
     // All LDS fragment reads of a phase are issued before its MFMAs (one read per MFMA would put an LDS round trip
@@ -665,14 +669,24 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
     if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
     p.vt_ld = a.vt_ld;
-    constexpr int smem = 3 * 2 * 64 * 64 * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute((const void*)attn_vt_d64, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-        return DF_EHIP;
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(attn_vt_d64, dim3((unsigned)nwg), dim3(256), smem, st, p);
+    // ring depth 3 (48 KB of LDS, three workgroups per compute unit): deeper rings were measured and do not help -
+    // the kernel is not bound by the latency of the K / V^T stream - while they cost occupancy
+    static const int forced_st = getenv("DF_ATTN_STAGES") ? atoi(getenv("DF_ATTN_STAGES")) : 0;   // tuning aid
+    const int nst = forced_st ? forced_st : 3;
+#define DF_ATTN_VT(NSTV)                                                                                            \
+  {                                                                                                                 \
+    constexpr int smem = NSTV * 2 * 64 * 64 * 2;                                                                    \
+    static bool attr_set = false;                                                                                   \
+    if (!attr_set) {                                                                                                \
+      if (hipFuncSetAttribute((const void*)attn_vt_d64<NSTV>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=  \
+          hipSuccess)                                                                                               \
+        return DF_EHIP;                                                                                             \
+      attr_set = true;                                                                                              \
+    }                                                                                                               \
+    hipLaunchKernelGGL(attn_vt_d64<NSTV>, dim3((unsigned)nwg), dim3(256), smem, st, p);                             \
+  }
+    if (nst <= 3) DF_ATTN_VT(3) else if (nst == 4) DF_ATTN_VT(4) else DF_ATTN_VT(6)
+#undef DF_ATTN_VT
   } else {
     hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
   }

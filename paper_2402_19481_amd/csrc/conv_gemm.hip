@@ -838,6 +838,141 @@ __global__ __launch_bounds__(256) void conv3x3_wave(const T* __restrict__ x, con
   }
 }
 
+// Four input channels (the latent entering the network): a thread owns one pixel and 8 consecutive output channels;
+// the 9 x 4 inputs are loaded once with 8-byte accesses and reused for the 8 outputs, the 46 KB of weights stay in L1.
+template <typename OutT>
+__global__ __launch_bounds__(256) void conv3x3_cin4(const bf16_t* __restrict__ x, const bf16_t* __restrict__ top,
+                                                    const bf16_t* __restrict__ bot, long long halo_bs,
+                                                    const bf16_t* __restrict__ w, const float* __restrict__ bias,
+                                                    const float* __restrict__ residual, OutT* __restrict__ y, int B, int R,
+                                                    int W, int Cout, int Ro, int Wo, int stride, int act) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int cg = Cout >> 3;
+  const long long total = (long long)B * Ro * Wo * cg;
+  if (idx >= total) return;
+  const int co = (int)(idx % cg) * 8;
+  long long pix = idx / cg;
+  const int c = (int)(pix % Wo);
+  const int r = (int)((pix / Wo) % Ro);
+  const int b = (int)(pix / ((long long)Wo * Ro));
+  float xin[9][4];
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky) {
+    const int ri = r * stride + ky - 1;
+    const bf16_t* rowp = nullptr;
+    if (ri < 0) { if (top) rowp = top + b * halo_bs; }
+    else if (ri >= R) { if (bot) rowp = bot + b * halo_bs; }
+    else rowp = x + ((long long)b * R + ri) * W * 4;
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) {
+      const int ci = c * stride + kx - 1;
+      u32x2 t = {0u, 0u};
+      if (rowp && ci >= 0 && ci < W) t = *reinterpret_cast<const u32x2*>(rowp + (long long)ci * 4);
+      xin[ky * 3 + kx][0] = __uint_as_float(t.x << 16); xin[ky * 3 + kx][1] = __uint_as_float(t.x & 0xffff0000u);
+      xin[ky * 3 + kx][2] = __uint_as_float(t.y << 16); xin[ky * 3 + kx][3] = __uint_as_float(t.y & 0xffff0000u);
+    }
+  }
+  float acc[8];
+#pragma unroll
+  for (int o = 0; o < 8; ++o) {
+    float a = bias ? bias[co + o] : 0.f;
+    const bf16_t* wp = w + (long long)(co + o) * 36;
+#pragma unroll
+    for (int tp = 0; tp < 9; ++tp) {
+      const u32x2 t = *reinterpret_cast<const u32x2*>(wp + tp * 4);
+      a = fmaf(xin[tp][0], __uint_as_float(t.x << 16), a);
+      a = fmaf(xin[tp][1], __uint_as_float(t.x & 0xffff0000u), a);
+      a = fmaf(xin[tp][2], __uint_as_float(t.y << 16), a);
+      a = fmaf(xin[tp][3], __uint_as_float(t.y & 0xffff0000u), a);
+    }
+    acc[o] = a;
+  }
+  const long long o0 = pix * Cout + co;
+  if (residual) {
+    float r8[8];
+    ld_vec(residual + o0, r8); ld_vec(residual + o0 + 4, r8 + 4);
+#pragma unroll
+    for (int o = 0; o < 8; ++o) acc[o] += r8[o];
+  }
+  if (act == 1) {
+#pragma unroll
+    for (int o = 0; o < 8; ++o) acc[o] = silu_f(acc[o]);
+  }
+  if constexpr (sizeof(OutT) == 4) { st_vec(y + o0, acc); st_vec(y + o0 + 4, acc + 4); }
+  else st_vec(y + o0, acc);
+}
+
+// Few output channels (the noise prediction leaving the network, Cout <= 4) and Cin % 8 == 0: a wave owns four
+// neighbouring pixels of one row; lanes split the 9 x Cin reduction in 16-byte chunks, each weight chunk is used for
+// the four pixels.
+template <typename OutT, int CO>
+__global__ __launch_bounds__(256) void conv3x3_fewout(const bf16_t* __restrict__ x, const bf16_t* __restrict__ top,
+                                                      const bf16_t* __restrict__ bot, long long halo_bs,
+                                                      const bf16_t* __restrict__ w, const float* __restrict__ bias,
+                                                      const float* __restrict__ residual, OutT* __restrict__ y, int B,
+                                                      int R, int W, int Cin, int Cout, int act) {
+  const int lane = threadIdx.x & 63;
+  const int wq = (W + 3) >> 2;                                  // pixel quads per row
+  const long long quad = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (quad >= (long long)B * R * wq) return;
+  const int c0 = (int)(quad % wq) * 4;
+  const int r = (int)((quad / wq) % R);
+  const int b = (int)(quad / ((long long)wq * R));
+  const int cpt = Cin >> 3;                                     // 16-byte chunks per tap
+  float acc[4][CO];
+#pragma unroll
+  for (int px = 0; px < 4; ++px)
+#pragma unroll
+    for (int o = 0; o < CO; ++o) acc[px][o] = 0.f;
+  for (int ch = lane; ch < 9 * cpt; ch += 64) {
+    const int tp = ch / cpt, k8 = (ch - tp * cpt) * 8;
+    const int ky = tp / 3, kx = tp - ky * 3;
+    const int ri = r + ky - 1;
+    const bf16_t* rowp = nullptr;
+    if (ri < 0) { if (top) rowp = top + b * halo_bs; }
+    else if (ri >= R) { if (bot) rowp = bot + b * halo_bs; }
+    else rowp = x + ((long long)b * R + ri) * W * Cin;
+    float wv[CO][8];
+#pragma unroll
+    for (int o = 0; o < CO; ++o) {
+      if (o < Cout) ld_vec(w + ((long long)o * 9 + tp) * Cin + k8, wv[o]);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wv[o][e] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int px = 0; px < 4; ++px) {
+      const int ci = c0 + px + kx - 1;
+      if (!rowp || ci < 0 || ci >= W) continue;
+      float xv[8];
+      ld_vec(rowp + (long long)ci * Cin + k8, xv);
+#pragma unroll
+      for (int o = 0; o < CO; ++o)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[px][o] = fmaf(xv[e], wv[o][e], acc[px][o]);
+    }
+  }
+#pragma unroll
+  for (int px = 0; px < 4; ++px)
+#pragma unroll
+    for (int o = 0; o < CO; ++o) acc[px][o] = wave_sum(acc[px][o]);
+  if (lane < 4 && c0 + lane < W) {
+    const long long pix = ((long long)b * R + r) * W + c0 + lane;
+#pragma unroll
+    for (int o = 0; o < CO; ++o) {
+      if (o >= Cout) break;
+      float v = 0.f;
+#pragma unroll
+      for (int px = 0; px < 4; ++px) if (px == lane) v = acc[px][o];
+      v += bias ? bias[o] : 0.f;
+      if (residual) v += residual[pix * Cout + o];
+      if (act == 1) v = silu_f(v);
+      Elem<OutT>::st(y + pix * Cout + o, v);
+    }
+  }
+}
+
 // ---- one-time weight re-layout for the pipelined kernel ----
 // out tile (n/64, k/64) is 64 rows x 64 k, row r = n % 64 holds global 16-byte chunk c at slot c ^ ((r >> 1) & 7)
 __global__ __launch_bounds__(256) void pack_weight_kernel(const bf16_t* __restrict__ w, const float* __restrict__ gamma,
@@ -1133,6 +1268,32 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
                      (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.w, a.bias, a.residual,  \
                      (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, Ro, Wo, a.stride, a.act)
   if ((total + 255) / 256 > 0x7fffffffLL) return DF_ESHAPE;
+  if (a.dtype == DF_BF16 && !a.chan_add && ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
+      ((uintptr_t)a.halo_top % 16 == 0) && ((uintptr_t)a.halo_bot % 16 == 0)) {
+    if (a.Cin == 4 && a.Cout % 8 == 0 && a.halo_bstride % 4 == 0 && ((uintptr_t)a.y % 16 == 0) &&
+        ((uintptr_t)a.residual % 16 == 0)) {
+      const long long n = M * (a.Cout / 8);
+#define DF_C4(OT)                                                                                                  \
+  hipLaunchKernelGGL((conv3x3_cin4<OT>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const bf16_t*)a.x,     \
+                     (const bf16_t*)a.halo_top, (const bf16_t*)a.halo_bot, a.halo_bstride, (const bf16_t*)a.w, a.bias, \
+                     a.residual, (OT*)a.y, a.B, a.R, a.W, a.Cout, Ro, Wo, a.stride, a.act)
+      if (a.out_dtype == DF_BF16) DF_C4(bf16_t); else DF_C4(float);
+#undef DF_C4
+      DF_LAUNCH_CHECK();
+      return DF_OK;
+    }
+    if (a.Cout <= 4 && a.Cin % 8 == 0 && a.stride == 1 && a.halo_bstride % 8 == 0) {
+      const long long quads = (long long)a.B * a.R * ((a.W + 3) / 4);
+#define DF_FEW(OT)                                                                                                 \
+  hipLaunchKernelGGL((conv3x3_fewout<OT, 4>), dim3((unsigned)((quads + 3) / 4)), dim3(256), 0, st, (const bf16_t*)a.x, \
+                     (const bf16_t*)a.halo_top, (const bf16_t*)a.halo_bot, a.halo_bstride, (const bf16_t*)a.w, a.bias, \
+                     a.residual, (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, a.act)
+      if (a.out_dtype == DF_BF16) DF_FEW(bf16_t); else DF_FEW(float);
+#undef DF_FEW
+      DF_LAUNCH_CHECK();
+      return DF_OK;
+    }
+  }
   const bool wave = a.Cout <= 8 && a.Cin >= 64 && !a.chan_add;
   if (a.dtype == DF_F32) {
     if (a.out_dtype != DF_F32) return DF_ESHAPE;

@@ -193,11 +193,16 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
     float a = 0.f, c = 0.f;
     if (part < parts) {
       const float* base = partial + (((long long)b * nseg + sg) * nblk) * G * 2;
-#pragma unroll 4
-      for (int k = part; k < nblk; k += parts) {
-        const float2 v = *reinterpret_cast<const float2*>(base + ((long long)k * G + g) * 2);
-        a += v.x;
-        c += v.y;
+      // 16 partials per trip are requested together (one memory round trip), then added in index order
+      for (int k0 = part; k0 < nblk; k0 += 16 * parts) {
+        float2 v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int k = k0 + i * parts;
+          v[i] = k < nblk ? *reinterpret_cast<const float2*>(base + ((long long)k * G + g) * 2) : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { a += v[i].x; c += v[i].y; }
       }
       s_red[0][part][g] = a;
       s_red[1][part][g] = c;
@@ -214,9 +219,31 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
     }
     __syncthreads();
   }
+  // the cached sums of the other patches: thread (part, g) fetches patch part's entry of group g (one round trip for
+  // all patches), thread (0, g) adds them in patch order
+  const bool need_stale = !(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE));
+  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  if (need_stale) {
+    for (int j0 = 0; j0 < N; j0 += parts) {
+      __syncthreads();
+      if (part < parts && j0 + part < N) {
+        const float* sp = stale + (((long long)(j0 + part) * B + b) * G + g) * 2;
+        s_red[0][part][g] = sp[0];
+        s_red[1][part][g] = sp[1];
+      }
+      __syncthreads();
+      if (part == 0) {
+        const int n = N - j0 < parts ? N - j0 : parts;
+        for (int j = 0; j < n; ++j) {
+          const float a = s_red[0][j][g], c = s_red[1][j][g];
+          if (j0 + j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
+        }
+      }
+    }
+  }
   if (part != 0) return;
   float mean, var;
-  gn_combine(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, stale, b, g, B, G, patch_idx, mean, var);
+  gn_combine_pre(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
   if (nseg == 1 && sums_out != nullptr) {  // written after the stale sums were read: may alias the own slot
     float* o = sums_out + ((long long)b * G + g) * 2;
     o[0] = tot_s; o[1] = tot_q;

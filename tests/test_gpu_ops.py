@@ -407,7 +407,8 @@ def test_attn_stale_vt(B, Lq, L, heads, packed):
     say("   rel_l2", e)
     assert np.isfinite(got).all() and e < TOL_BF16
     out2 = df.attn_stale_vt(dev(q, True), dev(k, True), vt_d, heads, L, packed=packed)
-    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    got2 = unpack_rows(host(out2), B * Lq, C)[0].reshape(B, Lq, C) if packed else host(out2)
+    np.testing.assert_array_equal(got, got2)            # reproducible (padding rows of a packed output are not written)
 
 
 @pytest.mark.parametrize("B,rows,C,TL,count,block", [
