@@ -91,8 +91,10 @@ __global__ __launch_bounds__(256) void cast_bf16_tail(const float* __restrict__ 
 }
 
 // out[p, 0:Ca] = a[p], out[p, Ca:Ca+Cb] = b[p]; float4 granularity
+// optionally also a bf16 copy (operand of the 1x1 shortcut convolution that follows)
 __global__ __launch_bounds__(256) void concat_kernel(const float* __restrict__ a, int Ca4, const float* __restrict__ b,
-                                                     int Cb4, float* __restrict__ out, long long pixels) {
+                                                     int Cb4, float* __restrict__ out, bf16_t* __restrict__ out_bf,
+                                                     long long pixels) {
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const int C4 = Ca4 + Cb4;
   if (idx >= pixels * C4) return;
@@ -101,6 +103,10 @@ __global__ __launch_bounds__(256) void concat_kernel(const float* __restrict__ a
   const f32x4 v = c < Ca4 ? *reinterpret_cast<const f32x4*>(a + (p * Ca4 + c) * 4)
                           : *reinterpret_cast<const f32x4*>(b + (p * Cb4 + (c - Ca4)) * 4);
   *reinterpret_cast<f32x4*>(out + idx * 4) = v;
+  if (out_bf) {
+    u32x2 t = {pack_bf2(v.x, v.y), pack_bf2(v.z, v.w)};
+    *reinterpret_cast<u32x2*>(out_bf + idx * 4) = t;
+  }
 }
 
 // x [B,R,W,C] float -> y [B,2R,2W,C] bf16, each pixel repeated 2x2
@@ -159,10 +165,11 @@ int launch_cast_bf16(const float* x, bf16_t* y, long long n, int silu, hipStream
   return DF_OK;
 }
 
-int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, long long pixels, hipStream_t st) {
+int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, bf16_t* out_bf, long long pixels,
+                  hipStream_t st) {
   if (Ca % 4 || Cb % 4) return DF_ESHAPE;
   const long long n = pixels * ((Ca + Cb) / 4);
-  hipLaunchKernelGGL(concat_kernel, dim3(blocks_for(n)), dim3(256), 0, st, a, Ca / 4, b, Cb / 4, out, pixels);
+  hipLaunchKernelGGL(concat_kernel, dim3(blocks_for(n)), dim3(256), 0, st, a, Ca / 4, b, Cb / 4, out, out_bf, pixels);
   DF_LAUNCH_CHECK();
   return DF_OK;
 }

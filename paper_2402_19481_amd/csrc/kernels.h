@@ -177,7 +177,8 @@ size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d);
 int launch_layernorm(const float* x, bf16_t* y, const float* gamma, const float* beta, int M, int C, float eps, hipStream_t st);
 int launch_geglu(const bf16_t* h, bf16_t* out, int M, int F, hipStream_t st);  // h [M, 2F] -> out [M, F]
 int launch_cast_bf16(const float* x, bf16_t* y, long long n, int silu, hipStream_t st);
-int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, long long pixels, hipStream_t st);
+int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, bf16_t* out_bf, long long pixels,
+                  hipStream_t st);   // out_bf: optional bf16 copy of the result
 int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C, hipStream_t st);
 int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st);
 int launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st);

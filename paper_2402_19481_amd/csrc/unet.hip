@@ -488,7 +488,8 @@ struct Exec {
     }
   }
 
-  void resblock(const BlockDesc& b, const float* x, const bf16_t* emb_act, float* out) {
+  // x_bf: bf16 copy of x if the caller already has one (operand of the 1x1 shortcut), else nullptr
+  void resblock(const BlockDesc& b, const float* x, const bf16_t* emb_act, float* out, const bf16_t* x_bf = nullptr) {
     const int R = rows(b.level), W = width(b.level);
     const size_t px = (size_t)B() * R * W;
     const size_t mark = top;
@@ -505,8 +506,12 @@ struct Exec {
     groupnorm(b.name + ".gn2", h1, DF_BF16, R, W, b.cout, 1e-5f, 1, a2, 0, e2);
     const float* residual = x;
     if (b.cin != b.cout) {
-      bf16_t* xb = (bf16_t*)alloc(px * b.cin * 2);
-      timed(PC_ELEMENTWISE, 0.0, 6.0 * px * b.cin, [&] { return launch_cast_bf16(x, xb, (long long)px * b.cin, 0, st); });
+      const bf16_t* xb = x_bf;
+      if (!xb) {
+        bf16_t* xc = (bf16_t*)alloc(px * b.cin * 2);
+        timed(PC_ELEMENTWISE, 0.0, 6.0 * px * b.cin, [&] { return launch_cast_bf16(x, xc, (long long)px * b.cin, 0, st); });
+        xb = xc;
+      }
       gemm(xb, b.cin, b.name + ".sc", true, nullptr, 0, out, b.cout, (int)px, b.cout, b.cin, DF_F32);
       residual = out;
     }
@@ -921,16 +926,20 @@ struct Exec {
           float* out = (float*)alloc(px * b.cout * 4);
           const size_t mark = top;
           const float* xin = cur;
+          const bf16_t* xin_bf = nullptr;
           if (b.concat) {
             const float* sk = skips.back();
             const int sc = skip_c.back();
             skips.pop_back();
             skip_c.pop_back();
             float* cat = (float*)alloc(px * (size_t)(cur_c + sc) * 4);
-            timed(PC_ELEMENTWISE, 0.0, 8.0 * px * (cur_c + sc), [&] { return launch_concat(cur, cur_c, sk, sc, cat, (long long)px, st); });
+            bf16_t* catb = (bf16_t*)alloc(px * (size_t)(cur_c + sc) * 2);   // the shortcut's operand, written by the same kernel
+            timed(PC_ELEMENTWISE, 0.0, 10.0 * px * (cur_c + sc),
+                  [&] { return launch_concat(cur, cur_c, sk, sc, cat, catb, (long long)px, st); });
             xin = cat;
+            xin_bf = dry ? nullptr : catb;
           }
-          resblock(b, xin, emb_act, out);
+          resblock(b, xin, emb_act, out, xin_bf);
           top = mark;
           cur = out; cur_c = b.cout;
           break;
