@@ -1137,19 +1137,33 @@ int split_override() {
   return v;
 }
 
-// Tile choice measured on the patch step (kernel trace, weights cold): fetch throughput of a compute unit grows with
-// the number of resident waves, so problems with many tiles take the 64x64 tile with two stages (32 KB of LDS, five
-// workgroups per unit) and problems with few tiles a four-stage ring; only very large problems use 128x128.  The
-// deepest reductions on few tiles (feed-forward output, K >= 4096) are split along K.
+// Tile and split choice, measured on the patch step (kernel trace, weights cold).  A compute unit delivers operands
+// to its waves at a fixed rate (about one 1 KB wave load per 32 cycles), so what counts is that every unit carries the
+// same number of equally long workgroups: a problem with T 64x64 tiles is split along K into ns parts such that
+// T * ns just fills the slots the chip offers for the chosen ring depth (two stages = 32 KB of LDS, three = 48 KB:
+// three workgroups per unit, 768 slots; four stages with eight waves: two per unit, 512 slots).  Measured optima this
+// reproduces: 375 tiles -> 2 parts, 190 tiles -> 4 parts, 100 tiles -> 5 parts; every part keeps at least 8 k-slabs.
+// Only very large problems use 128x128.
 template <bool kConv>
 int launch_auto(const TileParams& p, int out_dtype, hipStream_t st) {
   const long long big = (long long)cdiv(p.M, 128) * cdiv(p.N, 128);
   const long long nwg = (long long)cdiv(p.M, 64) * cdiv(p.N, 64);
-  int ns = (nwg <= 128 && p.K >= 4096) ? 4 : 1;
-  if (split_override() > 0) ns = split_override();
+  const int KT = p.K / 64;
+  auto parts_for = [&](long long slots) {
+    int ns = (int)((slots + nwg / 2) / nwg);
+    if (ns > 8) ns = 8;
+    while (ns > 1 && KT / ns < 8) --ns;
+    return ns < 1 ? 1 : ns;
+  };
+  if (split_override() > 0) return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, split_override(), st);
   if (big >= 1024 && !p.ln_s) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
-  if (nwg * ns >= 512 && ns == 1) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, 1, st);
-  return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, ns, st);   // few tiles: four stages, eight waves
+  if (nwg >= 512) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, 1, st);
+  if (nwg > 128) {
+    const int ns = parts_for(768);
+    if (ns <= 2) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, ns, st);
+    return launch_pipe<64, 64, 3, kConv>(p, out_dtype, ns, st);
+  }
+  return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, parts_for(512), st);   // few tiles: four stages, eight waves
 }
 
 template <bool kConv>
