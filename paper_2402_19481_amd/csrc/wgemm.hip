@@ -60,17 +60,20 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 template <int TM, int TN, int KSPLIT, int PF, bool LN, int XA>
 __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  constexpr int U = TM * TN * 4;            // float4 units of a wave's tile: (tm, tn, jj)
-  f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64]
+  // rows of token fragments reduced per pass: the whole tile when its partial tiles fit in 96 KB of LDS, else one row
+  constexpr int RP = (KSPLIT * TM * TN * 4 <= 96) ? TM : 1;
+  constexpr int U = RP * TN * 4;            // float4 units of a pass: (row, tn, jj)
+  f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64], reused per pass
   float* stat = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024);  // [KSPLIT][TM][32][2]
   u32x4* qlds = reinterpret_cast<u32x4*>(smem_raw + KSPLIT * U * 1024 + KSPLIT * TM * 32 * 2 * 4);   // [4][64] (XA)
+  constexpr int GP = TN >= 2 ? TN / 2 : 1;   // geglu: the tile's first GP fragments are value rows, the last GP their gates
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tok = lane & 31, g = lane >> 5;
   const int MT = (p.M + 31) >> 5;                      // 32-token fragments rows
   const int MG = (MT + TM - 1) / TM;                   // tile groups along M
   const int NTo = p.N >> 5;                            // 32-feature output fragments
-  const int NG = p.geglu ? NTo : NTo / TN;             // geglu: TN == 2 is (value, gate) of the same 32 outputs
+  const int NG = p.geglu ? NTo / GP : NTo / TN;        // geglu: fragment j < GP is paired with gate fragment j + GP
   const int nwg = MG * NG;
   int t = blockIdx.x;
   {
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int nt = p.geglu ? ng + j * NTo : ng * TN + j;
+    const int nt = p.geglu ? (j < GP ? ng * GP + j : NTo + ng * GP + (j - GP)) : ng * TN + j;
     wb[j] = p.Wp + ((size_t)nt * KF + kf0) * 64 + lane;
   }
 
@@ -112,22 +115,20 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
 
   // Epilogue operands of this wave's first pair unit (norm / bias vectors, residual) are requested before the K
   // loop: their latency would otherwise sit, un-overlapped, at the end of every one of these short kernels.
-  // A pair unit = (token fragment i, output fragment j, half f): 8 consecutive features per lane; pair units go
-  // round-robin over the waves, which run the epilogue for them.
-  const int npu = TM * (p.geglu ? 1 : TN) * 2;
+  // A pair unit = (token fragment row i, output fragment j, half f): 8 consecutive features per lane.  The tile is
+  // reduced and written in passes of RP rows; the pair units of a pass go round-robin over the waves, which run the
+  // epilogue for them.
+  const int JO = p.geglu ? GP : TN;                    // output fragments per row of the tile
+  const int npu = RP * JO * 2;
   struct Epi { float a[8], b[8], ga[8], gb[8], r[8]; };
-  auto pu_decode = [&](int pu, int& i, int& j, int& f) {
-    f = pu & 1;
-    j = p.geglu ? 0 : (pu >> 1) % TN;
-    i = p.geglu ? (pu >> 1) : (pu >> 1) / TN;
-  };
-  auto load_epi = [&](int pu, Epi& e) {
-    int i, j, f;
-    pu_decode(pu, i, j, f);
-    const int mt = mg * TM + i;
+  auto load_epi = [&](int i0, int pu, Epi& e, bool vecs) {
+    const int f = pu & 1, j = (pu >> 1) % JO;
+    const int mt = mg * TM + i0 + (pu >> 1) / JO;
     const int m = mt * 32 + tok;
-    const int n = (p.geglu ? ng : ng * TN + j) * 32 + 16 * f + 8 * g;
-    if (ln) {
+    const int n = (ng * JO + j) * 32 + 16 * f + 8 * g;
+    if (!vecs) {
+      // same features as the unit the vectors were loaded for
+    } else if (ln) {
       ld_vec(p.ln_s + n, e.a); ld_vec(p.ln_s + n + 4, e.a + 4);
       ld_vec(p.ln_t + n, e.b); ld_vec(p.ln_t + n + 4, e.b + 4);
       if (TN >= 2 && p.geglu) {
@@ -142,8 +143,12 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       ld_vec(p.residual + (long long)m * p.ldr + n, e.r); ld_vec(p.residual + (long long)m * p.ldr + n + 4, e.r + 4);
     }
   };
-  Epi epi0;
-  if (wave < npu) load_epi(wave, epi0);
+  constexpr int MAXU = (RP * TN * 2 + KSPLIT - 1) / KSPLIT;   // pair units of a pass per wave
+  constexpr int NPRE = MAXU < 3 ? MAXU : 3;
+  Epi epre[NPRE];
+#pragma unroll
+  for (int t = 0; t < NPRE; ++t)
+    if (wave + t * KSPLIT < npu) load_epi(0, wave + t * KSPLIT, epre[t], true);
   __builtin_amdgcn_sched_barrier(0);
 
   bf16x8 xr[PF][TM], wr[PF][TN];
@@ -198,16 +203,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     }
   }
 
-  // ---- add the KSPLIT partial tiles in wave order ----
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const f32x4 v = {acc[i][j][4 * jj], acc[i][j][4 * jj + 1], acc[i][j][4 * jj + 2], acc[i][j][4 * jj + 3]};
-        red[(wave * U + (i * TN + j) * 4 + jj) * 64 + lane] = v;
-      }
+  // ---- add the KSPLIT partial tiles in wave order, one token-fragment row at a time ----
   if (ln) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -219,22 +215,44 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       }
     }
   }
+#pragma unroll
+  for (int i0 = 0; i0 < TM; i0 += RP) {
+  if (i0 > 0) __syncthreads();                         // the previous pass's partial tiles have been read
+#pragma unroll
+  for (int il = 0; il < RP; ++il)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const f32x16& t = acc[i0 + il][j];
+        const f32x4 v = {t[4 * jj], t[4 * jj + 1], t[4 * jj + 2], t[4 * jj + 3]};
+        red[(wave * U + (il * TN + j) * 4 + jj) * 64 + lane] = v;
+      }
   __syncthreads();
 
-  for (int pu = wave; pu < npu; pu += KSPLIT) {
-    int i, j, f;
-    pu_decode(pu, i, j, f);
+#pragma unroll
+  for (int t = 0; t < MAXU; ++t) {
+    const int pu = wave + t * KSPLIT;
+    if (pu >= npu) break;
+    const int f = pu & 1, j = (pu >> 1) % JO, il = (pu >> 1) / JO;
+    const int i = i0 + il;
     const int mt = mg * TM + i;
     if (mt >= MT) continue;
-    Epi e = epi0;
-    if (pu != wave) load_epi(pu, e);
+    Epi e;
+    if (t < NPRE) {
+      // a wave's t-th unit covers the same features in every pass: only the residual differs from the prefetched one
+      e = epre[t < NPRE ? t : 0];
+      if (i0 > 0) load_epi(i0, pu, e, false);
+    } else {
+      load_epi(i0, pu, e, true);
+    }
     float v[8], gt[8];
     {
       f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
 #pragma unroll
       for (int w = 0; w < KSPLIT; ++w) {
-        a += red[(w * U + (i * TN + j) * 4 + 2 * f) * 64 + lane];
-        b += red[(w * U + (i * TN + j) * 4 + 2 * f + 1) * 64 + lane];
+        a += red[(w * U + (il * TN + j) * 4 + 2 * f) * 64 + lane];
+        b += red[(w * U + (il * TN + j) * 4 + 2 * f + 1) * 64 + lane];
       }
       v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
     }
@@ -242,13 +260,13 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
 #pragma unroll
       for (int w = 0; w < KSPLIT; ++w) {
-        a += red[(w * U + (i * TN + 1) * 4 + 2 * f) * 64 + lane];
-        b += red[(w * U + (i * TN + 1) * 4 + 2 * f + 1) * 64 + lane];
+        a += red[(w * U + (il * TN + j + GP) * 4 + 2 * f) * 64 + lane];
+        b += red[(w * U + (il * TN + j + GP) * 4 + 2 * f + 1) * 64 + lane];
       }
       gt[0] = a.x; gt[1] = a.y; gt[2] = a.z; gt[3] = a.w; gt[4] = b.x; gt[5] = b.y; gt[6] = b.z; gt[7] = b.w;
     }
     const int m = mt * 32 + tok;
-    const int nfrag = p.geglu ? ng : ng * TN + j;      // output fragment along the feature axis
+    const int nfrag = ng * JO + j;                     // output fragment along the feature axis
     const int n = nfrag * 32 + 16 * f + 8 * g;         // first of this lane's 8 consecutive features
     if (ln) {
       float sm = 0.f, sq = 0.f;
@@ -317,6 +335,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
         st_vec(p.out_rows + (long long)m * p.ld_rows + n, v);
       }
     }
+  }
   }
   if constexpr (XA > 0) {
     __syncthreads();
@@ -495,11 +514,12 @@ int launch_one(const WParams& p, hipStream_t st) {
   const int MT = (p.M + 31) / 32, MG = (MT + TM - 1) / TM;
   const int NTo = p.N / 32;
   if (!p.geglu && NTo % TN) return DF_ESHAPE;
-  if (p.geglu && TN != 2) return DF_ESHAPE;
-  const int NG = p.geglu ? NTo : NTo / TN;
+  if (p.geglu && (TN % 2 || NTo % (TN / 2))) return DF_ESHAPE;
+  const int NG = p.geglu ? NTo / (TN / 2) : NTo / TN;
   const int KF = p.K / 16;
   if (KF % KSPLIT) return DF_ESHAPE;
-  constexpr int smem = KSPLIT * TM * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0);
+  constexpr int RP = (KSPLIT * TM * TN * 4 <= 96) ? TM : 1;
+  constexpr int smem = KSPLIT * RP * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0);
   auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN, XA>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -618,14 +638,26 @@ int launch_wgemm(const WGemmArgs& a, hipStream_t st) {
     case 2: return launch_cfg<2, 2, 4, 5>(p, st);
     case 3: return launch_cfg<1, 2, 4, 10>(p, st);
     case 5: return launch_cfg<1, 2, 8, 5>(p, st);
+    case 6: return launch_cfg<2, 3, 4, 5>(p, st);
+    case 9: return launch_cfg<4, 4, 4, 2>(p, st);
     default: break;
   }
   const int nfrag = Nout / 32;
   if (!p.geglu && nfrag % 2) return launch_cfg<1, 1, 4, 5>(p, st);
-  // Measured on the patch step (kernel trace, cold weights): a wave tile of 32 tokens x 64 features keeps the most
-  // waves in flight and wins while the problem has few tiles; from ~320 workgroups on, the 64 x 64 tile's lower
-  // operand traffic per flop wins.
-  const long long wg12 = (long long)((a.M + 31) / 32) * (p.geglu ? nfrag : nfrag / 2);
+  // Measured on the patch step (kernel trace, cold weights).  A compute unit feeds its waves about one 1 KB operand
+  // fragment per 32 cycles, whatever the L2 hit rate, so a kernel's K loop lasts (fragment loads of the busiest unit)
+  // x 32 cycles, and every workgroup adds a fixed ramp and epilogue.  A wave tile of 32 tokens x 64 features keeps
+  // the most waves in flight and wins while the problem has few tiles; from ~320 workgroups on, the 64 x 64 tile's
+  // lower operand traffic per flop wins; and where a still larger tile (128 x 128 for the GEGLU projection, 64 x 96
+  // otherwise) covers the output with at most one workgroup per unit, its traffic per flop and its single round of
+  // workgroups win again, provided the reduction is long enough to amortise the row-by-row epilogue.
+  const int MT = (a.M + 31) / 32;
+  const long long wg12 = (long long)MT * (p.geglu ? nfrag : nfrag / 2);
+  const bool long_k = a.K / 16 / 4 >= 16;
+  if (wg12 >= 320 && long_k) {
+    if (p.geglu && nfrag % 2 == 0 && (long long)((MT + 3) / 4) * (nfrag / 2) <= 256) return launch_cfg<4, 4, 4, 2>(p, st);
+    if (!p.geglu && nfrag % 3 == 0 && (long long)((MT + 1) / 2) * (nfrag / 3) <= 256) return launch_cfg<2, 3, 4, 5>(p, st);
+  }
   if (wg12 >= 320) return launch_cfg<2, 2, 4, 5>(p, st);
   return launch_cfg<1, 2, 4, 5>(p, st);
 }
