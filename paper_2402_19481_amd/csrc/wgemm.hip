@@ -149,6 +149,20 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
 #pragma unroll
   for (int t = 0; t < NPRE; ++t)
     if (wave + t * KSPLIT < npu) load_epi(0, wave + t * KSPLIT, epre[t], true);
+  // fused cross-attention: the wave that runs it also requests the head's key fragments now
+  bf16x8 xkf[XA > 0 ? XA : 1][4];
+  const bf16x8* xkv_ptr = nullptr;
+  if constexpr (XA > 0) {
+    const int bi = (int)(((long long)mg * 32) / p.xa_rows);   // TM == 1; a fragment row never straddles batch items when
+                                                              // rows % 32 == 0, otherwise the launcher requires one item
+    xkv_ptr = p.xkv + (size_t)bi * p.xa_bstride + (size_t)ng * (12 * XA) * 64 + lane;
+    if (wave == 0) {
+#pragma unroll
+      for (int kt = 0; kt < XA; ++kt)
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds) xkf[kt][ds] = xkv_ptr[(size_t)(kt * 4 + ds) * 64];
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);
 
   bf16x8 xr[PF][TM], wr[PF][TN];
@@ -343,18 +357,16 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     // one wave: S^T = K Q^T over XA key tiles (lane = token, 16 keys per tile in natural order thanks to the row
     // permutation of the packed keys), softmax over the valid keys, O^T = V^T P^T, packed output
     const int mt = mg;                                   // TM == 1
-    const long long m0 = (long long)mt * 32;
-    const int bi = (int)(m0 / p.xa_rows);                // a fragment row never straddles batch items when rows % 32 == 0;
-                                                         // otherwise the launcher requires a single batch item
-    const bf16x8* kv = p.xkv + (size_t)bi * p.xa_bstride + (size_t)ng * (12 * XA) * 64 + lane;
+    const bf16x8* kv = xkv_ptr;
     bf16x8 qf[4];
 #pragma unroll
     for (int ds = 0; ds < 4; ++ds) qf[ds] = __builtin_bit_cast(bf16x8, qlds[ds * 64 + lane]);
-    bf16x8 kf[XA][4];
+    auto& kf = xkf;
+    bf16x8 vf[2][2 * XA];
 #pragma unroll
-    for (int kt = 0; kt < XA; ++kt)
+    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-      for (int ds = 0; ds < 4; ++ds) kf[kt][ds] = kv[(size_t)(kt * 4 + ds) * 64];
+      for (int ks = 0; ks < 2 * XA; ++ks) vf[dt][ks] = kv[(size_t)(4 * XA + dt * 2 * XA + ks) * 64];
     f32x16 sa[XA];
 #pragma unroll
     for (int kt = 0; kt < XA; ++kt) {
@@ -363,11 +375,6 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
 #pragma unroll
       for (int ds = 0; ds < 4; ++ds) sa[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kt][ds], qf[ds], sa[kt], 0, 0, 0);
     }
-    bf16x8 vf[2][2 * XA];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int ks = 0; ks < 2 * XA; ++ks) vf[dt][ks] = kv[(size_t)(4 * XA + dt * 2 * XA + ks) * 64];
     const float sc = p.xa_scale * 1.4426950408889634f;
     float mx = -INFINITY;
 #pragma unroll
