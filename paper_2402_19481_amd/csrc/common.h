@@ -30,6 +30,22 @@ __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack_bf2(f, 0.
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
+// GELU in its exact (erf) form, 0.5 x (1 + erf(x / sqrt 2)).  erfc(|z|) = t (a1 + t (a2 + t (a3 + t (a4 + t a5))))
+// exp(-z^2) with t = 1 / (1 + p |z|) (Abramowitz & Stegun 7.1.26: absolute error below 1.5e-7, the size of float
+// rounding of the result); for negative arguments 1 + erf(z) is erfc(|z|) itself, so nothing cancels.  A dozen
+// instructions per value where the library erff takes several times that; the GEGLU epilogues are otherwise bounded
+// by this function.
+__device__ __forceinline__ float gelu_erf(float x) {
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float poly = fmaf(t, 1.061405429f, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float erfc_abs = poly * t * __builtin_amdgcn_exp2f(-z * z * 1.4426950408889634f);
+  return 0.5f * x * (x >= 0.f ? 2.0f - erfc_abs : erfc_abs);
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   static constexpr int kVec = 4;  // elements per 16-byte access

@@ -561,7 +561,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
           }
           float r4[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) r4[q] = val[q] * (0.5f * gte[q] * (1.0f + erff(gte[q] * 0.70710678118654752f)));
+          for (int q = 0; q < 4; ++q) r4[q] = val[q] * gelu_erf(gte[q]);
           u32x2 t = {pack_bf2(r4[0], r4[1]), pack_bf2(r4[2], r4[3])};
           *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(p.out) + (long long)row * p.ldo + oc) = t;
         }
@@ -676,7 +676,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
               val = rstd * (acc[tm][0][e] - mean * sv) + tv;
               gte = rstd * (acc[tm][1][e] - mean * sg) + tg;
             }
-            const float gl = 0.5f * gte * (1.0f + erff(gte * 0.70710678118654752f));
+            const float gl = gelu_erf(gte);
             Elem<OutT>::st(out + (long long)row * p.ldo + oc, val * gl);
           }
       }

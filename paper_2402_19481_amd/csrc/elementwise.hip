@@ -54,7 +54,6 @@ __global__ __launch_bounds__(256) void layernorm_rows(const float* __restrict__ 
   }
 }
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
 // h [M, 2F] bf16 (value half, gate half) -> out [M, F] = value * gelu(gate)
 __global__ __launch_bounds__(256) void geglu_kernel(const bf16_t* __restrict__ h, bf16_t* __restrict__ out, long long M,

@@ -52,7 +52,6 @@ struct WParams {
   float xa_scale;
 };
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
 // XA > 0 (TM = 1, TN = 2, KSPLIT = 4, N = one head per workgroup): the 64 output features are the query of one
 // attention head; cross-attention against XA 32-key tiles of packed text keys / values runs in the epilogue and the
@@ -60,8 +59,8 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 template <int TM, int TN, int KSPLIT, int PF, bool LN, int XA>
 __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  // rows of token fragments reduced per pass: the whole tile when its partial tiles fit in 96 KB of LDS, else one row
-  constexpr int RP = (KSPLIT * TM * TN * 4 <= 96) ? TM : 1;
+  // rows of token fragments reduced per pass: as many as fit in 128 KB of LDS (the whole tile, half of it, or one row)
+  constexpr int RP = (KSPLIT * TM * TN * 4 <= 128) ? TM : (TM % 2 == 0 && KSPLIT * (TM / 2) * TN * 4 <= 128) ? TM / 2 : 1;
   constexpr int U = RP * TN * 4;            // float4 units of a pass: (row, tn, jj)
   f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64], reused per pass
   float* stat = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024);  // [KSPLIT][TM][32][2]
@@ -525,7 +524,7 @@ int launch_one(const WParams& p, hipStream_t st) {
   const int NG = p.geglu ? NTo / (TN / 2) : NTo / TN;
   const int KF = p.K / 16;
   if (KF % KSPLIT) return DF_ESHAPE;
-  constexpr int RP = (KSPLIT * TM * TN * 4 <= 96) ? TM : 1;
+  constexpr int RP = (KSPLIT * TM * TN * 4 <= 128) ? TM : (TM % 2 == 0 && KSPLIT * (TM / 2) * TN * 4 <= 128) ? TM / 2 : 1;
   constexpr int smem = KSPLIT * RP * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0);
   auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN, XA>;
   static bool attr_set = false;
