@@ -28,7 +28,10 @@ __device__ __forceinline__ unsigned int pack_bf2(float lo, float hi) {
 
 __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack_bf2(f, 0.f) & 0xffffu); }
 
-__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+// x * sigmoid(x); the hardware reciprocal (1 ulp) replaces the multi-instruction IEEE division
+__device__ __forceinline__ float silu_f(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
 
 // GELU in its exact (erf) form, 0.5 x (1 + erf(x / sqrt 2)).  erfc(|z|) = t (a1 + t (a2 + t (a3 + t (a4 + t a5))))
 // exp(-z^2) with t = 1 / (1 + p |z|) (Abramowitz & Stegun 7.1.26: absolute error below 1.5e-7, the size of float
