@@ -290,12 +290,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
 #define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-template <int NST>
-__global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
+// NGR = 2: eight waves in two groups of four.  Both groups hold the same 128 queries; of every 128 consecutive keys
+// group 0 takes the first 64 and group 1 the last 64, and the two running (max, sum, O) states are merged through LDS
+// at the end.  A SIMD then always has two waves in different phases of their tile, so one wave's softmax (vector ALU)
+// runs under the other's matrix instructions and LDS waits, which a single wave per SIMD leaves exposed.
+template <int NST, int NGR>
+__global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnParams p) {
   constexpr int D = 64, TK = 64;
-  constexpr int KB = TK * D * 2, STAGE = 2 * KB;           // bytes: K tile, V^T tile
+  constexpr int KB = TK * D * 2, STAGE = 2 * KB * NGR;     // bytes: K tiles of all groups, then their V^T tiles
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = wave >> 2, wq = wave & 3;
   const int g = lane >> 5, c = lane & 31;
   const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
   int t = blockIdx.x;
@@ -310,11 +315,11 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
   const int h = (t / nqb) % p.heads;
   const int zz = t / (nqb * p.heads);
   const int b = zz / p.nsplit, split = zz % p.nsplit;
-  const int q0 = qb * 128 + wave * 32;
+  const int q0 = qb * 128 + wq * 32;
   const int kv_lo = split * p.keys_per_split;              // multiple of 64
   int kv_hi = kv_lo + p.keys_per_split;
   if (kv_hi > p.L) kv_hi = p.L;
-  const int ntiles = (kv_hi - kv_lo + TK - 1) / TK;
+  const int ntiles = (kv_hi - kv_lo + TK * NGR - 1) / (TK * NGR);   // iterations: one 64-key tile per group each
 
   const bf16_t* kg = (const bf16_t*)p.ks + (long long)b * p.bsks + h * D;
   const bf16_t* vg = (const bf16_t*)p.vs + (long long)b * p.bsvs + (long long)h * D * p.vt_ld;
@@ -335,9 +340,9 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
   const int lr = lane >> 3, slot = lane & 7;
   auto issue = [&](int tl, int stage) {
     if (tl > ntiles - 1) tl = ntiles - 1;                  // past the end: re-read the last tile (keeps vmcnt uniform)
-    const int key0 = kv_lo + tl * TK;
+    const int key0 = kv_lo + tl * TK * NGR;
     char* sk = smem + stage * STAGE;
-    char* sv = sk + KB;
+    char* sv = sk + KB * NGR;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int row = (2 * wave + j) * 8 + lr;             // key within the tile
@@ -349,9 +354,11 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
     }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int d = (2 * wave + j) * 8 + lr;               // feature row of the V^T tile
+      const int d = ((2 * wave + j) & 7) * 8 + lr;         // feature row of the V^T tile (waves 4-7: second group's tile)
       const int ch = slot ^ (d & 7) ^ (d >> 3);            // 8-key chunk; the buffer is padded to whole tiles
-      __builtin_amdgcn_global_load_lds(DF_GPTR(vg + (long long)d * p.vt_ld + key0 + ch * 8),
+      long long vkey0 = key0 + TK * grp;
+      if (vkey0 > p.vt_ld - TK) vkey0 = p.vt_ld - TK;      // a tile wholly beyond the padded buffer: masked below
+      __builtin_amdgcn_global_load_lds(DF_GPTR(vg + (long long)d * p.vt_ld + vkey0 + ch * 8),
                                        DF_LPTR(sv + (2 * wave + j) * 1024), 16, 0, 0);
     }
   };
@@ -377,8 +384,10 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     issue(tl + NST - 1, nstage);                           // the stage every wave finished reading before the barrier
-    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE);
-    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB);
+    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + grp * KB);
+    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB * NGR + grp * KB);
+    const int tile_base = kv_lo + tl * TK * NGR + grp * TK;
+    if (tile_base < kv_hi) {                               // (wave-uniform) the last iteration may hold one tile only
     // All LDS fragment reads of a phase are issued before its MFMAs (one read per MFMA would put an LDS round trip
     // between every pair of matrix instructions), and the V^T fragments are requested before the softmax so that
     // they arrive while the vector ALU works.
@@ -412,7 +421,6 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    const int tile_base = kv_lo + tl * TK;
     const bool ragged = tile_base + TK > kv_hi;
     if (ragged) {
 #pragma unroll
@@ -474,10 +482,36 @@ __global__ __launch_bounds__(256, 2) void attn_vt_d64(AttnParams p) {
         o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pfrag, o_acc[db], 0, 0, 0);
       }
     }
+    }
     stage = (stage + 1 == NST) ? 0 : stage + 1;
     nstage = (nstage + 1 == NST) ? 0 : nstage + 1;
   }
   __builtin_amdgcn_s_waitcnt((0 & 0xF) | (0x7 << 4) | (0 << 8));     // drain the clamped tail loads
+
+  if constexpr (NGR == 2) {
+    // group 1 hands its state to group 0 (the ring is free once every wave has drained its loads)
+    __syncthreads();
+    float* mrg = reinterpret_cast<float*>(smem);           // [4 waves][34][64]: 32 accumulators, max, sum per lane
+    if (grp == 1) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mrg[(wq * 34 + i * 16 + e) * 64 + lane] = o_acc[i][e];
+      mrg[(wq * 34 + 32) * 64 + lane] = m_run;
+      mrg[(wq * 34 + 33) * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = mrg[(wq * 34 + 32) * 64 + lane], l1 = mrg[(wq * 34 + 33) * 64 + lane];
+    const float m_new = fmaxf(m_run, m1);                  // group 0 always holds at least one key: finite
+    const float a0 = __builtin_amdgcn_exp2f(m_run - m_new), a1 = __builtin_amdgcn_exp2f(m1 - m_new);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o_acc[i][e] = o_acc[i][e] * a0 + mrg[(wq * 34 + i * 16 + e) * 64 + lane] * a1;
+    l_run = l_run * a0 + l1 * a1;
+    m_run = m_new;
+  }
 
   const int qi = q0 + c;
   if (qi >= p.Lq) return;
@@ -653,15 +687,19 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   for (long long v : lds) if (v % 8) return DF_EINVAL;
   const void* ptrs[] = {a.q, a.k_fresh, a.v_fresh, a.k_stale, a.v_stale, a.out};
   for (const void* q : ptrs) if ((uintptr_t)q % 16) return DF_EINVAL;
-  const int ns = pick_splits(a.B, a.Lq, a.L, a.heads);
+  int ns = pick_splits(a.B, a.Lq, a.L, a.heads);
   if ((long long)a.B * ns > 65535) return DF_ESHAPE;
   if (ns > 1) {
-    char* scr = (char*)scratch_get(attention_scratch_bytes(a.B, a.Lq, a.L, a.heads, a.d));
-    if (!scr) return DF_ENOMEM;
-    p.nsplit = ns;
-    p.keys_per_split = cdiv(cdiv(a.L, ns), 64) * 64;
-    p.part_o = (float*)(scr + kScratchCounterBytes);
-    p.part_ml = p.part_o + (size_t)ns * a.B * a.heads * a.Lq * 64;
+    const int kps = cdiv(cdiv(a.L, ns), 128) * 128;      // whole 128-key iterations of the two-group kernel
+    ns = cdiv(a.L, kps);                                 // rounding up may leave the last ranges empty: drop them
+    if (ns > 1) {
+      char* scr = (char*)scratch_get(attention_scratch_bytes(a.B, a.Lq, a.L, a.heads, a.d));
+      if (!scr) return DF_ENOMEM;
+      p.nsplit = ns;
+      p.keys_per_split = kps;
+      p.part_o = (float*)(scr + kScratchCounterBytes);
+      p.part_ml = p.part_o + (size_t)ns * a.B * a.heads * a.Lq * 64;
+    }
   }
   const long long nwg = (long long)cdiv(a.Lq, 128) * a.heads * a.B * p.nsplit;
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
@@ -669,23 +707,27 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
     if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
     p.vt_ld = a.vt_ld;
-    // ring depth 3 (48 KB of LDS, three workgroups per compute unit): deeper rings were measured and do not help -
-    // the kernel is not bound by the latency of the K / V^T stream - while they cost occupancy
+    // Two groups of four waves and a two-stage ring (64 KB of LDS) by default.  Measured on the patch step: the second
+    // group gains ~5 % over one group with a three-stage ring, deeper rings lose again (the kernel is not bound by
+    // the latency of the K / V^T stream).
     static const int forced_st = getenv("DF_ATTN_STAGES") ? atoi(getenv("DF_ATTN_STAGES")) : 0;   // tuning aid
-    const int nst = forced_st ? forced_st : 3;
-#define DF_ATTN_VT(NSTV)                                                                                            \
+    static const int forced_gr = getenv("DF_ATTN_GROUPS") ? atoi(getenv("DF_ATTN_GROUPS")) : 0;   // tuning aid
+    const int ngr = forced_gr ? forced_gr : 2;
+    const int nst = forced_st ? forced_st : (ngr == 2 ? 2 : 3);
+#define DF_ATTN_VT(NSTV, NGRV)                                                                                      \
   {                                                                                                                 \
-    constexpr int smem = NSTV * 2 * 64 * 64 * 2;                                                                    \
+    constexpr int smem = NSTV * 2 * 64 * 64 * 2 * NGRV;                                                             \
     static bool attr_set = false;                                                                                   \
     if (!attr_set) {                                                                                                \
-      if (hipFuncSetAttribute((const void*)attn_vt_d64<NSTV>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=  \
-          hipSuccess)                                                                                               \
+      if (hipFuncSetAttribute((const void*)attn_vt_d64<NSTV, NGRV>, hipFuncAttributeMaxDynamicSharedMemorySize,     \
+                              smem) != hipSuccess)                                                                  \
         return DF_EHIP;                                                                                             \
       attr_set = true;                                                                                              \
     }                                                                                                               \
-    hipLaunchKernelGGL(attn_vt_d64<NSTV>, dim3((unsigned)nwg), dim3(256), smem, st, p);                             \
+    hipLaunchKernelGGL((attn_vt_d64<NSTV, NGRV>), dim3((unsigned)nwg), dim3(256 * NGRV), smem, st, p);              \
   }
-    if (nst <= 3) DF_ATTN_VT(3) else if (nst == 4) DF_ATTN_VT(4) else DF_ATTN_VT(6)
+    if (ngr == 2) { if (nst <= 2) DF_ATTN_VT(2, 2) else if (nst == 3) DF_ATTN_VT(3, 2) else DF_ATTN_VT(4, 2) }
+    else if (nst <= 3) DF_ATTN_VT(3, 1) else if (nst == 4) DF_ATTN_VT(4, 1) else DF_ATTN_VT(6, 1)
 #undef DF_ATTN_VT
   } else {
     hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);

@@ -389,7 +389,9 @@ def test_linear_packed(M, N, K, variant):
     (1, 300, 2400, 20, True),       # level 2 of the benchmark step: ragged last key tile, 2.3 query blocks
     (1, 1200, 9600, 10, False),     # level 1
     (2, 96, 200, 2, True),          # two batch items, key count not a multiple of 8
-    (1, 33, 64, 1, False),          # a single full tile, ragged queries
+    (1, 33, 64, 1, False),          # a single full tile, ragged queries: the second wave group has no keys
+    (1, 40, 600, 2, False),         # key ranges rounded up to 128: fewer ranges than first chosen, last one ragged
+    (1, 130, 1100, 3, True),        # odd number of 64-key tiles in a range: the second group's last tile is missing
 ])
 def test_attn_stale_vt(B, Lq, L, heads, packed):
     say("attn_stale_vt", B, Lq, L, heads, packed)
