@@ -520,8 +520,9 @@ int launch_one(const WParams& p, hipStream_t st) {
   const int MT = (p.M + 31) / 32, MG = (MT + TM - 1) / TM;
   const int NTo = p.N / 32;
   if (!p.geglu && NTo % TN) return DF_ESHAPE;
-  if (p.geglu && (TN % 2 || NTo % (TN / 2))) return DF_ESHAPE;
-  const int NG = p.geglu ? NTo / (TN / 2) : NTo / TN;
+  constexpr int GP = TN >= 2 ? TN / 2 : 1;             // (value, gate) fragment pairs of a geglu tile
+  if (p.geglu && (TN % 2 || NTo % GP)) return DF_ESHAPE;
+  const int NG = p.geglu ? NTo / GP : NTo / TN;
   const int KF = p.K / 16;
   if (KF % KSPLIT) return DF_ESHAPE;
   constexpr int RP = (KSPLIT * TM * TN * 4 <= 128) ? TM : (TM % 2 == 0 && KSPLIT * (TM / 2) * TN * 4 <= 128) ? TM / 2 : 1;
