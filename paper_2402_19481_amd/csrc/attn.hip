@@ -707,12 +707,15 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
     if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
     p.vt_ld = a.vt_ld;
-    // Two groups of four waves and a two-stage ring (64 KB of LDS) by default.  Measured on the patch step: the second
-    // group gains ~5 % over one group with a three-stage ring, deeper rings lose again (the kernel is not bound by
-    // the latency of the K / V^T stream).
+    // Up to ~600 workgroups (at most two per compute unit): two groups of four waves and a two-stage ring (64 KB of
+    // LDS); measured on the patch step, the second group gains ~9 % over one group with a three-stage ring.  Larger
+    // launches keep one group and three stages (48 KB, three workgroups per unit), which is faster there (the
+    // 480 x 480-latent share: 27.4 vs 31.5 ms of self-attention).  Deeper rings lose in both forms: the kernel is not
+    // bound by the latency of the K / V^T stream.
     static const int forced_st = getenv("DF_ATTN_STAGES") ? atoi(getenv("DF_ATTN_STAGES")) : 0;   // tuning aid
     static const int forced_gr = getenv("DF_ATTN_GROUPS") ? atoi(getenv("DF_ATTN_GROUPS")) : 0;   // tuning aid
-    const int ngr = forced_gr ? forced_gr : 2;
+    static const long long g2max = getenv("DF_ATTN_G2MAX") ? atoll(getenv("DF_ATTN_G2MAX")) : 600;   // tuning aid
+    const int ngr = forced_gr ? forced_gr : (nwg <= g2max ? 2 : 1);
     const int nst = forced_st ? forced_st : (ngr == 2 ? 2 : 3);
 #define DF_ATTN_VT(NSTV, NGRV)                                                                                      \
   {                                                                                                                 \
