@@ -234,9 +234,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly (no HIP graph replay)")
     ap.add_argument("--small", action="store_true", help="reduced-width UNet (plumbing check, not the benchmark)")
-    ap.add_argument("--workload", choices=["cfg4", "3840"], default="cfg4",
+    ap.add_argument("--workload", choices=["cfg4", "3840", "2048"], default="cfg4",
                     help="cfg4: the headline workload (1280x1920, N=8); 3840: one of 8 row patches of a 3840x3840 image "
-                         "(480x480 latent), the paper's best-scaling resolution - a second workload, not the headline")
+                         "(480x480 latent), the paper's best-scaling resolution; 2048: one of 4 row patches of a 2048x2048 "
+                         "image (256x256 latent), the shape of the multi-step configuration - further workloads, not the "
+                         "headline")
     ap.add_argument("--batch", type=int, default=1,
                     help="batch items through the same step (2 = both classifier-free-guidance branches); the headline is 1")
     ap.add_argument("--ops", action="store_true",
@@ -266,6 +268,11 @@ def main():
         patch = 3
         workload = ("SDXL-shaped UNet step for one patch: 3840x3840 image (480x480x4 latent), N=8 row patches "
                     "(60 latent rows), patch 3, DISPLACED + refresh")
+    elif args.workload == "2048":
+        cfg = ut.UNetCfg(H=256, W=256, N=4, **ut.SDXL)
+        patch = 1
+        workload = ("SDXL-shaped UNet step for one patch: 2048x2048 image (256x256x4 latent), N=4 row patches "
+                    "(64 latent rows), patch 1, DISPLACED + refresh")
     else:
         cfg = ut.UNetCfg(H=160, W=240, N=8, **ut.SDXL)
         patch = 3
@@ -314,6 +321,13 @@ def main():
             one()
         prof = net.profile_read()
         net.profile(False)
+        # the synchronous full-image step (what the first step of a run costs), outside the timed region
+        net.step(x_prev, emb, text, mode=df.MODE_FULL)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        net.step(x_prev, emb, text, mode=df.MODE_FULL)
+        torch.cuda.synchronize()
+        full_ms = (time.perf_counter() - t1) * 1e3
     # Every launch of a profiled step sits between two events, and an event costs the stream a few microseconds that
     # a graph-replayed step does not pay.  That per-launch cost is measured, not assumed: the event intervals of a
     # step must add up to the graph-replayed step time, so overhead = (sum of intervals - step time) / launches, and
@@ -372,6 +386,8 @@ def main():
         "refresh_hbm_gbs": breakdown.get("refresh", {}).get("gbs"),
         "breakdown": breakdown,
         "event_overhead_us_per_launch": round(ev_over_ms * 1e3, 2),
+        # the synchronous full-image step of the same latent (first step of a run; eager launches), for context
+        "full_image_step_ms": round(full_ms, 3),
     }
     if not args.no_cpu_baseline and args.workload == "cfg4" and Bn == 1:
         xin = x.cpu().numpy()
