@@ -340,6 +340,7 @@ def test_pack_rows_layout():
     (300, 3840, 1280, "ln"),           # 64 x 96 wave tile: a single round of workgroups, reduced row by row
     (300, 10240, 1280, "ln_geglu"),    # 128 x 128 wave tile (two value / gate fragment pairs), ragged third row group
     (270, 1024, 1024, "geglu"),        # 128 x 128 tile without the folded norm; 9 token fragments
+    (270, 3840, 1280, "plain"),        # 64 x 96 tile, odd number of token fragments (last row group half empty)
 ])
 def test_linear_packed(M, N, K, variant):
     say("linear_packed", M, N, K, variant)
