@@ -298,9 +298,14 @@ def main():
     stream = torch.cuda.Stream()
     torch.cuda.synchronize()
     with torch.cuda.stream(stream):
-        # the synchronous first step fills every stale buffer (untimed)
+        # the synchronous first step fills every stale buffer (outside the timed region); its second run is timed for
+        # context: what the first step of a sampling run costs
         net.step(x_prev, emb, text, mode=df.MODE_FULL)
         torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        net.step(x_prev, emb, text, mode=df.MODE_FULL)
+        torch.cuda.synchronize()
+        full_ms = (time.perf_counter() - t1) * 1e3
 
         def one():
             net.step(x, emb, text, patch_idx=patch, mode=df.MODE_DISPLACED, refresh=True, out=eps)
@@ -321,13 +326,6 @@ def main():
             one()
         prof = net.profile_read()
         net.profile(False)
-        # the synchronous full-image step (what the first step of a run costs), outside the timed region
-        net.step(x_prev, emb, text, mode=df.MODE_FULL)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        net.step(x_prev, emb, text, mode=df.MODE_FULL)
-        torch.cuda.synchronize()
-        full_ms = (time.perf_counter() - t1) * 1e3
     # Every launch of a profiled step sits between two events, and an event costs the stream a few microseconds that
     # a graph-replayed step does not pay.  That per-launch cost is measured, not assumed: the event intervals of a
     # step must add up to the graph-replayed step time, so overhead = (sum of intervals - step time) / launches, and
