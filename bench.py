@@ -9,7 +9,8 @@ Workload: SDXL-shaped UNet, 1280x1920 image (160x240 latent), N=8 row patches,
 patch 3, batch 1, bf16 with float accumulation, seeded synthetic inputs and
 random-init weights.  The stale state is left by one untimed FULL step.
 
-Prints one JSON line (see README / DESIGN).
+Prints one JSON line: metric, value (ms per step), roofline of the dominant kernel class, per-class breakdown,
+and the CPU oracle's time for the same step.
 """
 import argparse
 import json
@@ -330,7 +331,7 @@ def main():
     # a graph-replayed step does not pay.  That per-launch cost is measured, not assumed: the event intervals of a
     # step must add up to the graph-replayed step time, so overhead = (sum of intervals - step time) / launches, and
     # it is taken off every launch.  The resulting per-kernel averages agree with the rocprofv3 kernel trace of the
-    # same command (profiles/unet_step_cfg4_kernel_stats.md).
+    # same command.
     n_launch = sum(v["launches"] for v in prof.values()) / max(args.profile_steps, 1)
     raw_ms = sum(v["ms"] for v in prof.values()) / max(args.profile_steps, 1)
     ev_over_ms = max(0.0, (raw_ms - ms) / n_launch) if (n_launch and not args.no_graph) else 0.0
