@@ -299,8 +299,11 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
   constexpr int D = 64, TK = 64;
   constexpr int KB = TK * D * 2, STAGE = 2 * KB * NGR;     // bytes: K tiles of all groups, then their V^T tiles
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it (key range, masks of the
+                                                               // ragged tile, LDS addresses) stays off the vector ALU
   const int grp = wave >> 2, wq = wave & 3;
+  const int xor32 = (lane ^ 32) << 2;                          // byte index of the partner lane for ds_bpermute
   const int g = lane >> 5, c = lane & 31;
   const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
   int t = blockIdx.x;
@@ -336,31 +339,46 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
     }
   }
 
-  // direct loads: instruction j of a wave covers tile rows (2*wave + j)*8 + lane/8, 16-byte slot lane%8
+  // direct loads: instruction j of a wave covers tile rows (2*wave + j)*8 + lane/8, 16-byte slot lane%8.  A lane's
+  // offsets inside a tile never change (32-bit, the launcher bounds the pitches); a tile adds a scalar base.
   const int lr = lane >> 3, slot = lane & 7;
+  unsigned int kofs[2], vofs[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = (2 * wave + j) * 8 + lr;               // key within the iteration's K tiles
+    const int f = (row >> 1) & 7;                          // swizzle key: conflict-free 16-byte reads on 64 banks
+    kofs[j] = (unsigned int)row * (unsigned int)p.ldks + (unsigned int)((slot ^ f) * 8);
+    const int d = ((2 * wave + j) & 7) * 8 + lr;           // feature row of the V^T tile (waves 4-7: second group's tile)
+    const int ch = slot ^ (d & 7) ^ (d >> 3);              // 8-key chunk; the buffer is padded to whole tiles
+    vofs[j] = (unsigned int)d * (unsigned int)p.vt_ld + (unsigned int)(ch * 8);
+  }
   auto issue = [&](int tl, int stage) {
     if (tl > ntiles - 1) tl = ntiles - 1;                  // past the end: re-read the last tile (keeps vmcnt uniform)
     const int key0 = kv_lo + tl * TK * NGR;
     char* sk = smem + stage * STAGE;
     char* sv = sk + KB * NGR;
+    if (key0 + TK * NGR <= p.L) {                          // (uniform) every key row of the iteration exists
+      const bf16_t* kb = kg + (long long)key0 * p.ldks;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int row = (2 * wave + j) * 8 + lr;             // key within the tile
-      int key = key0 + row;
-      if (key > p.L - 1) key = p.L - 1;                    // rows beyond the last key are masked below
-      const int f = (row >> 1) & 7;                        // swizzle key: conflict-free 16-byte reads on 64 banks
-      __builtin_amdgcn_global_load_lds(DF_GPTR(kg + (long long)key * p.ldks + ((slot ^ f) * 8)),
-                                       DF_LPTR(sk + (2 * wave + j) * 1024), 16, 0, 0);
-    }
+      for (int j = 0; j < 2; ++j)
+        __builtin_amdgcn_global_load_lds(DF_GPTR(kb + kofs[j]), DF_LPTR(sk + (2 * wave + j) * 1024), 16, 0, 0);
+    } else {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int d = ((2 * wave + j) & 7) * 8 + lr;         // feature row of the V^T tile (waves 4-7: second group's tile)
-      const int ch = slot ^ (d & 7) ^ (d >> 3);            // 8-key chunk; the buffer is padded to whole tiles
-      long long vkey0 = key0 + TK * grp;
-      if (vkey0 > p.vt_ld - TK) vkey0 = p.vt_ld - TK;      // a tile wholly beyond the padded buffer: masked below
-      __builtin_amdgcn_global_load_lds(DF_GPTR(vg + (long long)d * p.vt_ld + vkey0 + ch * 8),
-                                       DF_LPTR(sv + (2 * wave + j) * 1024), 16, 0, 0);
+      for (int j = 0; j < 2; ++j) {
+        const int row = (2 * wave + j) * 8 + lr;
+        int key = key0 + row;
+        if (key > p.L - 1) key = p.L - 1;                  // rows beyond the last key are masked below
+        const int f = (row >> 1) & 7;
+        __builtin_amdgcn_global_load_lds(DF_GPTR(kg + (long long)key * p.ldks + ((slot ^ f) * 8)),
+                                         DF_LPTR(sk + (2 * wave + j) * 1024), 16, 0, 0);
+      }
     }
+    long long vkey0 = key0 + TK * grp;
+    if (vkey0 > p.vt_ld - TK) vkey0 = p.vt_ld - TK;        // a tile wholly beyond the padded buffer: masked below
+    const bf16_t* vb = vg + vkey0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      __builtin_amdgcn_global_load_lds(DF_GPTR(vb + vofs[j]), DF_LPTR(sv + (2 * wave + j) * 1024), 16, 0, 0);
   };
 
   f32x16 o_acc[2];
@@ -387,7 +405,11 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
     const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + grp * KB);
     const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB * NGR + grp * KB);
     const int tile_base = kv_lo + tl * TK * NGR + grp * TK;
-    if (tile_base < kv_hi) {                               // (wave-uniform) the last iteration may hold one tile only
+    // The tile's work in two copies: full tiles carry no mask code at all (written as one body with a run-time flag,
+    // the compiler evaluates the masks' comparisons ahead of the branch in every tile: a third of the loop's vector
+    // instructions).
+    auto tile = [&](auto raggedc) {
+    constexpr bool ragged = decltype(raggedc)::value;
     // All LDS fragment reads of a phase are issued before its MFMAs (one read per MFMA would put an LDS round trip
     // between every pair of matrix instructions), and the V^T fragments are requested before the softmax so that
     // they arrive while the vector ALU works.
@@ -421,8 +443,7 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    const bool ragged = tile_base + TK > kv_hi;
-    if (ragged) {
+    if constexpr (ragged) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -437,7 +458,7 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_acc[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;
+    mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(mx)))) * sc;
     const float m_new = fmaxf(m_run, mx);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float rs = 0.f;
@@ -449,7 +470,7 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
         s_acc[kb][e] = pv;
         rs += pv;
       }
-    rs += __shfl_xor(rs, 32, 64);
+    rs += __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(rs)));
     l_run = l_run * alpha + rs;
     m_run = m_new;
     // the running maximum rarely moves after the first tiles: rescale only when some query of the wave needs it
@@ -472,7 +493,7 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
         u32x4 vraw = vfr[ts][db];
-        if (ragged) {                                      // keys beyond the range: P is 0, V must be finite
+        if constexpr (ragged) {                            // keys beyond the range: P is 0, V must be finite
           const int key = tile_base + kchunk * 8;
           if (key + 0 >= kv_hi) vraw.x = 0u; else if (key + 1 >= kv_hi) vraw.x &= 0xffffu;
           if (key + 2 >= kv_hi) vraw.y = 0u; else if (key + 3 >= kv_hi) vraw.y &= 0xffffu;
@@ -482,7 +503,9 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
         o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pfrag, o_acc[db], 0, 0, 0);
       }
     }
-    }
+    };
+    if (tile_base + TK <= kv_hi) tile(std::false_type{});          // (wave-uniform branches)
+    else if (tile_base < kv_hi) tile(std::true_type{});            // the last iteration may hold one tile only
     stage = (stage + 1 == NST) ? 0 : stage + 1;
     nstage = (nstage + 1 == NST) ? 0 : nstage + 1;
   }
@@ -706,6 +729,7 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.v_transposed) {
     // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
     if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
+    if (a.ldks <= 0 || a.ldks >= (1 << 23) || a.vt_ld >= (1 << 25)) return DF_ESHAPE;   // 32-bit offsets inside a tile
     p.vt_ld = a.vt_ld;
     // Up to ~600 workgroups (at most two per compute unit): two groups of four waves and a two-stage ring (64 KB of
     // LDS); measured on the patch step, the second group gains ~9 % over one group with a three-stage ring.  Larger

@@ -254,7 +254,8 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
   static_assert(KS == 1, "one k-slab per ring stage");
   static_assert((STAGES - 1) * L < 64, "vmcnt field is 6 bits");
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: LDS bases and the compute / load-only split
   const int wm = (wave >> 1) & 1, wn = wave & 1;
   const bool computes = wave < 4;
   // workgroups round-robin over the 8 XCDs; give each XCD a contiguous run of tiles, M-tile fastest, so that the
@@ -325,6 +326,33 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
   }
   const int b_kstep = p.packed_w ? 4096 : 64;   // elements between consecutive k-tiles of the weight operand
 
+  // Convolution: a lane's source row changes only with the filter tap, i.e. every Cin / 64 slabs; its pointer (channel
+  // 0 of the tap's pixel in the fresh patch or a halo row, or the page of zeros for padding) is kept between slabs and
+  // a slab only adds its scalar channel offset.  (Recomputed per slab, the gather's address arithmetic - two divisions
+  // and a handful of 64-bit multiplies under divergent branches - outweighed the slab's four MFMAs.)
+  const bf16_t* a_tap[AJ];
+  bool a_pad[AJ];
+  int tap_k0 = -1;                          // first k of the tap the pointers are set for
+  auto set_tap = [&](int tap) {
+    const int ky = tap / 3, kx = tap - ky * 3;
+#pragma unroll
+    for (int j = 0; j < AJ; ++j) {
+      const int ri = a_ro[j] * p.stride + ky - 1;
+      const int ci = a_co[j] * p.stride + kx - 1;
+      const bf16_t* src = nullptr;
+      if (a_ok[j] && ci >= 0 && ci < p.W) {
+        if (ri < 0) {
+          if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin;
+        } else if (ri >= p.R) {
+          if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin;
+        } else {
+          src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin;
+        }
+      }
+      a_pad[j] = src == nullptr;
+      a_tap[j] = (src ? src : zeros) + kc_a(j) * 8;
+    }
+  };
   auto issue = [&](int kt, int stage) {
     if (kt > KT - 1) kt = KT - 1;           // past the end: reload the last tile into a free stage (keeps vmcnt uniform)
 #pragma unroll
@@ -334,24 +362,16 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
       char* sa = smem + stage * STAGE + sl * SLAB + (wave * (BM / NW)) * 128;
       char* sb = smem + stage * STAGE + sl * SLAB + A_BYTES + (wave * (BN / NW)) * 128;
       if constexpr (kConv) {
-        const int tap = k0 / p.Cin;
-        const int cin0 = k0 - tap * p.Cin;
-        const int ky = tap / 3, kx = tap - ky * 3;
+        if (tap_k0 < 0 || k0 < tap_k0 || k0 >= tap_k0 + p.Cin) {     // (uniform) a new tap
+          const int tap = k0 / p.Cin;
+          tap_k0 = tap * p.Cin;
+          set_tap(tap);
+        }
+        const int cin0 = k0 - tap_k0;
 #pragma unroll
         for (int j = 0; j < AJ; ++j) {
-          const int ri = a_ro[j] * p.stride + ky - 1;
-          const int ci = a_co[j] * p.stride + kx - 1;
-          const bf16_t* src = zeros;
-          if (a_ok[j] && ci >= 0 && ci < p.W) {
-            if (ri < 0) {
-              if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
-            } else if (ri >= p.R) {
-              if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin + cin0;
-            } else {
-              src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin + cin0;
-            }
-          }
-          __builtin_amdgcn_global_load_lds(DF_GPTR(src + kc_a(j) * 8), DF_LPTR(sa + j * 1024), 16, 0, 0);
+          const bf16_t* src = a_pad[j] ? a_tap[j] : a_tap[j] + cin0;
+          __builtin_amdgcn_global_load_lds(DF_GPTR(src), DF_LPTR(sa + j * 1024), 16, 0, 0);
         }
       } else {
 #pragma unroll
