@@ -67,7 +67,8 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   u32x4* qlds = reinterpret_cast<u32x4*>(smem_raw + KSPLIT * U * 1024 + KSPLIT * TM * 32 * 2 * 4);   // [4][64] (XA)
   constexpr int GP = TN >= 2 ? TN / 2 : 1;   // geglu: the tile's first GP fragments are value rows, the last GP their gates
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the k-walk and tile addresses stay off the vector ALU
   const int tok = lane & 31, g = lane >> 5;
   const int MT = (p.M + 31) >> 5;                      // 32-token fragments rows
   const int MG = (MT + TM - 1) / TM;                   // tile groups along M
