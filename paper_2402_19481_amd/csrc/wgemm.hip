@@ -122,8 +122,9 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   const int npu = RP * JO * 2;
   struct Epi { float a[8], b[8], ga[8], gb[8], r[8]; };
   auto load_epi = [&](int i0, int pu, Epi& e, bool vecs) {
-    const int f = pu & 1, j = (pu >> 1) % JO;
-    const int mt = mg * TM + i0 + (pu >> 1) / JO;
+    const int f = pu & 1;
+    const int j = p.geglu ? (pu >> 1) % GP : (pu >> 1) % TN;          // compile-time divisors (JO is a run-time value)
+    const int mt = mg * TM + i0 + (p.geglu ? (pu >> 1) / GP : (pu >> 1) / TN);
     const int m = mt * 32 + tok;
     const int n = (ng * JO + j) * 32 + 16 * f + 8 * g;
     if (!vecs) {
@@ -248,7 +249,9 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   for (int t = 0; t < MAXU; ++t) {
     const int pu = wave + t * KSPLIT;
     if (pu >= npu) break;
-    const int f = pu & 1, j = (pu >> 1) % JO, il = (pu >> 1) / JO;
+    const int f = pu & 1;
+    const int j = p.geglu ? (pu >> 1) % GP : (pu >> 1) % TN;
+    const int il = p.geglu ? (pu >> 1) / GP : (pu >> 1) / TN;
     const int i = i0 + il;
     const int mt = mg * TM + i;
     if (mt >= MT) continue;
@@ -289,9 +292,12 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
         sm += stat[((w * TM + i) * 32 + tok) * 2];
         sq += stat[((w * TM + i) * 32 + tok) * 2 + 1];
       }
-      const float mean = sm / (float)p.K;
-      const float var = fmaxf(sq / (float)p.K - mean * mean, 0.f);
-      const float rstd = 1.0f / sqrtf(var + p.ln_eps);
+      // hardware reciprocal and reciprocal square root (1 ulp) in place of the IEEE division and square root
+      // sequences: this epilogue runs once per workgroup and is not hidden behind anything
+      const float inv_k = __builtin_amdgcn_rcpf((float)p.K);
+      const float mean = sm * inv_k;
+      const float var = fmaxf(fmaf(sq, inv_k, -mean * mean), 0.f);
+      const float rstd = __builtin_amdgcn_rsqf(var + p.ln_eps);
 #pragma unroll
       for (int q = 0; q < 8; ++q) v[q] = rstd * (v[q] - mean * e.a[q]) + e.b[q];
       if (TN >= 2 && p.geglu) {
@@ -333,8 +339,10 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     }
     if (row_ok) {
       if (p.nseg > 0) {
-        const int sg = n / p.seg_w;                     // 8 features never straddle a segment (seg_w % 32 == 0)
-        const int bi = m / p.seg_rows_in[sg];
+        // 8 features never straddle a segment (seg_w % 32 == 0); at most three segments, usually one batch item:
+        // comparisons instead of integer divisions
+        const int sg = (n >= p.seg_w ? 1 : 0) + (n >= 2 * p.seg_w ? 1 : 0);
+        const int bi = m < p.seg_rows_in[sg] ? 0 : m / p.seg_rows_in[sg];
         if (p.seg_tr[sg]) {
           // feature-major output: the 32 tokens of a half wave are consecutive in memory for each feature
           bf16_t* o = p.seg_out[sg] + ((long long)bi * p.seg_w + (n - sg * p.seg_w)) * p.seg_ld[sg] + p.seg_row0[sg] +
