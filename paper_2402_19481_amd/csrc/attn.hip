@@ -577,25 +577,28 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
 // merges the per-split partials: one lane per (query, 4 consecutive d)
 __global__ __launch_bounds__(256) void attn_combine_d64(AttnParams p) {
   constexpr int D = 64;
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  const long long rows = (long long)p.B * p.heads * p.Lq;
+  // 32-bit index arithmetic (the launcher bounds rows * 16 below 2^31): the 64-bit divisions below were a tenth of
+  // this kernel's time
+  const unsigned int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned int rows = (unsigned int)(p.B * p.heads * p.Lq);
   if (idx >= rows * (D / 4)) return;
-  const long long row = idx / (D / 4);
+  const unsigned int row = idx / (D / 4);
   const int d4 = (int)(idx % (D / 4)) * 4;
   float m = -INFINITY;
-  for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, p.part_ml[(s * rows + row) * 2]);
+  for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, p.part_ml[((size_t)s * rows + row) * 2]);
   float l = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < p.nsplit; ++s) {
-    const float w = exp2f(p.part_ml[(s * rows + row) * 2] - m);
-    l += w * p.part_ml[(s * rows + row) * 2 + 1];
-    const f32x4 t = *reinterpret_cast<const f32x4*>(p.part_o + (s * rows + row) * D + d4);
+    const float w = __builtin_amdgcn_exp2f(p.part_ml[((size_t)s * rows + row) * 2] - m);
+    l += w * p.part_ml[((size_t)s * rows + row) * 2 + 1];
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p.part_o + ((size_t)s * rows + row) * D + d4);
     o += t * w;
   }
-  const float inv = 1.0f / l;
-  const int qi = (int)(row % p.Lq);
-  const int h = (int)((row / p.Lq) % p.heads);
-  const int b = (int)(row / ((long long)p.Lq * p.heads));
+  const float inv = __builtin_amdgcn_rcpf(l);
+  const unsigned int bh = row / (unsigned int)p.Lq;
+  const int qi = (int)(row - bh * (unsigned int)p.Lq);
+  const int b = (int)(bh / (unsigned int)p.heads);
+  const int h = (int)(bh - (unsigned int)b * (unsigned int)p.heads);
   bf16_t* op = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D + d4;
   if (p.out_packed) {
     const long long m = (long long)b * p.Lq + qi;
@@ -762,6 +765,7 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   DF_LAUNCH_CHECK();
   if (ns > 1) {
     const long long n = (long long)a.B * a.heads * a.Lq * 16;
+    if (n >= (1LL << 31)) return DF_ESHAPE;                // the merge kernel indexes with 32 bits
     hipLaunchKernelGGL(attn_combine_d64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
     DF_LAUNCH_CHECK();
   }

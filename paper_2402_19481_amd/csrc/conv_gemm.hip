@@ -1045,10 +1045,11 @@ int launch_tile(const TileParams& p, int out_dtype, hipStream_t st) {
 template <typename OutT>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(TileParams p, const float* __restrict__ partials, int nsplit,
                                                            int per) {
-  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  const int n4 = p.N / 4;
-  if (idx >= (long long)p.M * n4) return;
-  const int row = (int)(idx / n4), col = (int)(idx % n4) * 4;
+  // 32-bit index arithmetic (split launches have fewer than 1024 tiles of 64 x 64, far below 2^31 elements)
+  const unsigned int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const unsigned int n4 = (unsigned int)p.N / 4;
+  if (idx >= (unsigned int)p.M * n4) return;
+  const int row = (int)(idx / n4), col = (int)(idx - (idx / n4) * n4) * 4;
   f32x4 v = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < nsplit; ++s)
     v += *reinterpret_cast<const f32x4*>(partials + ((size_t)s * p.M + row) * p.N + col);
