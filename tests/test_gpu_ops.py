@@ -393,6 +393,8 @@ def test_linear_packed(M, N, K, variant):
     (1, 33, 64, 1, False),          # a single full tile, ragged queries: the second wave group has no keys
     (1, 40, 600, 2, False),         # key ranges rounded up to 128: fewer ranges than first chosen, last one ragged
     (1, 130, 1100, 3, True),        # odd number of 64-key tiles in a range: the second group's last tile is missing
+    (2, 300, 2400, 4, True),        # two batch items with split key ranges in the two-group kernel
+    (1, 4096, 8192, 10, False),     # > 600 workgroups: the single-group, three-stage form
 ])
 def test_attn_stale_vt(B, Lq, L, heads, packed):
     say("attn_stale_vt", B, Lq, L, heads, packed)
