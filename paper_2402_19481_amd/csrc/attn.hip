@@ -60,8 +60,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][TK * D];   // [key][d], 16-byte chunks XOR-swizzled by row
   __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * TK];   // [d][key], swizzled
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: the query rows, hence the key ranges and the
+                                                               // ragged-tile test, stay off the vector ALU
   const int g = lane >> 5, c = lane & 31;
+  const int xor32 = (lane ^ 32) << 2;                          // byte index of the partner lane for ds_bpermute
   const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);   // c with bits 2 and 3 swapped
   // 1-D grid; workgroups go round-robin over the 8 XCDs, so XCD x takes the x-th contiguous chunk of the
   // (query block fastest, head, batch*split) order: the query blocks that read the same K/V range share an L2
@@ -108,9 +111,43 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
   constexpr int PF = 3;
   u32x4 kreg[PF][2], vreg[PF][2];
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  // a lane's row offsets inside a tile (32-bit: the launcher bounds the pitches); a tile that lies wholly in the
+  // stale buffer or wholly in the fresh rows only adds a scalar base (the generic path below redoes a select and a
+  // 64-bit multiply per row and tile)
+  unsigned int kof_s[2], vof_s[2], kof_f[2], vof_f[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    kof_s[i] = (unsigned int)(ld_key + 32 * i) * (unsigned int)p.ldks + ld_ch * 8;
+    vof_s[i] = (unsigned int)(2 * ld_key + i) * (unsigned int)p.ldvs + ld_ch * 8;
+    kof_f[i] = (unsigned int)(ld_key + 32 * i) * (unsigned int)p.ldkf + ld_ch * 8;
+    vof_f[i] = (unsigned int)(2 * ld_key + i) * (unsigned int)p.ldvf + ld_ch * 8;
+  }
   auto load_tile = [&](int t, auto slot) {
     constexpr int S = decltype(slot)::value;
     const int base = kv_lo + t * TK;
+    if (base + TK <= kv_hi) {                              // (uniform) a full tile
+      const int rel = base - p.own_lo;
+      if (rel >= 0 && rel + TK <= p.own_n) {               // all rows fresh
+        const bf16_t* kb = kf + (long long)rel * p.ldkf;
+        const bf16_t* vb = vf + (long long)rel * p.ldvf;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          kreg[S][i] = *reinterpret_cast<const u32x4*>(kb + kof_f[i]);
+          vreg[S][i] = *reinterpret_cast<const u32x4*>(vb + vof_f[i]);
+        }
+        return;
+      }
+      if (rel + TK <= 0 || rel >= p.own_n) {               // all rows stale
+        const bf16_t* kb = ks + (long long)base * p.ldks;
+        const bf16_t* vb = vs + (long long)base * p.ldvs;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          kreg[S][i] = *reinterpret_cast<const u32x4*>(kb + kof_s[i]);
+          vreg[S][i] = *reinterpret_cast<const u32x4*>(vb + vof_s[i]);
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int jk = base + ld_key + 32 * i;
@@ -197,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_acc[kb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;    // scale > 0, so the maximum commutes with the scaling
+    mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(mx)))) * sc;   // scale > 0
     const float m_new = fmaxf(m_run, mx);           // finite: every tile holds at least one valid key
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // exp2(-inf) = 0 on the first tile
     float rs = 0.f;
@@ -209,13 +246,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
         s_acc[kb][e] = pv;
         rs += pv;
       }
-    rs += __shfl_xor(rs, 32, 64);
+    rs += __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(rs)));
     l_run = l_run * alpha + rs;
     m_run = m_new;
+    // the running maximum rarely moves after the first tiles: rescale only when some query of the wave needs it
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+    }
 
     // ---- O^T += V^T P^T : four 16-key steps; lane supplies P for its query and key slots 8g..8g+7 ----
 #pragma unroll
@@ -760,6 +800,8 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     else if (nst <= 3) DF_ATTN_VT(3, 1) else if (nst == 4) DF_ATTN_VT(4, 1) else DF_ATTN_VT(6, 1)
 #undef DF_ATTN_VT
   } else {
+    // 32-bit row offsets inside a 64-key tile
+    if (a.ldkf >= (1 << 24) || a.ldvf >= (1 << 24) || a.ldks >= (1 << 24) || a.ldvs >= (1 << 24)) return DF_ESHAPE;
     hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
   }
   DF_LAUNCH_CHECK();
