@@ -24,17 +24,31 @@ constexpr long long kGnGroupMaxElems = 80 * 1024;   // per (group, batch item): 
 struct GnHalo {
   bf16_t* out;      // nullptr: no boundary-row copy
   int W, rpp, patch0, npatch;
+  int single;       // the tensor holds exactly one patch (rpp rows): boundary rows follow from comparisons
 };
 
 // stores 4 or 8 bf16 values of pixel p (within its batch item), channels c0.., into the boundary-row state if the
 // pixel lies on the first or last row of its patch
 template <int V>
 __device__ __forceinline__ void halo_store(const GnHalo& h, int b, long long p, int C, int c0, const float* v) {
-  const int row = (int)(p / h.W), col = (int)(p - (long long)row * h.W);
-  const int pr = row % h.rpp, patch = h.patch0 + row / h.rpp;
+  // (this runs per pixel and lane: no 64-bit division, and none at all for the one-patch tensors of a displaced step)
+  const unsigned int pi = (unsigned int)p;
+  unsigned int row, col, pr, patch;
+  if (h.single) {
+    const unsigned int last0 = (unsigned int)(h.rpp - 1) * (unsigned int)h.W;
+    if (pi >= (unsigned int)h.W && pi < last0) return;           // an interior row
+    pr = pi < (unsigned int)h.W ? 0u : (unsigned int)(h.rpp - 1);
+    col = pi < (unsigned int)h.W ? pi : pi - last0;
+    row = pr; patch = (unsigned int)h.patch0;
+    if (h.rpp == 1) { pr = 0; col = pi; }
+  } else {
+    row = pi / (unsigned int)h.W; col = pi - row * (unsigned int)h.W;
+    const unsigned int q = row / (unsigned int)h.rpp;
+    pr = row - q * (unsigned int)h.rpp; patch = (unsigned int)h.patch0 + q;
+  }
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
-    if (pr != (which ? h.rpp - 1 : 0)) continue;
+    if ((int)pr != (which ? h.rpp - 1 : 0)) continue;
     bf16_t* o = h.out + ((((long long)b * h.npatch + patch) * 2 + which) * h.W + col) * C + c0;
     if constexpr (V == 8) {
       st_vec(o, v);
@@ -536,6 +550,7 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
       return DF_EINVAL;
     halo.out = (bf16_t*)a.halo_out; halo.W = a.W; halo.rpp = a.halo_rpp; halo.patch0 = a.halo_patch0;
     halo.npatch = a.halo_npatch;
+    halo.single = ((long long)a.Rseg * a.nseg == a.halo_rpp) ? 1 : 0;
   }
   if (pix_seg <= 0 || pix_seg * a.nseg > 0x7fffffffLL) return DF_ESHAPE;
   // small tensors: the whole GroupNorm in one launch, one workgroup per (group, batch item)
