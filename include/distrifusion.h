@@ -108,7 +108,8 @@ int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, 
  *   k_stale, v_stale    [B, L,  heads*d]   may be NULL when N == 1
  *   out                 [B, Lq, heads*d]
  * out = softmax(q k^T * scale) v per head, no mask.  d is 64 for DF_BF16,
- * at most 128 for DF_F32.
+ * at most 128 for DF_F32.  Returns DF_ESHAPE for heads*d >= 2^24 (row offsets
+ * inside a key tile are 32-bit) and when B * (key-range splits) exceeds 65535.
  */
 int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
                       const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
@@ -155,7 +156,8 @@ int df_linear_packed(const void* xp, const void* wp, const float* bias, const fl
  * buffers by the projection, so no splice is left for the attention kernel).  q [B, Lq, heads*64], k [B, L, heads*64],
  * vt [B, heads*64, vt_ld] with vt[b][c][j] = v[b][j][c], vt_ld >= L rounded up to a multiple of 64 (columns beyond L
  * are never used); out [B, Lq, heads*64] row-major, or fragment-packed (rows = B*Lq; the padding rows of the last
- * fragment row are left untouched) if out_packed.  bf16, d = 64.
+ * fragment row are left untouched) if out_packed.  bf16, d = 64.  DF_ESHAPE for heads*64 >= 2^23 or vt_ld >= 2^25
+ * (32-bit offsets inside a tile), DF_EINVAL for vt_ld % 8 != 0 or vt_ld below L rounded up to 64.
  *
  * df_cross_attn_packed: cross-attention to the text tokens fused into its query projection (Section 4: per-token
  * layers need no data of other patches).  out = softmax(q k^T * scale) v per head with q = LayerNorm(x) wq^T, the
