@@ -381,6 +381,27 @@ def test_linear_packed(M, N, K, variant):
     np.testing.assert_array_equal(host(outs["f32"]), host(outs2["f32"]))
 
 
+def test_geglu_gate_function_pointwise():
+    """The kernels' GELU against the erf definition, value by value: identity weights turn the GEGLU layer into
+    out[m, f] = x[m, f] * gelu(x[m, f]) with exact products, on a grid of bf16-representable arguments."""
+    say("geglu pointwise")
+    M, F = 256, 64
+    grid = (np.arange(M * F, dtype=np.float64) % 257 - 128.0) / 16.0          # -8 .. 8 in steps of 1/16
+    x = round_bf16(grid.reshape(M, F).astype(np.float32))
+    assert np.array_equal(x, grid.reshape(M, F).astype(np.float32))
+    eye = np.eye(F, dtype=np.float32)
+    w = np.concatenate([eye, eye], 0)                                          # value rows, then gate rows
+    xp = df.pack_rows(dev(x, True))
+    wp = df.pack_linear_weight(dev(w, True))
+    out = host(df.linear_packed(xp, wp, M, 2 * F, F, geglu=True, want=("f32",))["f32"]).astype(np.float64)
+    xd = x.astype(np.float64)
+    erf = np.vectorize(math.erf)
+    ref = xd * (0.5 * xd * (1.0 + erf(xd / math.sqrt(2.0))))
+    err = np.abs(out - ref)
+    say("   max abs err", err.max())
+    assert (err <= 4e-6 * np.maximum(1.0, xd * xd)).all()
+
+
 # ---------------------------------------------------------------------------------------------------------------
 # the attention forms of the UNet step: transposed values in the stale buffer; cross-attention fused into its
 # query projection
