@@ -26,17 +26,92 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
-def measured_traffic(cls):
-    """HBM bytes per step of a kernel class from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
-    calibrated against the copy kernel), or None."""
+TRAFFIC_PROFILE = os.path.join("profiles", "unet_step_cfg4_hbm_traffic.md")
+
+
+def traffic_from_profile(cls):
+    """HBM bytes per step of a kernel class as the committed rocprofv3 --pmc summary of this command states them
+    (FETCH_SIZE + WRITE_SIZE, calibrated with `bench.py --calibrate-copy`), or None.  Counter runs are separate
+    profiler runs by nature, so this is never a measurement of the present run and is labelled accordingly."""
     try:
-        for line in open(os.path.join(ROOT, "profiles", "unet_step_cfg4_hbm_traffic.md")):
+        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
             f = line.split()
             if len(f) == 3 and f[0] == "traffic_per_step_bytes" and f[1] == cls:
                 return float(f[2])
     except OSError:
         pass
     return None
+
+
+def calibrate_copy(df, torch, mib, reps):
+    """Plain copies of a known size through the library's copy kernel (df_copy_bytes), for calibrating the
+    FETCH_SIZE / WRITE_SIZE counters: run under `rocprofv3 --pmc FETCH_SIZE` (then WRITE_SIZE) and divide the
+    counter's KiB per dispatch of `copy_rows_vec16` by the KiB this prints."""
+    n = mib << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    dst = torch.empty_like(src)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        df.copy_bytes(dst, src)
+        st.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(reps):
+            df.copy_bytes(dst, src)
+        e1.record(st)
+        e1.synchronize()
+    assert torch.equal(dst, src)
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    print(json.dumps({"op": "calibrate_copy", "kernel": "copy_rows_vec16", "dispatches": reps + 1,
+                      "read_KiB_per_dispatch": n // 1024, "written_KiB_per_dispatch": n // 1024,
+                      "us_per_dispatch": round(us, 2), "gbs": round(2.0 * n / us / 1e3, 1)}), flush=True)
+
+
+def run_loop(df, torch, net, cfg, patch, steps, emb, text, workload):
+    """The multi-step configuration: `steps` Euler steps on a fixed sigma ladder, step 0 FULL on the whole latent,
+    then DISPLACED + refresh on the patch's rows (Section 4: the first step is synchronous), the scaled input and the
+    eps output at fixed addresses so that the displaced steps replay one HIP graph.  Per-step times from HIP events
+    on the stream the steps run on; one untimed pass of the loop first (it records the graph)."""
+    sig = [14.6 * (0.03 / 14.6) ** (k / steps) for k in range(steps + 1)]
+    R = cfg.H // cfg.N
+    g = torch.Generator(device="cuda:0").manual_seed(41)
+    x0 = torch.randn(1, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0") * sig[0]
+    st = torch.cuda.Stream()
+    times = None
+    with torch.cuda.stream(st):
+        for rep in range(2):
+            x_full = x0.clone()
+            xp = x_full[:, patch * R:(patch + 1) * R]
+            xin_full, eps_full = torch.empty_like(x_full), torch.empty_like(x_full)
+            if rep == 0:
+                xin, eps = torch.empty_like(xp), torch.empty_like(xp)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            st.synchronize()
+            t0 = time.perf_counter()
+            for k in range(steps):
+                ev[k].record(st)
+                if k == 0:
+                    net.step(df.scale_input(x_full, sig[0], out=xin_full), emb, text, 0, df.MODE_FULL, True, out=eps_full)
+                    df.euler_update(x_full, eps_full, sig[0], sig[1])
+                else:
+                    net.step(df.scale_input(xp, sig[k], out=xin), emb, text, patch, df.MODE_DISPLACED, True, out=eps)
+                    df.euler_update(xp, eps, sig[k], sig[k + 1])
+            ev[steps].record(st)
+            st.synchronize()
+            wall = (time.perf_counter() - t0) * 1e3
+            times = [ev[k].elapsed_time(ev[k + 1]) for k in range(steps)]
+        assert bool(torch.isfinite(x_full).all())
+    disp = times[1:]
+    from df_inputs import unet_table as ut
+    tflop = 2.0 * ut.count_macs(cfg)["total"] / 1e12
+    print(json.dumps({
+        "metric": "ms per patch UNet step (1 MI355X), multi-step loop", "value": round(sum(disp) / len(disp), 4),
+        "unit": "ms", "n_gpus": 1, "steps": steps, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": workload + ", %d-step Euler loop (step 0 FULL, then DISPLACED + refresh)" % steps},
+        "ms_per_step_list": [round(t, 3) for t in times], "full_first_step_ms": round(times[0], 3),
+        "displaced_step_ms_mean": round(sum(disp) / len(disp), 4), "displaced_step_ms_max": round(max(disp), 4),
+        "loop_wall_ms": round(wall, 3), "tflop_per_displaced_step": round(tflop, 4),
+        "displaced_tflops": round(tflop / (sum(disp) / len(disp) * 1e-3), 2)}), flush=True)
 
 
 def make_weights(df, torch, ccfg, seed):
@@ -242,6 +317,12 @@ def main():
                          "headline")
     ap.add_argument("--batch", type=int, default=1,
                     help="batch items through the same step (2 = both classifier-free-guidance branches); the headline is 1")
+    ap.add_argument("--loop", type=int, default=0,
+                    help="run the multi-step configuration's loop with this many Euler steps (step 0 FULL, the rest "
+                         "DISPLACED + refresh) on the chosen workload and print per-step times; --workload 2048 --loop 10 "
+                         "is that configuration as stated")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="only run plain copies of this many MiB through the library's copy kernel (counter calibration)")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -259,6 +340,9 @@ def main():
     torch.cuda.set_device(0)
     if args.ops:
         run_ops(df, torch)
+        return
+    if args.calibrate_copy:
+        calibrate_copy(df, torch, args.calibrate_copy, max(args.steps, 1))
         return
     if args.small:
         cfg = ut.UNetCfg(H=32, W=16, N=4, **ut.SMALL)
@@ -286,6 +370,13 @@ def main():
     net = df.PatchUNet(cfg, weights, B=Bn)
     if args.no_graph:
         net.set_graph(False)
+    if args.loop:
+        gl = torch.Generator(device="cuda:0").manual_seed(40)
+        emb_l = torch.randn(1, cfg.emb_dim, generator=gl, device="cuda:0")
+        text_l = torch.randn(1, cfg.text_len, cfg.text_dim, generator=gl, device="cuda:0").to(torch.bfloat16)
+        run_loop(df, torch, net, cfg, patch, args.loop, emb_l, text_l, workload.replace(", DISPLACED + refresh", ""))
+        net.close()
+        return
     g = torch.Generator(device="cuda:0").manual_seed(40)
     x_prev = torch.randn(Bn, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
     R = cfg.H // cfg.N
@@ -326,6 +417,7 @@ def main():
         for _ in range(args.profile_steps):
             one()
         prof = net.profile_read()
+        kernels = net.profile_kernels()
         net.profile(False)
     # Every launch of a profiled step sits between two events, and an event costs the stream a few microseconds that
     # a graph-replayed step does not pay.  That per-launch cost is measured, not assumed: the event intervals of a
@@ -346,24 +438,46 @@ def main():
                             tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["flops"] else None,
                             gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
                             event_ms_per_step=round(v["event_ms"] / args.profile_steps, 4))
-    dom = max(breakdown, key=lambda k: breakdown[k]["ms_per_step"])
+    # The roofline object is that of the single dominant KERNEL: one operation at one shape, i.e. the launches of one
+    # kernel instantiation with one grid (the library's profile keeps totals per such kernel).  The class it belongs
+    # to (all linear layers, all convolutions, ...) is reported beside it.
+    for kr in kernels:
+        kr["ms"] = max(kr["ms"] - ev_over_ms * kr["launches"], 1e-6)
+    kd = max(kernels, key=lambda kr: kr["ms"])
+    dom = kd["cls"]
     d = prof[dom]
-    traffic = None if (args.small or args.workload != "cfg4" or args.batch != 1) else measured_traffic(dom)
-    if traffic is not None:
-        traffic = round(traffic / (d["launches"] / args.profile_steps))      # per launch, like `achieved`
-    if d["flops"] > 0:
-        ach = d["flops"] / (d["ms"] * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel=dom, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=traffic,
-                        algorithmic_bytes_per_launch=round(d["bytes"] / d["launches"]),
-                        avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
-                        flops_per_launch=d["flops"] / d["launches"])
-    else:
-        ach = d["bytes"] / (d["ms"] * 1e-3) / 1e9
-        roofline = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(ach / PEAK_HBM_GBS, 4), traffic=traffic,
-                        avg_launch_us=round(d["ms"] * 1e3 / d["launches"], 3),
-                        bytes_per_launch=d["bytes"] / d["launches"])
+
+    def roof(rec, name, extra):
+        if rec["flops"] > 0:
+            ach = rec["flops"] / (rec["ms"] * 1e-3) / 1e12
+            out = dict(bound="mfma", kernel=name, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                       frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                       flops_per_launch=rec["flops"] / rec["launches"])
+        else:
+            ach = rec["bytes"] / (rec["ms"] * 1e-3) / 1e9
+            out = dict(bound="hbm", kernel=name, achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                       frac=round(ach / PEAK_HBM_GBS, 4), traffic=None)
+        out["algorithmic_bytes_per_launch"] = round(rec["bytes"] / rec["launches"])
+        out["avg_launch_us"] = round(rec["ms"] * 1e3 / rec["launches"], 3)
+        out["launches_per_step"] = rec["launches"] // args.profile_steps
+        out["ms_per_step"] = round(rec["ms"] / args.profile_steps, 4)
+        out.update(extra)
+        return out
+
+    roofline = roof(kd, kd["label"], {})
+    roofline["share_of_step"] = round(kd["ms"] / args.profile_steps / ms, 4)
+    cls_roof = roof(d, dom, {})
+    tr = None if (args.small or args.workload != "cfg4" or args.batch != 1) else traffic_from_profile(dom)
+    if tr is not None:
+        # not measured in this run: bytes per launch of the class in the committed counter profile of this command
+        cls_roof["traffic_from_profile"] = {"bytes_per_launch": round(tr / (d["launches"] / args.profile_steps)),
+                                            "source": TRAFFIC_PROFILE}
+    roofline["kernel_class"] = cls_roof
+    top = sorted(kernels, key=lambda kr: -kr["ms"])[:8]
+    top_kernels = [dict(kernel=kr["label"], ms_per_step=round(kr["ms"] / args.profile_steps, 4),
+                        launches_per_step=kr["launches"] // args.profile_steps,
+                        tflops=round(kr["flops"] / (kr["ms"] * 1e-3) / 1e12, 1) if kr["flops"] else None,
+                        gbs=round(kr["bytes"] / (kr["ms"] * 1e-3) / 1e9, 1)) for kr in top]
 
     macs = ut.count_macs(cfg)
     tflop = 2.0 * macs["total"] / 1e12 * Bn
@@ -384,6 +498,7 @@ def main():
         "groupnorm_hbm_gbs": breakdown.get("groupnorm", {}).get("gbs"),
         "refresh_hbm_gbs": breakdown.get("refresh", {}).get("gbs"),
         "breakdown": breakdown,
+        "top_kernels": top_kernels,
         "event_overhead_us_per_launch": round(ev_over_ms * 1e3, 2),
         # the synchronous full-image step of the same latent (first step of a run; eager launches), for context
         "full_image_step_ms": round(full_ms, 3),

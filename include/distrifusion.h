@@ -18,10 +18,19 @@
  *     on that stream and return after enqueueing.
  *   - Patches: a full tensor of H rows is split into N strips of R = H / N
  *     rows; patch i owns rows [i*R, (i+1)*R).  H % N must be 0.
- *   - Return value: DF_OK, or a negative error; nothing is launched on error.
- *     The library may keep a small per-device scratch allocation (GroupNorm
- *     partial sums, split-K partials); it is created on first use.
- *   - Calls on different streams must not share that scratch concurrently:
+ *   - Return value: DF_OK, or a negative error; arguments are checked before
+ *     the first launch, so nothing has been enqueued when an argument error
+ *     (DF_EINVAL, DF_ESHAPE, DF_ENOMEM) comes back.
+ *   - Scratch: the per-operation entry points keep one scratch region per device
+ *     (GroupNorm partial sums, split-K and split-key partials, a page of zeros).
+ *     It is allocated on first use and only ever grows; growing allocates a
+ *     further buffer and never frees or moves the previous one, so work that is
+ *     still queued, or a graph captured around these calls, keeps valid
+ *     addresses.  The allocation must not happen during stream capture: call an
+ *     entry point eagerly once with the shape before capturing it.  A UNet plan
+ *     does not use this region at all: its scratch is part of the workspace the
+ *     caller hands to df_unet_create.
+ *   - Calls on different streams must not share a scratch region concurrently:
  *     issue the library's calls for one device from one stream at a time.
  */
 #ifndef DISTRIFUSION_H
@@ -107,9 +116,10 @@ int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, 
  *   q, k_fresh, v_fresh [B, Lq, heads*d]
  *   k_stale, v_stale    [B, L,  heads*d]   may be NULL when N == 1
  *   out                 [B, Lq, heads*d]
- * out = softmax(q k^T * scale) v per head, no mask.  d is 64 for DF_BF16,
- * at most 128 for DF_F32.  Returns DF_ESHAPE for heads*d >= 2^24 (row offsets
- * inside a key tile are 32-bit) and when B * (key-range splits) exceeds 65535.
+ * out = softmax(q k^T * scale) v per head, no mask.  d is 64 for DF_BF16, 32
+ * or 64 for DF_F32.  scale must be positive and finite (DF_EINVAL otherwise).
+ * Returns DF_ESHAPE for heads*d >= 2^24 (row offsets inside a key tile are
+ * 32-bit), when B * (key-range splits) exceeds 65535 and when B*heads*Lq >= 2^27.
  */
 int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
                       const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
@@ -259,6 +269,13 @@ int df_unet_profile_reset(df_unet* u);
 int df_unet_profile_num_classes(void);
 const char* df_unet_profile_class_name(int cls);
 int df_unet_profile_read(df_unet* u, int cls, double* ms, double* flops, double* bytes, long long* launches);
+/* The same totals per kernel: one operation at one shape ("linear_packed 300x1280x1280", "self_attn 300x2400x1280",
+ * ...), i.e. launches of one kernel instantiation with one grid.  df_unet_profile_num_kernels synchronises the device
+ * and returns how many distinct kernels the profiled steps launched (or a negative error); df_unet_profile_kernel
+ * fills one entry: its label, class and totals. */
+int df_unet_profile_num_kernels(df_unet* u);
+int df_unet_profile_kernel(df_unet* u, int idx, char* label, int label_cap, int* cls, double* ms, double* flops,
+                           double* bytes, long long* launches);
 
 /* Sampler update on the patch's latent rows (Section 3, Eq. 1; Euler step): x += (sigma_next - sigma) * eps. */
 int df_euler_update(float* x, const float* eps, float sigma, float sigma_next, long long n, void* stream);

@@ -89,6 +89,10 @@ def lib():
     L.df_unet_profile_class_name.restype = ctypes.c_char_p
     dp = ctypes.POINTER(ctypes.c_double)
     L.df_unet_profile_read.argtypes = [vp, i, dp, dp, dp, ctypes.POINTER(ll)]
+    L.df_unet_profile_num_kernels.argtypes = [vp]
+    L.df_unet_profile_num_kernels.restype = i
+    L.df_unet_profile_kernel.argtypes = [vp, i, ctypes.c_char_p, i, ctypes.POINTER(i), dp, dp, dp, ctypes.POINTER(ll)]
+    L.df_unet_profile_kernel.restype = i
     for name in ("df_copy_bytes", "df_buffer_refresh", "df_groupnorm_stale", "df_conv3x3_halo", "df_attn_displaced",
                  "df_euler_update", "df_linear", "df_unet_set_gn_mode", "df_scale_input", "df_mfma_probe", "df_attn_stale_vt", "df_packed_text_kv_bytes", "df_pack_text_kv",
                  "df_cross_attn_packed", "df_packed_bytes", "df_pack_rows", "df_pack_linear_weight", "df_linear_packed", "df_unet_num_weights", "df_unet_weight_info", "df_unet_create",
@@ -337,28 +341,47 @@ class PatchUNet:
         """GroupNorm statistic mode of the displaced steps (GN_SUMS default, GN_EQ2, GN_SEPARATE, GN_STALE)."""
         _check(lib().df_unet_set_gn_mode(self.handle, int(stat_mode)))
 
+    def _loop_buffer(self, key, shape):
+        """Persistent float buffers of the sampling loop: the step's graph cache is keyed on its pointers, so the
+        scaled input and the eps output must live at the same addresses in every step for the graph to replay."""
+        bufs = self.__dict__.setdefault("_loop_bufs", {})
+        k = (key, tuple(shape))
+        if k not in bufs:
+            bufs[k] = torch.empty(shape, dtype=torch.float32, device=self.device)
+        return bufs[k]
+
     def sample_patch(self, x_full, emb, text, sigmas, patch_idx, n_warmup=1):
         """Euler sampling loop of one device: `n_warmup` synchronous steps on the whole latent (they fill the stale
         state; the paper runs the first steps this way), then displaced steps that advance the rows of patch
         `patch_idx` only and refresh its slots of the stale state.  x_full [B,H,W,4] float is updated in place (all rows
         during warm-up, then the patch's rows); every arithmetic step runs in the library.  Returns the list of the
-        per-step eps tensors (full image for warm-up steps, patch rows afterwards)."""
+        per-step eps tensors (full image for warm-up steps, patch rows afterwards).  The scaled input and the eps
+        output of the displaced steps sit in buffers the object keeps, so from the third displaced step on the whole
+        UNet step is one HIP-graph replay."""
         B, H, W, C = x_full.shape
         R = H // self.cfg.N
         rows = slice(patch_idx * R, (patch_idx + 1) * R)
         eps_all = []
+        xin_full, eps_full = self._loop_buffer("xin_full", x_full.shape), self._loop_buffer("eps_full", x_full.shape)
+        xin, eps_p = self._loop_buffer("xin", (B, R, W, C)), self._loop_buffer("eps", (B, R, W, C))
+        xp = x_full[:, rows]
+        own = xp.is_contiguous()                       # B == 1: the patch's rows are one block of x_full
+        if not own:
+            xp = self._loop_buffer("xp", (B, R, W, C))
+            xp.copy_(x_full[:, rows])
         for k in range(len(sigmas) - 1):
             s0, s1 = float(sigmas[k]), float(sigmas[k + 1])
             if k < n_warmup:
-                eps = self.step(scale_input(x_full, s0), emb, text, 0, MODE_FULL, True)
+                eps = self.step(scale_input(x_full, s0, out=xin_full), emb, text, 0, MODE_FULL, True, out=eps_full)
                 euler_update(x_full, eps, s0, s1)
+                if not own:
+                    xp.copy_(x_full[:, rows])
             else:
-                xp = x_full[:, rows].contiguous()          # the patch's rows (a view when B == 1)
-                eps = self.step(scale_input(xp, s0), emb, text, patch_idx, MODE_DISPLACED, True)
+                eps = self.step(scale_input(xp, s0, out=xin), emb, text, patch_idx, MODE_DISPLACED, True, out=eps_p)
                 euler_update(xp, eps, s0, s1)
-                if xp.data_ptr() != x_full[:, rows].data_ptr():
+                if not own:
                     buffer_refresh(x_full, xp, patch_idx, self.cfg.N)
-            eps_all.append(eps)
+            eps_all.append(eps.clone())
         return eps_all
 
     def set_graph(self, on):
@@ -380,6 +403,24 @@ class PatchUNet:
                                           ctypes.byref(n)))
             out[L.df_unet_profile_class_name(k).decode()] = dict(ms=ms.value, flops=fl.value, bytes=by.value,
                                                                  launches=n.value)
+        return out
+
+    def profile_kernels(self):
+        """[dict(label, cls, ms, flops, bytes, launches)] per kernel (one operation at one shape) since profiling was
+        switched on."""
+        L = lib()
+        n = L.df_unet_profile_num_kernels(self.handle)
+        if n < 0:
+            _check(n)
+        out = []
+        buf = ctypes.create_string_buffer(160)
+        for k in range(n):
+            cls, ms, fl, by, cnt = (ctypes.c_int(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double(),
+                                    ctypes.c_longlong())
+            _check(L.df_unet_profile_kernel(self.handle, k, buf, 160, ctypes.byref(cls), ctypes.byref(ms),
+                                            ctypes.byref(fl), ctypes.byref(by), ctypes.byref(cnt)))
+            out.append(dict(label=buf.value.decode(), cls=L.df_unet_profile_class_name(cls.value).decode(),
+                            ms=ms.value, flops=fl.value, bytes=by.value, launches=cnt.value))
         return out
 
     def stale_names(self):

@@ -15,31 +15,36 @@ DevScratch g_scratch[64];
 std::mutex g_scratch_mu;
 }  // namespace
 
-// Grown on demand.  Growing frees the old buffer after a device synchronise, so it must
-// not happen while a stream is being captured: plans reserve their maximum up front.
-void* scratch_get(size_t bytes) {
+int scratch_init(const Scratch& s) {
+  if (!s.ptr || s.bytes < kScratchCounterBytes) return DF_ENOMEM;
+  if (hipMemset(s.ptr, 0, kScratchCounterBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  return DF_OK;
+}
+
+// The per-device region of the per-operation entry points.  It only ever grows, and growing never frees: the
+// previous buffer stays allocated (and its reserved head stays zero) until the process ends, because launches that
+// are still queued, and graphs a caller captured around these entry points, hold its address.  Sizes double, so all
+// retired buffers together are smaller than the live one.  The allocation must not happen while the calling stream
+// is being captured; capture a call only after an eager call of the same shape.
+char* scratch_region(const Scratch* given, size_t bytes) {
+  if (given) return (given->ptr && given->bytes >= bytes) ? given->ptr : nullptr;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
   std::lock_guard<std::mutex> lock(g_scratch_mu);
   DevScratch& s = g_scratch[dev];
-  if (s.bytes >= bytes) return s.ptr;
-  size_t want = bytes < (8u << 20) ? (8u << 20) : bytes;
+  if (s.bytes >= bytes) return (char*)s.ptr;
+  size_t want = s.bytes ? s.bytes * 2 : (size_t)8 << 20;
+  if (want < bytes) want = bytes;
   want = (want + 255) / 256 * 256;
-  if (s.ptr) {
-    if (hipDeviceSynchronize() != hipSuccess) return nullptr;
-    (void)hipFree(s.ptr);
-    s.ptr = nullptr;
-    s.bytes = 0;
-  }
   void* p = nullptr;
-  if (hipMalloc(&p, want) != hipSuccess) return nullptr;
+  if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
   if (hipMemset(p, 0, kScratchCounterBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-    (void)hipFree(p);
+    (void)hipFree(p);                       // never handed out: nothing can hold its address
     return nullptr;
   }
-  s.ptr = p;
+  s.ptr = p;                                // the previous buffer is retired, not freed
   s.bytes = want;
-  return p;
+  return (char*)p;
 }
 
 }  // namespace df
@@ -82,16 +87,8 @@ int df_buffer_refresh(void* dst_full, const void* src_patch, int B, long long fu
 int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out,
                        const float* gamma, const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N,
                        float eps, int stat_mode, int fuse_silu, int dtype, void* stream) {
-  if (!x_fresh || !y || !gamma || !beta || bad_dtype(dtype)) return DF_EINVAL;
-  if (stat_mode < DF_GN_SUMS || stat_mode > DF_GN_STALE) return DF_EINVAL;
-  if (B <= 0 || R <= 0 || W <= 0 || C <= 0 || G <= 0 || N <= 0 || patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
-  if ((N > 1 || stat_mode == DF_GN_STALE) && !stale_stats) return DF_EINVAL;
-  if (((uintptr_t)x_fresh % 16) || ((uintptr_t)y % 16)) return DF_EINVAL;
-  GnArgs a = {};
-  a.x = x_fresh; a.y = y; a.stale = stale_stats; a.sums_out = fresh_stats_out; a.gamma = gamma; a.beta = beta;
-  a.B = B; a.Rseg = R; a.W = W; a.C = C; a.G = G; a.nseg = 1; a.patch_idx = patch_idx; a.N = N; a.eps = eps;
-  a.stat_mode = stat_mode; a.silu = fuse_silu ? 1 : 0; a.in_dtype = dtype; a.out_dtype = dtype;
-  return launch_groupnorm(a, (hipStream_t)stream);
+  return groupnorm_entry(x_fresh, y, stale_stats, fresh_stats_out, gamma, beta, B, R, W, C, G, patch_idx, N, eps,
+                         stat_mode, fuse_silu, dtype, nullptr, (hipStream_t)stream);
 }
 
 int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,

@@ -703,7 +703,7 @@ __global__ __launch_bounds__(256) void attn_f32(AttnParams p) {
 // number of partials.  (Plain "at least 512 workgroups" picked 800 for the 1200-query level: 768 run at once and
 // the last 32 had the chip to themselves for a full workgroup lifetime, +35 %.)
 int pick_splits(int B, int Lq, int L, int heads) {
-  static const int forced = getenv("DF_ATTN_SPLITS") ? atoi(getenv("DF_ATTN_SPLITS")) : 0;   // tuning aid
+  static const int forced = tune_env("DF_ATTN_SPLITS") ? atoi(tune_env("DF_ATTN_SPLITS")) : 0;   // tuning aid
   if (forced > 0) return (L / forced >= 64) ? forced : 1;
   const long long blocks = (long long)cdiv(Lq, 128) * heads * B;
   int best = 1;
@@ -728,6 +728,7 @@ size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d) {
 
 int launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.B <= 0 || a.Lq <= 0 || a.L <= 0 || a.heads <= 0) return DF_ESHAPE;
+  if (!(a.scale > 0.f) || !(a.scale < INFINITY)) return DF_EINVAL;   // the kernels fold the scale into exp2 arguments
   const bool own_all = a.own_lo <= 0 && a.own_lo + a.own_n >= a.L;
   if (!own_all && (!a.k_stale || !a.v_stale)) return DF_EINVAL;
   AttnParams p = {};
@@ -755,11 +756,12 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   for (const void* q : ptrs) if ((uintptr_t)q % 16) return DF_EINVAL;
   int ns = pick_splits(a.B, a.Lq, a.L, a.heads);
   if ((long long)a.B * ns > 65535) return DF_ESHAPE;
+  if ((long long)a.B * a.heads * a.Lq * 16 >= (1LL << 31)) return DF_ESHAPE;   // the merge kernel indexes with 32 bits
   if (ns > 1) {
     const int kps = cdiv(cdiv(a.L, ns), 128) * 128;      // whole 128-key iterations of the two-group kernel
     ns = cdiv(a.L, kps);                                 // rounding up may leave the last ranges empty: drop them
     if (ns > 1) {
-      char* scr = (char*)scratch_get(attention_scratch_bytes(a.B, a.Lq, a.L, a.heads, a.d));
+      char* scr = scratch_region(a.scr, attention_scratch_bytes(a.B, a.Lq, a.L, a.heads, a.d));
       if (!scr) return DF_ENOMEM;
       p.nsplit = ns;
       p.keys_per_split = kps;
@@ -779,9 +781,9 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
     // launches keep one group and three stages (48 KB, three workgroups per unit), which is faster there (the
     // 480 x 480-latent share: 27.4 vs 31.5 ms of self-attention).  Deeper rings lose in both forms: the kernel is not
     // bound by the latency of the K / V^T stream.
-    static const int forced_st = getenv("DF_ATTN_STAGES") ? atoi(getenv("DF_ATTN_STAGES")) : 0;   // tuning aid
-    static const int forced_gr = getenv("DF_ATTN_GROUPS") ? atoi(getenv("DF_ATTN_GROUPS")) : 0;   // tuning aid
-    static const long long g2max = getenv("DF_ATTN_G2MAX") ? atoll(getenv("DF_ATTN_G2MAX")) : 600;   // tuning aid
+    static const int forced_st = tune_env("DF_ATTN_STAGES") ? atoi(tune_env("DF_ATTN_STAGES")) : 0;   // tuning aid
+    static const int forced_gr = tune_env("DF_ATTN_GROUPS") ? atoi(tune_env("DF_ATTN_GROUPS")) : 0;   // tuning aid
+    static const long long g2max = tune_env("DF_ATTN_G2MAX") ? atoll(tune_env("DF_ATTN_G2MAX")) : 600;   // tuning aid
     const int ngr = forced_gr ? forced_gr : (nwg <= g2max ? 2 : 1);
     const int nst = forced_st ? forced_st : (ngr == 2 ? 2 : 3);
 #define DF_ATTN_VT(NSTV, NGRV)                                                                                      \
@@ -807,7 +809,6 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   DF_LAUNCH_CHECK();
   if (ns > 1) {
     const long long n = (long long)a.B * a.heads * a.Lq * 16;
-    if (n >= (1LL << 31)) return DF_ESHAPE;                // the merge kernel indexes with 32 bits
     hipLaunchKernelGGL(attn_combine_d64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p);
     DF_LAUNCH_CHECK();
   }

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include "../../include/distrifusion.h"
 
 namespace df {
@@ -92,6 +93,14 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
   return v;
 }
+
+// Kernel-selection overrides from the environment (DF_TILE, DF_SPLITK, DF_ATTN_*, ...) exist only in builds with
+// -DDF_TUNING; in the library as shipped every choice is a function of the call's arguments alone.
+#ifdef DF_TUNING
+static inline const char* tune_env(const char* name) { return getenv(name); }
+#else
+static inline const char* tune_env(const char*) { return nullptr; }
+#endif
 
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 

@@ -59,6 +59,7 @@ struct TileParams {
   bf16_t* out2;
   long long ldo2;
   int vec_epi;    // every epilogue pointer / stride allows 16-byte (float) and 8-byte (bf16) accesses
+  const Scratch* scr;   // host side only: where split-K partials and the page of zeros live
 };
 
 template <int BM, int BN, bool kConv, typename OutT>
@@ -1082,7 +1083,7 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
   const size_t part_bytes = nsplit > 1 ? (size_t)nsplit * p.M * p.N * sizeof(float) : 0;
   char* scr = nullptr;
   if (kConv || nsplit > 1) {
-    scr = (char*)scratch_get(kScratchCounterBytes + part_bytes);
+    scr = scratch_region(p.scr, kScratchCounterBytes + part_bytes);
     if (!scr) return DF_ENOMEM;
   }
   const bf16_t* zeros = scr ? (const bf16_t*)(scr + kScratchZeroPageOffset) : nullptr;
@@ -1133,12 +1134,12 @@ int launch_pipe(const TileParams& p, int out_dtype, int nsplit, hipStream_t st) 
 // aid); with DF_TUNE set they are re-read on every launch.
 bool tune_mode() {
   static int v = -1;
-  if (v < 0) v = getenv("DF_TUNE") ? 1 : 0;
+  if (v < 0) v = tune_env("DF_TUNE") ? 1 : 0;
   return v == 1;
 }
 
 int parse_tile() {
-  const char* e = getenv("DF_TILE");
+  const char* e = tune_env("DF_TILE");
   int bm = 0, bn = 0, st = 4;
   if (e && sscanf(e, "%dx%dx%d", &bm, &bn, &st) >= 2) return (bm * 1000 + bn) * 10 + st;
   return 0;
@@ -1152,9 +1153,9 @@ int tile_override() {
 }
 
 int split_override() {
-  if (tune_mode()) { const char* e = getenv("DF_SPLITK"); return e ? atoi(e) : 0; }
+  if (tune_mode()) { const char* e = tune_env("DF_SPLITK"); return e ? atoi(e) : 0; }
   static int v = -1;
-  if (v < 0) { const char* e = getenv("DF_SPLITK"); v = e ? atoi(e) : 0; }
+  if (v < 0) { const char* e = tune_env("DF_SPLITK"); v = e ? atoi(e) : 0; }
   return v;
 }
 
@@ -1243,6 +1244,7 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
   TileParams p = {};
   p.A = (const bf16_t*)a.A; p.Wt = (const bf16_t*)a.W; p.bias = a.bias; p.residual = a.residual; p.out = a.out;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldw = a.ldw; p.ldr = a.ldr; p.ldo = a.ldo; p.act = a.act;
+  p.scr = a.scr;
   const bool special = a.packed_w || a.ln_s || a.out2;
   if (special) {
     if (a.K % 64 || a.K < 128) return DF_ESHAPE;
@@ -1287,7 +1289,7 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
     p.A = (const bf16_t*)a.x; p.Wt = (const bf16_t*)a.w; p.bias = a.bias; p.residual = a.residual;
     p.chan_add = a.chan_add; p.chan_ld = a.chan_ld ? a.chan_ld : a.Cout; p.out = a.y;
     p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin; p.lda = 0; p.ldw = 9LL * a.Cin; p.ldr = a.Cout; p.ldo = a.Cout;
-    p.act = a.act;
+    p.act = a.act; p.scr = a.scr;
     p.top = (const bf16_t*)a.halo_top; p.bot = (const bf16_t*)a.halo_bot; p.halo_bs = a.halo_bstride;
     p.R = a.R; p.W = a.W; p.Cin = a.Cin; p.Ro = Ro; p.Wo = Wo; p.stride = a.stride;
     return pick_tile<true>(p, a.out_dtype, st);

@@ -11,6 +11,12 @@
 //                x comes from L2 / Infinity Cache at the sizes of one patch.
 // A lane keeps a fixed channel offset for its whole strip, so gamma/beta and
 // the statistics are fetched once per lane.
+//
+// Numerics: sums are taken of x - p, p being the group's first value of the batch
+// item (its "pivot"), and turned into the sums of x in double only where a group's
+// totals are known: E[x^2] - E[x]^2 of float sums loses (mean / sigma)^2 ulps, which
+// a tensor whose mean is far from zero cannot afford at float32 tolerance.  The
+// normalisation subtracts the mean as a (high, low) float pair before scaling.
 #include <cstdlib>
 #include "kernels.h"
 
@@ -85,15 +91,18 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
   const int p_lo = blk * pix_per_blk;
   int p_hi = p_lo + pix_per_blk;
   if (p_hi > pix_seg) p_hi = pix_seg;
-  float s[V], q[V];
+  float s[V], q[V], piv[V];
 #pragma unroll
-  for (int i = 0; i < V; ++i) { s[i] = 0.f; q[i] = 0.f; }
+  for (int i = 0; i < V; ++i) {
+    s[i] = 0.f; q[i] = 0.f;
+    piv[i] = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + ((c0 + i) / cg) * cg);   // the group's pivot
+  }
 #pragma unroll 4
   for (int p = p_lo + psub; p < p_hi; p += ppb) {
     float v[V];
     ld_vec(x + (seg_base + p) * C + c0, v);
 #pragma unroll
-    for (int i = 0; i < V; ++i) { s[i] += v[i]; q[i] = fmaf(v[i], v[i], q[i]); }
+    for (int i = 0; i < V; ++i) { const float d = v[i] - piv[i]; s[i] += d; q[i] = fmaf(d, d, q[i]); }
   }
   // Ordered fold of the lanes' per-channel sums into groups (no atomics: the result must not depend on timing -
   // the UNet amplifies even one-ulp differences of a statistic to the level of its bf16 rounding noise).
@@ -122,42 +131,57 @@ __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial,
   if (tid < G) { my[2 * tid] = s_sum[tid]; my[2 * tid + 1] = s_sq[tid]; }
 }
 
-// Mean and variance of one (batch item, group) from the fresh sums of this launch and the cached per-patch sums,
-// according to the statistic mode (Section 4, Eq. 2; Section 5.3).
-// `st_*`: sums of the cached entries of the other patches, `own_*`: the cached entry of this patch.
-__device__ __forceinline__ void gn_combine_pre(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
-                                               float st_s, float st_q, float own_s, float own_q, float& mean,
-                                               float& var) {
-  if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
-    // the whole image is fresh: exact statistics
-    const float n = n_loc * (float)nseg;
-    mean = tot_s / n;
-    var = fmaxf(tot_q / n - mean * mean, 0.f);
-    return;
-  }
-  const float n_glob = n_loc * (float)N;
-  const float loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
-  if (stat_mode == DF_GN_SUMS) {
-    mean = (tot_s + st_s) / n_glob;
-    var = fmaxf((tot_q + st_q) / n_glob - mean * mean, 0.f);
-  } else if (stat_mode == DF_GN_EQ2) {
-    mean = (st_s + own_s) / n_glob + (loc_m - own_s / n_loc);
-    const float m2 = (st_q + own_q) / n_glob + (loc_m2 - own_q / n_loc);
-    var = m2 - mean * mean;
-    if (var < 0.f) var = loc_m2 - loc_m * loc_m;
-  } else if (stat_mode == DF_GN_SEPARATE) {
-    mean = loc_m;
-    var = fmaxf(loc_m2 - loc_m * loc_m, 0.f);
-  } else {
-    mean = (st_s + own_s) / n_glob;
-    var = fmaxf((st_q + own_q) / n_glob - mean * mean, 0.f);
-  }
+// Sums of x from the sums of x - piv over n values (double: this is where the cancellation would happen).
+__device__ __forceinline__ void gn_unshift(float s, float q, double n, float piv, double& S, double& SS) {
+  const double p = (double)piv;
+  S = (double)s + n * p;
+  SS = (double)q + 2.0 * p * (double)s + n * p * p;
 }
 
-__device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc, int nseg, int N, int stat_mode,
-                                           const float* __restrict__ stale, int b, int g, int B, int G, int patch_idx,
-                                           float& mean, float& var) {
-  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+struct GnMoments { float mean_hi, mean_lo, rstd; };
+
+// Mean and variance of one (batch item, group) from the fresh sums of this launch and the cached per-patch sums,
+// according to the statistic mode (Section 4, Eq. 2; Section 5.3).  Runs once per group, in double.
+// `st_*`: sums of the cached entries of the other patches, `own_*`: the cached entry of this patch.
+__device__ __forceinline__ GnMoments gn_combine_pre(double tot_s, double tot_q, double n_loc, int nseg, int N,
+                                                    int stat_mode, double st_s, double st_q, double own_s,
+                                                    double own_q, float eps) {
+  double mean, var;
+  if (nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE)) {
+    // the whole image is fresh: exact statistics
+    const double n = n_loc * (double)nseg;
+    mean = tot_s / n;
+    var = fmax(tot_q / n - mean * mean, 0.0);
+  } else {
+    const double n_glob = n_loc * (double)N;
+    const double loc_m = tot_s / n_loc, loc_m2 = tot_q / n_loc;
+    if (stat_mode == DF_GN_SUMS) {
+      mean = (tot_s + st_s) / n_glob;
+      var = fmax((tot_q + st_q) / n_glob - mean * mean, 0.0);
+    } else if (stat_mode == DF_GN_EQ2) {
+      mean = (st_s + own_s) / n_glob + (loc_m - own_s / n_loc);
+      const double m2 = (st_q + own_q) / n_glob + (loc_m2 - own_q / n_loc);
+      var = m2 - mean * mean;
+      if (var < 0.0) var = loc_m2 - loc_m * loc_m;
+    } else if (stat_mode == DF_GN_SEPARATE) {
+      mean = loc_m;
+      var = fmax(loc_m2 - loc_m * loc_m, 0.0);
+    } else {
+      mean = (st_s + own_s) / n_glob;
+      var = fmax((st_q + own_q) / n_glob - mean * mean, 0.0);
+    }
+  }
+  GnMoments m;
+  m.mean_hi = (float)mean;
+  m.mean_lo = (float)(mean - (double)m.mean_hi);
+  m.rstd = (float)(1.0 / sqrt(var + (double)eps));
+  return m;
+}
+
+__device__ __forceinline__ GnMoments gn_combine(double tot_s, double tot_q, double n_loc, int nseg, int N, int stat_mode,
+                                                const float* stale, int b, int g, int B, int G, int patch_idx,
+                                                float eps) {
+  double st_s = 0.0, st_q = 0.0, own_s = 0.0, own_q = 0.0;
   if (!(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE))) {
     for (int j = 0; j < N; ++j) {
       const float* sp = stale + (((long long)j * B + b) * G + g) * 2;
@@ -165,15 +189,15 @@ __device__ __forceinline__ void gn_combine(float tot_s, float tot_q, float n_loc
       if (j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
     }
   }
-  gn_combine_pre(tot_s, tot_q, n_loc, nseg, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
+  return gn_combine_pre(tot_s, tot_q, n_loc, nseg, N, stat_mode, st_s, st_q, own_s, own_q, eps);
 }
 
 // The cached sums of one (batch item, group) gathered by a whole wave: lane j fetches patch j's entry (one memory
 // round trip for all patches instead of a chain of N), lane order fixes the order of the additions.
-__device__ __forceinline__ void gn_stale_wave(const float* __restrict__ stale, int b, int g, int B, int G, int N,
-                                              int patch_idx, int lane, float& st_s, float& st_q, float& own_s,
-                                              float& own_q) {
-  st_s = st_q = own_s = own_q = 0.f;
+__device__ __forceinline__ void gn_stale_wave(const float* stale, int b, int g, int B, int G, int N,
+                                              int patch_idx, int lane, double& st_s, double& st_q, double& own_s,
+                                              double& own_q) {
+  st_s = st_q = own_s = own_q = 0.0;
   if (stale == nullptr) return;
   for (int j0 = 0; j0 < N; j0 += 64) {
     float a = 0.f, c = 0.f;
@@ -192,8 +216,9 @@ __device__ __forceinline__ void gn_stale_wave(const float* __restrict__ stale, i
 // One workgroup per batch item: adds the partials in a fixed order, emits the fresh per-patch sums, combines them with
 // the stale sums of the other patches according to the statistic mode and stores mean / rstd.  A separate launch
 // instead of a "last workgroup" epilogue: the device-scope fences that pattern needs cost more than the launch.
+template <typename Tin>
 __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ partial, float* __restrict__ meanrstd,
-                                                    const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                    const float* stale, float* sums_out, const Tin* __restrict__ x,
                                                     int pix_seg, int C, int G, int nblk, int nseg, int B, int patch_idx,
                                                     int N, float eps, int stat_mode) {
   __shared__ float s_red[2][32][kMaxG];
@@ -202,7 +227,10 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
   const int cg = C / G;
   const int parts = blockDim.x / G < 32 ? blockDim.x / G : 32;
   const int g = tid % G, part = tid / G;
-  float tot_s = 0.f, tot_q = 0.f;  // over all segments (valid on part == 0 lanes)
+  double tot_s = 0.0, tot_q = 0.0;  // sums of x over all segments (valid on part == 0 lanes)
+  // the partials are sums of x - pivot, the pivot being the group's first value of the batch item
+  const float piv = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + g * cg);
+  const double n_seg = (double)pix_seg * (double)cg;
   for (int sg = 0; sg < nseg; ++sg) {
     float a = 0.f, c = 0.f;
     if (part < parts) {
@@ -225,10 +253,12 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
     if (part == 0) {
       float fs = 0.f, fq = 0.f;
       for (int k = 0; k < parts; ++k) { fs += s_red[0][k][g]; fq += s_red[1][k][g]; }
-      tot_s += fs; tot_q += fq;
+      double S, SS;
+      gn_unshift(fs, fq, n_seg, piv, S, SS);
+      tot_s += S; tot_q += SS;
       if (nseg > 1) {
         float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
-        o[0] = fs; o[1] = fq;
+        o[0] = (float)S; o[1] = (float)SS;
       }
     }
     __syncthreads();
@@ -236,7 +266,7 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
   // the cached sums of the other patches: thread (part, g) fetches patch part's entry of group g (one round trip for
   // all patches), thread (0, g) adds them in patch order
   const bool need_stale = !(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE));
-  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  double st_s = 0.0, st_q = 0.0, own_s = 0.0, own_q = 0.0;
   if (need_stale) {
     for (int j0 = 0; j0 < N; j0 += parts) {
       __syncthreads();
@@ -256,15 +286,13 @@ __global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ pa
     }
   }
   if (part != 0) return;
-  float mean, var;
-  gn_combine_pre(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
+  const GnMoments mo = gn_combine_pre(tot_s, tot_q, n_seg, nseg, N, stat_mode, st_s, st_q, own_s, own_q, eps);
   if (nseg == 1 && sums_out != nullptr) {  // written after the stale sums were read: may alias the own slot
     float* o = sums_out + ((long long)b * G + g) * 2;
-    o[0] = tot_s; o[1] = tot_q;
+    o[0] = (float)tot_s; o[1] = (float)tot_q;
   }
-  float* mr = meanrstd + ((long long)b * G + g) * 2;
-  mr[0] = mean;
-  mr[1] = 1.0f / sqrtf(var + eps);
+  float* mr = meanrstd + ((long long)b * G + g) * 4;
+  mr[0] = mo.mean_hi; mr[1] = mo.mean_lo; mr[2] = mo.rstd;
 }
 
 template <typename Tin, typename Tout>
@@ -277,15 +305,15 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
   const int c0 = (tid % tp) * V;
   const int psub = tid / tp;
   const int cg = C / G;
-  float sc[V], sh[V];
+  float sc[V], sh[V], mh[V], ml[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     const int c = c0 + i;
     const int g = c / cg;
-    const float mean = meanrstd[((long long)b * G + g) * 2];
-    const float rstd = meanrstd[((long long)b * G + g) * 2 + 1];
-    sc[i] = rstd * gamma[c];
-    sh[i] = beta[c] - mean * sc[i];
+    const float* mr = meanrstd + ((long long)b * G + g) * 4;
+    mh[i] = mr[0]; ml[i] = mr[1];
+    sc[i] = mr[2] * gamma[c];
+    sh[i] = beta[c];
   }
   const long long base = (long long)b * pix_b;
   const int p_lo = blockIdx.x * pix_per_blk;
@@ -296,7 +324,7 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
     ld_vec(x + (base + p) * C + c0, v);
 #pragma unroll
     for (int i = 0; i < V; ++i) {
-      float t = fmaf(v[i], sc[i], sh[i]);
+      float t = fmaf((v[i] - mh[i]) - ml[i], sc[i], sh[i]);
       v[i] = silu ? silu_f(t) : t;
     }
     Tout* o = y + (base + p) * C + c0;
@@ -323,12 +351,12 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
 // normalisation on a second read that hits L2.  Groups are independent, so no workgroup waits for another.
 template <typename Tin, typename Tout>
 __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ x, Tout* __restrict__ y,
-                                                        const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                        const float* stale, float* sums_out,
                                                         const float* __restrict__ gamma, const float* __restrict__ beta,
                                                         int pix_seg, int C, int G, int nseg, int B, int patch_idx, int N,
                                                         float eps, int stat_mode, int silu, int packed, GnHalo halo) {
   __shared__ float s_s[1024], s_q[1024];
-  __shared__ float s_mr[2];
+  __shared__ float s_mr[3];
   const int g = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63;
   const int cg = C / G, cgv = cg >> 2;              // channel vectors of 4 per group
@@ -336,7 +364,9 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
   const int cv = tid % cgv, psub = tid / cgv;
   const bool active = psub < ppass;
   const int c0 = g * cg + cv * 4;
-  float tot_s = 0.f, tot_q = 0.f;
+  const float piv = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + g * cg);   // sums are taken of x - piv
+  const double n_seg = (double)pix_seg * (double)cg;
+  double tot_s = 0.0, tot_q = 0.0;
   for (int sg = 0; sg < nseg; ++sg) {
     const long long base = ((long long)b * nseg + sg) * pix_seg;
     float a = 0.f, q = 0.f;
@@ -352,7 +382,7 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
           v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { a += v[i]; q = fmaf(v[i], v[i], q); }
+        for (int i = 0; i < 4; ++i) { const float d = v[i] - piv; a += d; q = fmaf(d, d, q); }
       }
     s_s[tid] = a; s_q[tid] = q;
     __syncthreads();
@@ -360,32 +390,32 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
       float fs = 0.f, fq = 0.f;
       for (int k = lane; k < (int)blockDim.x; k += 64) { fs += s_s[k]; fq += s_q[k]; }
       fs = wave_sum(fs); fq = wave_sum(fq);
-      tot_s += fs; tot_q += fq;
+      double S, SS;
+      gn_unshift(fs, fq, n_seg, piv, S, SS);
+      tot_s += S; tot_q += SS;
       if (nseg > 1 && lane == 0) {
         float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
-        o[0] = fs; o[1] = fq;
+        o[0] = (float)S; o[1] = (float)SS;
       }
     }
     __syncthreads();
   }
   if (tid == 0) {
-    float mean, var;
-    gn_combine(tot_s, tot_q, (float)pix_seg * (float)cg, nseg, N, stat_mode, stale, b, g, B, G, patch_idx, mean, var);
+    const GnMoments mo = gn_combine(tot_s, tot_q, n_seg, nseg, N, stat_mode, stale, b, g, B, G, patch_idx, eps);
     if (nseg == 1 && sums_out != nullptr) {          // after the stale sums were read: may alias the own slot
       float* o = sums_out + ((long long)b * G + g) * 2;
-      o[0] = tot_s; o[1] = tot_q;
+      o[0] = (float)tot_s; o[1] = (float)tot_q;
     }
-    s_mr[0] = mean;
-    s_mr[1] = 1.0f / sqrtf(var + eps);
+    s_mr[0] = mo.mean_hi; s_mr[1] = mo.mean_lo; s_mr[2] = mo.rstd;
   }
   __syncthreads();
   if (!active) return;
-  const float mean = s_mr[0], rstd = s_mr[1];
+  const float mean = s_mr[0], mean_lo = s_mr[1], rstd = s_mr[2];
   float sc[4], sh[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     sc[i] = rstd * gamma[c0 + i];
-    sh[i] = beta[c0 + i] - mean * sc[i];
+    sh[i] = beta[c0 + i];
   }
   const long long pix_b = (long long)pix_seg * nseg;
   const long long base = (long long)b * pix_b;
@@ -401,7 +431,7 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float t = fmaf(v[i], sc[i], sh[i]);
+      const float t = fmaf((v[i] - mean) - mean_lo, sc[i], sh[i]);
       v[i] = silu ? silu_f(t) : t;
     }
     const long long m = base + p;
@@ -422,12 +452,12 @@ __global__ __launch_bounds__(1024) void gn_group_kernel(const Tin* __restrict__ 
 // once.
 template <typename Tin, typename Tout, int NV>
 __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restrict__ x, Tout* __restrict__ y,
-                                                            const float* __restrict__ stale, float* __restrict__ sums_out,
+                                                            const float* stale, float* sums_out,
                                                             const float* __restrict__ gamma, const float* __restrict__ beta,
                                                             int pix, int C, int G, int B, int patch_idx, int N, float eps,
                                                             int stat_mode, int silu, int packed, GnHalo halo) {
   __shared__ float s_s[1024], s_q[1024];
-  __shared__ float s_mr[2];
+  __shared__ float s_mr[3];
   const int g = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63;
   const int cg = C / G, cgv = cg >> 2;
@@ -436,10 +466,11 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
   const bool active = psub < ppass;
   const int c0 = g * cg + cv * 4;
   const long long base = (long long)b * pix;
+  const float piv = Elem<Tin>::ld(x + base * C + g * cg);     // sums are taken of x - piv
   // everything that does not depend on x is requested first: affine parameters and the cached sums
   float gm[4] = {0.f, 0.f, 0.f, 0.f}, bt[4] = {0.f, 0.f, 0.f, 0.f};
   if (active) { ld_vec(gamma + c0, gm); ld_vec(beta + c0, bt); }
-  float st_s = 0.f, st_q = 0.f, own_s = 0.f, own_q = 0.f;
+  double st_s = 0.0, st_q = 0.0, own_s = 0.0, own_q = 0.0;
   if (tid < 64)
     gn_stale_wave((N == 1 && stat_mode != DF_GN_STALE) ? nullptr : stale, b, g, B, G, N, patch_idx, lane, st_s, st_q,
                   own_s, own_q);
@@ -462,9 +493,11 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
     }
   }
 #pragma unroll
-  for (int k = 0; k < NV; ++k)
+  for (int k = 0; k < NV; ++k) {
+    if (!(active && psub + k * ppass < pix)) continue;          // absent pixels hold zeros, not the pivot
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { a += v[k][i]; q = fmaf(v[k][i], v[k][i], q); }
+    for (int i = 0; i < 4; ++i) { const float d = v[k][i] - piv; a += d; q = fmaf(d, d, q); }
+  }
   s_s[tid] = a; s_q[tid] = q;
   __syncthreads();
   if (tid < 64) {
@@ -472,24 +505,25 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
     for (int k = lane; k < (int)blockDim.x; k += 64) { fs += s_s[k]; fq += s_q[k]; }
     fs = wave_sum(fs); fq = wave_sum(fq);
     if (tid == 0) {
-      float mean, var;
-      gn_combine_pre(fs, fq, (float)pix * (float)cg, 1, N, stat_mode, st_s, st_q, own_s, own_q, mean, var);
+      const double n_loc = (double)pix * (double)cg;
+      double S, SS;
+      gn_unshift(fs, fq, n_loc, piv, S, SS);
+      const GnMoments mo = gn_combine_pre(S, SS, n_loc, 1, N, stat_mode, st_s, st_q, own_s, own_q, eps);
       if (sums_out != nullptr) {                     // after the stale sums were read: may alias the own slot
         float* o = sums_out + ((long long)b * G + g) * 2;
-        o[0] = fs; o[1] = fq;
+        o[0] = (float)S; o[1] = (float)SS;
       }
-      s_mr[0] = mean;
-      s_mr[1] = 1.0f / sqrtf(var + eps);
+      s_mr[0] = mo.mean_hi; s_mr[1] = mo.mean_lo; s_mr[2] = mo.rstd;
     }
   }
   __syncthreads();
   if (!active) return;
-  const float mean = s_mr[0], rstd = s_mr[1];
+  const float mean = s_mr[0], mean_lo = s_mr[1], rstd = s_mr[2];
   float sc[4], sh[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     sc[i] = rstd * gm[i];
-    sh[i] = bt[i] - mean * sc[i];
+    sh[i] = bt[i];
   }
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
@@ -498,7 +532,7 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
     float o4[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float t = fmaf(v[k][i], sc[i], sh[i]);
+      const float t = fmaf((v[k][i] - mean) - mean_lo, sc[i], sh[i]);
       o4[i] = silu ? silu_f(t) : t;
     }
     const long long m = base + p;
@@ -533,7 +567,7 @@ GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_thr
 
 size_t groupnorm_scratch_bytes(int B, int nseg, int G) {
   // partials for at most 2048 blocks per batch item + mean/rstd
-  return kScratchCounterBytes + ((size_t)B * 2048 * G * 2 + (size_t)B * G * 2) * sizeof(float) + 1024;
+  return kScratchCounterBytes + ((size_t)B * 2048 * G * 2 + (size_t)B * G * 4) * sizeof(float) + 1024;
 }
 
 int launch_groupnorm(const GnArgs& a, hipStream_t st) {
@@ -557,7 +591,7 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   {
     const int cg = a.C / a.G;
     const long long per_group = pix_seg * a.nseg * cg;
-    static const bool no_fused = getenv("DF_GN_3K") != nullptr;   // tuning aid
+    static const bool no_fused = tune_env("DF_GN_3K") != nullptr;   // tuning aid
     if (!no_fused && cg % 4 == 0 && cg / 4 <= 1024 && per_group <= kGnGroupMaxElems) {
       dim3 grid(a.G, a.B);
       const int ppass = 1024 / (cg / 4);
@@ -592,10 +626,10 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   GnLayout L = gn_layout(a.C, vec, pix_seg, target, 256);
   if ((long long)L.nblk * a.nseg > 2048) return DF_ESHAPE;
   if (L.threads < a.G) return DF_ESHAPE;
-  char* scr = (char*)scratch_get(groupnorm_scratch_bytes(a.B, a.nseg, a.G));
+  char* scr = scratch_region(a.scr, groupnorm_scratch_bytes(a.B, a.nseg, a.G));
   if (!scr) return DF_ENOMEM;
   float* meanrstd = (float*)(scr + kScratchCounterBytes);
-  float* partial = meanrstd + (size_t)a.B * a.G * 2;
+  float* partial = meanrstd + (size_t)a.B * a.G * 4;
   dim3 gs(L.nblk, a.nseg, a.B);
   if (a.in_dtype == DF_BF16)
     hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), (size_t)2 * 8 * L.threads * sizeof(float), st, (const bf16_t*)a.x, partial, (int)pix_seg, a.C, a.G,
@@ -604,8 +638,12 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), (size_t)2 * 4 * L.threads * sizeof(float), st, (const float*)a.x, partial, (int)pix_seg, a.C, a.G,
                        L.tp, L.ppb, L.pix_per_blk, a.nseg);
   DF_LAUNCH_CHECK();
-  hipLaunchKernelGGL(gn_finalize, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out, (int)pix_seg, a.C,
-                     a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
+  if (a.in_dtype == DF_BF16)
+    hipLaunchKernelGGL(gn_finalize<bf16_t>, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out,
+                       (const bf16_t*)a.x, (int)pix_seg, a.C, a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
+  else
+    hipLaunchKernelGGL(gn_finalize<float>, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out,
+                       (const float*)a.x, (int)pix_seg, a.C, a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
   DF_LAUNCH_CHECK();
   const long long pix_b = pix_seg * a.nseg;
   GnLayout A = gn_layout(a.C, vec, pix_b, 2048, 256);
@@ -622,6 +660,23 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   }
   DF_LAUNCH_CHECK();
   return DF_OK;
+}
+
+// Argument validation shared by the two GroupNorm entry points of the C ABI.
+int groupnorm_entry(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out, const float* gamma,
+                    const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N, float eps, int stat_mode,
+                    int fuse_silu, int dtype, const Scratch* scr, hipStream_t st) {
+  if (!x_fresh || !y || !gamma || !beta || (dtype != DF_F32 && dtype != DF_BF16)) return DF_EINVAL;
+  if (stat_mode < DF_GN_SUMS || stat_mode > DF_GN_STALE) return DF_EINVAL;
+  if (B <= 0 || R <= 0 || W <= 0 || C <= 0 || G <= 0 || N <= 0 || patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  if ((N > 1 || stat_mode == DF_GN_STALE) && !stale_stats) return DF_EINVAL;
+  if (((uintptr_t)x_fresh % 16) || ((uintptr_t)y % 16)) return DF_EINVAL;
+  GnArgs a = {};
+  a.x = x_fresh; a.y = y; a.stale = stale_stats; a.sums_out = fresh_stats_out; a.gamma = gamma; a.beta = beta;
+  a.B = B; a.Rseg = R; a.W = W; a.C = C; a.G = G; a.nseg = 1; a.patch_idx = patch_idx; a.N = N; a.eps = eps;
+  a.stat_mode = stat_mode; a.silu = fuse_silu ? 1 : 0; a.in_dtype = dtype; a.out_dtype = dtype;
+  a.scr = scr;
+  return launch_groupnorm(a, st);
 }
 
 }  // namespace df

@@ -6,14 +6,27 @@
 
 namespace df {
 
-// ---- device scratch owned by the library (one per device, grown on demand) ----
-// Returns a 256-byte aligned device buffer of at least `bytes`, or nullptr.
-// The first 16 KiB are reserved: [0, 8 KiB) counters that every kernel leaves at zero,
-// [8 KiB, 16 KiB) a page of zeros nobody writes (source of the convolution's zero padding).
-void* scratch_get(size_t bytes);
+// ---- device scratch ----
+// Kernels that need device memory beyond their inputs and outputs (GroupNorm partial sums, split-K and split-key
+// partials, the page of zeros behind the convolution's padding) take it from a Scratch region.  A UNet plan carves
+// its region out of the caller's workspace, so the graphs it records only ever hold plan-owned addresses; the
+// per-operation entry points use one region per device that the library allocates on first use.  That region is
+// never freed or moved while the process lives: a larger request allocates a further buffer and the old one stays
+// valid for anything that still holds its address.
+// The first 16 KiB of a region are reserved: [0, 8 KiB) counters that every kernel leaves at zero,
+// [8 KiB, 16 KiB) a page of zeros nobody writes.
+struct Scratch {
+  char* ptr;
+  size_t bytes;
+};
 constexpr size_t kScratchCounterBytes = 16384;
 constexpr size_t kScratchZeroPageOffset = 8192;
 constexpr int kScratchNumCounters = 2048;
+// Region of at least `bytes` for a launch: `given` if non-null (nullptr result if it is too small), else the
+// library's per-device region.  Returns nullptr on failure.
+char* scratch_region(const Scratch* given, size_t bytes);
+// Zeroes the reserved head of a caller-provided region (synchronous; used once when a plan is created).
+int scratch_init(const Scratch& s);
 
 // ---- refresh.hip ----
 int launch_copy_rows(void* dst, const void* src, long long rows, long long row_bytes, long long dst_stride_bytes,
@@ -39,8 +52,13 @@ struct GnArgs {
   void* halo_out;
   int halo_rpp, halo_patch0, halo_npatch;
   int y_packed;         // bf16 output in the fragment-packed layout of wgemm.hip (rows = B*rows*W pixels, K = C)
+  const Scratch* scr;   // scratch region of the caller (a plan's), or nullptr: the library's per-device region
 };
 int launch_groupnorm(const GnArgs& a, hipStream_t st);
+// df_groupnorm_stale's arguments, validated and launched with the given scratch region (nullptr: the library's)
+int groupnorm_entry(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out, const float* gamma,
+                    const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N, float eps, int stat_mode,
+                    int fuse_silu, int dtype, const Scratch* scr, hipStream_t st);
 size_t groupnorm_scratch_bytes(int B, int nseg, int G);
 
 // ---- conv.hip / gemm ----
@@ -58,6 +76,7 @@ struct ConvArgs {
   int B, R, W, Cin, Cout, stride, act;
   int dtype;             // of x, halos and w
   int out_dtype;
+  const Scratch* scr;    // see GnArgs
 };
 int launch_conv3x3(const ConvArgs& a, hipStream_t st);
 
@@ -96,6 +115,7 @@ struct GemmArgs {
   // optional second output: the same values rounded to bf16, [M, N] with row stride ldo2 (plain outputs only)
   void* out2;
   long long ldo2;
+  const Scratch* scr;     // see GnArgs
 };
 int launch_gemm_bf16(const GemmArgs& a, hipStream_t st);
 // Weight re-layout for the pipelined kernel: 64x64 tiles [N/64][K/64][64][64] with the LDS swizzle baked in, optionally
@@ -169,6 +189,7 @@ struct AttnArgs {
   // bsvs) and every key is read from k_stale / v_stale (own_n must be 0; k_fresh / v_fresh are ignored); bf16, d = 64
   int v_transposed;
   long long vt_ld;
+  const Scratch* scr;   // see GnArgs
 };
 int launch_attention(const AttnArgs& a, hipStream_t st);
 size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d);

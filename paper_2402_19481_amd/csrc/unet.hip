@@ -185,7 +185,7 @@ inline bool fold_ok(int C) { return C % 64 == 0 && C >= 128; }
 // step on the whole image) the workgroup-tiled kernels, whose operand traffic per flop is lower.
 constexpr int kFragMaxRows = 2048;
 inline bool frag_path() {
-  static const bool off = getenv("DF_NO_FRAG") != nullptr;   // tuning aid
+  static const bool off = tune_env("DF_NO_FRAG") != nullptr;   // tuning aid
   return !off;
 }
 
@@ -208,21 +208,33 @@ inline int emb_total(const std::vector<BlockDesc>& blocks) {
 enum { PC_GEMM = 0, PC_CONV, PC_SELF_ATTN, PC_CROSS_ATTN, PC_GROUPNORM, PC_REFRESH, PC_LAYERNORM, PC_ELEMENTWISE, PC_COUNT };
 static const char* const kProfNames[PC_COUNT] = {"gemm", "conv3x3", "self_attn", "cross_attn", "groupnorm", "refresh",
                                                  "layernorm", "elementwise"};
-struct ProfRec { int cls; double flops, bytes; };
+struct ProfRec { int cls; double flops, bytes; int kernel; };
+// totals of one kernel = one operation at one shape (the launches that share a label run the same kernel
+// instantiation with the same grid)
+struct ProfKernel { std::string label; int cls; double ms, flops, bytes; long long launches; };
 struct Prof {
   bool on = false;
   std::vector<hipEvent_t> pool;
   std::vector<ProfRec> recs;       // launch k uses events 2k, 2k+1
   double ms[PC_COUNT] = {}, flops[PC_COUNT] = {}, bytes[PC_COUNT] = {};
   long long launches[PC_COUNT] = {};
-  bool begin(int cls, double fl, double by, hipStream_t st) {
+  std::vector<ProfKernel> kernels;
+  std::map<std::string, int> kernel_idx;
+  int kernel_of(const std::string& label, int cls) {
+    auto it = kernel_idx.find(label);
+    if (it != kernel_idx.end()) return it->second;
+    kernels.push_back({label, cls, 0.0, 0.0, 0.0, 0});
+    kernel_idx[label] = (int)kernels.size() - 1;
+    return (int)kernels.size() - 1;
+  }
+  bool begin(int cls, double fl, double by, hipStream_t st, const std::string& label) {
     const size_t k = recs.size();
     while (pool.size() < 2 * k + 2) {
       hipEvent_t e;
       if (hipEventCreate(&e) != hipSuccess) return false;
       pool.push_back(e);
     }
-    recs.push_back({cls, fl, by});
+    recs.push_back({cls, fl, by, kernel_of(label.empty() ? std::string(kProfNames[cls]) : label, cls)});
     return hipEventRecord(pool[2 * k], st) == hipSuccess;
   }
   bool end(hipStream_t st) { return hipEventRecord(pool[2 * recs.size() - 1], st) == hipSuccess; }
@@ -232,6 +244,8 @@ struct Prof {
       if (hipEventElapsedTime(&t, pool[2 * k], pool[2 * k + 1]) != hipSuccess) return false;
       const ProfRec& r = recs[k];
       ms[r.cls] += t; flops[r.cls] += r.flops; bytes[r.cls] += r.bytes; launches[r.cls] += 1;
+      ProfKernel& pk = kernels[r.kernel];
+      pk.ms += t; pk.flops += r.flops; pk.bytes += r.bytes; pk.launches += 1;
     }
     recs.clear();
     return true;
@@ -239,6 +253,8 @@ struct Prof {
   void reset() {
     for (int i = 0; i < PC_COUNT; ++i) { ms[i] = flops[i] = bytes[i] = 0; launches[i] = 0; }
     recs.clear();
+    kernels.clear();
+    kernel_idx.clear();
   }
   ~Prof() { for (hipEvent_t e : pool) (void)hipEventDestroy(e); }
 };
@@ -259,7 +275,7 @@ struct GraphEntry {
   void* stale;
   hipStream_t stream;
   int calls = 0;                 // eager calls seen with this key (the first one stays eager: it may still set
-                                 // function attributes or grow the scratch, which must not happen under capture)
+                                 // function attributes, which must not happen under capture)
   hipGraphExec_t exec = nullptr;
 };
 
@@ -284,6 +300,9 @@ struct df_unet {
   int kv_count[4] = {0, 0, 0, 0};
   size_t packed_bytes = 0;
   size_t emb_w_off = 0, emb_b_off = 0;   // concatenated conditioning-projection weights / biases
+  // scratch region of the step's kernels (GroupNorm partials, split-K / split-key partials, the page of zeros): part
+  // of the caller's workspace, right after the plan-owned weights, so recorded graphs hold plan-owned addresses only
+  Scratch scr = {nullptr, 0};
 };
 
 namespace {
@@ -309,6 +328,7 @@ struct Exec {
   Prof* prof = nullptr;
   const std::map<std::string, PackedW>* packed = nullptr;
   int gn_mode = DF_GN_SUMS;      // GroupNorm statistic mode of a DISPLACED step
+  const Scratch* scr = nullptr;  // the plan's scratch region
   const bf16_t* kv_packed[4] = {nullptr, nullptr, nullptr, nullptr};
   int kv_count[4] = {0, 0, 0, 0};
   int kv_cursor[4] = {0, 0, 0, 0};
@@ -320,11 +340,18 @@ struct Exec {
   int emb_n = 0, emb_cursor = 0;
 
   // run a launch, accounted to class `cls` when per-launch timing is on
+  std::string label;             // name of the next timed launch in the per-kernel totals (consumed by timed())
+  static std::string dims(std::initializer_list<long long> v) {
+    std::string o;
+    for (long long d : v) { if (!o.empty()) o += "x"; o += std::to_string(d); }
+    return o;
+  }
   template <typename F>
   void timed(int cls, double fl, double by, F&& launch) {
-    if (!live()) return;
+    if (!live()) { label.clear(); return; }
     const bool p = prof && prof->on;
-    if (p && !prof->begin(cls, fl, by, st)) { err = DF_EHIP; return; }
+    if (p && !prof->begin(cls, fl, by, st, label)) { err = DF_EHIP; return; }
+    label.clear();
     run(launch());
     if (p && !prof->end(st)) err = DF_EHIP;
   }
@@ -384,7 +411,7 @@ struct Exec {
       g.packed_w = 1;
       if (ln) { g.ln_s = it->second.s; g.ln_t = it->second.t; g.ln_eps = 1e-5f; }
       else if (bias) bp = (const float*)weight(wn + ".b");
-      static const bool no_pack = getenv("DF_NO_PACK") != nullptr;   // tuning aid: canonical layout where no norm is folded
+      static const bool no_pack = tune_env("DF_NO_PACK") != nullptr;   // tuning aid: canonical layout where no norm is folded
       if (no_pack && !ln) { W = weight(wn + ".w"); g.packed_w = 0; }
     }
     g.out2 = out2; g.ldo2 = Nn;
@@ -401,7 +428,9 @@ struct Exec {
     if (extra) g = *extra;   // epilogue variant (GEGLU / segmented output) prepared by the caller
     g.A = A; g.W = W; g.bias = bp; g.residual = residual; g.out = out;
     g.M = M; g.N = Nn; g.K = K; g.lda = lda; g.ldw = K; g.ldr = ldr; g.ldo = ldo; g.act = 0; g.out_dtype = out_dtype;
+    g.scr = scr;
     const double osz = out_dtype == DF_BF16 ? 2.0 : 4.0;
+    label = "linear " + dims({M, Nn, K}) + (g.geglu ? " geglu" : "") + (g.ln_s ? " ln" : "");
     timed(PC_GEMM, 2.0 * M * Nn * K, 2.0 * ((double)M * K + (double)Nn * K) + osz * M * Nn,
           [&] { return launch_gemm_bf16(g, st); });
   }
@@ -421,6 +450,7 @@ struct Exec {
     a.B = B(); a.W = W; a.C = C; a.G = G; a.eps = eps; a.silu = silu; a.in_dtype = in_dtype; a.out_dtype = DF_BF16;
     a.stat_mode = gn_mode;
     a.y_packed = y_packed;
+    a.scr = scr;
     if (halo_entry && (full() || refresh)) {
       // the consumer convolution's boundary-row state is refreshed by this kernel's store loop
       a.halo_out = halo_entry; a.halo_npatch = N();
@@ -434,6 +464,7 @@ struct Exec {
       a.sums_out = refresh ? entry + (size_t)patch * B() * G * 2 : nullptr;
     }
     const double el = (double)B() * level_rows * W * C;
+    label = "groupnorm " + dims({B() * level_rows, W, C}) + (in_dtype == DF_BF16 ? " bf16" : " f32");
     timed(PC_GROUPNORM, 0.0, el * (in_dtype == DF_BF16 ? 2.0 : 4.0) + el * 2.0, [&] { return launch_groupnorm(a, st); });
   }
 
@@ -457,7 +488,7 @@ struct Exec {
     ConvArgs a = {};
     a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.chan_ld = chan_ld ? chan_ld : Cout; a.residual = residual; a.y = out;
     a.B = B(); a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = 0;
-    a.dtype = DF_BF16; a.out_dtype = out_dtype;
+    a.dtype = DF_BF16; a.out_dtype = out_dtype; a.scr = scr;
     a.halo_bstride = (long long)N() * 2 * rowe;
     if (!full()) {
       if (patch > 0) a.halo_top = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;           // last row of the patch above
@@ -466,6 +497,7 @@ struct Exec {
     {
       const double opx = (double)B() * (R / stride) * (W / stride);
       const double halo = full() ? 0.0 : 2.0;
+      label = "conv3x3 " + dims({B() * R, W, Cin}) + "->" + std::to_string(Cout) + (stride == 2 ? " stride2" : "");
       timed(PC_CONV, 2.0 * 9 * Cin * Cout * opx,
             2.0 * B() * (R + halo) * rowe + 2.0 * 9 * Cin * Cout + opx * Cout * (out_dtype == DF_BF16 ? 2.0 : 4.0),
             [&] { return launch_conv3x3(a, st); });
@@ -535,6 +567,7 @@ struct Exec {
     g.residual = residual; g.ldr = No; g.out_f32 = out_f32; g.ldo = No; g.out_packed = out_packed;
     g.out_rows = out_rows; g.ld_rows = ld_rows;
     const double ob = (out_f32 ? 4.0 : 0.0) + (out_packed ? 2.0 : 0.0) + ((out_rows || g.nseg) ? 2.0 : 0.0);
+    label = "linear_packed " + dims({M, Nn, K}) + (g.geglu ? " geglu" : "") + (ln ? " ln" : "") + (g.nseg ? " qkv" : "");
     timed(PC_GEMM, 2.0 * M * Nn * K, 2.0 * ((double)M * K + (double)Nn * K) + ob * M * No,
           [&] { return launch_wgemm(g, st); });
   }
@@ -599,7 +632,8 @@ struct Exec {
         a.ldq = C; a.ldkf = a.ldvf = C; a.ldks = C; a.ldvs = C; a.ldo = C;
         a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
         a.bsks = (long long)L * C; a.bsvs = (long long)C * Lpad; a.bso = (long long)Lq * C;
-        a.scale = scale; a.dtype = DF_BF16;
+        a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
+        label = "self_attn " + dims({M, L, C});
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
       }
@@ -624,6 +658,7 @@ struct Exec {
           WGemmArgs g2 = ex;
           g2.Xp = hp; g2.Wp = it->second.f; g2.M = M; g2.N = C; g2.K = C;
           g2.ln_s = it->second.s; g2.ln_t = it->second.t; g2.ln_eps = 1e-5f; g2.out_packed = aop;
+          label = "cross_attn+q_proj " + dims({M, TL, C});
           timed(PC_CROSS_ATTN, 2.0 * M * C * C + 4.0 * M * TL * C, 2.0 * ((double)M * C + (double)C * C) + 2.0 * M * C,
                 [&] { return launch_wgemm(g2, st); });
         }
@@ -639,7 +674,7 @@ struct Exec {
           a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
           a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
           a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
-          a.scale = scale; a.dtype = DF_BF16;
+          a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
           timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
                 [&] { return launch_attention(a, st); });
         }
@@ -706,7 +741,8 @@ struct Exec {
         a.ldq = C; a.ldkf = a.ldvf = C; a.ldks = C; a.ldvs = C; a.ldo = C;
         a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)L * C;
         a.bsks = (long long)L * C; a.bsvs = (long long)C * Lpad; a.bso = (long long)Lq * C;
-        a.scale = scale; a.dtype = DF_BF16;
+        a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
+        label = "self_attn " + dims({M, L, C});
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
       }
@@ -726,7 +762,7 @@ struct Exec {
         a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
         a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
         a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
-        a.scale = scale; a.dtype = DF_BF16;
+        a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
         timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
               [&] { return launch_attention(a, st); });
       }
@@ -809,7 +845,8 @@ struct Exec {
           a.own_lo = full() ? 0 : patch * Lq; a.own_n = Lq;
           a.ldq = a.ldkf = a.ldvf = 3 * C; a.bsq = a.bskf = a.bsvf = (long long)Lq * 3 * C;
         }
-        a.scale = scale; a.dtype = DF_BF16;
+        a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
+        label = "self_attn " + dims({M, L, C});
         timed(PC_SELF_ATTN, 4.0 * M * L * C, 2.0 * (2.0 * M * C + 2.0 * B() * L * C),
               [&] { return launch_attention(a, st); });
       }
@@ -846,7 +883,7 @@ struct Exec {
         a.B = B(); a.Lq = Lq; a.L = TL; a.heads = heads; a.d = c.head_dim; a.own_lo = 0; a.own_n = TL;
         a.ldq = C; a.ldkf = a.ldvf = kvld; a.ldks = a.ldvs = kvld; a.ldo = C;
         a.bsq = (long long)Lq * C; a.bskf = a.bsvf = (long long)TL * kvld; a.bso = (long long)Lq * C;
-        a.scale = scale; a.dtype = DF_BF16;
+        a.scale = scale; a.dtype = DF_BF16; a.scr = scr;
         timed(PC_CROSS_ATTN, 4.0 * M * TL * C, 2.0 * (2.0 * M * C + 2.0 * B() * TL * C),
               [&] { return launch_attention(a, st); });
       }
@@ -1057,7 +1094,9 @@ DryResult dry_run(const df_unet_cfg& c, const std::vector<BlockDesc>& blocks) {
   r.emb_b_off = end;
   end += align256((size_t)emb_total(blocks) * sizeof(float));
   r.packed_bytes = end;
-  r.ws_bytes += end + 256;
+  if (r.scratch < kScratchCounterBytes) r.scratch = kScratchCounterBytes;
+  r.scratch = align256(r.scratch);
+  r.ws_bytes += end + r.scratch + 256;
   return r;
 }
 
@@ -1186,8 +1225,9 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
     }
     if (hipDeviceSynchronize() != hipSuccess) { delete u; return DF_EHIP; }
   }
-  // reserve the library scratch now, so that no step ever has to grow it
-  if (!scratch_get(d.scratch > kScratchCounterBytes ? d.scratch : kScratchCounterBytes)) { delete u; return DF_ENOMEM; }
+  u->scr.ptr = u->ws + d.packed_bytes;
+  u->scr.bytes = d.scratch;
+  if (scratch_init(u->scr) != DF_OK) { delete u; return DF_EHIP; }
   *out = u;
   return DF_OK;
 }
@@ -1225,7 +1265,8 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
   if (((uintptr_t)x % 16) || ((uintptr_t)text % 16) || ((uintptr_t)stale % 256) || ((uintptr_t)eps_out % 16))
     return DF_EINVAL;
   Exec e{u->cfg, u->blocks, &u->w, false, mode, mode == DF_MODE_FULL ? 0 : patch_idx, refresh ? 1 : 0,
-         (hipStream_t)stream, u->ws + u->packed_bytes, u->ws_bytes - u->packed_bytes};
+         (hipStream_t)stream, u->ws + u->packed_bytes + u->scr.bytes, u->ws_bytes - u->packed_bytes - u->scr.bytes};
+  e.scr = &u->scr;
   for (int lv = 0; lv < 4; ++lv) {
     e.kv_count[lv] = u->kv_count[lv];
     e.kv_packed[lv] = (const bf16_t*)(u->ws + u->kv_off[lv]);
@@ -1247,9 +1288,9 @@ int df_patch_unet_step(df_unet* u, const void* x, const void* emb, const void* t
     if (g.mode == mode && g.patch == e.patch && g.refresh == e.refresh && g.gn_mode == e.gn_mode && g.x == x && g.emb == emb && g.text == text &&
         g.eps == eps_out && g.stale == stale && g.stream == st) { ge = &g; break; }
   if (!ge) {
-    if (u->graphs.size() >= 64) {   // bound the cache: drop everything and start over
-      for (GraphEntry& g : u->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
-      u->graphs.clear();
+    if (u->graphs.size() >= 64) {   // bound the cache: drop the oldest entry
+      if (u->graphs.front().exec) (void)hipGraphExecDestroy(u->graphs.front().exec);
+      u->graphs.erase(u->graphs.begin());
     }
     GraphEntry g;
     g.mode = mode; g.patch = e.patch; g.refresh = e.refresh; g.gn_mode = e.gn_mode; g.x = x; g.emb = emb; g.text = text; g.eps = eps_out;
@@ -1309,6 +1350,24 @@ int df_unet_profile_reset(df_unet* u) {
 int df_unet_profile_num_classes(void) { return PC_COUNT; }
 
 const char* df_unet_profile_class_name(int cls) { return (cls >= 0 && cls < PC_COUNT) ? kProfNames[cls] : ""; }
+
+int df_unet_profile_num_kernels(df_unet* u) {
+  if (!u) return DF_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  if (!u->prof.collect()) return DF_EHIP;
+  return (int)u->prof.kernels.size();
+}
+
+int df_unet_profile_kernel(df_unet* u, int idx, char* label, int label_cap, int* cls, double* ms, double* flops,
+                           double* bytes, long long* launches) {
+  if (!u || !label || label_cap < 1 || !cls || !ms || !flops || !bytes || !launches) return DF_EINVAL;
+  if (idx < 0 || idx >= (int)u->prof.kernels.size()) return DF_EINVAL;
+  const ProfKernel& k = u->prof.kernels[idx];
+  std::strncpy(label, k.label.c_str(), (size_t)label_cap - 1);
+  label[label_cap - 1] = 0;
+  *cls = k.cls; *ms = k.ms; *flops = k.flops; *bytes = k.bytes; *launches = k.launches;
+  return DF_OK;
+}
 
 int df_unet_profile_read(df_unet* u, int cls, double* ms, double* flops, double* bytes, long long* launches) {
   if (!u || cls < 0 || cls >= PC_COUNT || !ms || !flops || !bytes || !launches) return DF_EINVAL;

@@ -520,7 +520,7 @@ __global__ void pack_text_kv_kernel(const bf16_t* __restrict__ kv, long long ld,
 }
 
 int tune_cfg() {
-  static const int v = [] { const char* e = getenv("DF_WGEMM_CFG"); return e ? atoi(e) : 0; }();
+  static const int v = [] { const char* e = tune_env("DF_WGEMM_CFG"); return e ? atoi(e) : 0; }();
   return v;
 }
 

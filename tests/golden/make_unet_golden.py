@@ -6,6 +6,9 @@ Calls only df_inputs (seeded inputs) and oracle/ (float64 CPU reference).  The G
 takes minutes of CPU time.
 
   python tests/golden/make_unet_golden.py cfg4     # 160x240 latent, N=8, patch 3 (SDXL-shaped)
+  python tests/golden/make_unet_golden.py cfg4far  # same, but the current input is 0.5 N(0,1) away from the previous one
+  python tests/golden/make_unet_golden.py loop     # 6-step Euler loop at a 64x64 latent
+  python tests/golden/make_unet_golden.py cfg5     # 10-step Euler loop at the 256x256 latent, N=4 (about two hours)
 
 Stored: eps of the FULL step on x_prev, eps of the DISPLACED step of the patch on x with the stale
 state that FULL step left (both float32), and the recipe's parameters.
@@ -24,9 +27,16 @@ from oracle import unet as ounet  # noqa: E402
 
 RECIPES = {
     "cfg4": dict(H=160, W=240, N=8, patch=3, seed=4, arch="SDXL"),
+    # the same FULL step, but the patch's current input differs from the previous step's by 0.5 N(0,1): the
+    # DISPLACED result is then far (many tolerances) from the previous step's rows, so a step that confused
+    # fresh and stale data cannot pass
+    "cfg4far": dict(H=160, W=240, N=8, patch=3, seed=4, arch="SDXL", stale_std=0.5),
     # multi-step loop of configuration 5 at a latent size the oracle finishes in minutes: SDXL architecture,
     # 64x64 latent, N=4 (16 latent rows per patch), patch 1, 6 Euler steps (1 FULL + 5 DISPLACED with refresh)
     "loop": dict(H=64, W=64, N=4, patch=1, seed=5, arch="SDXL", steps=6),
+    # the multi-step configuration at its stated size: 2048x2048 image = 256x256 latent, N=4 (64 latent rows),
+    # patch 1, 10 Euler steps (1 FULL + 9 DISPLACED with refresh)
+    "cfg5": dict(H=256, W=256, N=4, patch=1, seed=5, arch="SDXL", steps=10),
 }
 
 # sigma ladder of the multi-step loop: geometric from 14.6 to 0.03 (the range of SDXL's Euler schedule)
@@ -74,7 +84,7 @@ def main(which):
     t0 = time.time()
     weights = configs.unet_weights(cfg, seed=r["seed"], threads=8)
     print("weights", round(time.time() - t0, 1), "s", flush=True)
-    t = configs.unet_inputs(cfg, seed=r["seed"])
+    t = configs.unet_inputs(cfg, seed=r["seed"], stale_std=r.get("stale_std", 0.02))
     bl = ut.blocks(cfg)
     P = ounet.Params(weights)
     stale = {}
