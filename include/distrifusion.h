@@ -93,6 +93,20 @@ int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, f
                        int patch_idx, int N, float eps, int stat_mode, int fuse_silu, int dtype, void* stream);
 
 /*
+ * df_groupnorm_stale for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but the statistics pass keeps
+ * its partial sums in a fixed array of DF_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every GPU
+ * the library runs on holds it until the process ends) instead of the library's allocated scratch.  The call never
+ * allocates or frees.  Shapes whose partial sums do not fit (roughly B * G > 120) return DF_ENOMEM and launch nothing.
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams) race; issue them from
+ * one stream at a time.  The array keeps the previous call's contents; nothing in it has to start at zero.
+ */
+#define DF_NOALLOC_SCRATCH_BYTES (2u << 20)
+int df_groupnorm_stale_noalloc(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out,
+                               const float* gamma, const float* beta, int B, int R, int W, int C, int G,
+                               int patch_idx, int N, float eps, int stat_mode, int fuse_silu, int dtype, void* stream);
+
+/*
  * Sparse 3x3 convolution of one patch (Section 4, Sparse operations; Section 5.3:
  * only the rows at the patch boundary come from other patches).
  *   x_fresh    [B, R, W, Cin]      fresh input rows s..e-1, R = H/N, s = patch_idx*R

@@ -49,6 +49,9 @@ def lib():
     L.df_buffer_refresh.argtypes = [vp, vp, i, ll, i, i, i, vp]
     L.df_groupnorm_stale.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, i, i, vp]
     L.df_conv3x3_halo.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, vp]
+    if hasattr(L, "df_groupnorm_stale_noalloc"):
+        L.df_groupnorm_stale_noalloc.argtypes = L.df_groupnorm_stale.argtypes
+        L.df_groupnorm_stale_noalloc.restype = i
     L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
@@ -151,6 +154,16 @@ def groupnorm_stale(x_fresh, stale_stats, gamma, beta, G, patch_idx, N, eps=1e-5
     _check(lib().df_groupnorm_stale(_ptr(x_fresh), _ptr(y), _ptr(stale_stats), _ptr(fresh_stats_out), _ptr(gamma),
                                     _ptr(beta), B, R, W, C, G, patch_idx, N, eps, stat_mode, int(fuse_silu),
                                     _dt(x_fresh), _stream()))
+    return y, fresh_stats_out
+
+
+def groupnorm_stale_noalloc(x_fresh, stale_stats, gamma, beta, G, patch_idx, N, y, fresh_stats_out, eps=1e-5,
+                            stat_mode=GN_SUMS, fuse_silu=False):
+    """df_groupnorm_stale_noalloc: the caller passes every buffer (y, fresh_stats_out); nothing is allocated."""
+    B, R, W, C = x_fresh.shape
+    _check(lib().df_groupnorm_stale_noalloc(_ptr(x_fresh), _ptr(y), _ptr(stale_stats), _ptr(fresh_stats_out),
+                                            _ptr(gamma), _ptr(beta), B, R, W, C, G, patch_idx, N, eps, stat_mode,
+                                            int(fuse_silu), _dt(x_fresh), _stream()))
     return y, fresh_stats_out
 
 

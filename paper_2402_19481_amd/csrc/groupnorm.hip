@@ -18,6 +18,7 @@
 // a tensor whose mean is far from zero cannot afford at float32 tolerance.  The
 // normalisation subtracts the mean as a (high, low) float pair before scaling.
 #include <cstdlib>
+#include <mutex>
 #include "kernels.h"
 
 namespace df {
@@ -680,3 +681,49 @@ int groupnorm_entry(const void* x_fresh, void* y, const float* stale_stats, floa
 }
 
 }  // namespace df
+
+// ---- the entry point for callers that cannot allocate ----
+// Its kernels take their partial sums from this array instead of an allocated region.  Every GPU the library runs on
+// holds its own copy until the process ends; host code reaches it only through the address hipGetSymbolAddress
+// returns for the current device.
+static constexpr size_t kStaticScratchBytes = DF_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+void* g_static_scratch[64];            // per device: address of that device's copy of `scratch`
+std::mutex g_static_scratch_mu;
+
+int static_scratch_region(df::Scratch* out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DF_EHIP;
+  std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+  if (!g_static_scratch[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return DF_EHIP; }
+    g_static_scratch[dev] = ptr;
+  }
+  out->ptr = (char*)g_static_scratch[dev];
+  out->bytes = kStaticScratchBytes;
+  return DF_OK;
+}
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int df_groupnorm_stale_noalloc(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out,
+                               const float* gamma, const float* beta, int B, int R, int W, int C, int G, int patch_idx,
+                               int N, float eps, int stat_mode, int fuse_silu, int dtype, void* stream) {
+  if (B <= 0 || G <= 0) return DF_ESHAPE;
+  // the statistics pass keeps up to 2048 partial (sum, sum of squares) pairs per batch item and group
+  if (df::groupnorm_scratch_bytes(B, 1, G) > kStaticScratchBytes) return DF_ENOMEM;
+  df::Scratch region = {nullptr, 0};
+  const int rc = static_scratch_region(&region);
+  if (rc != DF_OK) return rc;
+  // nothing in the region has to start at zero: every partial and every statistic is written before it is read
+  return df::groupnorm_entry(x_fresh, y, stale_stats, fresh_stats_out, gamma, beta, B, R, W, C, G, patch_idx, N, eps,
+                             stat_mode, fuse_silu, dtype, &region, (hipStream_t)stream);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -63,10 +63,10 @@ TOL_BF16 = 2e-2   # relative L2 error, bf16 storage with float accumulation
 # that attended to the wrong keys) cannot hide inside the whole-tensor norm.  An element of a bf16 result is off by up
 # to half a bf16 ulp of its own magnitude (2^-9) plus the accumulated operand rounding, a row by about the
 # whole-tensor figure; the bounds leave a factor of two to four over the worst value seen.
-ROW_BF16 = 4e-2   # worst row: ||g_r - o_r|| / RMS row norm
-ELT_BF16 = 4e-2   # worst element: max|g - o| / max|o|
-ROW_F32 = 5e-5
-ELT_F32 = 5e-5
+ROW_BF16 = 2e-2   # worst row: ||g_r - o_r|| / RMS row norm (single operations; the UNet tests pass 4e-2)
+ELT_BF16 = 2e-2   # worst element: max|g - o| / max|o|
+ROW_F32 = 1e-5
+ELT_F32 = 1e-5
 
 
 def check(got, ref, bf16, name="", row_axes=1, tol=None, row_tol=None, elt_tol=None, say=None):

@@ -43,7 +43,7 @@ def _sdxl_weights_on_device(seed):
 
 def check_eps(got, ref, name):
     """eps tensors [B, R, W, 4]: a "row" is one latent row (W x 4 values); a single pixel has only 4 channels."""
-    return check(got, ref, True, name, row_axes=2, say=say)
+    return check(got, ref, True, name, row_axes=2, row_tol=4e-2, elt_tol=4e-2, say=say)
 
 
 def _stale_as_oracle(net, name, cfg, B, ostale):
