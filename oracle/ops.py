@@ -12,7 +12,10 @@ and the rows of the fresh region are the result.  The functions below write
 exactly that: they materialise the scattered tensor, call a textbook
 full-image routine and slice.  Activations are channels-last,
 [B, H, W, C] (equivalently [B, L, C] with L = H*W); patches are horizontal
-strips of H/N rows.
+strips of H/N rows (split_axis=1, the default) or vertical strips of W/N
+columns (split_axis=2; Section 5.1, Baselines: the naive patch split
+alternates between the two directions, and nothing in Section 4 depends on the
+direction).
 
 Pins (tests/test_oracle_*.py): brute-force loops on tiny inputs, N=1 and
 stale==fresh invariants, hand-evaluated Eq. 2 values (tests/golden/), locality,
@@ -44,24 +47,29 @@ def patch_rows(H, patch_idx, N):
     return patch_idx * R, (patch_idx + 1) * R
 
 
-def scatter(stale_full, fresh, patch_idx, N):
-    """Scatter (Section 4): copy of the stale full tensor with the fresh patch placed at its rows.
+def _region(shape, patch_idx, N, axis):
+    """Index tuple of the patch's strip along `axis` of a [B, H, W, ...] (or [B, L, ...]) tensor."""
+    s, e = patch_rows(shape[axis], patch_idx, N)
+    return (slice(None),) * axis + (slice(s, e),)
 
-    Works on [B, H, ...] tensors, splitting axis 1.
+
+def scatter(stale_full, fresh, patch_idx, N, axis=1):
+    """Scatter (Section 4): copy of the stale full tensor with the fresh patch placed at its location.
+
+    Works on [B, H, ...] tensors; the patches split `axis` (1: strips of rows, 2: strips of columns).
     """
     out = _f64(stale_full).copy()
-    s, e = patch_rows(out.shape[1], patch_idx, N)
+    reg = _region(out.shape, patch_idx, N, axis)
     fresh = _f64(fresh)
-    if fresh.shape[1] != e - s:
-        raise ValueError("fresh patch has the wrong number of rows")
-    out[:, s:e] = fresh
+    if fresh.shape != out[reg].shape:
+        raise ValueError("fresh patch has the wrong shape")
+    out[reg] = fresh
     return out
 
 
-def buffer_refresh(dst_full, src_patch, patch_idx, N):
-    """The device's own part of the stale-buffer update (Section 4): rows [s,e) <- fresh patch, in place."""
-    s, e = patch_rows(dst_full.shape[1], patch_idx, N)
-    dst_full[:, s:e] = src_patch
+def buffer_refresh(dst_full, src_patch, patch_idx, N, axis=1):
+    """The device's own part of the stale-buffer update (Section 4): the patch's strip <- fresh patch, in place."""
+    dst_full[_region(dst_full.shape, patch_idx, N, axis)] = src_patch
     return dst_full
 
 
@@ -104,20 +112,20 @@ def conv3x3_full(X, w, bias=None, stride=1):
     return Y
 
 
-def conv3x3_halo(x_fresh, stale_full, w, bias, patch_idx, N, stride=1, act=0):
+def conv3x3_halo(x_fresh, stale_full, w, bias, patch_idx, N, stride=1, act=0, split_axis=1):
     """Sparse convolution of one patch (Section 4, Sparse operations).
 
-    The fresh rows are scattered into the stale full input, the full-image
-    convolution is applied, and the output rows of the patch are returned.
-    Only the stale rows next to the patch boundary can influence the result.
-    act: 0 none, 1 SiLU.
+    The fresh strip is scattered into the stale full input, the full-image
+    convolution is applied, and the output pixels of the patch are returned.
+    Only the stale rows (columns, for split_axis=2) next to the patch boundary
+    can influence the result.  act: 0 none, 1 SiLU.
     """
-    X = scatter(stale_full, x_fresh, patch_idx, N)
+    X = scatter(stale_full, x_fresh, patch_idx, N, split_axis)
     Y = conv3x3_full(X, w, bias, stride)
-    s, e = patch_rows(X.shape[1], patch_idx, N)
+    s, e = patch_rows(X.shape[split_axis], patch_idx, N)
     if s % stride or e % stride:
-        raise ValueError("patch rows not aligned to the stride")
-    out = Y[:, s // stride:e // stride]
+        raise ValueError("patch not aligned to the stride")
+    out = Y[:, s // stride:e // stride] if split_axis == 1 else Y[:, :, s // stride:e // stride]
     return silu(out) if act == 1 else out
 
 
@@ -147,16 +155,28 @@ def attention_dense(q, k, v, heads, scale=None):
     return out
 
 
-def attn_displaced(q, k_fresh, v_fresh, k_stale, v_stale, heads, patch_idx, N, scale=None):
+def attn_displaced(q, k_fresh, v_fresh, k_stale, v_stale, heads, patch_idx, N, scale=None, split_axis=1, hw=None):
     """Self-attention turned into cross-attention (Section 4, Sparse operations).
 
     Queries come from the fresh tokens only; keys and values cover the whole
-    feature map and are the scatter output: the patch's own rows fresh, all
-    other rows from the stale buffers.  q,k_fresh,v_fresh [B,Lq,C];
-    k_stale,v_stale [B,L,C].
+    feature map and are the scatter output: the patch's own tokens fresh, all
+    others from the stale buffers.  q,k_fresh,v_fresh [B,Lq,C];
+    k_stale,v_stale [B,L,C], tokens in row-major pixel order.  With
+    split_axis=2 the patch is a strip of columns of the hw = (H, W) token
+    grid: its tokens are [H, W/N] pixels in row-major order, scattered into
+    columns [i*W/N, (i+1)*W/N) of every row.
     """
-    K = scatter(k_stale, k_fresh, patch_idx, N)
-    V = scatter(v_stale, v_fresh, patch_idx, N)
+    if split_axis == 1:
+        K = scatter(k_stale, k_fresh, patch_idx, N)
+        V = scatter(v_stale, v_fresh, patch_idx, N)
+    else:
+        H, W = hw
+        B, L, C = np.shape(k_stale)
+        if L != H * W or W % N:
+            raise ValueError("token grid does not match")
+        K = scatter(_f64(k_stale).reshape(B, H, W, C), _f64(k_fresh).reshape(B, H, W // N, C), patch_idx, N, 2)
+        V = scatter(_f64(v_stale).reshape(B, H, W, C), _f64(v_fresh).reshape(B, H, W // N, C), patch_idx, N, 2)
+        K, V = K.reshape(B, L, C), V.reshape(B, L, C)
     return attention_dense(q, K, V, heads, scale)
 
 
@@ -173,10 +193,10 @@ def group_sums(x, G):
     return np.stack([xg.sum(axis=(1, 3)), (xg * xg).sum(axis=(1, 3))], axis=-1)
 
 
-def patch_group_sums(x_full, G, N):
+def patch_group_sums(x_full, G, N, axis=1):
     """Per-patch group sums of a full tensor: [N, B, G, 2], the content of the GroupNorm stale cache."""
-    H = x_full.shape[1]
-    return np.stack([group_sums(x_full[:, patch_rows(H, j, N)[0]:patch_rows(H, j, N)[1]], G) for j in range(N)])
+    x_full = _f64(x_full)
+    return np.stack([group_sums(x_full[_region(x_full.shape, j, N, axis)], G) for j in range(N)])
 
 
 def groupnorm_stale(x_fresh, stale_stats, gamma, beta, G, patch_idx, N, eps=1e-5,

@@ -398,3 +398,104 @@ def test_per_token_ops():
     u = ops.upsample_nearest2x(np.arange(6.0).reshape(1, 2, 3, 1))
     assert u.shape == (1, 4, 6, 1)
     np.testing.assert_array_equal(u[0, :, :, 0], [[0, 0, 1, 1, 2, 2], [0, 0, 1, 1, 2, 2], [3, 3, 4, 4, 5, 5], [3, 3, 4, 4, 5, 5]])
+
+
+# ---------------------------------------------------------------- vertical strips (split_axis=2)
+# Section 5.1, Baselines: the naive patch split alternates between rows and columns.  The column split is pinned by
+# brute force on the explicitly spliced image, by tiling, by locality (only stale columns s-1 and e reach the output)
+# and by the transposition symmetry that links it to the row split.
+
+@pytest.mark.parametrize("stride", [1, 2])
+@pytest.mark.parametrize("N,patch", [(1, 0), (2, 1), (4, 0), (4, 2)])
+def test_conv_halo_columns_brute_force_and_tiling(stride, N, patch):
+    H, W, Cin, Cout = 5 if stride == 1 else 6, 8, 3, 4
+    full = normal(41, "full", (1, H, W, Cin)).astype(np.float64)
+    stale = full + 0.1 * normal(41, "noise", (1, H, W, Cin)).astype(np.float64)
+    w = normal(41, "w", (Cout, 3, 3, Cin)).astype(np.float64)
+    b = normal(41, "b", (Cout,)).astype(np.float64)
+    Wp = W // N
+    s, e = patch * Wp, (patch + 1) * Wp
+    fresh = full[:, :, s:e]
+    got = ops.conv3x3_halo(fresh, stale, w, b, patch, N, stride, split_axis=2)
+    X = stale.copy()
+    X[:, :, s:e] = fresh
+    np.testing.assert_allclose(got, brute_conv(X, w, b, stride)[:, :, s // stride:e // stride], rtol=1e-12, atol=1e-12)
+    # stale == fresh: the strips tile the full-image output
+    tiles = [ops.conv3x3_halo(full[:, :, j * Wp:(j + 1) * Wp], full, w, b, j, N, stride, split_axis=2) for j in range(N)]
+    np.testing.assert_allclose(np.concatenate(tiles, axis=2), brute_conv(full, w, b, stride), rtol=1e-12, atol=1e-12)
+
+
+def test_conv_halo_columns_locality_and_transposition():
+    H, W, C, N, patch = 5, 12, 3, 3, 1
+    s, e = 4, 8
+    full = normal(42, "full", (1, H, W, C)).astype(np.float64)
+    stale = normal(42, "stale", (1, H, W, C)).astype(np.float64)
+    w = normal(42, "w", (4, 3, 3, C)).astype(np.float64)
+    b = normal(42, "b", (4,)).astype(np.float64)
+    fresh = full[:, :, s:e]
+    base = ops.conv3x3_halo(fresh, stale, w, b, patch, N, split_axis=2)
+    far = stale.copy()
+    far[:, :, :s - 1] += 7.0
+    far[:, :, e + 1:] -= 5.0
+    far[:, :, s:e] = 123.0                    # own columns of the stale buffer are never read
+    np.testing.assert_array_equal(ops.conv3x3_halo(fresh, far, w, b, patch, N, split_axis=2), base)
+    near = stale.copy()
+    near[:, :, s - 1] += 1.0
+    d = ops.conv3x3_halo(fresh, near, w, b, patch, N, split_axis=2) - base
+    assert np.abs(d[:, :, 0]).max() > 1e-3 and np.abs(d[:, :, 1:]).max() == 0.0
+    near = stale.copy()
+    near[:, :, e] += 1.0
+    d = ops.conv3x3_halo(fresh, near, w, b, patch, N, split_axis=2) - base
+    assert np.abs(d[:, :, -1]).max() > 1e-3 and np.abs(d[:, :, :-1]).max() == 0.0
+    # transposing image and kernel turns the column split into the row split
+    t = lambda a: np.swapaxes(a, 1, 2)
+    wt = np.swapaxes(w, 1, 2)
+    rows = ops.conv3x3_halo(t(fresh), t(stale), wt, b, patch, N, split_axis=1)
+    np.testing.assert_allclose(t(rows), base, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("N,patch", [(2, 0), (4, 3)])
+def test_attn_displaced_columns_brute_force_and_invariants(N, patch):
+    B, H, W, C, heads = 1, 3, 4, 4, 2
+    L, Wp = H * W, W // N
+    kfull = normal(43, "k", (B, L, C)).astype(np.float64)
+    vfull = normal(43, "v", (B, L, C)).astype(np.float64)
+    ks = kfull + 0.3 * normal(43, "kn", (B, L, C)).astype(np.float64)
+    vs = vfull + 0.3 * normal(43, "vn", (B, L, C)).astype(np.float64)
+    own = np.array([r * W + c for r in range(H) for c in range(patch * Wp, (patch + 1) * Wp)])   # the strip's tokens
+    q = normal(43, "q", (B, len(own), C)).astype(np.float64)
+    kf, vf = kfull[:, own], vfull[:, own]
+    got = ops.attn_displaced(q, kf, vf, ks, vs, heads, patch, N, split_axis=2, hw=(H, W))
+    K, V = ks.copy(), vs.copy()
+    K[:, own], V[:, own] = kf, vf                                   # explicit splice, token by token
+    np.testing.assert_allclose(got, brute_attention(q, K, V, heads, 1.0 / math.sqrt(C // heads)), rtol=1e-11, atol=1e-12)
+    # the own tokens of the stale buffers are never read
+    ks2, vs2 = ks.copy(), vs.copy()
+    ks2[:, own], vs2[:, own] = 99.0, -99.0
+    np.testing.assert_array_equal(ops.attn_displaced(q, kf, vf, ks2, vs2, heads, patch, N, split_axis=2, hw=(H, W)), got)
+    # stale == fresh: rows of dense self-attention over the full map
+    dense = ops.attention_dense(q, kfull, vfull, heads)
+    np.testing.assert_allclose(ops.attn_displaced(q, kf, vf, kfull, vfull, heads, patch, N, split_axis=2, hw=(H, W)),
+                               dense, rtol=1e-12, atol=1e-13)
+
+
+def test_gn_sums_and_refresh_for_column_strips():
+    B, H, W, C, G, N = 2, 4, 6, 8, 2, 3
+    x = normal(44, "x", (B, H, W, C)).astype(np.float64)
+    st = ops.patch_group_sums(x, G, N, axis=2)
+    Wp = W // N
+    for j in range(N):
+        strip = x[:, :, j * Wp:(j + 1) * Wp].reshape(B, H * Wp, G, C // G)
+        np.testing.assert_allclose(st[j, :, :, 0], strip.sum(axis=(1, 3)), rtol=1e-13)
+        np.testing.assert_allclose(st[j, :, :, 1], (strip ** 2).sum(axis=(1, 3)), rtol=1e-13)
+    np.testing.assert_allclose(st.sum(axis=0), ops.group_sums(x, G), rtol=1e-13)   # strips partition the image
+    # GroupNorm of a strip with the other strips' sums = GroupNorm of the scatter output (sums mode)
+    fresh = x[:, :, Wp:2 * Wp] + 0.5
+    gamma, beta = np.linspace(0.5, 1.5, C), np.linspace(-1, 1, C)
+    y, _ = ops.groupnorm_stale(fresh, st, gamma, beta, G, 1, N)
+    X = ops.scatter(x, fresh, 1, N, axis=2)
+    full, _ = ops.groupnorm_stale(X, ops.group_sums(X, G)[None], gamma, beta, G, 0, 1)
+    np.testing.assert_allclose(y, full[:, :, Wp:2 * Wp], rtol=1e-11, atol=1e-12)
+    d = x.copy()
+    ops.buffer_refresh(d, fresh, 1, N, axis=2)
+    np.testing.assert_array_equal(d, X)
