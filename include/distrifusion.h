@@ -62,6 +62,11 @@ enum {
 
 enum { DF_MODE_FULL = 0, DF_MODE_DISPLACED = 1 };
 
+/* Direction of the patch split.  Rows: N horizontal strips of H/N rows (the default of every entry point without a
+ * split_axis argument).  Columns: N vertical strips of W/N columns (Section 5.1, Baselines: the naive patch split
+ * alternates between the two; nothing in Section 4 depends on the direction). */
+enum { DF_SPLIT_ROWS = 0, DF_SPLIT_COLS = 1 };
+
 const char* df_strerror(int err);
 
 /*
@@ -138,6 +143,28 @@ int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, 
 int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
                       const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
                       float scale, int dtype, void* stream);
+
+/*
+ * The three spatially mixing operations for either split direction (Section 4; Section 5.1, Baselines).  With
+ * DF_SPLIT_ROWS they are df_buffer_refresh / df_conv3x3_halo / df_attn_displaced.  With DF_SPLIT_COLS patch i owns
+ * columns [i*W/N, (i+1)*W/N) of every row (W % N == 0):
+ *   df_conv3x3_halo_axis   x_fresh [B, H, W/N, Cin], stale_full [B, H, W, Cin] (only columns s-1 and e are read; zero
+ *                          beyond the image), y [B, H/stride, (W/N)/stride, Cout]; stride 2 needs H and W/N even.
+ *   df_attn_displaced_axis tokens are the pixels of an H x W grid in row-major order; q, k_fresh, v_fresh
+ *                          [B, H*(W/N), heads*d] hold the strip's tokens in row-major order, k_stale, v_stale
+ *                          [B, H*W, heads*d]; key (r, c) is taken from the fresh tensors iff c lies in the strip.
+ *   df_buffer_refresh_axis dst_full [B, H, row_elems] (row_elems = W * channels), src_patch [B, H, row_elems/N]: every
+ *                          row of the full buffer receives the strip's part of that row.
+ * df_groupnorm_stale needs no direction: it only sees the patch's values and the per-patch sums.
+ */
+int df_buffer_refresh_axis(void* dst_full, const void* src_patch, int B, int H, long long row_elems, int patch_idx,
+                           int N, int dtype, int split_axis, void* stream);
+int df_conv3x3_halo_axis(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,
+                         int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act, int dtype,
+                         int split_axis, void* stream);
+int df_attn_displaced_axis(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
+                           const void* v_stale, void* out, int B, int H, int W, int heads, int d, int patch_idx, int N,
+                           float scale, int dtype, int split_axis, void* stream);
 
 /*
  * Linear layer on the fresh tokens (Section 4, Sparse operations: linear layers run on the fresh region only

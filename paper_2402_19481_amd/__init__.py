@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdistrifusion.so")
 
 DF_F32, DF_BF16 = 0, 1
 GN_SUMS, GN_EQ2, GN_SEPARATE, GN_STALE = 0, 1, 2, 3
+SPLIT_ROWS, SPLIT_COLS = 0, 1
 MODE_FULL, MODE_DISPLACED = 0, 1
 
 _lib = None
@@ -53,6 +54,11 @@ def lib():
         L.df_groupnorm_stale_noalloc.argtypes = L.df_groupnorm_stale.argtypes
         L.df_groupnorm_stale_noalloc.restype = i
     L.df_attn_displaced.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, f, i, vp]
+    L.df_buffer_refresh_axis.argtypes = [vp, vp, i, i, ll, i, i, i, i, vp]
+    L.df_conv3x3_halo_axis.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, i, i, i, i, vp]
+    L.df_attn_displaced_axis.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, i, i, f, i, i, vp]
+    for name in ("df_buffer_refresh_axis", "df_conv3x3_halo_axis", "df_attn_displaced_axis"):
+        getattr(L, name).restype = i
     L.df_euler_update.argtypes = [vp, vp, f, f, ll, vp]
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.df_scale_input.argtypes = [vp, vp, f, ll, vp]
@@ -187,6 +193,36 @@ def attn_displaced(q, k_fresh, v_fresh, k_stale, v_stale, heads, patch_idx, N, s
         out = torch.empty_like(q)
     _check(lib().df_attn_displaced(_ptr(q), _ptr(k_fresh), _ptr(v_fresh), _ptr(k_stale), _ptr(v_stale), _ptr(out), B,
                                    L, heads, d, patch_idx, N, scale, _dt(q), _stream()))
+    return out
+
+
+def buffer_refresh_cols(dst_full, src_patch, patch_idx, N):
+    """dst_full [B, H, W, ...] <- src_patch [B, H, W/N, ...] at the patch's columns (in place)."""
+    B, H = dst_full.shape[:2]
+    _check(lib().df_buffer_refresh_axis(_ptr(dst_full), _ptr(src_patch), B, H, dst_full.numel() // (B * H), patch_idx, N,
+                                        _dt(dst_full), SPLIT_COLS, _stream()))
+    return dst_full
+
+
+def conv3x3_halo_cols(x_fresh, stale_full, w, bias, patch_idx, N, stride=1, act=0):
+    """Vertical strip: x_fresh [B, H, W/N, Cin], stale_full [B, H, W, Cin]."""
+    B, H, Wp, Cin = x_fresh.shape
+    Cout = w.shape[0]
+    y = torch.empty(B, H // stride, Wp // stride, Cout, dtype=x_fresh.dtype, device=x_fresh.device)
+    _check(lib().df_conv3x3_halo_axis(_ptr(x_fresh), _ptr(stale_full), _ptr(w), _ptr(bias), _ptr(y), B, H, Wp * N, Cin,
+                                      Cout, patch_idx, N, stride, act, _dt(x_fresh), SPLIT_COLS, _stream()))
+    return y
+
+
+def attn_displaced_cols(q, k_fresh, v_fresh, k_stale, v_stale, heads, H, W, patch_idx, N, scale=None):
+    """Vertical strip of an H x W token grid: q, k_fresh, v_fresh [B, H*W/N, C], k_stale, v_stale [B, H*W, C]."""
+    B, Lq, C = q.shape
+    d = C // heads
+    if scale is None:
+        scale = d ** -0.5
+    out = torch.empty_like(q)
+    _check(lib().df_attn_displaced_axis(_ptr(q), _ptr(k_fresh), _ptr(v_fresh), _ptr(k_stale), _ptr(v_stale), _ptr(out),
+                                        B, H, W, heads, d, patch_idx, N, scale, _dt(q), SPLIT_COLS, _stream()))
     return out
 
 

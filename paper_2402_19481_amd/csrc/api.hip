@@ -91,46 +91,97 @@ int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, f
                          stat_mode, fuse_silu, dtype, nullptr, (hipStream_t)stream);
 }
 
-int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,
-                    int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act, int dtype,
-                    void* stream) {
+int df_conv3x3_halo_axis(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,
+                         int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act, int dtype,
+                         int split_axis, void* stream) {
   if (!x_fresh || !w || !y || bad_dtype(dtype)) return DF_EINVAL;
   if (act != 0 && act != 1) return DF_EINVAL;
-  if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || N <= 0 || H % N) return DF_ESHAPE;
+  if (split_axis != DF_SPLIT_ROWS && split_axis != DF_SPLIT_COLS) return DF_EINVAL;
+  if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || N <= 0) return DF_ESHAPE;
+  if ((split_axis == DF_SPLIT_ROWS ? H : W) % N) return DF_ESHAPE;
   if (patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
   if (N > 1 && !stale_full) return DF_EINVAL;
-  const int R = H / N;
   const long long row = (long long)W * Cin;
   const size_t es = esize(dtype);
   ConvArgs a = {};
   a.x = x_fresh; a.w = w; a.bias = bias; a.y = y;
-  a.B = B; a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = act;
+  a.B = B; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = act;
   a.dtype = dtype; a.out_dtype = dtype;
-  a.halo_bstride = (long long)H * row;
-  const int s = patch_idx * R, e = s + R;
-  a.halo_top = (s > 0) ? (const char*)stale_full + (size_t)(s - 1) * row * es : nullptr;
-  a.halo_bot = (e < H && stride == 1) ? (const char*)stale_full + (size_t)e * row * es : nullptr;
+  if (split_axis == DF_SPLIT_ROWS) {
+    const int R = H / N;
+    a.R = R; a.W = W;
+    a.halo_bstride = (long long)H * row;
+    const int s = patch_idx * R, e = s + R;
+    a.halo_top = (s > 0) ? (const char*)stale_full + (size_t)(s - 1) * row * es : nullptr;
+    a.halo_bot = (e < H && stride == 1) ? (const char*)stale_full + (size_t)e * row * es : nullptr;
+  } else {
+    // vertical strip: the patch has all H rows and W/N columns; the stale buffer supplies column s-1 and column e
+    const int Wp = W / N;
+    a.R = H; a.W = Wp;
+    const int s = patch_idx * Wp, e = s + Wp;
+    a.side_bstride = (long long)H * row;
+    a.side_rstride = row;
+    a.halo_left = (s > 0) ? (const char*)stale_full + (size_t)(s - 1) * Cin * es : nullptr;
+    a.halo_right = (e < W && stride == 1) ? (const char*)stale_full + (size_t)e * Cin * es : nullptr;
+  }
   return launch_conv3x3(a, (hipStream_t)stream);
 }
 
-int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
-                      const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
-                      float scale, int dtype, void* stream) {
+int df_conv3x3_halo(const void* x_fresh, const void* stale_full, const void* w, const float* bias, void* y, int B,
+                    int H, int W, int Cin, int Cout, int patch_idx, int N, int stride, int act, int dtype,
+                    void* stream) {
+  return df_conv3x3_halo_axis(x_fresh, stale_full, w, bias, y, B, H, W, Cin, Cout, patch_idx, N, stride, act, dtype,
+                              DF_SPLIT_ROWS, stream);
+}
+
+int df_attn_displaced_axis(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
+                           const void* v_stale, void* out, int B, int H, int W, int heads, int d, int patch_idx, int N,
+                           float scale, int dtype, int split_axis, void* stream) {
   if (!q || !k_fresh || !v_fresh || !out || bad_dtype(dtype)) return DF_EINVAL;
-  if (B <= 0 || L <= 0 || heads <= 0 || d <= 0 || N <= 0 || L % N) return DF_ESHAPE;
+  if (split_axis != DF_SPLIT_ROWS && split_axis != DF_SPLIT_COLS) return DF_EINVAL;
+  if (B <= 0 || H <= 0 || W <= 0 || heads <= 0 || d <= 0 || N <= 0) return DF_ESHAPE;
+  if ((long long)H * W > 0x7fffffffLL || (split_axis == DF_SPLIT_ROWS ? ((long long)H * W) % N : W % N)) return DF_ESHAPE;
   if (patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
   if (N > 1 && (!k_stale || !v_stale)) return DF_EINVAL;
-  const int Lq = L / N;
+  const int L = H * W, Lq = L / N;
   const long long C = (long long)heads * d;
   AttnArgs a = {};
   a.q = q; a.k_fresh = k_fresh; a.v_fresh = v_fresh; a.k_stale = k_stale; a.v_stale = v_stale; a.out = out;
   a.B = B; a.Lq = Lq; a.L = L; a.heads = heads; a.d = d;
-  a.own_lo = patch_idx * Lq; a.own_n = Lq;
+  if (split_axis == DF_SPLIT_ROWS) {
+    a.own_lo = patch_idx * Lq; a.own_n = Lq;           // a block of consecutive tokens
+  } else {
+    a.own_period = W; a.own_n = W / N; a.own_lo = patch_idx * a.own_n;   // W/N tokens of every grid row
+  }
   a.ldq = a.ldkf = a.ldvf = a.ldks = a.ldvs = a.ldo = C;
   a.bsq = a.bskf = a.bsvf = a.bso = (long long)Lq * C;
   a.bsks = a.bsvs = (long long)L * C;
   a.scale = scale; a.dtype = dtype;
   return launch_attention(a, (hipStream_t)stream);
+}
+
+int df_attn_displaced(const void* q, const void* k_fresh, const void* v_fresh, const void* k_stale,
+                      const void* v_stale, void* out, int B, int L, int heads, int d, int patch_idx, int N,
+                      float scale, int dtype, void* stream) {
+  if (L <= 0) return (!q || !k_fresh || !v_fresh || !out || bad_dtype(dtype)) ? DF_EINVAL : DF_ESHAPE;
+  return df_attn_displaced_axis(q, k_fresh, v_fresh, k_stale, v_stale, out, B, 1, L, heads, d, patch_idx, N, scale,
+                                dtype, DF_SPLIT_ROWS, stream);
+}
+
+int df_buffer_refresh_axis(void* dst_full, const void* src_patch, int B, int H, long long row_elems, int patch_idx,
+                           int N, int dtype, int split_axis, void* stream) {
+  if (!dst_full || !src_patch || bad_dtype(dtype)) return DF_EINVAL;
+  if (split_axis != DF_SPLIT_ROWS && split_axis != DF_SPLIT_COLS) return DF_EINVAL;
+  if (B <= 0 || H <= 0 || N <= 0 || row_elems < 0 || patch_idx < 0 || patch_idx >= N) return DF_ESHAPE;
+  if (split_axis == DF_SPLIT_ROWS) {
+    if (H % N) return DF_ESHAPE;
+    return df_buffer_refresh(dst_full, src_patch, B, (long long)H * row_elems, patch_idx, N, dtype, stream);
+  }
+  if (row_elems % N) return DF_ESHAPE;
+  // every row of the full buffer receives the patch's part of that row: B*H pieces of row_elems/N elements
+  const long long piece = row_elems / N * (long long)esize(dtype), full = row_elems * (long long)esize(dtype);
+  return launch_copy_rows((char*)dst_full + (long long)patch_idx * piece, src_patch, (long long)B * H, piece, full,
+                          piece, (hipStream_t)stream);
 }
 
 int df_attn_stale_vt(const void* q, const void* k, const void* vt, void* out, int B, int Lq, int L, int heads,

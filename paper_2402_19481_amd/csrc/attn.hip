@@ -34,6 +34,8 @@ struct AttnParams {
   float* part_ml;  // [nsplit][B][heads][Lq][2]
   int B, Lq, L, heads;
   int own_lo, own_n;
+  int own_period;  // 0: keys [own_lo, own_lo + own_n) are fresh; P > 0: key j is fresh iff j % P lies in that range
+                   // (a vertical strip of a token grid with P columns) and is row (j / P) * own_n + j % P - own_lo
   long long ldq, ldkf, ldvf, ldks, ldvs, ldo;
   long long bsq, bskf, bsvf, bsks, bsvs, bso;
   float scale;
@@ -43,10 +45,21 @@ struct AttnParams {
   long long vt_ld;
 };
 
-__device__ __forceinline__ const bf16_t* key_row(const bf16_t* fresh, const bf16_t* stale, long long ldf, long long lds,
-                                                 int own_lo, int own_n, int j) {
+// Row of the fresh tensor that holds key j, or -1 if the key comes from the stale buffer (Section 4: the keys and
+// values are the scatter output; the scatter is resolved here, key by key).
+__device__ __forceinline__ long long fresh_row(int own_lo, int own_n, int period, int j) {
+  if (period > 0) {
+    const int r = j / period, rel = j - r * period - own_lo;
+    return (rel >= 0 && rel < own_n) ? (long long)r * own_n + rel : -1;
+  }
   const int rel = j - own_lo;
-  return (rel >= 0 && rel < own_n) ? fresh + (long long)rel * ldf : stale + (long long)j * lds;
+  return (rel >= 0 && rel < own_n) ? (long long)rel : -1;
+}
+
+__device__ __forceinline__ const bf16_t* key_row(const bf16_t* fresh, const bf16_t* stale, long long ldf, long long lds,
+                                                 int own_lo, int own_n, int period, int j) {
+  const long long fr = fresh_row(own_lo, own_n, period, j);
+  return fr >= 0 ? fresh + fr * ldf : stale + (long long)j * lds;
 }
 
 // physical key (0..31) loaded into MFMA row rho of a 32-key block
@@ -125,7 +138,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
   auto load_tile = [&](int t, auto slot) {
     constexpr int S = decltype(slot)::value;
     const int base = kv_lo + t * TK;
-    if (base + TK <= kv_hi) {                              // (uniform) a full tile
+    if (base + TK <= kv_hi && p.own_period == 0) {         // (uniform) a full tile of a contiguous split
       const int rel = base - p.own_lo;
       if (rel >= 0 && rel + TK <= p.own_n) {               // all rows fresh
         const bf16_t* kb = kf + (long long)rel * p.ldkf;
@@ -151,10 +164,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int jk = base + ld_key + 32 * i;
-      kreg[S][i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, jk) + ld_ch * 8)
+      kreg[S][i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, p.own_period, jk) + ld_ch * 8)
                               : zero4;
       const int jv = base + 2 * ld_key + i;
-      vreg[S][i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, jv) + ld_ch * 8)
+      vreg[S][i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, p.own_period, jv) + ld_ch * 8)
                               : zero4;
     }
   };
@@ -671,10 +684,9 @@ __global__ __launch_bounds__(256) void attn_f32(AttnParams p) {
 #pragma unroll
   for (int i = 0; i < D; ++i) acc[i] = 0.f;
   for (int j = lane; j < p.L; j += 64) {
-    const int rel = j - p.own_lo;
-    const bool own = rel >= 0 && rel < p.own_n;
-    const float* kr = own ? kf + (long long)rel * p.ldkf : ks + (long long)j * p.ldks;
-    const float* vr = own ? vf + (long long)rel * p.ldvf : vs + (long long)j * p.ldvs;
+    const long long fr = fresh_row(p.own_lo, p.own_n, p.own_period, j);
+    const float* kr = fr >= 0 ? kf + fr * p.ldkf : ks + (long long)j * p.ldks;
+    const float* vr = fr >= 0 ? vf + fr * p.ldvf : vs + (long long)j * p.ldvs;
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < D; ++i) s = fmaf(qv[i], kr[i], s);
@@ -729,11 +741,14 @@ size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d) {
 int launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.B <= 0 || a.Lq <= 0 || a.L <= 0 || a.heads <= 0) return DF_ESHAPE;
   if (!(a.scale > 0.f) || !(a.scale < INFINITY)) return DF_EINVAL;   // the kernels fold the scale into exp2 arguments
-  const bool own_all = a.own_lo <= 0 && a.own_lo + a.own_n >= a.L;
+  if (a.own_period < 0 || (a.own_period > 0 && (a.L % a.own_period || a.own_lo < 0 || a.own_lo + a.own_n > a.own_period)))
+    return DF_ESHAPE;
+  const bool own_all = a.own_lo <= 0 && a.own_lo + a.own_n >= (a.own_period > 0 ? a.own_period : a.L);
   if (!own_all && (!a.k_stale || !a.v_stale)) return DF_EINVAL;
   AttnParams p = {};
   p.q = a.q; p.kf = a.k_fresh; p.vf = a.v_fresh; p.ks = a.k_stale; p.vs = a.v_stale; p.out = a.out;
   p.B = a.B; p.Lq = a.Lq; p.L = a.L; p.heads = a.heads; p.own_lo = a.own_lo; p.own_n = a.own_n;
+  p.own_period = a.own_period;
   p.ldq = a.ldq; p.ldkf = a.ldkf; p.ldvf = a.ldvf; p.ldks = a.ldks; p.ldvs = a.ldvs; p.ldo = a.ldo;
   p.bsq = a.bsq; p.bskf = a.bskf; p.bsvf = a.bsvf; p.bsks = a.bsks; p.bsvs = a.bsvs; p.bso = a.bso;
   p.scale = a.scale;
@@ -773,7 +788,7 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   if (nwg > 0x7fffffffLL) return DF_ESHAPE;
   if (a.v_transposed) {
     // every key from k_stale (row-major) / v_stale (V^T, row pitch vt_ld >= L rounded up to whole 64-key tiles)
-    if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
+    if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.own_period != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
     if (a.ldks <= 0 || a.ldks >= (1 << 23) || a.vt_ld >= (1 << 25)) return DF_ESHAPE;   // 32-bit offsets inside a tile
     p.vt_ld = a.vt_ld;
     // Up to ~600 workgroups (at most two per compute unit): two groups of four waves and a two-stage ring (64 KB of

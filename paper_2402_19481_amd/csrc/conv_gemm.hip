@@ -6,7 +6,9 @@
 // A-operand loader gathers each 32- or 64-channel slice of a tap straight from the
 // fresh patch, or - for the row above / below the patch - from the stale halo
 // row (Section 5.3: only boundary rows come from other patches), or zero at the
-// image border.  The scatter is never materialised.
+// image border.  The scatter is never materialised.  Patches that are vertical
+// strips take the column left / right of the patch from the stale buffer in the
+// same way (one pixel per input row, strided).
 //
 // Two tile kernels: mfma_pipe_kernel (BM x BN x 64 slabs, operands loaded
 // global -> LDS directly into a multi-stage ring, used whenever K % 64 == 0)
@@ -44,6 +46,9 @@ struct TileParams {
   const bf16_t* top;
   const bf16_t* bot;
   long long halo_bs;
+  const bf16_t* left;    // stale column left / right of a vertical strip: pixel (b, row) at left + b*side_bs + row*side_rs
+  const bf16_t* right;
+  long long side_bs, side_rs;
   int R, W, Cin, Ro, Wo, stride;
   // epilogue variants of the pipelined kernel (see GemmArgs)
   int geglu;      // F (half of N) or 0
@@ -61,6 +66,22 @@ struct TileParams {
   int vec_epi;    // every epilogue pointer / stride allows 16-byte (float) and 8-byte (bf16) accesses
   const Scratch* scr;   // host side only: where split-K partials and the page of zeros live
 };
+
+// Source pixel (channel 0) of one filter tap: the fresh patch, a stale halo row (patches are horizontal strips) or
+// halo column (vertical strips), or nullptr where the tap falls on the zero padding around the image.
+template <typename T>
+__device__ __forceinline__ const T* conv_tap_src(const T* x, const T* top, const T* bot, long long halo_bs, const T* left,
+                                                 const T* right, long long side_bs, long long side_rs, int b, int ri,
+                                                 int ci, int R, int W, int Cin) {
+  if (ci < 0 || ci >= W) {
+    const T* side = ci < 0 ? left : right;
+    if (!side || ri < 0 || ri >= R) return nullptr;
+    return side + b * side_bs + ri * side_rs;
+  }
+  if (ri < 0) return top ? top + b * halo_bs + (long long)ci * Cin : nullptr;
+  if (ri >= R) return bot ? bot + b * halo_bs + (long long)ci * Cin : nullptr;
+  return x + (((long long)b * R + ri) * W + ci) * Cin;
+}
 
 template <int BM, int BN, bool kConv, typename OutT>
 __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
@@ -126,16 +147,9 @@ __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
       for (int i = 0; i < A_CH; ++i) {
         const int ri = a_ro[i] * p.stride + ky - 1;
         const int ci = a_co[i] * p.stride + kx - 1;
-        const bf16_t* src = nullptr;
-        if (a_ok[i] && ci >= 0 && ci < p.W) {
-          if (ri < 0) {
-            if (p.top) src = p.top + a_b[i] * p.halo_bs + (long long)ci * p.Cin;
-          } else if (ri >= p.R) {
-            if (p.bot) src = p.bot + a_b[i] * p.halo_bs + (long long)ci * p.Cin;
-          } else {
-            src = p.A + (((long long)a_b[i] * p.R + ri) * p.W + ci) * p.Cin;
-          }
-        }
+        const bf16_t* src = a_ok[i] ? conv_tap_src(p.A, p.top, p.bot, p.halo_bs, p.left, p.right, p.side_bs, p.side_rs,
+                                                   a_b[i], ri, ci, p.R, p.W, p.Cin)
+                                    : nullptr;
         a_reg[i] = src ? *reinterpret_cast<const u32x4*>(src + cin0 + a_kc[i] * 8) : zero4;
       }
     } else {
@@ -340,16 +354,9 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
     for (int j = 0; j < AJ; ++j) {
       const int ri = a_ro[j] * p.stride + ky - 1;
       const int ci = a_co[j] * p.stride + kx - 1;
-      const bf16_t* src = nullptr;
-      if (a_ok[j] && ci >= 0 && ci < p.W) {
-        if (ri < 0) {
-          if (p.top) src = p.top + a_b[j] * p.halo_bs + (long long)ci * p.Cin;
-        } else if (ri >= p.R) {
-          if (p.bot) src = p.bot + a_b[j] * p.halo_bs + (long long)ci * p.Cin;
-        } else {
-          src = p.A + (((long long)a_b[j] * p.R + ri) * p.W + ci) * p.Cin;
-        }
-      }
+      const bf16_t* src = a_ok[j] ? conv_tap_src(p.A, p.top, p.bot, p.halo_bs, p.left, p.right, p.side_bs, p.side_rs,
+                                                 a_b[j], ri, ci, p.R, p.W, p.Cin)
+                                  : nullptr;
       a_pad[j] = src == nullptr;
       a_tap[j] = (src ? src : zeros) + kc_a(j) * 8;
     }
@@ -761,6 +768,8 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
 template <typename T, typename OutT>
 __global__ __launch_bounds__(256) void conv3x3_direct(const T* __restrict__ x, const T* __restrict__ top,
                                                       const T* __restrict__ bot, long long halo_bs,
+                                                      const T* __restrict__ left, const T* __restrict__ right,
+                                                      long long side_bs, long long side_rs,
                                                       const T* __restrict__ w, const float* __restrict__ bias,
                                                       const float* __restrict__ chan_add,
                                                       const float* __restrict__ residual, OutT* __restrict__ y, int B,
@@ -778,20 +787,10 @@ __global__ __launch_bounds__(256) void conv3x3_direct(const T* __restrict__ x, c
   float acc = bias ? bias[co] : 0.f;
   for (int ky = 0; ky < 3; ++ky) {
     const int ri = r * stride + ky - 1;
-    const T* rowp;
-    if (ri < 0) {
-      if (!top) continue;
-      rowp = top + b * halo_bs;
-    } else if (ri >= R) {
-      if (!bot) continue;
-      rowp = bot + b * halo_bs;
-    } else {
-      rowp = x + ((long long)b * R + ri) * W * Cin;
-    }
     for (int kx = 0; kx < 3; ++kx) {
       const int ci = c * stride + kx - 1;
-      if (ci < 0 || ci >= W) continue;
-      const T* xp = rowp + (long long)ci * Cin;
+      const T* xp = conv_tap_src(x, top, bot, halo_bs, left, right, side_bs, side_rs, b, ri, ci, R, W, Cin);
+      if (!xp) continue;
       const T* wp = w + (((long long)co * 3 + ky) * 3 + kx) * Cin;
       float s = 0.f;
       for (int i = 0; i < Cin; ++i) s = fmaf(Elem<T>::ld(xp + i), Elem<T>::ld(wp + i), s);
@@ -1281,9 +1280,12 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
   const int Ro = a.R / a.stride, Wo = a.W / a.stride;
   const long long M = (long long)a.B * Ro * Wo;
   if (M <= 0 || M > 0x7fffffffLL) return DF_ESHAPE;
+  const bool sides = a.halo_left || a.halo_right;
+  if (sides && (a.halo_top || a.halo_bot)) return DF_EINVAL;     // a patch is a strip along one direction
   const bool mfma = a.dtype == DF_BF16 && a.Cin % BK == 0 && a.Cout % 32 == 0 && ((uintptr_t)a.x % 16 == 0) &&
                     ((uintptr_t)a.w % 16 == 0) && ((uintptr_t)a.halo_top % 16 == 0) &&
-                    ((uintptr_t)a.halo_bot % 16 == 0) && (a.halo_bstride % 8 == 0);
+                    ((uintptr_t)a.halo_bot % 16 == 0) && (a.halo_bstride % 8 == 0) && ((uintptr_t)a.halo_left % 16 == 0) &&
+                    ((uintptr_t)a.halo_right % 16 == 0) && (a.side_bstride % 8 == 0) && (a.side_rstride % 8 == 0);
   if (mfma) {
     TileParams p = {};
     p.A = (const bf16_t*)a.x; p.Wt = (const bf16_t*)a.w; p.bias = a.bias; p.residual = a.residual;
@@ -1291,6 +1293,8 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
     p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin; p.lda = 0; p.ldw = 9LL * a.Cin; p.ldr = a.Cout; p.ldo = a.Cout;
     p.act = a.act; p.scr = a.scr;
     p.top = (const bf16_t*)a.halo_top; p.bot = (const bf16_t*)a.halo_bot; p.halo_bs = a.halo_bstride;
+    p.left = (const bf16_t*)a.halo_left; p.right = (const bf16_t*)a.halo_right; p.side_bs = a.side_bstride;
+    p.side_rs = a.side_rstride;
     p.R = a.R; p.W = a.W; p.Cin = a.Cin; p.Ro = Ro; p.Wo = Wo; p.stride = a.stride;
     return pick_tile<true>(p, a.out_dtype, st);
   }
@@ -1298,14 +1302,15 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
   const long long total = M * a.Cout;
 #define DF_DIRECT(T, OT)                                                                                              \
   hipLaunchKernelGGL((conv3x3_direct<T, OT>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const T*)a.x, \
-                     (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.w, a.bias, a.chan_add,  \
+                     (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.halo_left,               \
+                     (const T*)a.halo_right, a.side_bstride, a.side_rstride, (const T*)a.w, a.bias, a.chan_add,       \
                      a.residual, (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, Ro, Wo, a.stride, a.act)
 #define DF_WAVE(T, OT)                                                                                                \
   hipLaunchKernelGGL((conv3x3_wave<T, OT, 8>), dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, (const T*)a.x,        \
                      (const T*)a.halo_top, (const T*)a.halo_bot, a.halo_bstride, (const T*)a.w, a.bias, a.residual,  \
                      (OT*)a.y, a.B, a.R, a.W, a.Cin, a.Cout, Ro, Wo, a.stride, a.act)
   if ((total + 255) / 256 > 0x7fffffffLL) return DF_ESHAPE;
-  if (a.dtype == DF_BF16 && !a.chan_add && ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
+  if (!sides && a.dtype == DF_BF16 && !a.chan_add && ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.w % 16 == 0) &&
       ((uintptr_t)a.halo_top % 16 == 0) && ((uintptr_t)a.halo_bot % 16 == 0)) {
     if (a.Cin == 4 && a.Cout % 8 == 0 && a.halo_bstride % 4 == 0 && ((uintptr_t)a.y % 16 == 0) &&
         ((uintptr_t)a.residual % 16 == 0)) {
@@ -1331,7 +1336,7 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
       return DF_OK;
     }
   }
-  const bool wave = a.Cout <= 8 && a.Cin >= 64 && !a.chan_add;
+  const bool wave = a.Cout <= 8 && a.Cin >= 64 && !a.chan_add && !sides;   // the wave kernel knows row halos only
   if (a.dtype == DF_F32) {
     if (a.out_dtype != DF_F32) return DF_ESHAPE;
     if (wave) DF_WAVE(float, float); else DF_DIRECT(float, float);

@@ -67,6 +67,11 @@ struct ConvArgs {
   const void* halo_top;  // row above the patch [B][W*Cin] with batch stride halo_bstride elements, or nullptr (zero)
   const void* halo_bot;  // row below the patch, or nullptr
   long long halo_bstride;
+  // patches that are vertical strips: the stale pixel left / right of input row r of batch item b sits at
+  // halo_left + b*side_bstride + r*side_rstride (elements), nullptr = zero (image border); excludes the row halos
+  const void* halo_left;
+  const void* halo_right;
+  long long side_bstride, side_rstride;
   const void* w;         // [Cout, 3, 3, Cin]
   const float* bias;     // [Cout] or nullptr
   const float* chan_add; // [B, Cout] added per batch item and channel (row stride chan_ld), or nullptr
@@ -180,6 +185,8 @@ struct AttnArgs {
   void* out;            // [B, Lq, heads*d]
   int B, Lq, L, heads, d;
   int own_lo, own_n;    // key rows [own_lo, own_lo+own_n) come from the fresh tensors (row 0 of fresh = key own_lo)
+  int own_period;       // P > 0 (vertical strip of a token grid with P columns, L % P == 0): key j is fresh iff j % P is
+                        // in [own_lo, own_lo+own_n), and is then row (j / P) * own_n + j % P - own_lo of the fresh tensors
   long long ldq, ldkf, ldvf, ldks, ldvs, ldo;
   long long bsq, bskf, bsvf, bsks, bsvs, bso;  // batch strides in elements
   float scale;

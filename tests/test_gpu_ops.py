@@ -607,3 +607,110 @@ def test_share_3840_layer_shapes():
     o = df.attn_displaced(dev(t["q"], True), dev(t["kf"], True), dev(t["vf"], True), dev(t["ks"], True),
                           dev(t["vs"], True), 20, patch, N)
     check(host(o), ref, True, "3840 share attention 1800 x 14400 x 1280", say=say)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# vertical strips (Section 5.1, Baselines: the patch split may run along either direction)
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_buffer_refresh_columns_bit_exact(dtype):
+    g = torch.Generator().manual_seed(6)
+    B, H, W, C, N = 2, 5, 12, 24, 4
+    full = torch.randn(B, H, W, C, generator=g).to(dtype).to(DEV)
+    Wp = W // N
+    bits = torch.int16 if dtype == torch.bfloat16 else torch.int32
+    for i in range(N):
+        patch = torch.randn(B, H, Wp, C, generator=g).to(dtype).to(DEV)
+        want = full.clone()
+        want[:, :, i * Wp:(i + 1) * Wp] = patch
+        got = df.buffer_refresh_cols(full.clone(), patch, i, N)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(bits), want.view(bits))
+
+
+@pytest.mark.parametrize("B,H,W,Cin,Cout,N,stride,bf16", [
+    (1, 16, 16, 32, 32, 2, 1, False),    # the tiny configuration, split along columns
+    (2, 6, 12, 5, 7, 3, 1, False),       # odd channel counts
+    (1, 8, 16, 8, 12, 4, 2, False),      # stride 2: only the left column is needed
+    (1, 8, 8, 4, 64, 2, 1, True),        # 4 input channels
+    (1, 8, 8, 128, 4, 2, 1, True),       # 4 output channels
+    (2, 12, 16, 64, 96, 4, 1, True),     # MFMA tile path, ragged M and N tiles
+    (1, 24, 16, 96, 64, 4, 2, True),     # MFMA, stride 2
+    (1, 40, 32, 64, 320, 2, 1, True),    # MFMA, several N tiles
+    (1, 128, 128, 320, 320, 4, 1, True), # configuration 3's layer, vertical strips of 32 columns
+])
+def test_conv_halo_columns_all_patches(B, H, W, Cin, Cout, N, stride, bf16):
+    say("conv columns", B, H, W, Cin, Cout, N, stride, bf16)
+    full, stale, w, b = _conv_case(12, B, H, W, Cin, Cout, bf16)
+    Wp = W // N
+    for i in (range(N) if H * W <= 4096 else (0, 1, N - 1)):
+        xf = np.ascontiguousarray(full[:, :, i * Wp:(i + 1) * Wp])
+        ref = ops.conv3x3_halo(xf, stale, w, b, i, N, stride, 1, split_axis=2)
+        y = df.conv3x3_halo_cols(dev(xf, bf16), dev(stale, bf16), dev(w, bf16), dev(b), i, N, stride, 1)
+        check(host(y), ref, bf16, "conv columns patch %d" % i, say=say)
+    # the columns next to the strip matter and nothing else of the stale buffer does
+    i = N - 1 if N > 1 else 0
+    xf = np.ascontiguousarray(full[:, :, i * Wp:(i + 1) * Wp])
+    far = stale.copy()
+    far[:, :, :max(i * Wp - 1, 0)] = 77.0
+    far[:, :, i * Wp:(i + 1) * Wp] = -77.0
+    y0 = df.conv3x3_halo_cols(dev(xf, bf16), dev(stale, bf16), dev(w, bf16), dev(b), i, N, stride, 0)
+    y1 = df.conv3x3_halo_cols(dev(xf, bf16), dev(far, bf16), dev(w, bf16), dev(b), i, N, stride, 0)
+    np.testing.assert_array_equal(host(y0), host(y1))
+
+
+@pytest.mark.parametrize("B,H,W,C,heads,N,patch,bf16", [
+    (1, 16, 16, 32, 1, 2, 0, False),     # the tiny configuration's token grid
+    (2, 6, 9, 128, 2, 3, 1, False),      # d = 64 in float32
+    (1, 16, 32, 128, 2, 4, 2, True),     # bf16 MFMA kernel: 8 own tokens of every 32
+    (2, 10, 60, 64, 1, 4, 3, True),      # ragged tiles, batch 2
+    (1, 40, 60, 192, 3, 4, 1, True),     # level-2 grid of the 1280x1920 image as four vertical strips, split keys
+])
+def test_attention_displaced_columns(B, H, W, C, heads, N, patch, bf16):
+    say("attn columns", B, H, W, C, heads, N, patch, bf16)
+    L, Wp = H * W, W // N
+    rnd = round_bf16 if bf16 else (lambda a: a)
+    kfull, vfull = normal(23, "k", (B, L, C)), normal(23, "v", (B, L, C))
+    own = np.array([r * W + c for r in range(H) for c in range(patch * Wp, (patch + 1) * Wp)])
+    q = rnd(normal(23, "q", (B, len(own), C)))
+    kf, vf = rnd(kfull[:, own].copy()), rnd(vfull[:, own].copy())
+    ks = rnd(kfull + normal(23, "kn", (B, L, C), std=0.5))
+    vs = rnd(vfull + normal(23, "vn", (B, L, C), std=0.5))
+    ref = ops.attn_displaced(q, kf, vf, ks, vs, heads, patch, N, split_axis=2, hw=(H, W))
+    o = df.attn_displaced_cols(dev(q, bf16), dev(kf, bf16), dev(vf, bf16), dev(ks, bf16), dev(vs, bf16), heads, H, W,
+                               patch, N)
+    check(host(o), ref, bf16, "attn columns", say=say)
+    ks2, vs2 = ks.copy(), vs.copy()
+    ks2[:, own], vs2[:, own] = 50.0, -50.0                  # the strip's own tokens of the stale buffers are not read
+    o2 = df.attn_displaced_cols(dev(q, bf16), dev(kf, bf16), dev(vf, bf16), dev(ks2, bf16), dev(vs2, bf16), heads, H, W,
+                                patch, N)
+    np.testing.assert_array_equal(host(o2), host(o))
+    # and the splice matters: as horizontal strips the same buffers give something else
+    far = rel_l2(ops.attn_displaced(q, kf, vf, ks, vs, heads, patch, N), ref)
+    assert far > (5 * TOL_BF16 if bf16 else 1e-3)
+
+
+def test_tiny_block_chain_columns_f32():
+    """The tiny configuration's GroupNorm -> conv3x3 -> attention block on vertical strips."""
+    t = configs.tiny_block()
+    m = t["meta"]
+    H, W, C, N, G = m["H"], m["W"], m["C"], m["N"], m["G"]
+    x, xs = t["x_full"], t["x_full"] + t["stale_noise"]
+    gn_s, _ = ops.groupnorm_stale(xs, ops.group_sums(xs, G)[None], t["gamma"], t["beta"], G, 0, 1, m["eps"])
+    st_stats = ops.patch_group_sums(xs, G, N, axis=2).astype(np.float32)
+    conv_s = ops.conv3x3_full(gn_s, t["conv_w"], t["conv_b"])
+    kv_s = conv_s.reshape(1, H * W, C)
+    Wp = W // N
+    for i in range(N):
+        xf = np.ascontiguousarray(x[:, :, i * Wp:(i + 1) * Wp])
+        r1, _ = ops.groupnorm_stale(xf, st_stats, t["gamma"], t["beta"], G, i, N, m["eps"])
+        r2 = ops.conv3x3_halo(r1, gn_s, t["conv_w"], t["conv_b"], i, N, split_axis=2)
+        tok = r2.reshape(1, H * Wp, C)
+        r3 = ops.attn_displaced(tok, tok, tok, kv_s, kv_s, 1, i, N, split_axis=2, hw=(H, W))
+        g1, _ = df.groupnorm_stale(dev(xf), dev(st_stats), dev(t["gamma"]), dev(t["beta"]), G, i, N, m["eps"])
+        g2 = df.conv3x3_halo_cols(g1, dev(gn_s), dev(t["conv_w"]), dev(t["conv_b"]), i, N)
+        gt = g2.reshape(1, H * Wp, C)
+        g3 = df.attn_displaced_cols(gt, gt, gt, dev(kv_s), dev(kv_s), 1, H, W, i, N)
+        for nm, g, r in (("gn", g1, r1), ("conv", g2, r2), ("attn", g3, r3)):
+            check(host(g), r.reshape(host(g).shape), False, "tiny block columns patch %d %s" % (i, nm), say=say)
