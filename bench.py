@@ -323,6 +323,7 @@ def main():
                          "is that configuration as stated")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run plain copies of this many MiB through the library's copy kernel (counter calibration)")
+    ap.add_argument("--all-kernels", action="store_true", help="list every kernel of the step in `top_kernels`, not the top 8")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -473,7 +474,7 @@ def main():
         cls_roof["traffic_from_profile"] = {"bytes_per_launch": round(tr / (d["launches"] / args.profile_steps)),
                                             "source": TRAFFIC_PROFILE}
     roofline["kernel_class"] = cls_roof
-    top = sorted(kernels, key=lambda kr: -kr["ms"])[:8]
+    top = sorted(kernels, key=lambda kr: -kr["ms"])[:(None if args.all_kernels else 8)]
     top_kernels = [dict(kernel=kr["label"], ms_per_step=round(kr["ms"] / args.profile_steps, 4),
                         launches_per_step=kr["launches"] // args.profile_steps,
                         tflops=round(kr["flops"] / (kr["ms"] * 1e-3) / 1e12, 1) if kr["flops"] else None,

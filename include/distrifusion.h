@@ -102,7 +102,7 @@ int df_groupnorm_stale(const void* x_fresh, void* y, const float* stale_stats, f
  * loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but the statistics pass keeps
  * its partial sums in a fixed array of DF_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every GPU
  * the library runs on holds it until the process ends) instead of the library's allocated scratch.  The call never
- * allocates or frees.  Shapes whose partial sums do not fit (roughly B * G > 120) return DF_ENOMEM and launch nothing.
+ * allocates or frees.  Shapes whose partial sums do not fit (roughly B * G > 1000) return DF_ENOMEM and launch nothing.
  * All calls on one GPU share the array: calls that overlap on one GPU (different streams) race; issue them from
  * one stream at a time.  The array keeps the previous call's contents; nothing in it has to start at zero.
  */

@@ -68,7 +68,11 @@ __device__ __forceinline__ int key_of_mfma_row(int rho) {
   return 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
 }
 
+// PERIODIC: the fresh keys are a vertical strip of the token grid (own_period > 0); a separate instantiation, so that
+// the contiguous split keeps its tile-level fast paths and carries none of the per-key index arithmetic.
+template <bool PERIODIC>
 __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
+  const int period = PERIODIC ? p.own_period : 0;
   constexpr int D = 64, TK = 64;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[2][TK * D];   // [key][d], 16-byte chunks XOR-swizzled by row
   __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * TK];   // [d][key], swizzled
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
   auto load_tile = [&](int t, auto slot) {
     constexpr int S = decltype(slot)::value;
     const int base = kv_lo + t * TK;
-    if (base + TK <= kv_hi && p.own_period == 0) {         // (uniform) a full tile of a contiguous split
+    if (!PERIODIC && base + TK <= kv_hi) {         // (uniform) a full tile of a contiguous split
       const int rel = base - p.own_lo;
       if (rel >= 0 && rel + TK <= p.own_n) {               // all rows fresh
         const bf16_t* kb = kf + (long long)rel * p.ldkf;
@@ -164,10 +168,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int jk = base + ld_key + 32 * i;
-      kreg[S][i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, p.own_period, jk) + ld_ch * 8)
+      kreg[S][i] = jk < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(kf, ks, p.ldkf, p.ldks, p.own_lo, p.own_n, period, jk) + ld_ch * 8)
                               : zero4;
       const int jv = base + 2 * ld_key + i;
-      vreg[S][i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, p.own_period, jv) + ld_ch * 8)
+      vreg[S][i] = jv < kv_hi ? *reinterpret_cast<const u32x4*>(key_row(vf, vs, p.ldvf, p.ldvs, p.own_lo, p.own_n, period, jv) + ld_ch * 8)
                               : zero4;
     }
   };
@@ -819,7 +823,8 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   } else {
     // 32-bit row offsets inside a 64-key tile
     if (a.ldkf >= (1 << 24) || a.ldvf >= (1 << 24) || a.ldks >= (1 << 24) || a.ldvs >= (1 << 24)) return DF_ESHAPE;
-    hipLaunchKernelGGL(attn_bf16_d64, dim3((unsigned)nwg), dim3(256), 0, st, p);
+    if (a.own_period > 0) hipLaunchKernelGGL(attn_bf16_d64<true>, dim3((unsigned)nwg), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(attn_bf16_d64<false>, dim3((unsigned)nwg), dim3(256), 0, st, p);
   }
   DF_LAUNCH_CHECK();
   if (ns > 1) {

@@ -1,14 +1,16 @@
 // Corrected asynchronous GroupNorm (Section 4, Eq. 2) for channels-last patches.
 //
-// Three launches, the two big ones HBM-bound streaming passes with 16-byte accesses:
+// Large tensors take two launches, both streaming passes with 16-byte accesses:
 //   gn_stats     every block sums a strip of pixels into per-group (sum, sum of
-//                squares) partials.
-//   gn_finalize  one workgroup per batch item adds the partials in a fixed order,
-//                emits the fresh per-patch sums, combines them with the stale sums
-//                of the other patches according to the statistic mode and stores
-//                mean / rstd (and refreshes the patch's slot of the cache).
-//   gn_apply     y = (x - mean) * rstd * gamma + beta (+ SiLU); the second read of
-//                x comes from L2 / Infinity Cache at the sizes of one patch.
+//                squares) partials; one block also snapshots the cached sums.
+//   gn_apply     every block first adds all partials in the same fixed order (so
+//                all blocks hold bit-identical statistics without a third launch or
+//                a grid-wide wait: an in-kernel barrier across the eight XCDs costs
+//                more than a kernel boundary here), combines them with the stale
+//                sums of the other patches according to the statistic mode, then
+//                y = (x - mean) * rstd * gamma + beta (+ SiLU) on the strip it summed
+//                in the first launch; block 0 also emits the fresh per-patch sums.
+// Small tensors take one launch, one workgroup per (group, batch item).
 // A lane keeps a fixed channel offset for its whole strip, so gamma/beta and
 // the statistics are fetched once per lane.
 //
@@ -26,7 +28,10 @@ namespace df {
 namespace {
 
 constexpr int kMaxG = 64;
-constexpr long long kGnGroupMaxElems = 80 * 1024;   // per (group, batch item): above this the three-kernel path
+constexpr long long kGnGroupMaxElems = 24 * 1024;   // per (group, batch item): above this the two-launch path (unless
+                                                    // the patch fits the registers of one workgroup per group)
+constexpr int kGnMaxPpb = 32;                      // pixels a block of that path handles per iteration, at most
+constexpr int kGnMaxStrips = 256;                   // pixel strips (= blocks per launch) per batch item on that path
 
 struct GnHalo {
   bf16_t* out;      // nullptr: no boundary-row copy
@@ -66,6 +71,21 @@ __device__ __forceinline__ void halo_store(const GnHalo& h, int b, long long p, 
   }
 }
 
+// NCH (template parameter of the two-launch kernels): 16-byte loads a lane keeps in flight, 1, 2, 4 or 8
+
+// 16 bytes as loaded -> kVec float values
+template <typename T>
+__device__ __forceinline__ void unpack_vec(const u32x4& t, float* v) {
+  if constexpr (sizeof(T) == 4) {
+    v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+  } else {
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+    v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u);
+    v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
+  }
+}
+
 struct GnLayout {
   int tp;        // lanes per pixel (C / vec)
   int ppb;       // pixels per block iteration
@@ -74,56 +94,108 @@ struct GnLayout {
   int pix_per_blk;
 };
 
-template <typename Tin>
+template <typename Tin, int NCH>
 __global__ void gn_stats(const Tin* __restrict__ x, float* __restrict__ partial, int pix_seg, int C, int G, int tp,
-                         int ppb, int pix_per_blk, int nseg) {
+                         int ppb, int pix_per_blk, int nseg, const float* stale, float* __restrict__ stale_copy,
+                         int stale_n) {
   constexpr int V = Elem<Tin>::kVec;
-  __shared__ float s_sum[kMaxG], s_sq[kMaxG];
+  __shared__ float s_sum[kMaxG], s_sq[kMaxG], s_piv[kMaxG];
   const int blk = blockIdx.x, seg = blockIdx.y, b = blockIdx.z;
   const int nblk = gridDim.x;
   const int cg = C / G;
   const int tid = threadIdx.x;
-  if (tid < G) { s_sum[tid] = 0.f; s_sq[tid] = 0.f; }
-  __syncthreads();
-
   const int c0 = (tid % tp) * V;
   const int psub = tid / tp;
   const long long seg_base = ((long long)b * nseg + seg) * pix_seg;
   const int p_lo = blk * pix_per_blk;
   int p_hi = p_lo + pix_per_blk;
   if (p_hi > pix_seg) p_hi = pix_seg;
+  // a lane requests NCH pixels at once (a strip is usually one chunk: the whole tensor is in flight together);
+  // the first chunk goes out before anything else
+  u32x4 raw[NCH];
+#pragma unroll
+  for (int k = 0; k < NCH; ++k) {
+    const int p = p_lo + psub + k * ppb;
+    raw[k] = *reinterpret_cast<const u32x4*>(x + (seg_base + (p < p_hi ? p : p_lo)) * C + c0);
+  }
+  if (tid < G) s_piv[tid] = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + tid * cg);   // the groups' pivots
+  // The second launch may overwrite the patch's own slot of the cached sums (in-place refresh) while other blocks of
+  // it still need the old value: it reads this snapshot instead.
+  if (stale != nullptr && blk == 0 && seg == 0 && b == 0)
+    for (int i = tid; i < stale_n; i += blockDim.x) stale_copy[i] = stale[i];
+  __syncthreads();
+
+  const int ga = c0 / cg;                       // group of the lane's first channel
   float s[V], q[V], piv[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     s[i] = 0.f; q[i] = 0.f;
-    piv[i] = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + ((c0 + i) / cg) * cg);   // the group's pivot
+    piv[i] = s_piv[cg >= V ? (c0 + i >= (ga + 1) * cg ? ga + 1 : ga) : (c0 + i) / cg];
   }
-#pragma unroll 4
-  for (int p = p_lo + psub; p < p_hi; p += ppb) {
-    float v[V];
-    ld_vec(x + (seg_base + p) * C + c0, v);
+  for (int p0 = p_lo + psub; p0 < p_hi; p0 += NCH * ppb) {
+    if (p0 != p_lo + psub) {
 #pragma unroll
-    for (int i = 0; i < V; ++i) { const float d = v[i] - piv[i]; s[i] += d; q[i] = fmaf(d, d, q[i]); }
+      for (int k = 0; k < NCH; ++k) {
+        const int p = p0 + k * ppb;
+        raw[k] = *reinterpret_cast<const u32x4*>(x + (seg_base + (p < p_hi ? p : p0)) * C + c0);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      if (p0 + k * ppb >= p_hi) break;
+      float v[V];
+      unpack_vec<Tin>(raw[k], v);
+#pragma unroll
+      for (int i = 0; i < V; ++i) { const float d = v[i] - piv[i]; s[i] += d; q[i] = fmaf(d, d, q[i]); }
+    }
   }
   // Ordered fold of the lanes' per-channel sums into groups (no atomics: the result must not depend on timing -
   // the UNet amplifies even one-ulp differences of a statistic to the level of its bf16 rounding noise).
-  extern __shared__ float s_lane[];            // [2][V][blockDim.x]: per-channel-slot sums of every lane
+  // Two levels: thread (g, ps) adds group g's channels over the lanes of pixel slot ps, then thread g adds the slots.
+  extern __shared__ float s_lane[];            // fast path: float4 per lane; general path: [V][blockDim.x]
+  __shared__ float s_lvl[2][kGnMaxPpb][kMaxG];
   const int nthr = blockDim.x;
+  if (cg >= V) {
+    // a lane's V consecutive channels touch at most two groups: it leaves (sum, sum of squares) of the part in its
+    // first group and of the part in the next one
+    f32x4 mine = {0.f, 0.f, 0.f, 0.f};
+    const int nb = (ga + 1) * cg - c0;          // channels of the lane that belong to group ga
 #pragma unroll
-  for (int i = 0; i < V; ++i) {
-    s_lane[i * nthr + tid] = s[i];
-    s_lane[(V + i) * nthr + tid] = q[i];
+    for (int i = 0; i < V; ++i) {
+      if (i < nb) { mine.x += s[i]; mine.y += q[i]; } else { mine.z += s[i]; mine.w += q[i]; }
+    }
+    reinterpret_cast<f32x4*>(s_lane)[tid] = mine;
+    __syncthreads();
+    for (int role = tid; role < G * ppb; role += nthr) {
+      const int fg = role % G, fps = role / G;
+      const int t_lo = (fg * cg) / V, t_hi = ((fg + 1) * cg - 1) / V;
+      float as = 0.f, aq = 0.f;
+      for (int tc = t_lo; tc <= t_hi; ++tc) {
+        const f32x4 e = reinterpret_cast<const f32x4*>(s_lane)[fps * tp + tc];
+        if ((tc * V) / cg == fg) { as += e.x; aq += e.y; } else { as += e.z; aq += e.w; }
+      }
+      s_lvl[0][fps][fg] = as;
+      s_lvl[1][fps][fg] = aq;
+    }
+    __syncthreads();
+  } else {
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) s_lane[i * nthr + tid] = pass ? q[i] : s[i];
+      __syncthreads();
+      for (int role = tid; role < G * ppb; role += nthr) {
+        const int fg = role % G, fps = role / G;
+        float acc = 0.f;
+        for (int ch = fg * cg; ch < (fg + 1) * cg; ++ch) acc += s_lane[(ch % V) * nthr + fps * tp + ch / V];
+        s_lvl[pass][fps][fg] = acc;
+      }
+      __syncthreads();
+    }
   }
-  __syncthreads();
   if (tid < G) {
     float ss = 0.f, qq = 0.f;
-    for (int ch = tid * cg; ch < (tid + 1) * cg; ++ch) {
-      const int tcol = ch / V, i = ch % V;
-      for (int ps = 0; ps < ppb; ++ps) {
-        ss += s_lane[i * nthr + ps * tp + tcol];
-        qq += s_lane[(V + i) * nthr + ps * tp + tcol];
-      }
-    }
+    for (int ps = 0; ps < ppb; ++ps) { ss += s_lvl[0][ps][tid]; qq += s_lvl[1][ps][tid]; }
     s_sum[tid] = ss;
     s_sq[tid] = qq;
   }
@@ -214,125 +286,130 @@ __device__ __forceinline__ void gn_stale_wave(const float* stale, int b, int g, 
   }
 }
 
-// One workgroup per batch item: adds the partials in a fixed order, emits the fresh per-patch sums, combines them with
-// the stale sums of the other patches according to the statistic mode and stores mean / rstd.  A separate launch
-// instead of a "last workgroup" epilogue: the device-scope fences that pattern needs cost more than the launch.
-template <typename Tin>
-__global__ __launch_bounds__(1024) void gn_finalize(const float* __restrict__ partial, float* __restrict__ meanrstd,
-                                                    const float* stale, float* sums_out, const Tin* __restrict__ x,
-                                                    int pix_seg, int C, int G, int nblk, int nseg, int B, int patch_idx,
-                                                    int N, float eps, int stat_mode) {
+// Second launch of the large path.  Every block adds the partials of its batch item in the same fixed order, combines
+// them with the cached sums and normalises the strip of pixels it was given.
+template <typename Tin, typename Tout, int NCH>
+__global__ __launch_bounds__(1024) void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y,
+                                                 const float* __restrict__ partial, const float* __restrict__ stale_copy,
+                                                 float* sums_out, const float* __restrict__ gamma,
+                                                 const float* __restrict__ beta, int pix_seg, int C, int G, int nblk,
+                                                 int nseg, int B, int patch_idx, int N, float eps, int stat_mode, int tp,
+                                                 int ppb, int pix_per_blk, int silu, int packed, GnHalo halo) {
+  constexpr int V = Elem<Tin>::kVec;
   __shared__ float s_red[2][32][kMaxG];
-  const int b = blockIdx.x;
+  __shared__ float s_mom[kMaxG][3];
+  const int blk = blockIdx.x, seg = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int cg = C / G;
-  const int parts = blockDim.x / G < 32 ? blockDim.x / G : 32;
-  const int g = tid % G, part = tid / G;
-  double tot_s = 0.0, tot_q = 0.0;  // sums of x over all segments (valid on part == 0 lanes)
-  // the partials are sums of x - pivot, the pivot being the group's first value of the batch item
-  const float piv = Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + g * cg);
-  const double n_seg = (double)pix_seg * (double)cg;
-  for (int sg = 0; sg < nseg; ++sg) {
-    float a = 0.f, c = 0.f;
-    if (part < parts) {
-      const float* base = partial + (((long long)b * nseg + sg) * nblk) * G * 2;
-      // 16 partials per trip are requested together (one memory round trip), then added in index order
-      for (int k0 = part; k0 < nblk; k0 += 16 * parts) {
-        float2 v[16];
+  // The lane's first NCH pixels are requested before anything else: the fold of the partials below then runs
+  // while they are on their way (usually that is the lane's whole share of the strip).
+  const bool works = tid < tp * ppb;
+  const int c0 = (tid % tp) * V;
+  const int psub = tid / tp;
+  const long long base = ((long long)b * nseg + seg) * pix_seg;     // pixels before this segment
+  const int p_lo = blk * pix_per_blk;
+  int p_hi = p_lo + pix_per_blk;
+  if (p_hi > pix_seg) p_hi = pix_seg;
+  u32x4 raw[NCH];
+  if (works) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int k = k0 + i * parts;
-          v[i] = k < nblk ? *reinterpret_cast<const float2*>(base + ((long long)k * G + g) * 2) : make_float2(0.f, 0.f);
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { a += v[i].x; c += v[i].y; }
-      }
-      s_red[0][part][g] = a;
-      s_red[1][part][g] = c;
+    for (int k = 0; k < NCH; ++k) {
+      const int p = p_lo + psub + k * ppb;
+      raw[k] = *reinterpret_cast<const u32x4*>(x + (base + (p < p_hi ? p : p_lo)) * C + c0);
     }
-    __syncthreads();
-    if (part == 0) {
-      float fs = 0.f, fq = 0.f;
-      for (int k = 0; k < parts; ++k) { fs += s_red[0][k][g]; fq += s_red[1][k][g]; }
-      double S, SS;
-      gn_unshift(fs, fq, n_seg, piv, S, SS);
-      tot_s += S; tot_q += SS;
-      if (nseg > 1) {
-        float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
-        o[0] = (float)S; o[1] = (float)SS;
-      }
-    }
-    __syncthreads();
   }
-  // the cached sums of the other patches: thread (part, g) fetches patch part's entry of group g (one round trip for
-  // all patches), thread (0, g) adds them in patch order
-  const bool need_stale = !(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE));
-  double st_s = 0.0, st_q = 0.0, own_s = 0.0, own_q = 0.0;
-  if (need_stale) {
-    for (int j0 = 0; j0 < N; j0 += parts) {
-      __syncthreads();
-      if (part < parts && j0 + part < N) {
-        const float* sp = stale + (((long long)(j0 + part) * B + b) * G + g) * 2;
-        s_red[0][part][g] = sp[0];
-        s_red[1][part][g] = sp[1];
+  {
+    const int parts = (int)blockDim.x / G < 32 ? (int)blockDim.x / G : 32;
+    const int g = tid % G, part = tid / G;
+    const bool folds = part < parts;
+    double tot_s = 0.0, tot_q = 0.0;  // sums of x over all segments (valid where part == 0)
+    // the partials are sums of x - pivot, the pivot being the group's first value of the batch item
+    const float piv = folds ? Elem<Tin>::ld(x + (long long)b * nseg * pix_seg * C + g * cg) : 0.f;
+    const double n_seg = (double)pix_seg * (double)cg;
+    for (int sg = 0; sg < nseg; ++sg) {
+      float a = 0.f, c = 0.f;
+      if (folds) {
+        const float* base = partial + (((long long)b * nseg + sg) * nblk) * G * 2;
+        // 8 partials per trip are requested together (one memory round trip), then added in index order
+        for (int k0 = part; k0 < nblk; k0 += 8 * parts) {
+          float2 v[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int k = k0 + i * parts;
+            v[i] = k < nblk ? *reinterpret_cast<const float2*>(base + ((long long)k * G + g) * 2) : make_float2(0.f, 0.f);
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) { a += v[i].x; c += v[i].y; }
+        }
+        s_red[0][part][g] = a;
+        s_red[1][part][g] = c;
       }
       __syncthreads();
       if (part == 0) {
-        const int n = N - j0 < parts ? N - j0 : parts;
-        for (int j = 0; j < n; ++j) {
-          const float a = s_red[0][j][g], c = s_red[1][j][g];
-          if (j0 + j == patch_idx) { own_s = a; own_q = c; } else { st_s += a; st_q += c; }
+        float fs = 0.f, fq = 0.f;
+        for (int k = 0; k < parts; ++k) { fs += s_red[0][k][g]; fq += s_red[1][k][g]; }
+        double S, SS;
+        gn_unshift(fs, fq, n_seg, piv, S, SS);
+        tot_s += S; tot_q += SS;
+        if (nseg > 1 && blk == 0 && seg == 0) {        // full image: the per-patch sums are the cache's new content
+          float* o = sums_out + (((long long)sg * B + b) * G + g) * 2;
+          o[0] = (float)S; o[1] = (float)SS;
         }
       }
+      __syncthreads();
     }
+    if (part == 0) {
+      double st_s = 0.0, st_q = 0.0, own_s = 0.0, own_q = 0.0;
+      if (!(nseg > 1 || (N == 1 && stat_mode != DF_GN_STALE))) {
+        for (int j = 0; j < N; ++j) {                  // patch order fixes the order of the additions
+          const float* sp = stale_copy + (((long long)j * B + b) * G + g) * 2;
+          const float av = sp[0], cv = sp[1];
+          if (j == patch_idx) { own_s = av; own_q = cv; } else { st_s += av; st_q += cv; }
+        }
+      }
+      const GnMoments mo = gn_combine_pre(tot_s, tot_q, n_seg, nseg, N, stat_mode, st_s, st_q, own_s, own_q, eps);
+      if (nseg == 1 && sums_out != nullptr && blk == 0) {   // may alias the patch's slot of the cache: every block reads
+        float* o = sums_out + ((long long)b * G + g) * 2;   // the snapshot, never the cache itself
+        o[0] = (float)tot_s; o[1] = (float)tot_q;
+      }
+      s_mom[g][0] = mo.mean_hi; s_mom[g][1] = mo.mean_lo; s_mom[g][2] = mo.rstd;
+    }
+    __syncthreads();
   }
-  if (part != 0) return;
-  const GnMoments mo = gn_combine_pre(tot_s, tot_q, n_seg, nseg, N, stat_mode, st_s, st_q, own_s, own_q, eps);
-  if (nseg == 1 && sums_out != nullptr) {  // written after the stale sums were read: may alias the own slot
-    float* o = sums_out + ((long long)b * G + g) * 2;
-    o[0] = (float)tot_s; o[1] = (float)tot_q;
-  }
-  float* mr = meanrstd + ((long long)b * G + g) * 4;
-  mr[0] = mo.mean_hi; mr[1] = mo.mean_lo; mr[2] = mo.rstd;
-}
-
-template <typename Tin, typename Tout>
-__global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const float* __restrict__ meanrstd,
-                         const float* __restrict__ gamma, const float* __restrict__ beta, int pix_b, int C, int G,
-                         int tp, int ppb, int pix_per_blk, int silu, int packed, GnHalo halo) {
-  constexpr int V = Elem<Tin>::kVec;
-  const int b = blockIdx.y;
-  const int tid = threadIdx.x;
-  const int c0 = (tid % tp) * V;
-  const int psub = tid / tp;
-  const int cg = C / G;
+  if (!works) return;
   float sc[V], sh[V], mh[V], ml[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) {
     const int c = c0 + i;
     const int g = c / cg;
-    const float* mr = meanrstd + ((long long)b * G + g) * 4;
-    mh[i] = mr[0]; ml[i] = mr[1];
-    sc[i] = mr[2] * gamma[c];
+    mh[i] = s_mom[g][0]; ml[i] = s_mom[g][1];
+    sc[i] = s_mom[g][2] * gamma[c];
     sh[i] = beta[c];
   }
-  const long long base = (long long)b * pix_b;
-  const int p_lo = blockIdx.x * pix_per_blk;
-  int p_hi = p_lo + pix_per_blk;
-  if (p_hi > pix_b) p_hi = pix_b;
-  for (int p = p_lo + psub; p < p_hi; p += ppb) {
+  for (int p0 = p_lo + psub; p0 < p_hi; p0 += NCH * ppb) {
+    if (p0 != p_lo + psub) {                   // further chunks of a long strip
+#pragma unroll
+      for (int k = 0; k < NCH; ++k) {
+        const int p = p0 + k * ppb;
+        raw[k] = *reinterpret_cast<const u32x4*>(x + (base + (p < p_hi ? p : p0)) * C + c0);
+      }
+    }
+#pragma unroll
+   for (int k = 0; k < NCH; ++k) {
+    const int p = p0 + k * ppb;
+    if (p >= p_hi) break;
     float v[V];
-    ld_vec(x + (base + p) * C + c0, v);
+    unpack_vec<Tin>(raw[k], v);
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       float t = fmaf((v[i] - mh[i]) - ml[i], sc[i], sh[i]);
       v[i] = silu ? silu_f(t) : t;
     }
-    Tout* o = y + (base + p) * C + c0;
+    const long long m = base + p;
+    Tout* o = y + m * C + c0;
     if (packed) {
-      // fragment-packed bf16 operand of the linear layers: pixel m = base + p is row m%32 of fragment row m/32, the
+      // fragment-packed bf16 operand of the linear layers: pixel m is row m%32 of fragment row m/32, the
       // 8 channels from c0 & ~7 sit in slot (m%32) + 32*((c0/8)%2) of fragment column c0/16
-      const long long m = base + p;
       o = y + (((m >> 5) * (C >> 4) + (c0 >> 4)) * 64 + (m & 31) + 32 * ((c0 >> 3) & 1)) * 8 + (c0 & 7);
     }
     if constexpr (sizeof(Tout) == sizeof(Tin)) {
@@ -342,8 +419,9 @@ __global__ void gn_apply(const Tin* __restrict__ x, Tout* __restrict__ y, const 
       *reinterpret_cast<u32x2*>(o) = t;
     }
     if constexpr (sizeof(Tout) == 2) {
-      if (halo.out) halo_store<V>(halo, b, p, C, c0, v);
+      if (halo.out) halo_store<V>(halo, b, (long long)seg * pix_seg + p, C, c0, v);
     }
+   }
   }
 }
 
@@ -549,15 +627,19 @@ __global__ __launch_bounds__(1024) void gn_group_reg_kernel(const Tin* __restric
   }
 }
 
-GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_threads) {
+// Strips of the two-launch path: as close to target_blocks strips as the pixel count allows (the chip has 256
+// compute units and a strip is one block in either launch); a small tensor gets short strips and blocks with few
+// pixel slots rather than few blocks.
+GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_threads, int min_threads) {
   GnLayout L;
   L.tp = C / vec;
+  long long per = (pix + target_blocks - 1) / target_blocks;
   L.ppb = max_threads / L.tp;
+  if (L.ppb > kGnMaxPpb) L.ppb = kGnMaxPpb;
+  if (L.ppb > per) L.ppb = (int)per;
+  if (L.ppb * L.tp < min_threads) L.ppb = (min_threads + L.tp - 1) / L.tp;   // the kernels give every group a thread
   if (L.ppb < 1) L.ppb = 1;
   L.threads = L.tp * L.ppb;
-  long long per = (pix + target_blocks - 1) / target_blocks;
-  long long min_per = (long long)L.ppb * 4;
-  if (per < min_per) per = min_per;
   per = (per + L.ppb - 1) / L.ppb * L.ppb;
   L.pix_per_blk = (int)per;
   L.nblk = (int)((pix + per - 1) / per);
@@ -566,9 +648,10 @@ GnLayout gn_layout(int C, int vec, long long pix, int target_blocks, int max_thr
 
 }  // namespace
 
-size_t groupnorm_scratch_bytes(int B, int nseg, int G) {
-  // partials for at most 2048 blocks per batch item + mean/rstd
-  return kScratchCounterBytes + ((size_t)B * 2048 * G * 2 + (size_t)B * G * 4) * sizeof(float) + 1024;
+size_t groupnorm_scratch_bytes(int B, int nseg, int G, int N) {
+  // snapshot of the cached sums + partials of at most kGnMaxStrips strips per batch item
+  (void)nseg;
+  return kScratchCounterBytes + ((size_t)B * kGnMaxStrips * G * 2 + (size_t)N * B * G * 2 + 64) * sizeof(float) + 1024;
 }
 
 int launch_groupnorm(const GnArgs& a, hipStream_t st) {
@@ -593,10 +676,11 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
     const int cg = a.C / a.G;
     const long long per_group = pix_seg * a.nseg * cg;
     static const bool no_fused = tune_env("DF_GN_3K") != nullptr;   // tuning aid
-    if (!no_fused && cg % 4 == 0 && cg / 4 <= 1024 && per_group <= kGnGroupMaxElems) {
+    const int ppass = (cg % 4 == 0 && cg / 4 <= 1024) ? 1024 / (cg / 4) : 0;
+    const bool fits_regs = a.nseg == 1 && pix_seg <= (long long)ppass * 8;
+    if (!no_fused && cg % 4 == 0 && cg / 4 <= 1024 && (fits_regs || per_group <= kGnGroupMaxElems)) {
       dim3 grid(a.G, a.B);
-      const int ppass = 1024 / (cg / 4);
-      if (a.nseg == 1 && pix_seg <= (long long)ppass * 8) {
+      if (fits_regs) {
         // one patch, at most 8 pixels per lane: single read of x
 #define DF_GN_REG(TI, TO)                                                                                             \
   hipLaunchKernelGGL((gn_group_reg_kernel<TI, TO, 8>), grid, dim3(1024), 0, st, (const TI*)a.x, (TO*)a.y, a.stale,     \
@@ -621,44 +705,43 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
       return DF_OK;
     }
   }
-  // up to 512 partial blocks per batch item: the finalize workgroup folds them with 32 lanes per group
-  int target = 512 / a.nseg;
+  // Both launches use the same partition of the pixels into strips, at most kGnMaxStrips per batch item: every block
+  // of the second launch reads all partials of its batch item, so their number is bounded, and a block normalises
+  // the strip whose sums it (or a block on the same XCD) took, which is then still in that XCD's L2 for tensors of a
+  // few MB per XCD.
+  int target = kGnMaxStrips / a.nseg;
   if (target < 1) target = 1;
-  GnLayout L = gn_layout(a.C, vec, pix_seg, target, 256);
-  if ((long long)L.nblk * a.nseg > 2048) return DF_ESHAPE;
-  if (L.threads < a.G) return DF_ESHAPE;
-  char* scr = scratch_region(a.scr, groupnorm_scratch_bytes(a.B, a.nseg, a.G));
+  GnLayout L = gn_layout(a.C, vec, pix_seg, target, 1024, a.G);
+  if (L.threads > 1024 || L.ppb > kGnMaxPpb) return DF_ESHAPE;
+  char* scr = scratch_region(a.scr, groupnorm_scratch_bytes(a.B, a.nseg, a.G, a.N));
   if (!scr) return DF_ENOMEM;
-  float* meanrstd = (float*)(scr + kScratchCounterBytes);
-  float* partial = meanrstd + (size_t)a.B * a.G * 4;
+  const bool need_stale = !(a.nseg > 1 || (a.N == 1 && a.stat_mode != DF_GN_STALE));
+  const int stale_n = need_stale ? a.N * a.B * a.G * 2 : 0;
+  float* stale_copy = (float*)(scr + kScratchCounterBytes);
+  float* partial = stale_copy + (((size_t)a.N * a.B * a.G * 2 + 63) / 64) * 64;
   dim3 gs(L.nblk, a.nseg, a.B);
-  if (a.in_dtype == DF_BF16)
-    hipLaunchKernelGGL(gn_stats<bf16_t>, gs, dim3(L.threads), (size_t)2 * 8 * L.threads * sizeof(float), st, (const bf16_t*)a.x, partial, (int)pix_seg, a.C, a.G,
-                       L.tp, L.ppb, L.pix_per_blk, a.nseg);
-  else
-    hipLaunchKernelGGL(gn_stats<float>, gs, dim3(L.threads), (size_t)2 * 4 * L.threads * sizeof(float), st, (const float*)a.x, partial, (int)pix_seg, a.C, a.G,
-                       L.tp, L.ppb, L.pix_per_blk, a.nseg);
-  DF_LAUNCH_CHECK();
-  if (a.in_dtype == DF_BF16)
-    hipLaunchKernelGGL(gn_finalize<bf16_t>, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out,
-                       (const bf16_t*)a.x, (int)pix_seg, a.C, a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
-  else
-    hipLaunchKernelGGL(gn_finalize<float>, dim3(a.B), dim3(1024), 0, st, partial, meanrstd, a.stale, a.sums_out,
-                       (const float*)a.x, (int)pix_seg, a.C, a.G, L.nblk, a.nseg, a.B, a.patch_idx, a.N, a.eps, a.stat_mode);
-  DF_LAUNCH_CHECK();
-  const long long pix_b = pix_seg * a.nseg;
-  GnLayout A = gn_layout(a.C, vec, pix_b, 2048, 256);
-  dim3 ga(A.nblk, a.B);
-  if (a.in_dtype == DF_BF16) {
-    hipLaunchKernelGGL((gn_apply<bf16_t, bf16_t>), ga, dim3(A.threads), 0, st, (const bf16_t*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
-  } else if (a.out_dtype == DF_BF16) {
-    hipLaunchKernelGGL((gn_apply<float, bf16_t>), ga, dim3(A.threads), 0, st, (const float*)a.x, (bf16_t*)a.y,
-                       meanrstd, a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
-  } else {
-    hipLaunchKernelGGL((gn_apply<float, float>), ga, dim3(A.threads), 0, st, (const float*)a.x, (float*)a.y, meanrstd,
-                       a.gamma, a.beta, (int)pix_b, a.C, a.G, A.tp, A.ppb, A.pix_per_blk, a.silu, a.y_packed, halo);
+  const size_t lds = (size_t)vec * L.threads * sizeof(float);
+  const int thr_apply = L.threads < a.G ? a.G : L.threads;   // the fold needs a lane per group
+  const int iters = L.pix_per_blk / L.ppb;              // pixels per lane and strip
+#define DF_GN_STATS(TI, NCHV)                                                                                         \
+  hipLaunchKernelGGL((gn_stats<TI, NCHV>), gs, dim3(L.threads), lds, st, (const TI*)a.x, partial, (int)pix_seg, a.C,  \
+                     a.G, L.tp, L.ppb, L.pix_per_blk, a.nseg, need_stale ? a.stale : nullptr, stale_copy, stale_n)
+#define DF_GN_APPLY(TI, TO, NCHV)                                                                                     \
+  hipLaunchKernelGGL((gn_apply<TI, TO, NCHV>), gs, dim3(thr_apply), 0, st, (const TI*)a.x, (TO*)a.y, partial,         \
+                     stale_copy, a.sums_out, a.gamma, a.beta, (int)pix_seg, a.C, a.G, L.nblk, a.nseg, a.B, a.patch_idx, \
+                     a.N, a.eps, a.stat_mode, L.tp, L.ppb, L.pix_per_blk, a.silu, a.y_packed, halo)
+#define DF_GN_BOTH(NCHV)                                                                                              \
+  {                                                                                                                   \
+    if (a.in_dtype == DF_BF16) DF_GN_STATS(bf16_t, NCHV); else DF_GN_STATS(float, NCHV);                              \
+    DF_LAUNCH_CHECK();                                                                                                \
+    if (a.in_dtype == DF_BF16) DF_GN_APPLY(bf16_t, bf16_t, NCHV);                                                     \
+    else if (a.out_dtype == DF_BF16) DF_GN_APPLY(float, bf16_t, NCHV);                                                \
+    else DF_GN_APPLY(float, float, NCHV);                                                                             \
   }
+  if (iters <= 1) DF_GN_BOTH(1) else if (iters <= 2) DF_GN_BOTH(2) else if (iters <= 4) DF_GN_BOTH(4) else DF_GN_BOTH(8)
+#undef DF_GN_BOTH
+#undef DF_GN_APPLY
+#undef DF_GN_STATS
   DF_LAUNCH_CHECK();
   return DF_OK;
 }
@@ -715,8 +798,9 @@ int df_groupnorm_stale_noalloc(const void* x_fresh, void* y, const float* stale_
                                const float* gamma, const float* beta, int B, int R, int W, int C, int G, int patch_idx,
                                int N, float eps, int stat_mode, int fuse_silu, int dtype, void* stream) {
   if (B <= 0 || G <= 0) return DF_ESHAPE;
-  // the statistics pass keeps up to 2048 partial (sum, sum of squares) pairs per batch item and group
-  if (df::groupnorm_scratch_bytes(B, 1, G) > kStaticScratchBytes) return DF_ENOMEM;
+  // the statistics pass keeps up to 256 partial (sum, sum of squares) pairs per batch item and group, plus a snapshot
+  // of the cached sums
+  if (N <= 0 || df::groupnorm_scratch_bytes(B, 1, G, N) > kStaticScratchBytes) return DF_ENOMEM;
   df::Scratch region = {nullptr, 0};
   const int rc = static_scratch_region(&region);
   if (rc != DF_OK) return rc;

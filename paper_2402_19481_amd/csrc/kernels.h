@@ -59,7 +59,7 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st);
 int groupnorm_entry(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out, const float* gamma,
                     const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N, float eps, int stat_mode,
                     int fuse_silu, int dtype, const Scratch* scr, hipStream_t st);
-size_t groupnorm_scratch_bytes(int B, int nseg, int G);
+size_t groupnorm_scratch_bytes(int B, int nseg, int G, int N);
 
 // ---- conv.hip / gemm ----
 struct ConvArgs {

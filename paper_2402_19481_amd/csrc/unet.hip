@@ -440,7 +440,7 @@ struct Exec {
     // level_rows: rows of x in this mode
     const int G = c.groups;
     float* entry = (float*)stale_buf(name + ".stats", (size_t)N() * B() * G * 2 * sizeof(float));
-    const size_t need = groupnorm_scratch_bytes(B(), full() ? N() : 1, G);
+    const size_t need = groupnorm_scratch_bytes(B(), full() ? N() : 1, G, N());
     if (need > scratch_need) scratch_need = need;
     const float* gamma = (const float*)weight(name + ".g");
     const float* beta = (const float*)weight(name + ".beta");

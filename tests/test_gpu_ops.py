@@ -91,6 +91,9 @@ def test_groupnorm_tiny_f32_all_modes(mode, silu):
     (1, 128, 128, 320, 32, 4, 1, True),  # configuration 3
     (1, 40, 48, 960, 32, 8, 3, True),   # widest concat input of the UNet, group size 30
     (1, 4, 4, 1280, 32, 1, 0, False),
+    (1, 192, 256, 128, 32, 2, 1, True),  # two-launch path with groups narrower than a lane's 8 channels
+    (2, 64, 256, 960, 32, 2, 0, True),   # the multi-step configuration's largest GroupNorm, two batch items
+    (1, 96, 128, 320, 32, 2, 1, False),  # two-launch path, float32
 ])
 def test_groupnorm_shapes(B, H, W, C, G, N, patch, bf16):
     say("gn", B, H, W, C, G, N, patch, bf16)

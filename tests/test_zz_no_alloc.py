@@ -50,9 +50,9 @@ def test_noalloc_groupnorm_matches_allocating_entry_point(bf16):
 
 
 def test_noalloc_groupnorm_rejects_what_does_not_fit():
-    # 4 batch items x 64 groups need more partial-sum space than the fixed array holds
-    x = torch.zeros(4, 2, 2, 256, device=DEV)
-    st = torch.zeros(2, 4, 64, 2, device=DEV)
+    # 16 batch items x 64 groups need more partial-sum space than the fixed array holds
+    x = torch.zeros(16, 2, 2, 256, device=DEV)
+    st = torch.zeros(2, 16, 64, 2, device=DEV)
     g, b = torch.ones(256, device=DEV), torch.zeros(256, device=DEV)
     with pytest.raises(df.DfError):
-        df.groupnorm_stale_noalloc(x, st, g, b, 64, 0, 2, torch.empty_like(x), torch.empty(4, 64, 2, device=DEV))
+        df.groupnorm_stale_noalloc(x, st, g, b, 64, 0, 2, torch.empty_like(x), torch.empty(16, 64, 2, device=DEV))
