@@ -246,6 +246,32 @@ def run_ops(df, torch):
         fl[0] = df.mfma_probe(2048, 8192)
     probe()
     timed("mfma_probe_register_resident", probe, flops=fl[0])
+    # what a grid-wide wait costs: kernel boundary vs fenced in-kernel barrier vs fence-free tagged exchange
+    nblk, iters = 256, 200
+    pbuf = torch.zeros(df.sync_probe_bytes(nblk), dtype=torch.uint8, device=dev)
+    for mode, nm in ((0, "kernel_boundary_per_phase_graph_replay"), (1, "in_kernel_barrier_with_fences"),
+                     (2, "in_kernel_tagged_exchange_no_fences")):
+        with torch.cuda.stream(stream):
+            df.sync_probe(pbuf, nblk, iters, mode)
+            stream.synchronize()
+            graph = None
+            if mode == 0:                 # the step replays its launches from a HIP graph: time the boundaries that way
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=stream):
+                    df.sync_probe(pbuf, nblk, iters, mode)
+                graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            e0.record(stream)
+            if graph is not None:
+                graph.replay()
+            else:
+                df.sync_probe(pbuf, nblk, iters, mode)
+            e1.record(stream)
+            e1.synchronize()
+        flag = int(pbuf[:4].view(torch.int32).item())
+        print(json.dumps({"op": "sync_probe_" + nm, "workgroups": nblk, "phases": iters,
+                          "us_per_phase": round(e0.elapsed_time(e1) * 1e3 / iters, 2), "fail_flag": flag}), flush=True)
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     big2 = torch.empty_like(big)
     timed("copy_1GiB", lambda: df.copy_bytes(big2, big), nbytes=2.0 * big.numel())

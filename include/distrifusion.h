@@ -330,6 +330,17 @@ int df_scale_input(float* y, const float* x, float sigma, long long n, void* str
  * is not written.  The achieved rate is the matrix-pipe ceiling the kernels are compared with besides the nominal one. */
 int df_mfma_probe(float* out, int blocks, int iters, double* flops, void* stream);
 
+/* Measurement support: the cost of making every workgroup wait for all others, which decides between one launch per
+ * layer and a persistent kernel for the step (Section 5.1 removes launch overhead with CUDAGraph; this is the
+ * measurement behind this build's choice of graph-replayed separate launches).  `iters` dependent phases over `blocks`
+ * workgroups (34 <= blocks <= number of compute units), each phase = write 1 KB per workgroup, then read what another
+ * workgroup wrote: mode 0 one kernel per phase, mode 1 one kernel with a fenced counter barrier per phase, mode 2 one
+ * kernel exchanging 32 tagged words per workgroup through relaxed device-scope atomics (no fences).  Every wait is
+ * bounded.  `buf`: df_sync_probe_bytes(blocks) bytes of device memory, 256-byte aligned, zero before the first call;
+ * its first word is non-zero afterwards if a wait ran out (1) or a value arrived wrong (2).  Time it with events. */
+size_t df_sync_probe_bytes(int blocks);
+int df_sync_probe(void* buf, int blocks, int iters, int mode, void* stream);
+
 /* Plain device-to-device copy of `bytes` bytes with the refresh kernel (bandwidth calibration). */
 int df_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
 

@@ -63,6 +63,10 @@ def lib():
     L.df_linear.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.df_scale_input.argtypes = [vp, vp, f, ll, vp]
     L.df_mfma_probe.argtypes = [vp, i, i, ctypes.POINTER(ctypes.c_double), vp]
+    L.df_sync_probe_bytes.argtypes = [i]
+    L.df_sync_probe_bytes.restype = sz
+    L.df_sync_probe.argtypes = [vp, i, i, i, vp]
+    L.df_sync_probe.restype = i
     L.df_attn_stale_vt.argtypes = [vp, vp, vp, vp, i, i, i, i, ll, f, i, vp]
     L.df_packed_text_kv_bytes.restype = sz
     L.df_packed_text_kv_bytes.argtypes = [i, i, i, i]
@@ -274,6 +278,15 @@ def mfma_probe(blocks=2048, iters=4096):
     fl = ctypes.c_double()
     _check(lib().df_mfma_probe(_ptr(out), blocks, iters, ctypes.byref(fl), _stream()))
     return fl.value
+
+
+def sync_probe(buf, blocks, iters, mode):
+    """Runs the synchronisation probe (see the header); buf: zero-initialised uint8 tensor of sync_probe_bytes(blocks)."""
+    _check(lib().df_sync_probe(_ptr(buf), blocks, iters, mode, _stream()))
+
+
+def sync_probe_bytes(blocks):
+    return lib().df_sync_probe_bytes(blocks)
 
 
 def scale_input(x, sigma, out=None):

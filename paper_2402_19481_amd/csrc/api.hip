@@ -241,6 +241,13 @@ int df_mfma_probe(float* out, int blocks, int iters, double* flops, void* stream
   return launch_mfma_probe(out, blocks, iters, (hipStream_t)stream);
 }
 
+size_t df_sync_probe_bytes(int blocks) { return blocks > 0 ? sync_probe_bytes(blocks) : 0; }
+
+int df_sync_probe(void* buf, int blocks, int iters, int mode, void* stream) {
+  if (!buf || ((uintptr_t)buf % 256)) return DF_EINVAL;
+  return launch_sync_probe(buf, blocks, iters, mode, (hipStream_t)stream);
+}
+
 int df_scale_input(float* y, const float* x, float sigma, long long n, void* stream) {
   if (!x || !y) return DF_EINVAL;
   if (n < 0) return DF_ESHAPE;

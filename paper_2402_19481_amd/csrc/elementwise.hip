@@ -204,6 +204,125 @@ int launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st) {
   return DF_OK;
 }
 
+// ---- synchronisation probe (measurement support): what it costs to make every workgroup wait for all others ----
+// Three ways to run `iters` dependent phases over `blocks` workgroups, each phase = every workgroup writes 1 KB and
+// then reads the 1 KB another workgroup wrote in that phase:
+//   mode 0  one kernel per phase (the kernel boundary is the barrier): what the UNet step does;
+//   mode 1  one persistent kernel, a counter barrier with device-scope release / acquire fences between phases;
+//   mode 2  one persistent kernel, no fences: every 32-bit value travels in a 64-bit word together with the phase
+//           number, written and polled with relaxed device-scope atomics (two hops: all -> reducers -> all).
+// All waits are bounded (a spin limit sets the fail flag and lets every wave run to its end), and the launcher admits
+// at most one workgroup per compute unit, so that all of them are resident together.
+// Layout of `buf` (unsigned words): [0] fail flag, [1] barrier counter, [2] generation, [64 ..] tagged words,
+// then the float payload.
+typedef unsigned long long u64_t;
+constexpr unsigned int kProbeSpinLimit = 1u << 20;
+
+__global__ __launch_bounds__(256) void sync_probe_phase(float* __restrict__ pay, unsigned int* __restrict__ ctl, int it) {
+  const int nb = gridDim.x, b = blockIdx.x, tid = threadIdx.x;
+  if (it > 0) {
+    const int ob = (b + nb / 2 + 1) % nb;
+    if (pay[((size_t)((it - 1) & 1) * nb + ob) * 256 + tid] != (float)(it - 1 + ob)) ctl[0] = 2u;
+  }
+  pay[((size_t)(it & 1) * nb + b) * 256 + tid] = (float)(it + b);
+}
+
+__global__ __launch_bounds__(256) void sync_probe_fence(float* __restrict__ pay, unsigned int* __restrict__ ctl, int iters) {
+  const int nb = gridDim.x, b = blockIdx.x, tid = threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+    pay[((size_t)(it & 1) * nb + b) * 256 + tid] = (float)(it + b);
+    __syncthreads();
+    if (tid == 0) {
+      __threadfence();
+      __hip_atomic_fetch_add(ctl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned int spins = 0;
+      while (__hip_atomic_load(ctl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (unsigned int)(it + 1) * nb) {
+        if (++spins > kProbeSpinLimit) { ctl[0] = 1u; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      __threadfence();
+    }
+    __syncthreads();
+    const int ob = (b + nb / 2 + 1) % nb;
+    if (ctl[0] == 0u && pay[((size_t)(it & 1) * nb + ob) * 256 + tid] != (float)(it + ob)) ctl[0] = 2u;
+  }
+}
+
+__device__ __forceinline__ void probe_put(u64_t* p, float v, unsigned int tag) {
+  __hip_atomic_store(p, ((u64_t)tag << 32) | (u64_t)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float probe_get(const u64_t* p, unsigned int tag, unsigned int* fail) {
+  for (unsigned int spins = 0;; ++spins) {
+    const u64_t w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned int)(w >> 32) == tag) return __uint_as_float((unsigned int)w);
+    if (spins > kProbeSpinLimit) { *fail = 1u; return 0.f; }
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
+// 32 values per workgroup reach 32 reducer workgroups, whose sums reach everybody (what a single-kernel GroupNorm
+// with 32 groups would exchange)
+__global__ __launch_bounds__(256) void sync_probe_tagged(u64_t* __restrict__ part, u64_t* __restrict__ red,
+                                                         unsigned int* __restrict__ ctl, int iters) {
+  constexpr int G = 32;
+  const int nb = gridDim.x, b = blockIdx.x, tid = threadIdx.x;
+  __shared__ float s_v[256];
+  __shared__ unsigned int s_tag;
+  if (tid == 0) s_tag = ctl[2];                      // the generation is read before anything is produced
+  __syncthreads();
+  unsigned int tag = s_tag;
+  for (int it = 0; it < iters; ++it) {
+    tag += 1;
+    if (tid < G) probe_put(part + (size_t)tid * nb + b, (float)(b + tid + it), tag);
+    if (b < G) {
+      float acc = 0.f;
+      for (int k = tid; k < nb; k += 256) acc += probe_get(part + (size_t)b * nb + k, tag, ctl);
+      s_v[tid] = acc;
+      __syncthreads();
+      if (tid == 0) {
+        float t = 0.f;
+        for (int k = 0; k < 256; ++k) t += s_v[k];
+        probe_put(red + b, t, tag);
+      }
+      __syncthreads();
+    }
+    if (tid < G) {
+      const float v = probe_get(red + tid, tag, ctl);
+      const float want = (float)nb * (float)(tid + it) + (float)nb * (float)(nb - 1) * 0.5f;
+      if (ctl[0] == 0u && v != want) ctl[0] = 2u;
+    }
+  }
+  if (b == 0 && tid == 0) ctl[2] = tag;              // the next launch starts from here (visible at the kernel boundary)
+}
+
+__global__ void probe_clear(unsigned int* ctl, int n, int keep_gen) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n && !(keep_gen && i == 2)) ctl[i] = 0u;
+}
+
+size_t sync_probe_bytes(int blocks) { return 256 + (size_t)33 * blocks * 8 + 256 + (size_t)2 * blocks * 256 * 4 + 256; }
+
+int launch_sync_probe(void* buf, int blocks, int iters, int mode, hipStream_t st) {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return DF_EHIP;
+  if (blocks < 34 || blocks > cus || blocks > 1024 || iters < 1 || mode < 0 || mode > 2) return DF_ESHAPE;
+  unsigned int* ctl = (unsigned int*)buf;
+  u64_t* part = (u64_t*)((char*)buf + 256);
+  u64_t* red = part + (size_t)32 * blocks;
+  float* pay = (float*)((char*)buf + 256 + (size_t)33 * blocks * 8 + 256);
+  hipLaunchKernelGGL(probe_clear, dim3(1), dim3(64), 0, st, ctl, 64, 1);
+  if (mode == 0) {
+    for (int it = 0; it < iters; ++it) hipLaunchKernelGGL(sync_probe_phase, dim3(blocks), dim3(256), 0, st, pay, ctl, it);
+  } else if (mode == 1) {
+    hipLaunchKernelGGL(sync_probe_fence, dim3(blocks), dim3(256), 0, st, pay, ctl, iters);
+  } else {
+    hipLaunchKernelGGL(sync_probe_tagged, dim3(blocks), dim3(256), 0, st, part, red, ctl, iters);
+  }
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
 __global__ void scale_kernel(float* __restrict__ y, const float* __restrict__ x, float alpha, long long n) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) y[i] = alpha * x[i];

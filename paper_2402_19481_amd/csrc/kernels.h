@@ -210,6 +210,8 @@ int launch_concat(const float* a, int Ca, const float* b, int Cb, float* out, bf
 int launch_upsample2x_bf16(const float* x, bf16_t* y, int B, int R, int W, int C, hipStream_t st);
 int launch_axpy(float* x, const float* e, float alpha, long long n, hipStream_t st);
 int launch_mfma_probe(float* out, int blocks, int iters, hipStream_t st);
+size_t sync_probe_bytes(int blocks);
+int launch_sync_probe(void* buf, int blocks, int iters, int mode, hipStream_t st);
 int launch_scale(float* y, const float* x, float alpha, long long n, hipStream_t st);
 
 }  // namespace df
