@@ -122,7 +122,7 @@ class Params:
 
 
 def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL, refresh=True,
-              stat_mode=ops.STAT_SUMS, trace=None):
+              stat_mode=ops.STAT_SUMS, trace=None, resume=None, on_block=None):
     """One UNet forward.
 
     x: FULL [B,H,W,in_ch]; DISPLACED [B,H/N,W,in_ch] (the patch's rows).
@@ -130,6 +130,9 @@ def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL,
     fills and DISPLACED reads (and refreshes in place).  `blocks` is
     df_inputs.unet_table.blocks(cfg).  Returns the predicted noise for the rows
     of x.  `trace`, if a dict, receives the output of every block by name.
+    Long runs can be interrupted and continued: `on_block(n, h, skips)` is called after the n-th entry of the block
+    list with the activation and the pending skip connections, and `resume=(n, h, skips)` starts after that entry
+    (with `stale` as it stood then).  Neither changes what is computed.
     """
     P = weights if isinstance(weights, Params) else Params(weights)
     ctx = _Ctx(cfg, mode, stale, patch_idx, refresh, stat_mode)
@@ -138,13 +141,17 @@ def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL,
     text = np.asarray(text, dtype=np.float64)
     skips = []
     h = x
-    for b in blocks:
+    start = 0
+    if resume is not None:
+        start, h, skips = resume[0], np.asarray(resume[1], dtype=np.float64), list(resume[2])
+    for bi, b in enumerate(blocks):
+        if bi < start:
+            continue
         kind = b[0]
         if kind == "conv_in":
             h = ctx.conv(b[1], h, P[b[1] + ".w"], P[b[1] + ".b"])
         elif kind == "push":
             skips.append(h)
-            continue
         elif kind == "res":
             _, name, cin, cout, _, concat = b
             if concat:
@@ -162,6 +169,8 @@ def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL,
             h = ctx.conv(b[1] + ".conv", h, P[b[1] + ".conv.w"], P[b[1] + ".conv.b"])
         if trace is not None and kind != "push":
             trace[b[1]] = h
+        if on_block is not None:
+            on_block(bi + 1, h, skips)
     return h
 
 

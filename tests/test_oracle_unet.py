@@ -132,3 +132,43 @@ def test_ablation_emulation_invariants():
     for mode in (ops.STAT_SUMS, ops.STAT_EQ2, ops.STAT_STALE):
         b = ablation.run(cfg, weights, t, flat, 1, mode)
         assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-9, mode
+
+
+def test_golden_loop_script_resumes_bit_identically(tmp_path):
+    """The script that writes the multi-step golden values checkpoints after every block and may be killed at any
+    point: a run interrupted twice (inside the FULL step and inside a DISPLACED step) and resumed must write exactly
+    what an uninterrupted run writes."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location(
+        "make_unet_golden", os.path.join(os.path.dirname(__file__), "golden", "make_unet_golden.py"))
+    mk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mk)
+    plain = tmp_path / "plain"
+    plain.mkdir()
+    ref = np.load(mk.main_loop("smallloop", None, str(plain)))
+
+    class Stop(Exception):
+        pass
+
+    ck, out = tmp_path / "ck", tmp_path / "resumed"
+    out.mkdir()
+    orig = mk._Checkpoint.block_done
+    for stop_after in (7, 25, None):                 # 7 blocks in: FULL step; 25 more: inside a DISPLACED step
+        calls = [0]
+
+        def hooked(self, *a, **k):
+            orig(self, *a, **k)
+            calls[0] += 1
+            if stop_after is not None and calls[0] == stop_after:
+                raise Stop()
+        mk._Checkpoint.block_done = hooked
+        try:
+            path = mk.main_loop("smallloop", str(ck), str(out))
+        except Stop:
+            continue
+        finally:
+            mk._Checkpoint.block_done = orig
+    got = np.load(path)
+    np.testing.assert_array_equal(got["eps"], ref["eps"])
+    np.testing.assert_array_equal(got["x"], ref["x"])
