@@ -19,8 +19,13 @@ The network is the SDXL-shaped table of df_inputs.unet_table (data only).
 Pins (tests/test_oracle_unet.py): DISPLACED with N=1 equals FULL; with the
 buffers a FULL pass leaves on the same input (stale == fresh), every patch's
 DISPLACED output equals its rows of the FULL output and the patches tile it;
-the table's MAC count matches the paper's 6,763 GMACs.  The chain as a whole
-has no value printed in the paper to compare with.
+the table's MAC count matches the paper's 6,763 GMACs.
+
+PARITY UNPINNED: the wiring of _resblock / _transformer / unet_step (order of
+the skip concatenation, norm epsilons, SiLU on the embedding, where residuals
+enter).  The paper names the network ("SDXL") without defining its wiring and
+prints no value of the chain; the pins above hold for any wiring of the same
+shapes.  The layer operations themselves (oracle.ops) are pinned.
 """
 import numpy as np
 
