@@ -204,6 +204,62 @@ def measured_mfma_peak(df, torch):
     return round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
 
 
+def run_tile_sweep(df, torch):
+    """Every tile shape / ring depth of the LDS-tiled MFMA kernel on convolution and linear shapes of the larger
+    workloads (2048x2048 and 3840x3840 shares, the synchronous full-image step), no split along K.  Needs the tuning
+    build (python -m paper_2402_19481_amd.build --tuning): the library proper has no override switches.  One JSON
+    line per shape: microseconds and TFLOP/s per tile configuration ("auto" = the library's own choice)."""
+    import math
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(1)
+    bf = lambda t: t.to(torch.bfloat16).contiguous()
+    rn = lambda *s: torch.randn(*s, generator=g, device=dev)
+    stream = torch.cuda.Stream()
+
+    def timed(fn, rep=20):
+        with torch.cuda.stream(stream):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            e0.record(stream)
+            for _ in range(rep):
+                fn()
+            e1.record(stream)
+            e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / rep
+
+    tiles = ["", "64x64x2", "64x64x3", "64x64x4", "128x64x3", "64x128x2", "128x128x2", "128x128x3"]
+    convs = [("conv 32x128 320->320 (configuration 3)", 32, 128, 320, 320), ("conv 64x256 320->320", 64, 256, 320, 320),
+             ("conv 64x256 960->320", 64, 256, 960, 320), ("conv 32x128 640->640", 32, 128, 640, 640),
+             ("conv 32x128 1920->640", 32, 128, 1920, 640), ("conv 16x64 1280->1280", 16, 64, 1280, 1280),
+             ("conv 160x240 320->320 (full image)", 160, 240, 320, 320)]
+    gemms = [("linear 4096x640x640", 4096, 640, 640), ("linear 4096x1920x640", 4096, 1920, 640),
+             ("linear 4096x640x2560", 4096, 640, 2560), ("linear 4096x5120x640", 4096, 5120, 640),
+             ("linear 9600x640x640 (full image)", 9600, 640, 640), ("linear 2400x1280x1280 (full image)", 2400, 1280, 1280),
+             ("linear 2400x1280x5120 (full image)", 2400, 1280, 5120), ("linear 38400x320x960 (full image)", 38400, 320, 960)]
+    os.environ["DF_TUNE"] = "1"
+
+    def sweep(name, flops, fn):
+        rec = {"op": name, "gflop": round(flops / 1e9, 2)}
+        for t in tiles:
+            if t:
+                os.environ["DF_TILE"] = t
+            else:
+                os.environ.pop("DF_TILE", None)
+            us = timed(fn)
+            rec[t or "auto"] = {"us": round(us, 1), "tflops": round(flops / us / 1e6)}
+        print(json.dumps(rec), flush=True)
+
+    for name, R, W, Cin, Cout in convs:
+        x, st = bf(rn(1, R, W, Cin)), bf(rn(1, R * 4, W, Cin))
+        w, b = bf(rn(Cout, 3, 3, Cin) / math.sqrt(9 * Cin)), rn(Cout)
+        sweep(name, 2.0 * 9 * Cin * Cout * R * W, lambda: df.conv3x3_halo(x, st, w, b, 1, 4))
+    for name, M, N, K in gemms:
+        x, w, b = bf(rn(M, K)), bf(rn(N, K) / math.sqrt(K)), rn(N)
+        sweep(name, 2.0 * M * N * K, lambda: df.linear(x, w, b))
+
+
 def run_ops(df, torch):
     """Single operations at the shapes of configurations 2, 3 and 5 plus the two ceilings (register-resident MFMA
     loop, plain copy).  Every case runs REP times back to back on a side stream; the time is the HIP-event span divided
@@ -350,6 +406,8 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="only run plain copies of this many MiB through the library's copy kernel (counter calibration)")
     ap.add_argument("--all-kernels", action="store_true", help="list every kernel of the step in `top_kernels`, not the top 8")
+    ap.add_argument("--tile-sweep", action="store_true",
+                    help="tile-shape sweep of the LDS-tiled MFMA kernel on large shapes (needs the tuning build)")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -365,6 +423,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.tile_sweep:
+        tune = os.path.join(os.path.dirname(df.LIB_PATH), "libdistrifusion_tune.so")
+        if not os.path.exists(tune):
+            print("bench.py --tile-sweep: build the tuning library first: python -m paper_2402_19481_amd.build --tuning",
+                  file=sys.stderr)
+            sys.exit(1)
+        df.LIB_PATH = tune
+        run_tile_sweep(df, torch)
+        return
     if args.ops:
         run_ops(df, torch)
         return
