@@ -38,26 +38,27 @@ DISPLACED = 1
 class _Ctx:
     """Spatially mixing layers of one step; per-token layers do not need it."""
 
-    def __init__(self, cfg, mode, stale, patch_idx, refresh, stat_mode):
+    def __init__(self, cfg, mode, stale, patch_idx, refresh, stat_mode, split_axis=1):
         self.cfg, self.mode, self.stale = cfg, mode, stale
         self.i, self.refresh, self.stat_mode = patch_idx, refresh, stat_mode
         self.N = cfg.N
+        self.axis = split_axis          # 1: horizontal strips (rows), 2: vertical strips (columns)
 
     def conv(self, name, x, w, b, stride=1):
         key = name + ".in"
         if self.mode == FULL:
             self.stale[key] = np.array(x, dtype=np.float64)
             return ops.conv3x3_full(x, w, b, stride)
-        y = ops.conv3x3_halo(x, self.stale[key], w, b, self.i, self.N, stride)
+        y = ops.conv3x3_halo(x, self.stale[key], w, b, self.i, self.N, stride, split_axis=self.axis)
         if self.refresh:
-            ops.buffer_refresh(self.stale[key], x, self.i, self.N)
+            ops.buffer_refresh(self.stale[key], x, self.i, self.N, axis=self.axis)
         return y
 
     def groupnorm(self, name, x, gamma, beta, eps, silu):
         key = name + ".stats"
         G = self.cfg.groups
         if self.mode == FULL:
-            self.stale[key] = ops.patch_group_sums(x, G, self.N)
+            self.stale[key] = ops.patch_group_sums(x, G, self.N, axis=self.axis)
             y, _ = ops.groupnorm_stale(x, ops.group_sums(x, G)[None], gamma, beta, G, 0, 1, eps, ops.STAT_SUMS, silu)
             return y
         y, fresh = ops.groupnorm_stale(x, self.stale[key], gamma, beta, G, self.i, self.N, eps, self.stat_mode, silu)
@@ -65,16 +66,24 @@ class _Ctx:
             self.stale[key][self.i] = fresh
         return y
 
-    def self_attention(self, name, q, k, v, heads):
+    def self_attention(self, name, q, k, v, heads, hw):
+        """q, k, v: the fresh tokens [B, Lq, C] in row-major pixel order of the patch; hw: the full token grid."""
         if self.mode == FULL:
             self.stale[name + ".k"] = np.array(k, dtype=np.float64)
             self.stale[name + ".v"] = np.array(v, dtype=np.float64)
             return ops.attention_dense(q, k, v, heads)
         ks, vs = self.stale[name + ".k"], self.stale[name + ".v"]
-        o = ops.attn_displaced(q, k, v, ks, vs, heads, self.i, self.N)
+        o = ops.attn_displaced(q, k, v, ks, vs, heads, self.i, self.N, split_axis=self.axis, hw=hw)
         if self.refresh:
-            ops.buffer_refresh(ks, k, self.i, self.N)
-            ops.buffer_refresh(vs, v, self.i, self.N)
+            if self.axis == 1:
+                ops.buffer_refresh(ks, k, self.i, self.N)
+                ops.buffer_refresh(vs, v, self.i, self.N)
+            else:               # the strip's tokens go to its columns of the [B, H, W, C] view of the buffers
+                B, C = k.shape[0], k.shape[-1]
+                H, W = hw
+                for buf, new in ((ks, k), (vs, v)):
+                    ops.buffer_refresh(buf.reshape(B, H, W, C), np.asarray(new).reshape(B, H, W // self.N, C), self.i,
+                                       self.N, axis=2)
         return o
 
 
@@ -93,13 +102,15 @@ def _transformer(ctx, P, name, x, text, C, depth):
     cfg = ctx.cfg
     heads = C // cfg.head_dim
     B, R, W, _ = x.shape
+    # the full token grid of this level (x holds the whole image, or one strip of it)
+    hw = (R, W) if ctx.mode == FULL else ((R * ctx.N, W) if ctx.axis == 1 else (R, W * ctx.N))
     h = ctx.groupnorm(name + ".gn", x, P[name + ".gn.g"], P[name + ".gn.beta"], 1e-6, False)
     h = ops.linear(h.reshape(B, R * W, C), P[name + ".pin.w"], P[name + ".pin.b"])
     for d in range(depth):
         p = f"{name}.b{d}"
         n = ops.layernorm(h, P[p + ".ln1.g"], P[p + ".ln1.beta"])
         qkv = ops.linear(n, P[p + ".attn1.qkv.w"])
-        a = ctx.self_attention(p + ".attn1", qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], heads)
+        a = ctx.self_attention(p + ".attn1", qkv[..., :C], qkv[..., C:2 * C], qkv[..., 2 * C:], heads, hw)
         h = h + ops.linear(a, P[p + ".attn1.o.w"], P[p + ".attn1.o.b"])
         n = ops.layernorm(h, P[p + ".ln2.g"], P[p + ".ln2.beta"])
         q = ops.linear(n, P[p + ".attn2.q.w"])
@@ -127,10 +138,11 @@ class Params:
 
 
 def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL, refresh=True,
-              stat_mode=ops.STAT_SUMS, trace=None, resume=None, on_block=None):
+              stat_mode=ops.STAT_SUMS, trace=None, resume=None, on_block=None, split_axis=1):
     """One UNet forward.
 
-    x: FULL [B,H,W,in_ch]; DISPLACED [B,H/N,W,in_ch] (the patch's rows).
+    x: FULL [B,H,W,in_ch]; DISPLACED [B,H/N,W,in_ch] (the patch's rows), or [B,H,W/N,in_ch] with split_axis=2
+    (vertical strips; Section 5.1, Baselines).
     emb [B,emb_dim], text [B,text_len,text_dim].  `stale` is a dict that FULL
     fills and DISPLACED reads (and refreshes in place).  `blocks` is
     df_inputs.unet_table.blocks(cfg).  Returns the predicted noise for the rows
@@ -140,7 +152,7 @@ def unet_step(cfg, blocks, weights, x, emb, text, stale, patch_idx=0, mode=FULL,
     (with `stale` as it stood then).  Neither changes what is computed.
     """
     P = weights if isinstance(weights, Params) else Params(weights)
-    ctx = _Ctx(cfg, mode, stale, patch_idx, refresh, stat_mode)
+    ctx = _Ctx(cfg, mode, stale, patch_idx, refresh, stat_mode, split_axis)
     x = np.asarray(x, dtype=np.float64)
     emb = np.asarray(emb, dtype=np.float64)
     text = np.asarray(text, dtype=np.float64)

@@ -512,10 +512,12 @@ struct Exec {
                                   (long long)B() * N(), rb, 2 * rb, (long long)Rp * rb, st);
         });
     } else if (refresh) {
-      for (int which = 0; which < 2; ++which)
-        timed(PC_REFRESH, 0.0, 2.0 * B() * rb, [&] {
-          return launch_copy_rows(entry + ((size_t)patch * 2 + which) * rowe, x + (size_t)which * (R - 1) * rowe, B(),
-                                  rb, (long long)N() * 2 * rb, (long long)R * rb, st);
+      // first and last row of the patch in one launch per batch item: two "rows" of the copy, (R-1) rows apart in
+      // the source, adjacent in the boundary-row state
+      for (int bi = 0; bi < B(); ++bi)
+        timed(PC_REFRESH, 0.0, 4.0 * rb, [&] {
+          return launch_copy_rows(entry + ((size_t)bi * N() + patch) * 2 * rowe, x + (size_t)bi * R * rowe, 2, rb, rb,
+                                  (long long)(R - 1) * rb, st);
         });
     }
   }

@@ -172,3 +172,35 @@ def test_golden_loop_script_resumes_bit_identically(tmp_path):
     got = np.load(path)
     np.testing.assert_array_equal(got["eps"], ref["eps"])
     np.testing.assert_array_equal(got["x"], ref["x"])
+
+
+def test_unet_vertical_strips_invariants():
+    """Vertical strips (split_axis=2) through the whole step: with the buffers a FULL pass leaves on the same input
+    every strip's DISPLACED output equals its columns of the FULL output and the strips tile it; transposing the
+    image (and every 3x3 kernel) maps the column split onto the row split."""
+    cfg = ut.UNetCfg(H=8, W=16, N=2, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=21, threads=4)
+    t = configs.unet_inputs(cfg, seed=21, stale_std=0.4)
+    bl = ut.blocks(cfg)
+    P = unet.Params(weights)
+    stale = {}
+    full = unet.unet_step(cfg, bl, P, t["x_prev"], t["emb"], t["text"], stale, mode=unet.FULL, split_axis=2)
+    Wp = cfg.W // cfg.N
+    tiles = [unet.unet_step(cfg, bl, P, t["x_prev"][:, :, j * Wp:(j + 1) * Wp], t["emb"], t["text"],
+                             {k: v.copy() for k, v in stale.items()}, j, unet.DISPLACED, split_axis=2)
+             for j in range(cfg.N)]
+    np.testing.assert_allclose(np.concatenate(tiles, axis=2), full, rtol=1e-9, atol=1e-10)
+    # a new input for strip 1 with the old state: compare with the row split of the transposed problem
+    xs = t["x"][:, :, Wp:2 * Wp]
+    cols = unet.unet_step(cfg, bl, P, xs, t["emb"], t["text"], {k: v.copy() for k, v in stale.items()}, 1,
+                           unet.DISPLACED, split_axis=2)
+    assert np.abs(cols - tiles[1]).max() > 1e-3                       # the new input matters
+    cfg_t = ut.UNetCfg(H=cfg.W, W=cfg.H, N=cfg.N, **ut.SMALL)
+    wt = [(n, (np.ascontiguousarray(np.swapaxes(a, 1, 2)) if a.ndim == 4 else a)) for n, a in weights]
+    Pt = unet.Params(wt)
+    stale_t = {}
+    unet.unet_step(cfg_t, ut.blocks(cfg_t), Pt, np.swapaxes(t["x_prev"], 1, 2), t["emb"], t["text"], stale_t,
+                    mode=unet.FULL)
+    rows = unet.unet_step(cfg_t, ut.blocks(cfg_t), Pt, np.swapaxes(xs, 1, 2), t["emb"], t["text"], stale_t, 1,
+                           unet.DISPLACED)
+    np.testing.assert_allclose(np.swapaxes(rows, 1, 2), cols, rtol=1e-8, atol=1e-9)
