@@ -399,6 +399,9 @@ def main():
                          "headline")
     ap.add_argument("--batch", type=int, default=1,
                     help="batch items through the same step (2 = both classifier-free-guidance branches); the headline is 1")
+    ap.add_argument("--split-axis", choices=["rows", "cols"], default="rows",
+                    help="direction of the patch split (cols: vertical strips; the latent width must divide by 4N, so "
+                         "not for the headline workload)")
     ap.add_argument("--loop", type=int, default=0,
                     help="run the multi-step configuration's loop with this many Euler steps (step 0 FULL, the rest "
                          "DISPLACED + refresh) on the chosen workload and print per-step times; --workload 2048 --loop 10 "
@@ -461,7 +464,10 @@ def main():
     specs = df.unet_weight_specs(ccfg)
     weights = make_weights(df, torch, ccfg, seed=4)
     Bn = args.batch
-    net = df.PatchUNet(cfg, weights, B=Bn)
+    cols = args.split_axis == "cols"
+    if cols:
+        workload = workload.replace("row patches", "column patches (vertical strips)").replace("latent rows)", "latent columns)")
+    net = df.PatchUNet(cfg, weights, B=Bn, split_axis=df.SPLIT_COLS if cols else df.SPLIT_ROWS)
     if args.no_graph:
         net.set_graph(False)
     if args.loop:
@@ -474,7 +480,12 @@ def main():
     g = torch.Generator(device="cuda:0").manual_seed(40)
     x_prev = torch.randn(Bn, cfg.H, cfg.W, cfg.in_ch, generator=g, device="cuda:0")
     R = cfg.H // cfg.N
-    x = (x_prev + 0.02 * torch.randn(x_prev.shape, generator=g, device="cuda:0"))[:, patch * R:(patch + 1) * R].contiguous()
+    x = x_prev + 0.02 * torch.randn(x_prev.shape, generator=g, device="cuda:0")
+    if cols:
+        Wp = cfg.W // cfg.N
+        x = x[:, :, patch * Wp:(patch + 1) * Wp].contiguous()
+    else:
+        x = x[:, patch * R:(patch + 1) * R].contiguous()
     emb = torch.randn(Bn, cfg.emb_dim, generator=g, device="cuda:0")
     text = torch.randn(Bn, cfg.text_len, cfg.text_dim, generator=g, device="cuda:0").to(torch.bfloat16)
     eps = torch.empty_like(x)

@@ -240,6 +240,9 @@ typedef struct df_unet_cfg {
   int emb_dim;       /* width of the conditioning embedding vector */
   int text_len, text_dim;
   int res_per_level; /* residual blocks per down level (up levels have one more) */
+  int split_axis;    /* DF_SPLIT_ROWS (0): N strips of H/N rows; DF_SPLIT_COLS: N strips of W/N columns, then a
+                        DISPLACED step takes x [B, H, W/N, in_ch] and the boundary state of a convolution holds the
+                        first and last column of every patch, [B, N, 2, rows, Cin] */
 } df_unet_cfg;
 
 typedef struct df_unet df_unet;
@@ -260,7 +263,8 @@ int df_unet_create(df_unet** out, const df_unet_cfg* cfg, const void* const* wei
 void df_unet_destroy(df_unet* u);
 
 /* Location of one named stale buffer inside the blob (tests and tools).  Names: "<conv>.in" (boundary
- * rows [B, N, 2, W, Cin] bf16: first and last input row of every patch), "<attn>.k" ([B, L, C] bf16),
+ * rows [B, N, 2, W, Cin] bf16: first and last input row of every patch; for vertical strips the first and last input
+ * column, [B, N, 2, rows, Cin]), "<attn>.k" ([B, L, C] bf16),
  * "<attn>.v" (values stored transposed, [B, C, Lp] bf16 with Lp = L rounded up to a multiple of 64 - the key index
  * is contiguous so that the attention kernel streams V^T tiles; columns L .. Lp-1 are never written and never
  * contribute; layers whose width is not a multiple of 64 or is below 128 keep [B, L, C]),
@@ -273,7 +277,7 @@ int df_unet_stale_name(const df_unet* u, int idx, char* name, int name_cap);
  * One UNet forward for one patch (Section 4; Section 3, Eq. 1: eps = eps_theta(x_t, t, c)).
  *   mode DF_MODE_FULL       x [B, H, W, in_ch] float: the synchronous first step on the whole image;
  *                           fills every stale buffer.  patch_idx is ignored.
- *   mode DF_MODE_DISPLACED  x [B, H/N, W, in_ch] float: patch `patch_idx` with stale context; if
+ *   mode DF_MODE_DISPLACED  x [B, H/N, W, in_ch] float ([B, H, W/N, in_ch] for vertical strips): patch `patch_idx` with stale context; if
  *                           `refresh`, the patch's own rows of every stale buffer are overwritten.
  *   emb [B, emb_dim] float, text [B, text_len, text_dim] bf16, stale: blob of df_unet_stale_bytes,
  *   eps_out: float, same shape as x.

@@ -32,7 +32,7 @@ class UNetCfgC(ctypes.Structure):
                 ("in_ch", ctypes.c_int), ("n_levels", ctypes.c_int), ("levels", ctypes.c_int * 4),
                 ("depths", ctypes.c_int * 4), ("head_dim", ctypes.c_int), ("groups", ctypes.c_int),
                 ("emb_dim", ctypes.c_int), ("text_len", ctypes.c_int), ("text_dim", ctypes.c_int),
-                ("res_per_level", ctypes.c_int)]
+                ("res_per_level", ctypes.c_int), ("split_axis", ctypes.c_int)]
 
 
 def lib():
@@ -337,7 +337,7 @@ def euler_update(x, eps, sigma, sigma_next):
     return x
 
 
-def make_cfg(cfg, B=1):
+def make_cfg(cfg, B=1, split_axis=SPLIT_ROWS):
     """df_inputs.unet_table.UNetCfg (or anything with the same fields) -> C struct."""
     c = UNetCfgC()
     c.H, c.W, c.N, c.B, c.in_ch = cfg.H, cfg.W, cfg.N, B, cfg.in_ch
@@ -347,6 +347,7 @@ def make_cfg(cfg, B=1):
         c.depths[k] = cfg.depths[k]
     c.head_dim, c.groups, c.emb_dim = cfg.head_dim, cfg.groups, cfg.emb_dim
     c.text_len, c.text_dim, c.res_per_level = cfg.text_len, cfg.text_dim, cfg.res_per_level
+    c.split_axis = split_axis
     return c
 
 
@@ -369,10 +370,11 @@ def unet_weight_specs(ccfg):
 class PatchUNet:
     """Owns the plan, its workspace and the stale-state blob of one UNet on one GPU."""
 
-    def __init__(self, cfg, weights, B=1, device="cuda:0"):
-        """weights: list of device tensors in `unet_weight_specs` order (bf16 matrices, float vectors)."""
+    def __init__(self, cfg, weights, B=1, device="cuda:0", split_axis=SPLIT_ROWS):
+        """weights: list of device tensors in `unet_weight_specs` order (bf16 matrices, float vectors).
+        split_axis: SPLIT_ROWS (horizontal strips) or SPLIT_COLS (vertical strips)."""
         L = lib()
-        self.cfg, self.ccfg, self.B = cfg, make_cfg(cfg, B), B
+        self.cfg, self.ccfg, self.B, self.split_axis = cfg, make_cfg(cfg, B, split_axis), B, split_axis
         self.device = torch.device(device)
         self.weights = list(weights)
         specs = unet_weight_specs(self.ccfg)
@@ -421,27 +423,35 @@ class PatchUNet:
         output of the displaced steps sit in buffers the object keeps, so from the third displaced step on the whole
         UNet step is one HIP-graph replay."""
         B, H, W, C = x_full.shape
-        R = H // self.cfg.N
-        rows = slice(patch_idx * R, (patch_idx + 1) * R)
+        if self.split_axis == SPLIT_COLS:
+            Wp = W // self.cfg.N
+            region = (slice(None), slice(None), slice(patch_idx * Wp, (patch_idx + 1) * Wp))
+            pshape = (B, H, Wp, C)
+        else:
+            R = H // self.cfg.N
+            region = (slice(None), slice(patch_idx * R, (patch_idx + 1) * R))
+            pshape = (B, R, W, C)
         eps_all = []
         xin_full, eps_full = self._loop_buffer("xin_full", x_full.shape), self._loop_buffer("eps_full", x_full.shape)
-        xin, eps_p = self._loop_buffer("xin", (B, R, W, C)), self._loop_buffer("eps", (B, R, W, C))
-        xp = x_full[:, rows]
-        own = xp.is_contiguous()                       # B == 1: the patch's rows are one block of x_full
+        xin, eps_p = self._loop_buffer("xin", pshape), self._loop_buffer("eps", pshape)
+        xp = x_full[region]
+        own = xp.is_contiguous()                       # B == 1, horizontal strips: the patch is one block of x_full
         if not own:
-            xp = self._loop_buffer("xp", (B, R, W, C))
-            xp.copy_(x_full[:, rows])
+            xp = self._loop_buffer("xp", pshape)
+            xp.copy_(x_full[region])
         for k in range(len(sigmas) - 1):
             s0, s1 = float(sigmas[k]), float(sigmas[k + 1])
             if k < n_warmup:
                 eps = self.step(scale_input(x_full, s0, out=xin_full), emb, text, 0, MODE_FULL, True, out=eps_full)
                 euler_update(x_full, eps, s0, s1)
                 if not own:
-                    xp.copy_(x_full[:, rows])
+                    xp.copy_(x_full[region])
             else:
                 eps = self.step(scale_input(xp, s0, out=xin), emb, text, patch_idx, MODE_DISPLACED, True, out=eps_p)
                 euler_update(xp, eps, s0, s1)
-                if not own:
+                if not own and self.split_axis == SPLIT_COLS:
+                    buffer_refresh_cols(x_full, xp, patch_idx, self.cfg.N)
+                elif not own:
                     buffer_refresh(x_full, xp, patch_idx, self.cfg.N)
             eps_all.append(eps.clone())
         return eps_all

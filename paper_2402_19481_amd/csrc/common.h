@@ -102,6 +102,13 @@ static inline const char* tune_env(const char* name) { return getenv(name); }
 static inline const char* tune_env(const char*) { return nullptr; }
 #endif
 
+// Position of row m (within its batch item) of a segmented GEMM output inside the destination buffer's batch item:
+// identity, or - for a vertical strip of a token grid, pin > 0 - grid row m / pin, column m % pin of the strip, in a
+// destination whose grid rows are pout tokens long (the caller's row offset selects the strip's first column).
+__device__ __forceinline__ long long seg_pos(int m, int pin, int pout) {
+  return pin > 0 ? (long long)(m / pin) * pout + (m % pin) : (long long)m;
+}
+
 static inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 }  // namespace df

@@ -57,6 +57,7 @@ struct TileParams {
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
   int seg_tr[3];
+  int seg_pin[3], seg_pout[3];
   int packed_w;
   const float* ln_s;
   const float* ln_t;
@@ -611,7 +612,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
           else if (p.bias) v += p.bias[col];
           const int bi = row / p.seg_rows_in[sg];
           obase[((long long)bi * p.seg_w + (col - sg * p.seg_w)) * p.seg_ld[sg] + p.seg_row0[sg] +
-                (row - bi * p.seg_rows_in[sg])] = f2bf(v);
+                seg_pos(row - bi * p.seg_rows_in[sg], p.seg_pin[sg], p.seg_pout[sg])] = f2bf(v);
         }
         return;
       }
@@ -642,7 +643,8 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
         old = p.seg_ld[sg];
         ocol = col - sg * p.seg_w;
         const int bi = row / p.seg_rows_in[sg];
-        orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (row - bi * p.seg_rows_in[sg]);
+        orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] +
+               seg_pos(row - bi * p.seg_rows_in[sg], p.seg_pin[sg], p.seg_pout[sg]);
       }
       if constexpr (sizeof(OutT) == 4) {
         *reinterpret_cast<f32x4*>(obase + orow * old + ocol) = v;
@@ -720,7 +722,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
     // segmented output: the 32 columns of a block never straddle a segment (seg_w % 32 == 0)
     OutT* obase = out;
     long long old = p.ldo, orow0 = 0, orows_out = 0;
-    int ocol = col, orows_in = 0x7fffffff;
+    int ocol = col, orows_in = 0x7fffffff, opin = 0, opout = 0;
     bool otr = false;
     if (p.nseg > 0) {
       const int sg = col / p.seg_w;
@@ -728,6 +730,7 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
       old = p.seg_ld[sg]; orow0 = p.seg_row0[sg]; orows_out = p.seg_rows_out[sg]; orows_in = p.seg_rows_in[sg];
       ocol = col - sg * p.seg_w;
       otr = p.seg_tr[sg] != 0;
+      opin = p.seg_pin[sg]; opout = p.seg_pout[sg];
     }
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -747,9 +750,10 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
         long long orow = row;
         if (p.nseg > 0) {
           const int bi = row / orows_in;
-          orow = (long long)bi * orows_out + orow0 + (row - bi * orows_in);
+          const long long pos = seg_pos(row - bi * orows_in, opin, opout);
+          orow = (long long)bi * orows_out + orow0 + pos;
           if (otr) {   // feature-major segment
-            Elem<OutT>::st(obase + ((long long)bi * p.seg_w + ocol) * old + orow0 + (row - bi * orows_in), v);
+            Elem<OutT>::st(obase + ((long long)bi * p.seg_w + ocol) * old + orow0 + pos, v);
             continue;
           }
         }
@@ -1266,6 +1270,7 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
       if (!a.seg_out[i] || a.seg_rows_in[i] <= 0) return DF_EINVAL;
       p.seg_out[i] = a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i]; p.seg_tr[i] = a.seg_tr[i];
+      p.seg_pin[i] = a.seg_pin[i]; p.seg_pout[i] = a.seg_pout[i];
     }
     if ((long long)cdiv(a.M, 64) * cdiv(a.N, 64) >= 512) return launch_pipe<64, 64, 2, false>(p, DF_BF16, 1, st);
     return launch_pipe<64, 64, 4, false, 1, 8>(p, DF_BF16, 1, st);

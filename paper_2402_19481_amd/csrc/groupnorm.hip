@@ -37,6 +37,7 @@ struct GnHalo {
   bf16_t* out;      // nullptr: no boundary-row copy
   int W, rpp, patch0, npatch;
   int single;       // the tensor holds exactly one patch (rpp rows): boundary rows follow from comparisons
+  int cols, rows;   // cols != 0: vertical strips of rpp columns, the state holds boundary columns of `rows` pixels
 };
 
 // stores 4 or 8 bf16 values of pixel p (within its batch item), channels c0.., into the boundary-row state if the
@@ -46,6 +47,23 @@ __device__ __forceinline__ void halo_store(const GnHalo& h, int b, long long p, 
   // (this runs per pixel and lane: no 64-bit division, and none at all for the one-patch tensors of a displaced step)
   const unsigned int pi = (unsigned int)p;
   unsigned int row, col, pr, patch;
+  if (h.cols) {
+    row = pi / (unsigned int)h.W; col = pi - row * (unsigned int)h.W;
+    const unsigned int q = col / (unsigned int)h.rpp;
+    const unsigned int pc = col - q * (unsigned int)h.rpp;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      if ((int)pc != (which ? h.rpp - 1 : 0)) continue;
+      bf16_t* o = h.out + ((((long long)b * h.npatch + (h.patch0 + q)) * 2 + which) * h.rows + row) * C + c0;
+      if constexpr (V == 8) {
+        st_vec(o, v);
+      } else {
+        u32x2 t = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3])};
+        *reinterpret_cast<u32x2*>(o) = t;
+      }
+    }
+    return;
+  }
   if (h.single) {
     const unsigned int last0 = (unsigned int)(h.rpp - 1) * (unsigned int)h.W;
     if (pi >= (unsigned int)h.W && pi < last0) return;           // an interior row
@@ -662,7 +680,13 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
   if (a.y_packed && (a.out_dtype != DF_BF16 || a.C % 16)) return DF_ESHAPE;
   const long long pix_seg = (long long)a.Rseg * a.W;
   GnHalo halo = {};
-  if (a.halo_out) {
+  if (a.halo_out && a.halo_cols) {
+    if (a.out_dtype != DF_BF16 || a.y_packed || a.halo_rpp <= 0 || a.W % a.halo_rpp || a.halo_patch0 < 0 ||
+        a.halo_patch0 + a.W / a.halo_rpp > a.halo_npatch || ((uintptr_t)a.halo_out % 16))
+      return DF_EINVAL;
+    halo.out = (bf16_t*)a.halo_out; halo.W = a.W; halo.rpp = a.halo_rpp; halo.patch0 = a.halo_patch0;
+    halo.npatch = a.halo_npatch; halo.cols = 1; halo.rows = a.Rseg * a.nseg;
+  } else if (a.halo_out) {
     if (a.out_dtype != DF_BF16 || a.y_packed || a.halo_rpp <= 0 || ((long long)a.Rseg * a.nseg) % a.halo_rpp ||
         a.halo_patch0 < 0 || a.halo_patch0 + (a.Rseg * a.nseg) / a.halo_rpp > a.halo_npatch || ((uintptr_t)a.halo_out % 16))
       return DF_EINVAL;
@@ -742,6 +766,48 @@ int launch_groupnorm(const GnArgs& a, hipStream_t st) {
 #undef DF_GN_BOTH
 #undef DF_GN_APPLY
 #undef DF_GN_STATS
+  DF_LAUNCH_CHECK();
+  return DF_OK;
+}
+
+// Per-strip sums of a full image for vertical strips (the synchronous step only: not on the hot path).  One
+// workgroup per (strip, group, batch item); sums of x minus the group's pivot, ordered fold, turned into sums of x
+// in double.
+template <typename Tin>
+__global__ __launch_bounds__(256) void gn_strip_sums_kernel(const Tin* __restrict__ x, float* __restrict__ sums, int B,
+                                                            int R, int W, int C, int G, int N) {
+  __shared__ float s_s[256], s_q[256];
+  const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int cg = C / G, Wp = W / N;
+  const float piv = Elem<Tin>::ld(x + (long long)b * R * W * C + g * cg);
+  const long long n = (long long)R * Wp * cg;
+  float a = 0.f, q = 0.f;
+  for (long long i = tid; i < n; i += 256) {
+    const int ch = (int)(i % cg);
+    const long long px = i / cg;
+    const int c = (int)(px % Wp), r = (int)(px / Wp);
+    const float d = Elem<Tin>::ld(x + (((long long)b * R + r) * W + j * Wp + c) * C + g * cg + ch) - piv;
+    a += d; q = fmaf(d, d, q);
+  }
+  s_s[tid] = a; s_q[tid] = q;
+  __syncthreads();
+  if (tid == 0) {
+    float fs = 0.f, fq = 0.f;
+    for (int k = 0; k < 256; ++k) { fs += s_s[k]; fq += s_q[k]; }
+    double S, SS;
+    gn_unshift(fs, fq, (double)n, piv, S, SS);
+    float* o = sums + (((long long)j * B + b) * G + g) * 2;
+    o[0] = (float)S; o[1] = (float)SS;
+  }
+}
+
+int launch_gn_strip_sums(const void* x, int in_dtype, float* sums, int B, int R, int W, int C, int G, int N, hipStream_t st) {
+  if (B <= 0 || R <= 0 || W <= 0 || C <= 0 || G <= 0 || N <= 0 || C % G || W % N || G > 65535 || B > 65535) return DF_ESHAPE;
+  dim3 grid(N, G, B);
+  if (in_dtype == DF_BF16)
+    hipLaunchKernelGGL(gn_strip_sums_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)x, sums, B, R, W, C, G, N);
+  else
+    hipLaunchKernelGGL(gn_strip_sums_kernel<float>, grid, dim3(256), 0, st, (const float*)x, sums, B, R, W, C, G, N);
   DF_LAUNCH_CHECK();
   return DF_OK;
 }

@@ -51,10 +51,17 @@ struct GnArgs {
   // as that patch's first (r % halo_rpp == 0) and / or last (== halo_rpp - 1) row
   void* halo_out;
   int halo_rpp, halo_patch0, halo_npatch;
+  // halo_cols != 0: the patches are vertical strips of halo_rpp columns; the state is [B, halo_npatch, 2, rows, C]
+  // (first and last column of every patch, rows = Rseg * nseg) and pixel column c belongs to patch
+  // halo_patch0 + c / halo_rpp
+  int halo_cols;
   int y_packed;         // bf16 output in the fragment-packed layout of wgemm.hip (rows = B*rows*W pixels, K = C)
   const Scratch* scr;   // scratch region of the caller (a plan's), or nullptr: the library's per-device region
 };
 int launch_groupnorm(const GnArgs& a, hipStream_t st);
+// Per-strip (sum, sum of squares) of a full image split into N vertical strips: x [B, R, W, C] (float or bf16) ->
+// sums [N, B, G, 2], the content of the GroupNorm cache after a synchronous step on vertical strips.
+int launch_gn_strip_sums(const void* x, int in_dtype, float* sums, int B, int R, int W, int C, int G, int N, hipStream_t st);
 // df_groupnorm_stale's arguments, validated and launched with the given scratch region (nullptr: the library's)
 int groupnorm_entry(const void* x_fresh, void* y, const float* stale_stats, float* fresh_stats_out, const float* gamma,
                     const float* beta, int B, int R, int W, int C, int G, int patch_idx, int N, float eps, int stat_mode,
@@ -108,6 +115,9 @@ struct GemmArgs {
   // seg_tr[s] != 0: segment s is written transposed, out[(b * seg_w + col) * seg_ld[s] + seg_row0[s] + row_in_batch]
   // (feature-major, rows contiguous: the V^T layout of the attention kernel); seg_rows_out is ignored for it
   int seg_tr[3];
+  // seg_pin[s] > 0: row m of a batch item is token (m / seg_pin, m % seg_pin) of a vertical strip and lands on row
+  // seg_row0 + (m / seg_pin) * seg_pout + m % seg_pin of the destination's batch item (its grid rows are seg_pout long)
+  int seg_pin[3], seg_pout[3];
   // W is in the tiled layout written by launch_pack_weight (requires N % 64 == 0, K % 64 == 0, K >= 128).
   int packed_w;
   // LayerNorm folded into the GEMM: A holds the un-normalised rows (bf16), W was packed with the norm scale
@@ -156,6 +166,7 @@ struct WGemmArgs {
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
   int seg_tr[3];          // transposed segments, as in GemmArgs
+  int seg_pin[3], seg_pout[3];   // strip-of-a-grid row mapping, as in GemmArgs
   // Fused cross-attention: the layer is a query projection with N = heads * 64 and a folded LayerNorm; instead of
   // the projection the kernel writes out_packed = softmax(q k^T * xa_scale) v per head, against xa_keys text tokens
   // whose keys / values were packed by launch_pack_text_kv (xa_kv: this block's fragments, batch stride

@@ -45,17 +45,23 @@ struct BlockDesc {
   bool concat = false;
 };
 
+inline bool fold_ok(int C) { return C % 64 == 0 && C >= 128; }
+
 bool cfg_ok(const df_unet_cfg* c) {
   if (!c) return false;
   if (c->n_levels < 1 || c->n_levels > 4 || c->B < 1 || c->N < 1 || c->H < 1 || c->W < 1) return false;
   if (c->head_dim != 64 || c->groups < 1 || c->groups > 64 || c->in_ch < 1 || c->res_per_level < 1) return false;
   if (c->emb_dim % 32 || c->text_dim % 32 || c->text_len < 1 || c->in_ch % 4) return false;
   const int down = 1 << (c->n_levels - 1);
-  if (c->H % (c->N * down) || c->W % down) return false;
+  if (c->split_axis != DF_SPLIT_ROWS && c->split_axis != DF_SPLIT_COLS) return false;
+  const bool cols = c->split_axis == DF_SPLIT_COLS;
+  if (cols ? (c->W % (c->N * down) || c->H % down) : (c->H % (c->N * down) || c->W % down)) return false;
   for (int l = 0; l < c->n_levels; ++l) {
     const int ch = c->levels[l];
     if (ch % 64 || ch % c->groups || c->depths[l] < 0) return false;
-    if (l + 1 < c->n_levels && ((c->H >> l) / c->N) % 2) return false;  // stride-2 conv needs even patch rows
+    // a stride-2 conv needs patches with an even number of rows (columns, for vertical strips)
+    if (l + 1 < c->n_levels && (((cols ? c->W : c->H) >> l) / c->N) % 2) return false;
+    if (cols && c->depths[l] > 0 && !fold_ok(ch)) return false;   // narrow attention layers: horizontal strips only
   }
   return true;
 }
@@ -178,8 +184,6 @@ struct PackSpec {
   size_t w_off, s_off, t_off;   // byte offsets inside the packed region (s/t only with a folded norm)
   size_t f_off;                 // the same weight in the fragment layout of the wave-level GEMM
 };
-
-inline bool fold_ok(int C) { return C % 64 == 0 && C >= 128; }
 
 // Token counts up to this use the fragment-packed transformer (wave-level GEMMs); larger ones (the synchronous first
 // step on the whole image) the workgroup-tiled kernels, whose operand traffic per flop is lower.
@@ -359,8 +363,9 @@ struct Exec {
   int B() const { return c.B; }
   int N() const { return c.N; }
   bool full() const { return mode == DF_MODE_FULL; }
-  int rows(int level) const { return full() ? (c.H >> level) : (c.H >> level) / c.N; }
-  int width(int level) const { return c.W >> level; }
+  bool cols() const { return c.split_axis == DF_SPLIT_COLS; }     // patches are vertical strips
+  int rows(int level) const { return (full() || cols()) ? (c.H >> level) : (c.H >> level) / c.N; }
+  int width(int level) const { return (full() || !cols()) ? (c.W >> level) : (c.W >> level) / c.N; }
 
   void* alloc(size_t bytes) {
     bytes = align256(bytes);
@@ -452,12 +457,19 @@ struct Exec {
     a.y_packed = y_packed;
     a.scr = scr;
     if (halo_entry && (full() || refresh)) {
-      // the consumer convolution's boundary-row state is refreshed by this kernel's store loop
+      // the consumer convolution's boundary-row (boundary-column) state is refreshed by this kernel's store loop
       a.halo_out = halo_entry; a.halo_npatch = N();
-      a.halo_rpp = full() ? level_rows / N() : level_rows;
+      a.halo_cols = cols() ? 1 : 0;
+      a.halo_rpp = cols() ? (full() ? W / N() : W) : (full() ? level_rows / N() : level_rows);
       a.halo_patch0 = full() ? 0 : patch;
     }
-    if (full()) {
+    if (full() && cols()) {
+      // vertical strips are not contiguous pixel ranges: the image is normalised as one segment and the per-strip sums
+      // of the cache come from a kernel of their own (synchronous step only)
+      a.nseg = 1; a.Rseg = level_rows; a.N = 1; a.patch_idx = 0; a.stale = nullptr; a.sums_out = nullptr;
+      const int Bn = B(), Nn = N();
+      timed(PC_GROUPNORM, 0.0, 0.0, [&] { return launch_gn_strip_sums(x, in_dtype, entry, Bn, level_rows, W, C, G, Nn, st); });
+    } else if (full()) {
       a.nseg = N(); a.Rseg = level_rows / N(); a.N = 1; a.patch_idx = 0; a.stale = nullptr; a.sums_out = entry;
     } else {
       a.nseg = 1; a.Rseg = level_rows; a.N = N(); a.patch_idx = patch; a.stale = entry;
@@ -469,15 +481,17 @@ struct Exec {
   }
 
   // x: bf16 [B, R, W, Cin] rows of this mode; out: [B, R/stride, W/stride, Cout]
-  bf16_t* conv_entry(const std::string& name, int W, int Cin) {
-    return (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * (size_t)W * Cin * sizeof(bf16_t));
+  // boundary state of a convolution: first and last input row of every patch, [B, N, 2, W, Cin]; for vertical strips
+  // the first and last input column, [B, N, 2, R, Cin] (`edge` = W or R: the length of the patch's shared edge)
+  bf16_t* conv_entry(const std::string& name, int edge, int Cin) {
+    return (bf16_t*)stale_buf(name + ".in", (size_t)B() * N() * 2 * (size_t)edge * Cin * sizeof(bf16_t));
   }
   // `entry_in` non-null: the stale entry was looked up by the caller and the producer of x has already refreshed it
   void conv(const std::string& name, const bf16_t* x, int R, int W, int Cin, int Cout, int stride, void* out,
             int out_dtype, const float* chan_add, const float* residual, bf16_t* entry_in = nullptr,
             bool halo_done = false, long long chan_ld = 0) {
-    const size_t rowe = (size_t)W * Cin;
-    bf16_t* entry = halo_done ? entry_in : conv_entry(name, W, Cin);
+    const size_t rowe = cols() ? (size_t)R * Cin : (size_t)W * Cin;     // elements of one boundary row / column
+    bf16_t* entry = halo_done ? entry_in : conv_entry(name, cols() ? R : W, Cin);
     const void* wt = weight(name + ".w");
     const float* bias = (const float*)weight(name + ".b");
     {
@@ -489,10 +503,18 @@ struct Exec {
     a.x = x; a.w = wt; a.bias = bias; a.chan_add = chan_add; a.chan_ld = chan_ld ? chan_ld : Cout; a.residual = residual; a.y = out;
     a.B = B(); a.R = R; a.W = W; a.Cin = Cin; a.Cout = Cout; a.stride = stride; a.act = 0;
     a.dtype = DF_BF16; a.out_dtype = out_dtype; a.scr = scr;
-    a.halo_bstride = (long long)N() * 2 * rowe;
-    if (!full()) {
-      if (patch > 0) a.halo_top = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;           // last row of the patch above
-      if (patch + 1 < N() && stride == 1) a.halo_bot = entry + ((size_t)(patch + 1) * 2) * rowe;  // first row of the patch below
+    if (cols()) {
+      a.side_bstride = (long long)N() * 2 * rowe; a.side_rstride = Cin;
+      if (!full()) {
+        if (patch > 0) a.halo_left = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;        // last column of the strip to the left
+        if (patch + 1 < N() && stride == 1) a.halo_right = entry + ((size_t)(patch + 1) * 2) * rowe;
+      }
+    } else {
+      a.halo_bstride = (long long)N() * 2 * rowe;
+      if (!full()) {
+        if (patch > 0) a.halo_top = entry + ((size_t)(patch - 1) * 2 + 1) * rowe;           // last row of the patch above
+        if (patch + 1 < N() && stride == 1) a.halo_bot = entry + ((size_t)(patch + 1) * 2) * rowe;  // first row of the patch below
+      }
     }
     {
       const double opx = (double)B() * (R / stride) * (W / stride);
@@ -504,6 +526,22 @@ struct Exec {
     }
     if (!live() || halo_done) return;
     const long long rb = (long long)rowe * sizeof(bf16_t);
+    if (cols()) {
+      // boundary columns: R pieces of Cin elements each, one pixel per input row (x is [B, R, W, Cin] in this mode)
+      const long long cb = (long long)Cin * sizeof(bf16_t);
+      const int Wp = full() ? W / N() : W;
+      if (full() || refresh)
+        for (int bi = 0; bi < B(); ++bi)
+          for (int j = full() ? 0 : patch; j < (full() ? N() : patch + 1); ++j)
+            for (int which = 0; which < 2; ++which) {
+              const int col = (full() ? j * Wp : 0) + which * (Wp - 1);
+              timed(PC_REFRESH, 0.0, 2.0 * rb, [&] {
+                return launch_copy_rows(entry + (((size_t)bi * N() + j) * 2 + which) * rowe,
+                                        x + ((size_t)bi * R * W + col) * Cin, R, cb, cb, (long long)W * cb, st);
+              });
+            }
+      return;
+    }
     if (full()) {
       const int Rp = R / N();
       for (int which = 0; which < 2; ++which)
@@ -532,8 +570,8 @@ struct Exec {
     bf16_t* a2 = (bf16_t*)alloc(px * b.cout * 2);
     const float* embp = emb_all ? emb_all + emb_cursor : nullptr;     // this block's columns of the hoisted projection
     emb_cursor += b.cout;
-    bf16_t* e1 = conv_entry(b.name + ".conv1", W, b.cin);
-    bf16_t* e2 = conv_entry(b.name + ".conv2", W, b.cout);
+    bf16_t* e1 = conv_entry(b.name + ".conv1", cols() ? R : W, b.cin);
+    bf16_t* e2 = conv_entry(b.name + ".conv2", cols() ? R : W, b.cout);
     const bool hd = dry || e1 != nullptr;      // the GroupNorm kernels refresh the boundary rows of the convolutions
     groupnorm(b.name + ".gn1", x, DF_F32, R, W, b.cin, 1e-5f, 1, a1, 0, e1);
     conv(b.name + ".conv1", a1, R, W, b.cin, b.cout, 1, h1, DF_BF16, embp, nullptr, e1, hd, emb_n);
@@ -579,7 +617,7 @@ struct Exec {
   // the consuming layers; attention reads row-major Q/K/V and writes its output packed.
   void transformer_frag(const BlockDesc& b, const float* x, float* out, int R, int W) {
     const int C = b.cin;
-    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int Lq = R * W, L = (c.H >> b.level) * (c.W >> b.level), heads = C / c.head_dim;
     const int M = B() * Lq, TL = c.text_len;
     const float scale = 1.0f / sqrtf((float)c.head_dim);
     const size_t pC = packed_rows_bytes(M, C);
@@ -601,7 +639,11 @@ struct Exec {
       const std::string p = b.name + ".b" + std::to_string(d);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
       bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * C * Lpad * 2);   // V^T: [B, C, Lpad]
-      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      // where the patch's tokens start in the key / value buffers: a block of Lq rows, or - vertical strips - W
+      // tokens of every grid row starting at the strip's first column
+      const bool strip = cols() && !full();
+      const size_t row0 = full() ? 0 : (strip ? (size_t)patch * W : (size_t)patch * Lq);
+      const int pin = strip ? W : 0, pout = strip ? (c.W >> b.level) : 0;
       if (!(full() || refresh)) {
         // no refresh: the patch's keys and values go into private copies of the two buffers
         if (live()) {
@@ -619,6 +661,7 @@ struct Exec {
         ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
         ex.seg_out[2] = vs; ex.seg_ld[2] = Lpad; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = 0; ex.seg_row0[2] = (long long)row0;
         ex.seg_tr[2] = 1;
+        ex.seg_pin[1] = ex.seg_pin[2] = pin; ex.seg_pout[1] = ex.seg_pout[2] = pout;
         wg(hp, p + ".attn1.qkv", false, true, nullptr, nullptr, nullptr, nullptr, 0, M, 3 * C, C, &ex);
       }
       {
@@ -698,7 +741,7 @@ struct Exec {
   void transformer_folded(const BlockDesc& b, const float* x, float* out, bf16_t* nb, float* h, bf16_t* qkv, bf16_t* ao,
                           bf16_t* fg, int R, int W) {
     const int C = b.cin;
-    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int Lq = R * W, L = (c.H >> b.level) * (c.W >> b.level), heads = C / c.head_dim;
     const int M = B() * Lq, TL = c.text_len;
     const float scale = 1.0f / sqrtf((float)c.head_dim);
     bf16_t* hb = (bf16_t*)alloc((size_t)M * C * 2);      // bf16 copy of the hidden state
@@ -713,7 +756,11 @@ struct Exec {
       const std::string p = b.name + ".b" + std::to_string(d);
       bf16_t* ks = (bf16_t*)stale_buf(p + ".attn1.k", (size_t)B() * L * C * 2);
       bf16_t* vs = (bf16_t*)stale_buf(p + ".attn1.v", (size_t)B() * C * Lpad * 2);   // V^T: [B, C, Lpad]
-      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      // where the patch's tokens start in the key / value buffers: a block of Lq rows, or - vertical strips - W
+      // tokens of every grid row starting at the strip's first column
+      const bool strip = cols() && !full();
+      const size_t row0 = full() ? 0 : (strip ? (size_t)patch * W : (size_t)patch * Lq);
+      const int pin = strip ? W : 0, pout = strip ? (c.W >> b.level) : 0;
       if (!(full() || refresh)) {
         if (live()) {
           timed(PC_REFRESH, 0.0, 4.0 * B() * L * C, [&] { return launch_copy_rows(ks_tmp, ks, 1, (long long)B() * L * C * 2, 0, 0, st); });
@@ -728,6 +775,7 @@ struct Exec {
         ex.seg_out[1] = ks; ex.seg_ld[1] = C; ex.seg_rows_in[1] = Lq; ex.seg_rows_out[1] = L; ex.seg_row0[1] = (long long)row0;
         ex.seg_out[2] = vs; ex.seg_ld[2] = Lpad; ex.seg_rows_in[2] = Lq; ex.seg_rows_out[2] = 0; ex.seg_row0[2] = (long long)row0;
         ex.seg_tr[2] = 1;
+        ex.seg_pin[1] = ex.seg_pin[2] = pin; ex.seg_pout[1] = ex.seg_pout[2] = pout;
         gemm_packed(hb, C, p + ".attn1.qkv", false, true, nullptr, 0, qkv, C, M, 3 * C, C, DF_BF16, nullptr, &ex);
       }
       {
@@ -782,7 +830,7 @@ struct Exec {
 
   void transformer(const BlockDesc& b, const float* x, const bf16_t* text, float* out) {
     const int R = rows(b.level), W = width(b.level), C = b.cin;
-    const int Lq = R * W, L = (c.H >> b.level) * W, heads = C / c.head_dim;
+    const int Lq = R * W, L = (c.H >> b.level) * (c.W >> b.level), heads = C / c.head_dim;
     const int M = B() * Lq;
     const int TL = c.text_len;
     const size_t mark = top;
@@ -799,6 +847,7 @@ struct Exec {
       top = mark;
       return;
     }
+    if (cols() && b.depth > 0 && !fold_ok(C)) { err = DF_ESHAPE; return; }   // (cfg_ok rejects such plans up front)
     groupnorm(b.name + ".gn", x, DF_F32, R, W, C, 1e-6f, 0, nb);
     if (fold_ok(C)) {
       transformer_folded(b, x, out, nb, h, qkv, ao, fg, R, W);
@@ -818,7 +867,12 @@ struct Exec {
       // (the refresh costs nothing) and attention reads every key from there; without refresh they go to a scratch
       // tensor and are spliced in by the attention loader.
       const bool fused_kv = (full() || refresh) && C % 64 == 0 && C >= 128;
-      const size_t row0 = full() ? 0 : (size_t)patch * Lq;
+      // where the patch's tokens start in the key / value buffers: a block of Lq rows, or - vertical strips - W
+      // tokens of every grid row starting at the strip's first column
+      const bool strip = cols() && !full();
+      const size_t row0 = full() ? 0 : (strip ? (size_t)patch * W : (size_t)patch * Lq);
+      const int pin = strip ? W : 0, pout = strip ? (c.W >> b.level) : 0;
+      (void)pin; (void)pout;             // (vertical strips never reach this path)
       if (fused_kv) {
         GemmArgs ex = {};
         ex.nseg = 3; ex.seg_w = C;

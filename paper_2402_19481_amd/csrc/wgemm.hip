@@ -44,6 +44,7 @@ struct WParams {
   long long seg_ld[3], seg_rows_out[3], seg_row0[3];
   int seg_rows_in[3];
   int seg_tr[3];
+  int seg_pin[3], seg_pout[3];
   // fused cross-attention (XA > 0): per (batch item, head) 8*XA key fragments then 4*XA value fragments
   const bf16x8* xkv;
   int xa_keys;          // valid text tokens
@@ -346,11 +347,12 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
         if (p.seg_tr[sg]) {
           // feature-major output: the 32 tokens of a half wave are consecutive in memory for each feature
           bf16_t* o = p.seg_out[sg] + ((long long)bi * p.seg_w + (n - sg * p.seg_w)) * p.seg_ld[sg] + p.seg_row0[sg] +
-                      (m - bi * p.seg_rows_in[sg]);
+                      seg_pos(m - bi * p.seg_rows_in[sg], p.seg_pin[sg], p.seg_pout[sg]);
 #pragma unroll
           for (int q = 0; q < 8; ++q) o[q * p.seg_ld[sg]] = f2bf(v[q]);
         } else {
-          const long long orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] + (m - bi * p.seg_rows_in[sg]);
+          const long long orow = (long long)bi * p.seg_rows_out[sg] + p.seg_row0[sg] +
+                                 seg_pos(m - bi * p.seg_rows_in[sg], p.seg_pin[sg], p.seg_pout[sg]);
           st_vec(p.seg_out[sg] + orow * p.seg_ld[sg] + (n - sg * p.seg_w), v);
         }
       } else if (p.out_rows) {
@@ -623,7 +625,7 @@ int launch_wgemm(const WGemmArgs& a, hipStream_t st) {
     for (int i = 0; i < a.nseg; ++i) {
       if (!a.seg_out[i] || a.seg_rows_in[i] <= 0 || (!a.seg_tr[i] && (a.seg_ld[i] % 8 || !al(a.seg_out[i], 16))))
         return DF_EINVAL;
-      p.seg_tr[i] = a.seg_tr[i];
+      p.seg_tr[i] = a.seg_tr[i]; p.seg_pin[i] = a.seg_pin[i]; p.seg_pout[i] = a.seg_pout[i];
       p.seg_out[i] = (bf16_t*)a.seg_out[i]; p.seg_ld[i] = a.seg_ld[i]; p.seg_rows_out[i] = a.seg_rows_out[i];
       p.seg_row0[i] = a.seg_row0[i]; p.seg_rows_in[i] = a.seg_rows_in[i];
     }

@@ -46,12 +46,18 @@ def check_eps(got, ref, name):
     return check(got, ref, True, name, row_axes=2, row_tol=4e-2, elt_tol=4e-2, say=say)
 
 
-def _stale_as_oracle(net, name, cfg, B, ostale):
+def _stale_as_oracle(net, name, cfg, B, ostale, cols=False):
     """GPU stale buffer -> array comparable with the oracle's entry of the same name."""
     raw = net.stale_view(name)
     o = ostale[name]
     if name.endswith(".stats"):
         return host(raw.view(torch.float32).reshape(o.shape)), o
+    if name.endswith(".in") and cols:           # vertical strips: first and last input column of every patch
+        _, H, W, C = o.shape
+        Wp = W // cfg.N
+        g = host(raw.view(torch.bfloat16).reshape(B, cfg.N, 2, H, C))
+        want = np.stack([np.stack([o[:, :, j * Wp], o[:, :, (j + 1) * Wp - 1]], axis=1) for j in range(cfg.N)], axis=1)
+        return g, want
     if name.endswith(".in"):
         _, H, W, C = o.shape
         Rp = H // cfg.N
@@ -116,6 +122,56 @@ def test_small_unet_full_and_displaced(H, W, N, B):
     # refresh=0 leaves the state untouched
     net.stale.copy_(stale0)
     net.step(dev(x[:, :R]), emb_d, text_d, patch_idx=0, mode=df.MODE_DISPLACED, refresh=False)
+    torch.cuda.synchronize()
+    assert torch.equal(net.stale, stale0)
+    net.close()
+
+
+@pytest.mark.parametrize("H,W,N,B", [(8, 16, 2, 1), (16, 32, 4, 1), (8, 16, 2, 2)])
+def test_small_unet_vertical_strips(H, W, N, B):
+    """The whole step with the patch split running along the columns (Section 5.1, Baselines): FULL eps and stale
+    state, then every strip's DISPLACED eps and refreshed state, against the oracle with split_axis=2."""
+    say("small unet, vertical strips", H, W, N, B)
+    cfg = ut.UNetCfg(H=H, W=W, N=N, **ut.SMALL)
+    weights = configs.unet_weights(cfg, seed=8, threads=8)
+    t = configs.unet_inputs(cfg, seed=8, stale_std=0.5)
+    x_prev = np.concatenate([t["x_prev"]] * B) * np.arange(1, B + 1).reshape(B, 1, 1, 1)
+    x = np.concatenate([t["x"]] * B) * np.arange(1, B + 1).reshape(B, 1, 1, 1)
+    emb = np.concatenate([t["emb"]] * B)
+    text = np.concatenate([t["text"]] * B)
+    bl = ut.blocks(cfg)
+    P = ounet.Params(weights)
+    ostale = {}
+    o_full = ounet.unet_step(cfg, bl, P, x_prev, emb, text, ostale, mode=ounet.FULL, split_axis=2)
+    net = df.PatchUNet(cfg, _upload(weights), B=B, device=DEV, split_axis=df.SPLIT_COLS)
+    emb_d, text_d = dev(emb), dev(text, True)
+    g_full = net.step(dev(x_prev), emb_d, text_d, mode=df.MODE_FULL)
+    check_eps(host(g_full), o_full, "FULL eps")
+    names = net.stale_names()
+    assert sorted(names) == sorted(ostale.keys())
+    for nm in names:
+        g, o = _stale_as_oracle(net, nm, cfg, B, ostale, cols=True)
+        assert rel_l2(g, o) < TOL_BF16, nm
+    Wp = W // N
+    stale0 = net.stale.clone()
+    for i in range(N):
+        net.stale.copy_(stale0)
+        snap = {k: v.copy() for k, v in ostale.items()}
+        xs = np.ascontiguousarray(x[:, :, i * Wp:(i + 1) * Wp])
+        o_disp = ounet.unet_step(cfg, bl, P, xs, emb, text, snap, i, ounet.DISPLACED, split_axis=2)
+        g_disp = net.step(dev(xs), emb_d, text_d, patch_idx=i, mode=df.MODE_DISPLACED)
+        e = check_eps(host(g_disp), o_disp, "DISPLACED strip %d eps" % i)
+        far = rel_l2(o_full[:, :, i * Wp:(i + 1) * Wp], o_disp)
+        say("  DISPLACED strip", i, "rel_l2", e, "(distance to the stale step's eps:", far, ")")
+        assert far > 5 * TOL_BF16
+        worst = 0.0
+        for nm in names:
+            g, o = _stale_as_oracle(net, nm, cfg, B, snap, cols=True)
+            worst = max(worst, rel_l2(g, o))
+            assert rel_l2(g, o) < TOL_BF16, nm
+        say("     refreshed stale buffers worst rel_l2", worst)
+    net.stale.copy_(stale0)
+    net.step(dev(np.ascontiguousarray(x[:, :, :Wp])), emb_d, text_d, patch_idx=0, mode=df.MODE_DISPLACED, refresh=False)
     torch.cuda.synchronize()
     assert torch.equal(net.stale, stale0)
     net.close()
