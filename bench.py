@@ -229,7 +229,7 @@ def run_tile_sweep(df, torch):
             e1.synchronize()
         return e0.elapsed_time(e1) * 1e3 / rep
 
-    tiles = ["", "64x64x2", "64x64x3", "64x64x4", "128x64x3", "64x128x2", "128x128x2", "128x128x3"]
+    tiles = ["", "64x64x2", "64x64x3", "64x64x7", "64x64x6", "128x64x3", "128x64x7", "64x128x2", "128x128x2", "128x128x3", "128x128x7", "128x128x6"]
     convs = [("conv 32x128 320->320 (configuration 3)", 32, 128, 320, 320), ("conv 64x256 320->320", 64, 256, 320, 320),
              ("conv 64x256 960->320", 64, 256, 960, 320), ("conv 32x128 640->640", 32, 128, 640, 640),
              ("conv 32x128 1920->640", 32, 128, 1920, 640), ("conv 16x64 1280->1280", 16, 64, 1280, 1280),
@@ -258,6 +258,85 @@ def run_tile_sweep(df, torch):
     for name, M, N, K in gemms:
         x, w, b = bf(rn(M, K)), bf(rn(N, K) / math.sqrt(K)), rn(N)
         sweep(name, 2.0 * M * N * K, lambda: df.linear(x, w, b))
+
+
+def run_timeline(df, torch, tune_path):
+    """In-kernel timelines from the tuning build (cycle stamps written by the kernels themselves): where a k-slab of the
+    LDS-tiled MFMA kernel spends its cycles, and how a wave-level linear layer of the patch step divides into
+    prologue, K loop and reduction + epilogue.  One JSON line per case."""
+    import ctypes
+    import math
+    import statistics
+    lib = ctypes.CDLL(tune_path)
+    dev = "cuda:0"
+    g = torch.Generator(device="cpu").manual_seed(1)
+    rn = lambda *s: torch.randn(*s, generator=g).to(dev)
+    bf = lambda t: t.to(torch.bfloat16)
+    os.environ["DF_TUNE"] = "1"
+
+    def pipe(name, fn, tile, KT):
+        os.environ["DF_TILE"] = tile
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        n = 8 + 4 * KT
+        buf = (ctypes.c_longlong * n)()
+        if lib.df_tune_pipe_trace(buf, n) != 0:
+            raise RuntimeError("df_tune_pipe_trace failed")
+        t = list(buf)
+        ph = [(t[8 + 4 * k + 1] - t[8 + 4 * k], t[8 + 4 * k + 2] - t[8 + 4 * k + 1], t[8 + 4 * k + 3] - t[8 + 4 * k + 2],
+               (t[8 + 4 * (k + 1)] if k + 1 < KT else t[2]) - t[8 + 4 * k + 3]) for k in range(KT)]
+        mid = ph[3:-2] if KT > 8 else ph
+        m = [round(statistics.mean(x[i] for x in mid)) for i in range(4)]
+        print(json.dumps({"kernel": "mfma_pipe_kernel", "op": name, "tile": tile, "k_slabs": KT,
+                          "cycles_before_first_slab": t[8] - t[0], "cycles_k_loop": t[2] - t[8],
+                          "per_slab_cycles": {"wait_own_loads": m[0], "barrier": m[1], "issue_loads_and_lds_reads": m[2],
+                                              "mfma": m[3], "total": sum(m)},
+                          "note": "each of the four stamps of a slab costs ~90 cycles itself"}), flush=True)
+
+    M, N, K = 2400, 1280, 5120
+    x, w, b = bf(rn(M, K)), bf(rn(N, K) / math.sqrt(K)), rn(N)
+    for tile in ("64x64x2", "128x128x3", "128x128x7"):
+        pipe("linear 2400x1280x5120", lambda: df.linear(x, w, b), tile, K // 64)
+    R, W, Cin, Cout = 64, 256, 960, 320
+    x2, st = bf(rn(1, R, W, Cin)), bf(rn(1, R * 4, W, Cin))
+    w2, b2 = bf(rn(Cout, 3, 3, Cin) / math.sqrt(9 * Cin)), rn(Cout)
+    for tile in ("64x64x3", "128x128x7"):
+        pipe("conv 64x256 960->320", lambda: df.conv3x3_halo(x2, st, w2, b2, 1, 4), tile, 9 * Cin // 64)
+    os.environ.pop("DF_TILE", None)
+
+    def wgemm(name, fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        n = 1024 * 8
+        buf = (ctypes.c_longlong * n)()
+        if lib.df_tune_wgemm_trace(buf, n) != 0:
+            raise RuntimeError("df_tune_wgemm_trace failed")
+        t = [list(buf[i * 8:(i + 1) * 8]) for i in range(1024)]
+        smax = max(r[0] for r in t)
+        t = [r for r in t if r[0] > smax - 100000 and r[5] >= r[0]]   # this launch's workgroups (100 MHz clock: 1 ms)
+        s0 = min(r[0] for r in t)
+        mean = lambda v: round(statistics.mean(v))
+        print(json.dumps({"kernel": "wgemm_kernel", "op": name, "workgroups": len(t),
+                          "first_start_to_last_end_us": round((max(r[5] for r in t) - s0) / 100.0, 2),
+                          "last_start_us": round((max(r[0] for r in t) - s0) / 100.0, 2),
+                          "cycles": {"prologue": mean([r[2] - r[1] for r in t]), "k_loop": mean([r[3] - r[2] for r in t]),
+                                     "reduce_and_epilogue": mean([r[4] - r[3] for r in t])}}), flush=True)
+
+    M = 300
+    for name, N, K, geglu, ln in (("linear_packed 300x10240x1280 geglu ln", 10240, 1280, True, True),
+                                  ("linear_packed 300x1280x5120", 1280, 5120, False, False),
+                                  ("linear_packed 300x1280x1280", 1280, 1280, False, False),
+                                  ("linear_packed 300x3840x1280 ln", 3840, 1280, False, True)):
+        xw, ww, bw = bf(rn(M, K)), bf(rn(N, K) / math.sqrt(K)), rn(N)
+        xp, wp = df.pack_rows(xw), df.pack_linear_weight(ww)
+        kw = dict(geglu=geglu, want=("packed",))
+        if ln:
+            kw.update(ln_s=rn(N), ln_t=rn(N))
+        else:
+            kw.update(bias=bw)
+        wgemm(name, lambda: df.linear_packed(xp, wp, M, N, K, **kw))
 
 
 def run_ops(df, torch):
@@ -411,6 +490,8 @@ def main():
     ap.add_argument("--all-kernels", action="store_true", help="list every kernel of the step in `top_kernels`, not the top 8")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="tile-shape sweep of the LDS-tiled MFMA kernel on large shapes (needs the tuning build)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="in-kernel cycle stamps of the tiled MFMA kernel and the wave-level linear layers (needs the tuning build)")
     ap.add_argument("--ops", action="store_true",
                     help="single-operation measurements at the shapes of the other configurations instead of the step")
     args = ap.parse_args()
@@ -426,14 +507,17 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    if args.tile_sweep:
+    if args.tile_sweep or args.timeline:
         tune = os.path.join(os.path.dirname(df.LIB_PATH), "libdistrifusion_tune.so")
         if not os.path.exists(tune):
-            print("bench.py --tile-sweep: build the tuning library first: python -m paper_2402_19481_amd.build --tuning",
+            print("bench.py --tile-sweep / --timeline: build the tuning library first: python -m paper_2402_19481_amd.build --tuning",
                   file=sys.stderr)
             sys.exit(1)
         df.LIB_PATH = tune
-        run_tile_sweep(df, torch)
+        if args.timeline:
+            run_timeline(df, torch, tune)
+        else:
+            run_tile_sweep(df, torch)
         return
     if args.ops:
         run_ops(df, torch)

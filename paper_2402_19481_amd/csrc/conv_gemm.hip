@@ -244,6 +244,18 @@ __global__ __launch_bounds__(256) void mfma_tile_kernel(TileParams p) {
 #define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+#ifdef DF_TUNING
+// Tuning build only: cycle stamps of workgroup 0 / wave 0 at four points of every k-slab iteration.
+__device__ long long g_pipe_trace[4 * 512 + 8];
+#define DF_TRACE(slot)                                                                           \
+  do {                                                                                           \
+    if (blockIdx.x == 0 && blockIdx.y == 0 && wave == 0 && lane == 0 && (slot) < 4 * 512 + 8)    \
+      g_pipe_trace[(slot)] = (long long)__builtin_readcyclecounter();                            \
+  } while (0)
+#else
+#define DF_TRACE(slot) do {} while (0)
+#endif
+
 template <int VM>
 __device__ __forceinline__ void wait_vm_and_lds() {
   // s_waitcnt vmcnt(VM) lgkmcnt(0): gfx9 encoding vmcnt[3:0]=imm[3:0], vmcnt[5:4]=imm[15:14], expcnt=imm[6:4], lgkmcnt=imm[11:8]
@@ -401,8 +413,10 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  DF_TRACE(0);
 #pragma unroll
   for (int s = 0; s < STAGES; ++s) issue(s, s);
+  DF_TRACE(1);
 
   const int lrow = lane & 31, g = lane >> 5;
   const int sw = (lrow >> 1) & 7;
@@ -446,14 +460,18 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
     constexpr int cur = decltype(curc)::value;
     // own loads of slab kt+1 have landed (at most STAGES-2 younger slabs outstanding); own fragment reads of slab kt
     // are complete
+    DF_TRACE(8 + 4 * kt);
     wait_vm_and_lds<(STAGES - 2) * L>();
     asm volatile("" ::: "memory");
+    DF_TRACE(8 + 4 * kt + 1);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    DF_TRACE(8 + 4 * kt + 2);
     issue(kt + STAGES, stage);                // stage of slab kt: every wave holds its fragments in registers
     if (computes) {
       if (kt + 1 < KT) read_frags(stage + 1 == STAGES ? 0 : stage + 1, nxtc);
       __builtin_amdgcn_sched_barrier(0);
+      DF_TRACE(8 + 4 * kt + 3);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
@@ -510,7 +528,9 @@ __global__ __launch_bounds__(64 * NW) void mfma_pipe_kernel(TileParams p, const 
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[i][j] += acc2[i][j];
   }
+  DF_TRACE(2);
   wait_vm_and_lds<0>();                      // drain the clamped tail loads before the workgroup ends
+  DF_TRACE(3);
 
   // ---- epilogue ----
   // The accumulators are staged through LDS (the operand ring is free now) so that every lane then handles four
@@ -1181,7 +1201,7 @@ int launch_auto(const TileParams& p, int out_dtype, hipStream_t st) {
     return ns < 1 ? 1 : ns;
   };
   if (split_override() > 0) return launch_pipe<64, 64, 4, kConv, 1, 8>(p, out_dtype, split_override(), st);
-  if (big >= 1024 && !p.ln_s) return launch_pipe<128, 128, 2, kConv>(p, out_dtype, 1, st);
+  if (big >= 1024 && !p.ln_s) return launch_pipe<128, 128, 3, kConv, 1, 8>(p, out_dtype, 1, st);   // eight waves: four only load
   if (nwg >= 512) return launch_pipe<64, 64, 2, kConv>(p, out_dtype, 1, st);
   if (nwg > 128) {
     const int ns = parts_for(768);
@@ -1201,6 +1221,10 @@ int pick_tile(const TileParams& p, int out_dtype, hipStream_t st) {
       case 1281284: return launch_pipe<128, 128, 4, kConv>(p, out_dtype, so, st);
       case 1281283: return launch_pipe<128, 128, 3, kConv>(p, out_dtype, so, st);
       case 1281282: return launch_pipe<128, 128, 2, kConv>(p, out_dtype, so, st);
+      case 1281286: return launch_pipe<128, 128, 4, kConv, 1, 8>(p, out_dtype, so, st);   // 'x6': four stages, eight waves
+      case 1281287: return launch_pipe<128, 128, 3, kConv, 1, 8>(p, out_dtype, so, st);   // 'x7': three stages, eight waves
+      case 1280647: return launch_pipe<128, 64, 3, kConv, 1, 8>(p, out_dtype, so, st);
+      case 640647: return launch_pipe<64, 64, 3, kConv, 1, 8>(p, out_dtype, so, st);
       case 1280643: return launch_pipe<128, 64, 3, kConv>(p, out_dtype, so, st);
       case 640644: return launch_pipe<64, 64, 4, kConv>(p, out_dtype, so, st);
       case 640642: return launch_pipe<64, 64, 2, kConv>(p, out_dtype, so, st);
@@ -1354,5 +1378,15 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t st) {
   DF_LAUNCH_CHECK();
   return DF_OK;
 }
+
+#ifdef DF_TUNING
+// Tuning build only: copies the cycle stamps of the last mfma_pipe_kernel launch to host memory (synchronises).
+extern "C" __attribute__((visibility("default"))) int df_tune_pipe_trace(long long* out, int n) {
+  if (!out || n <= 0 || n > 4 * 512 + 8) return DF_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_pipe_trace), (size_t)n * sizeof(long long)) != hipSuccess) return DF_EHIP;
+  return DF_OK;
+}
+#endif
 
 }  // namespace df

@@ -57,9 +57,22 @@ struct WParams {
 // XA > 0 (TM = 1, TN = 2, KSPLIT = 4, N = one head per workgroup): the 64 output features are the query of one
 // attention head; cross-attention against XA 32-key tiles of packed text keys / values runs in the epilogue and the
 // kernel writes the attention output (packed) instead of the projection.
+#ifdef DF_TUNING
+// Tuning build only: per workgroup (wave 0), the constant-rate clock at entry and exit and cycle stamps between.
+__device__ long long g_wg_trace[1024 * 8];
+#define DF_WTRACE(slot, expr)                                                                   \
+  do {                                                                                          \
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg_trace[blockIdx.x * 8 + (slot)] = (long long)(expr); \
+  } while (0)
+#else
+#define DF_WTRACE(slot, expr) do {} while (0)
+#endif
+
 template <int TM, int TN, int KSPLIT, int PF, bool LN, int XA>
 __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  DF_WTRACE(0, wall_clock64());
+  DF_WTRACE(1, __builtin_readcyclecounter());
   // rows of token fragments reduced per pass: as many as fit in 128 KB of LDS (the whole tile, half of it, or one row)
   constexpr int RP = (KSPLIT * TM * TN * 4 <= 128) ? TM : (TM % 2 == 0 && KSPLIT * (TM / 2) * TN * 4 <= 128) ? TM / 2 : 1;
   constexpr int U = RP * TN * 4;            // float4 units of a pass: (row, tn, jj)
@@ -187,6 +200,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     for (int j = 0; j < TN; ++j) wr[s][j] = wb[j][o];
   }
   __builtin_amdgcn_sched_barrier(0);
+  DF_WTRACE(2, __builtin_readcyclecounter());
   for (int kf = 0; kf < KFw; kf += PF) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
@@ -219,6 +233,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     }
   }
 
+  DF_WTRACE(3, __builtin_readcyclecounter());
   // ---- add the KSPLIT partial tiles in wave order, one token-fragment row at a time ----
   if (ln) {
 #pragma unroll
@@ -361,6 +376,8 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     }
   }
   }
+  DF_WTRACE(4, __builtin_readcyclecounter());
+  DF_WTRACE(5, wall_clock64());
   if constexpr (XA > 0) {
     __syncthreads();
     if (wave != 0) return;
@@ -566,6 +583,16 @@ int launch_cfg(const WParams& p, hipStream_t st) {
 }
 
 }  // namespace
+
+#ifdef DF_TUNING
+// Tuning build only: copies the stamps of the last wgemm_kernel launch to host memory (synchronises).
+extern "C" __attribute__((visibility("default"))) int df_tune_wgemm_trace(long long* out, int n) {
+  if (!out || n <= 0 || n > 1024 * 8) return DF_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wg_trace), (size_t)n * sizeof(long long)) != hipSuccess) return DF_EHIP;
+  return DF_OK;
+}
+#endif
 
 size_t packed_text_kv_bytes(int B, int TL, int count, int C) {
   const int XA = (TL + 31) / 32;
