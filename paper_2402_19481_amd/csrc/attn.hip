@@ -631,6 +631,280 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
   }
 }
 
+// Self-attention of a patch with few queries (the deepest level: 300-1024 query rows against the whole image's keys).
+// One workgroup = one 32-query block of one head; its NW waves take contiguous runs of 64-key tiles and merge their
+// (max, sum, O) states through LDS at the end, so nothing is split across workgroups and no second kernel runs.
+// Nothing is shared between waves inside the loop: every wave stages its own K and V^T tiles (global -> LDS with
+// direct loads, 1 KB contiguous per instruction; a wave reading its MFMA operands straight from the row-major buffers
+// touches 32 cache lines per instruction and ran at a quarter of the rate) in a private 16 KB of LDS, so the loop has no
+// barrier: a tile's fragments go LDS -> registers, then the next tile's loads are issued into the same LDS while the
+// tile computes.  Same operand conventions and swizzles as attn_vt_d64.
+#ifdef DF_TUNING
+// Tuning build only: per workgroup (waves 0 and 5; wave 5's rows follow at +256), 32 stamps: the constant-rate clock at entry and exit, cycle stamps between.
+__device__ long long g_attn_trace[512 * 32];
+#define DF_ATRACE(slot, expr)                                                                             \
+  do {                                                                                                    \
+    const unsigned wg_ = blockIdx.x + gridDim.x * blockIdx.y;                                            \
+    if ((threadIdx.x == 0 || threadIdx.x == 320) && wg_ < 256 && (slot) < 32)                             \
+      g_attn_trace[(wg_ + (threadIdx.x ? 256 : 0)) * 32 + (slot)] = (long long)(expr);                    \
+  } while (0)
+#else
+#define DF_ATRACE(slot, expr) do {} while (0)
+#endif
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void attn_wave_d64(AttnParams p) {
+  constexpr int D = 64, TK = 64;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  DF_ATRACE(0, wall_clock64());
+  DF_ATRACE(1, __builtin_readcyclecounter());
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xor32 = (lane ^ 32) << 2;
+  const int g = lane >> 5, c = lane & 31;
+  const int csig = (c & 0x13) | ((c & 4) << 1) | ((c & 8) >> 1);
+  // Grid (heads rounded up to a multiple of 8, query blocks, batch): workgroups go round-robin over the 8 XCDs in
+  // x-fastest order, so every query block of head h runs on XCD h % 8 and the blocks of a head, which read the same
+  // K / V^T, share an L2 - without any index arithmetic (the divisions of a linear index were a tenth of this kernel).
+  const int h = blockIdx.x, qb = blockIdx.y, b = blockIdx.z;
+  if (h >= p.heads) return;
+  const int q0 = qb * 32;
+  const int NT = (p.L + TK - 1) / TK;
+  const int t_lo = (int)((long long)wave * NT / NW), t_hi = (int)((long long)(wave + 1) * NT / NW);
+
+  const bf16_t* kg = (const bf16_t*)p.ks + (long long)b * p.bsks + h * D;
+  const bf16_t* vg = (const bf16_t*)p.vs + (long long)b * p.bsvs + (long long)h * D * p.vt_ld;
+
+  bf16x8 qreg[4];
+  {
+    const int qi = q0 + c;
+    const bf16_t* qp = (const bf16_t*)p.q + (long long)b * p.bsq + (long long)qi * p.ldq + h * D;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 tq = {0u, 0u, 0u, 0u};
+      if (qi < p.Lq) tq = *reinterpret_cast<const u32x4*>(qp + 16 * s + 8 * g);
+      qreg[s] = __builtin_bit_cast(bf16x8, tq);
+    }
+  }
+  // direct loads: instruction j of the wave covers tile rows j*8 + lane/8, 16-byte slot lane%8 (swizzled on the source
+  // side); a lane's offsets inside a tile never change (32-bit, the launcher bounds the pitches)
+  const int lr = lane >> 3, slot = lane & 7;
+  unsigned int kofs[8], vofs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = j * 8 + lr;
+    kofs[j] = (unsigned int)row * (unsigned int)p.ldks + (unsigned int)((slot ^ ((row >> 1) & 7)) * 8);
+    vofs[j] = (unsigned int)row * (unsigned int)p.vt_ld + (unsigned int)((slot ^ (row & 7) ^ (row >> 3)) * 8);
+  }
+  char* sk = smem + wave * (2 * TK * D * 2);                 // this wave's K tile [key][d], then its V^T tile [d][key]
+  char* sv = sk + TK * D * 2;
+  auto issue = [&](int tl) {
+    const int key0 = tl * TK;
+    if (key0 + TK <= p.L) {                                  // (uniform) every key row of the tile exists
+      const bf16_t* kb0 = kg + (long long)key0 * p.ldks;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) __builtin_amdgcn_global_load_lds(DF_GPTR(kb0 + kofs[j]), DF_LPTR(sk + j * 1024), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = j * 8 + lr;
+        int key = key0 + row;
+        if (key > p.L - 1) key = p.L - 1;                    // rows beyond the last key are masked in the tile body
+        __builtin_amdgcn_global_load_lds(DF_GPTR(kg + (long long)key * p.ldks + ((slot ^ ((row >> 1) & 7)) * 8)),
+                                         DF_LPTR(sk + j * 1024), 16, 0, 0);
+      }
+    }
+    const bf16_t* vb0 = vg + key0;                           // the V^T buffer is padded to whole tiles
+#pragma unroll
+    for (int j = 0; j < 8; ++j) __builtin_amdgcn_global_load_lds(DF_GPTR(vb0 + vofs[j]), DF_LPTR(sv + j * 1024), 16, 0, 0);
+  };
+  bf16x8 kfr[2][4];
+  u32x4 vfr[4][2];
+  auto read_frags = [&]() {
+    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(sk);
+    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(sv);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int row = 32 * kb + key_of_mfma_row(c);
+      const int f = (row >> 1) & 7;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kfr[kb][s] = *reinterpret_cast<const bf16x8*>(&Ks[row * D + (((2 * s + g) ^ f) * 8)]);
+    }
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      const int kchunk = 4 * (ts >> 1) + 2 * (ts & 1) + g;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const int d = 32 * db + csig;
+        vfr[ts][db] = *reinterpret_cast<const u32x4*>(&Vt[d * TK + (kchunk ^ (d & 7) ^ (d >> 3)) * 8]);
+      }
+    }
+  };
+
+  f32x16 o_acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = p.scale * kLog2e;
+
+  auto tile = [&](int tl, auto raggedc) {
+    constexpr bool ragged = decltype(raggedc)::value;
+    const int tile_base = tl * TK;
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kb][s], qreg[s], s_acc[kb], 0, 0, 0);
+    if constexpr (ragged) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = e >> 2, r = e & 3;
+          const int key = tile_base + 32 * kb + 16 * (j >> 1) + 8 * g + 4 * (j & 1) + r;
+          if (key >= p.L) s_acc[kb][e] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s_acc[kb][e]);
+    mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(mx)))) * sc;
+    const float m_new = fmaxf(m_run, mx);                    // finite: a tile holds at least one key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][e], sc, -m_new));
+        s_acc[kb][e] = pv;
+        rs += pv;
+      }
+    l_run = l_run * alpha + rs;                              // this lane's half of the keys; the halves meet at the end
+    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+    }
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      const int kb = ts >> 1, half = ts & 1;
+      u32x4 pk;
+      pk.x = pack_bf2(s_acc[kb][8 * half + 0], s_acc[kb][8 * half + 1]);
+      pk.y = pack_bf2(s_acc[kb][8 * half + 2], s_acc[kb][8 * half + 3]);
+      pk.z = pack_bf2(s_acc[kb][8 * half + 4], s_acc[kb][8 * half + 5]);
+      pk.w = pack_bf2(s_acc[kb][8 * half + 6], s_acc[kb][8 * half + 7]);
+      const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        u32x4 vraw = vfr[ts][db];
+        if constexpr (ragged) {                              // keys beyond the range: P is 0, V must be finite
+          const int key = tile_base + (4 * kb + 2 * half + g) * 8;
+          if (key + 0 >= p.L) vraw.x = 0u; else if (key + 1 >= p.L) vraw.x &= 0xffffu;
+          if (key + 2 >= p.L) vraw.y = 0u; else if (key + 3 >= p.L) vraw.y &= 0xffffu;
+          if (key + 4 >= p.L) vraw.z = 0u; else if (key + 5 >= p.L) vraw.z &= 0xffffu;
+          if (key + 6 >= p.L) vraw.w = 0u; else if (key + 7 >= p.L) vraw.w &= 0xffffu;
+        }
+        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vraw), pfrag, o_acc[db], 0, 0, 0);
+      }
+    }
+  };
+  // The query blocks of a head read the same keys; started on the same tile they would all wait for the same cache
+  // lines while the rest of the head's K / V^T (cold: other patches' rows, last touched a step ago) is not even
+  // requested.  Block qb therefore walks each wave's run of tiles from a different starting tile, wrapping around:
+  // ten blocks keep ten tiles per wave slot in flight and find the others' tiles in L2.  The order is a fixed
+  // function of the indices, so results stay reproducible.
+  const int nt = t_hi - t_lo;
+  const int rot = ((qb & 7) * nt) >> 3;                      // < nt, spread over the run
+  auto tile_at = [&](int i) { const int k = i + rot; return t_lo + (k < nt ? k : k - nt); };
+  if (nt > 0) issue(tile_at(0));
+  DF_ATRACE(2, __builtin_readcyclecounter());
+  for (int i = 0; i < nt; ++i) {
+    const int tl = tile_at(i);
+    __builtin_amdgcn_s_waitcnt((0 & 0xF) | (0x7 << 4) | (0xF << 8));   // vmcnt(0): the tile has landed in LDS
+    asm volatile("" ::: "memory");
+    DF_ATRACE(3 + 3 * i, __builtin_readcyclecounter());
+    read_frags();
+    __builtin_amdgcn_s_waitcnt((0x3F & 0xF) | ((0x3F >> 4) << 14) | (0x7 << 4) | (0 << 8));   // lgkmcnt(0): fragments in registers
+    asm volatile("" ::: "memory");
+    DF_ATRACE(4 + 3 * i, __builtin_readcyclecounter());
+    if (i + 1 < nt) issue(tile_at(i + 1));                   // (uniform) into the LDS just read, under this tile's work
+    __builtin_amdgcn_sched_barrier(0);
+    if (tl * TK + TK <= p.L) tile(tl, std::false_type{});
+    else tile(tl, std::true_type{});
+    __builtin_amdgcn_sched_barrier(0);
+    DF_ATRACE(5 + 3 * i, __builtin_readcyclecounter());
+  }
+  __builtin_amdgcn_s_waitcnt((0 & 0xF) | (0x7 << 4) | (0 << 8));
+  l_run += __int_as_float(__builtin_amdgcn_ds_bpermute(xor32, __float_as_int(l_run)));
+
+  // ---- merge the NW states in wave order ----
+  __syncthreads();                                           // every wave is done with its tiles: the LDS is free
+  float* mrg = reinterpret_cast<float*>(smem);               // [NW][34][64]: 32 accumulators, max, sum per lane
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mrg[(wave * 34 + i * 16 + e) * 64 + lane] = o_acc[i][e];
+  mrg[(wave * 34 + 32) * 64 + lane] = m_run;
+  mrg[(wave * 34 + 33) * 64 + lane] = l_run;
+  __syncthreads();
+  DF_ATRACE(28, __builtin_readcyclecounter());
+  DF_ATRACE(31, nt);
+  const int qi = q0 + c;
+  if (qi >= p.Lq) return;
+  float mw[NW], m_all = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { mw[w] = mrg[(w * 34 + 32) * 64 + lane]; m_all = fmaxf(m_all, mw[w]); }
+  float l_all = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    mw[w] = __builtin_amdgcn_exp2f(mw[w] - m_all);           // a wave without keys has max -inf: weight 0
+    l_all = fmaf(mw[w], mrg[(w * 34 + 33) * 64 + lane], l_all);
+  }
+  const float inv = __builtin_amdgcn_rcpf(l_all);
+  // wave w finishes accumulators 4w .. 4w+3 (NW == 8) of every lane: 4 consecutive features of the lane's query
+  constexpr int PER = 32 / NW;
+  static_assert(PER == 4 || PER == 8, "four or eight waves");
+  float o[PER];
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) v = fmaf(mw[w], mrg[(w * 34 + wave * PER + k) * 64 + lane], v);
+    o[k] = v * inv;
+  }
+  const int e0 = wave * PER;                                 // accumulator index = 16 * db + 8 * f + e
+  const int db = e0 >> 4, f = (e0 >> 3) & 1, eo = e0 & 7;
+  bf16_t* dst;
+  if (p.out_packed) {
+    const long long m = (long long)b * p.Lq + qi;
+    dst = (bf16_t*)p.out + (((m >> 5) * (long long)(p.heads * D / 16) + h * (D / 16)) * 64 + (m & 31) + 32 * g) * 8 +
+          (2 * db + f) * 512 + eo;
+  } else {
+    dst = (bf16_t*)p.out + (long long)b * p.bso + (long long)qi * p.ldo + h * D + 32 * db + 16 * f + 8 * g + eo;
+  }
+  if constexpr (PER == 4) {
+    u32x2 tq = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3])};
+    *reinterpret_cast<u32x2*>(dst) = tq;
+  } else {
+    u32x4 tq = {pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3]), pack_bf2(o[4], o[5]), pack_bf2(o[6], o[7])};
+    *reinterpret_cast<u32x4*>(dst) = tq;
+  }
+  DF_ATRACE(29, __builtin_readcyclecounter());
+  DF_ATRACE(30, wall_clock64());
+}
+
 // merges the per-split partials: one lane per (query, 4 consecutive d)
 __global__ __launch_bounds__(256) void attn_combine_d64(AttnParams p) {
   constexpr int D = 64;
@@ -736,6 +1010,16 @@ int pick_splits(int B, int Lq, int L, int heads) {
 
 }  // namespace
 
+#ifdef DF_TUNING
+// Tuning build only: copies the stamps of the last attn_wave_d64 launch to host memory (synchronises).
+extern "C" __attribute__((visibility("default"))) int df_tune_attn_trace(long long* out, int n) {
+  if (!out || n <= 0 || n > 512 * 32) return DF_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_trace), (size_t)n * sizeof(long long)) != hipSuccess) return DF_EHIP;
+  return DF_OK;
+}
+#endif
+
 size_t attention_scratch_bytes(int B, int Lq, int L, int heads, int d) {
   const int ns = pick_splits(B, Lq, L, heads);
   if (ns == 1) return kScratchCounterBytes;
@@ -773,6 +1057,31 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   for (long long v : lds) if (v % 8) return DF_EINVAL;
   const void* ptrs[] = {a.q, a.k_fresh, a.v_fresh, a.k_stale, a.v_stale, a.out};
   for (const void* q : ptrs) if ((uintptr_t)q % 16) return DF_EINVAL;
+  // Few queries against many keys (the patch at the deepest level): one workgroup per 32-query block and head whose
+  // waves split the keys; no partials, no merge kernel.  Each block streams the head's whole K / V^T, so this pays
+  // only while the query blocks are few: a compute unit then pulls Lq / 32 x the head's keys through its load path where
+  // the LDS-tiled kernel pulls Lq / 128 x.  Measured: 300 queries x 2400 keys 17.9 -> 16.6 us (both launches of the
+  // split form counted), 1024 x 4096 49.2 -> 56.4 us.
+  static const int wave_lq = tune_env("DF_ATTN_WAVE_LQ") ? atoi(tune_env("DF_ATTN_WAVE_LQ")) : 512;   // tuning aid
+  if (a.v_transposed && a.Lq <= wave_lq && a.L >= 512) {
+    if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.own_period != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
+    if (a.ldks <= 0 || a.ldks >= (1 << 23) || a.vt_ld >= (1 << 25)) return DF_ESHAPE;   // 32-bit offsets inside a tile
+    p.vt_ld = a.vt_ld;
+    if (a.B > 65535 || cdiv(a.Lq, 32) > 65535) return DF_ESHAPE;
+    const dim3 grid((unsigned)(cdiv(a.heads, 8) * 8), (unsigned)cdiv(a.Lq, 32), (unsigned)a.B);
+    constexpr int NW = 8;
+    constexpr int smem = NW * 2 * 64 * 64 * 2;          // a K and a V^T tile per wave; the merge reuses it
+    static_assert(NW * 34 * 64 * 4 <= smem, "the merge fits");
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute((const void*)attn_wave_d64<NW>, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+        return DF_EHIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(attn_wave_d64<NW>, grid, dim3(64 * NW), smem, st, p);
+    DF_LAUNCH_CHECK();
+    return DF_OK;
+  }
   int ns = pick_splits(a.B, a.Lq, a.L, a.heads);
   if ((long long)a.B * ns > 65535) return DF_ESHAPE;
   if ((long long)a.B * a.heads * a.Lq * 16 >= (1LL << 31)) return DF_ESHAPE;   // the merge kernel indexes with 32 bits

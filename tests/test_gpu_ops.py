@@ -434,6 +434,10 @@ def test_geglu_gate_function_pointwise():
     (1, 130, 1100, 3, True),        # odd number of 64-key tiles in a range: the second group's last tile is missing
     (2, 300, 2400, 4, True),        # two batch items with split key ranges in the two-group kernel
     (1, 4096, 8192, 10, False),     # > 600 workgroups: the single-group, three-stage form
+    (1, 512, 4096, 2, False),       # the largest query count of the form whose waves split the keys
+    (2, 70, 1003, 3, False),        # that form: ragged queries, 11 valid keys in the last tile, two batch items
+    (1, 300, 515, 1, True),         # that form: 9 tiles on 8 waves, 3 valid keys in the last tile
+    (1, 32, 512, 1, True),          # that form: one tile per wave
 ])
 def test_attn_stale_vt(B, Lq, L, heads, packed):
     say("attn_stale_vt", B, Lq, L, heads, packed)
