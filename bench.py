@@ -29,15 +29,17 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC_PROFILE = os.path.join("profiles", "unet_step_cfg4_hbm_traffic.md")
 
 
-def traffic_from_profile(cls):
-    """HBM bytes per step of a kernel class as the committed rocprofv3 --pmc summary of this command states them
-    (FETCH_SIZE + WRITE_SIZE, calibrated with `bench.py --calibrate-copy`), or None.  Counter runs are separate
-    profiler runs by nature, so this is never a measurement of the present run and is labelled accordingly."""
+def traffic_from_profile(cls=None, kernel=None):
+    """HBM bytes of a kernel class per step, or of one kernel per launch, as the committed rocprofv3 --pmc summary of
+    this command states them (FETCH_SIZE + WRITE_SIZE, calibrated with `bench.py --calibrate-copy`), or None.  Counter
+    runs are separate profiler runs by nature, so this is never a measurement of the present run and is labelled so."""
     try:
         for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
             f = line.split()
-            if len(f) == 3 and f[0] == "traffic_per_step_bytes" and f[1] == cls:
+            if cls and len(f) == 3 and f[0] == "traffic_per_step_bytes" and f[1] == cls:
                 return float(f[2])
+            if kernel and len(f) > 2 and f[0] == "traffic_per_launch_bytes" and " ".join(f[2:]) == kernel:
+                return float(f[1])
     except OSError:
         pass
     return None
@@ -337,6 +339,35 @@ def run_timeline(df, torch, tune_path):
         else:
             kw.update(bias=bw)
         wgemm(name, lambda: df.linear_packed(xp, wp, M, N, K, **kw))
+
+    # self-attention of the deepest level (300 queries x 2400 keys x 20 heads): waves 0 and 5 of every workgroup
+    B, Lq, L, heads = 1, 300, 2400, 20
+    q, k = bf(rn(B, Lq, heads * 64)), bf(rn(B, L, heads * 64))
+    vt = bf(rn(B, heads * 64, (L + 63) // 64 * 64))
+    for _ in range(4):
+        df.attn_stale_vt(q, k, vt, heads, L, packed=True)
+    torch.cuda.synchronize()
+    n = 512 * 32
+    buf = (ctypes.c_longlong * n)()
+    if lib.df_tune_attn_trace(buf, n) != 0:
+        raise RuntimeError("df_tune_attn_trace failed")
+    mean = lambda v: round(statistics.mean(v))
+    for wv, off in ((0, 0), (5, 256)):
+        t = [r for r in (list(buf[(off + i) * 32:(off + i + 1) * 32]) for i in range(256)) if r[31] > 0 and r[30] > 0]
+        s0 = min(r[0] for r in t)
+        tiles = []
+        for i in range(max(r[31] for r in t)):
+            rows = [r for r in t if r[31] > i]
+            prev = (lambda r: r[2]) if i == 0 else (lambda r, i=i: r[5 + 3 * (i - 1)])
+            tiles.append({"wait_loads": mean([r[3 + 3 * i] - prev(r) for r in rows]),
+                          "lds_to_registers": mean([r[4 + 3 * i] - r[3 + 3 * i] for r in rows]),
+                          "issue_next_and_compute": mean([r[5 + 3 * i] - r[4 + 3 * i] for r in rows])})
+        print(json.dumps({"kernel": "attn_wave_d64", "op": "self_attn 300x2400x1280", "wave": wv, "workgroups": len(t),
+                          "first_start_to_last_end_us": round((max(r[30] for r in t) - s0) / 100.0, 2),
+                          "cycles": {"prologue": mean([r[2] - r[1] for r in t]), "tiles": tiles,
+                                     "wait_for_slowest_wave": mean([r[28] - r[5 + 3 * (r[31] - 1)] for r in t]),
+                                     "merge_and_store": mean([r[29] - r[28] for r in t]),
+                                     "total": mean([r[29] - r[1] for r in t])}}), flush=True)
 
 
 def run_ops(df, torch):
@@ -656,11 +687,17 @@ def main():
     roofline = roof(kd, kd["label"], {})
     roofline["share_of_step"] = round(kd["ms"] / args.profile_steps / ms, 4)
     cls_roof = roof(d, dom, {})
-    tr = None if (args.small or args.workload != "cfg4" or args.batch != 1) else traffic_from_profile(dom)
+    headline = not (args.small or args.workload != "cfg4" or args.batch != 1)
+    tr = traffic_from_profile(cls=dom) if headline else None
+    trk = traffic_from_profile(kernel=kd["label"]) if headline else None
+    # Counters cannot be read in a timed run: `traffic` is the bytes per launch that the committed counter profile of
+    # this same command states (two separate rocprofv3 --pmc runs), not a measurement of the present run.
+    if trk is not None:
+        roofline["traffic"] = round(trk)
+        roofline["traffic_source"] = TRAFFIC_PROFILE + " (separate rocprofv3 --pmc runs of this command)"
     if tr is not None:
-        # not measured in this run: bytes per launch of the class in the committed counter profile of this command
-        cls_roof["traffic_from_profile"] = {"bytes_per_launch": round(tr / (d["launches"] / args.profile_steps)),
-                                            "source": TRAFFIC_PROFILE}
+        cls_roof["traffic"] = round(tr / (d["launches"] / args.profile_steps))
+        cls_roof["traffic_source"] = TRAFFIC_PROFILE + " (separate rocprofv3 --pmc runs of this command)"
     roofline["kernel_class"] = cls_roof
     top = sorted(kernels, key=lambda kr: -kr["ms"])[:(None if args.all_kernels else 8)]
     top_kernels = [dict(kernel=kr["label"], ms_per_step=round(kr["ms"] / args.profile_steps, 4),
