@@ -323,7 +323,11 @@ def run_timeline(df, torch, tune_path):
         print(json.dumps({"kernel": "wgemm_kernel", "op": name, "workgroups": len(t),
                           "first_start_to_last_end_us": round((max(r[5] for r in t) - s0) / 100.0, 2),
                           "last_start_us": round((max(r[0] for r in t) - s0) / 100.0, 2),
-                          "cycles": {"prologue": mean([r[2] - r[1] for r in t]), "k_loop": mean([r[3] - r[2] for r in t]),
+                          "cycles": {"prologue": mean([r[2] - r[1] for r in t]),
+                                     "prologue_tile_indices": mean([r[6] - r[1] for r in t]),
+                                     "prologue_epilogue_operand_requests": mean([r[7] - r[6] for r in t]),
+                                     "prologue_first_operand_requests": mean([r[2] - r[7] for r in t]),
+                                     "k_loop": mean([r[3] - r[2] for r in t]),
                                      "reduce_and_epilogue": mean([r[4] - r[3] for r in t])}}), flush=True)
 
     M = 300

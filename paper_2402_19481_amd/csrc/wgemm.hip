@@ -79,8 +79,15 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   f32x4* red = reinterpret_cast<f32x4*>(smem_raw);                       // [KSPLIT][U][64], reused per pass
   float* stat = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024);  // [KSPLIT][TM][32][2]
   u32x4* qlds = reinterpret_cast<u32x4*>(smem_raw + KSPLIT * U * 1024 + KSPLIT * TM * 32 * 2 * 4);   // [4][64] (XA)
+  float* vecs = reinterpret_cast<float*>(smem_raw + KSPLIT * U * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0));   // [4][128]
   constexpr int GP = TN >= 2 ? TN / 2 : 1;   // geglu: the tile's first GP fragments are value rows, the last GP their gates
 
+  // Every kernel argument the prologue needs is requested here, in one batch: left to the compiler, the scalar loads
+  // of arguments first used under a condition (norm vectors, bias, residual, operand pointers) are issued where that
+  // code starts, and the prologue of these few-microsecond kernels became a chain of four or five dependent round
+  // trips to the scalar cache.
+  asm volatile("" ::"s"(p.Xp), "s"(p.Wp), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.bias), "s"(p.ln_s), "s"(p.ln_t),
+               "s"(p.residual), "s"(p.ldr), "s"(p.geglu));
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the k-walk and tile addresses stay off the vector ALU
   const int tok = lane & 31, g = lane >> 5;
@@ -100,6 +107,10 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   const int mg = t % MG, ng = t / MG;
   const int KF = p.K >> 4, KFw = KF / KSPLIT;
   const int kf0 = wave * KFw;
+#ifdef DF_TUNING
+  asm volatile("" ::"s"(kf0), "s"(mg), "s"(ng));
+#endif
+  DF_WTRACE(6, __builtin_readcyclecounter());
 
   const bf16x8* xb[TM];
   const bf16x8* wb[TN];
@@ -127,33 +138,34 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   for (int i = 0; i < TM; ++i) { ln_sum[i] = 0.f; ln_sq[i] = 0.f; }
   constexpr bool ln = LN;
 
-  // Epilogue operands of this wave's first pair unit (norm / bias vectors, residual) are requested before the K
-  // loop: their latency would otherwise sit, un-overlapped, at the end of every one of these short kernels.
-  // A pair unit = (token fragment row i, output fragment j, half f): 8 consecutive features per lane.  The tile is
-  // reduced and written in passes of RP rows; the pair units of a pass go round-robin over the waves, which run the
-  // epilogue for them.
+  // Epilogue operands are requested before the K loop: their latency would otherwise sit, un-overlapped, at the end
+  // of every one of these short kernels.  A pair unit = (token fragment row i, output fragment j, half f): 8
+  // consecutive features per lane.  The tile is reduced and written in passes of RP rows; the pair units of a pass go
+  // round-robin over the waves, which run the epilogue for them.
+  // The per-feature vectors (norm scale / shift or bias, of the value and of the gate half) are the same for every
+  // token: wave v < 4 fetches vector v for the tile's whole feature range with ONE load (<= 128 floats) and parks it
+  // in LDS for the epilogue.  Fetched per unit and lane they were 8-32 extra vector-memory instructions per wave, each
+  // of which costs the compute unit's load path as much as a 1 KB operand fragment.
   const int JO = p.geglu ? GP : TN;                    // output fragments per row of the tile
   const int npu = RP * JO * 2;
-  struct Epi { float a[8], b[8], ga[8], gb[8], r[8]; };
-  auto load_epi = [&](int i0, int pu, Epi& e, bool vecs) {
+  static_assert(KSPLIT >= 4, "one wave per parked vector");
+  f32x4 vec_pre = {0.f, 0.f, 0.f, 0.f};
+  {
+    const int n0 = ng * JO * 32;
+    const bool gg = TN >= 2 && p.geglu;
+    const float* src = nullptr;                        // (uniform)
+    if (ln) src = wave == 0 ? p.ln_s + n0 : wave == 1 ? p.ln_t + n0 : (gg && wave == 2) ? p.ln_s + p.N + n0
+                                                          : (gg && wave == 3) ? p.ln_t + p.N + n0 : nullptr;
+    else if (p.bias) src = wave == 0 ? p.bias + n0 : (gg && wave == 2) ? p.bias + p.N + n0 : nullptr;
+    if (src && lane * 4 < JO * 32) vec_pre = *reinterpret_cast<const f32x4*>(src + 4 * lane);
+  }
+  struct Epi { float r[8]; };
+  auto load_epi = [&](int i0, int pu, Epi& e) {
     const int f = pu & 1;
     const int j = p.geglu ? (pu >> 1) % GP : (pu >> 1) % TN;          // compile-time divisors (JO is a run-time value)
     const int mt = mg * TM + i0 + (p.geglu ? (pu >> 1) / GP : (pu >> 1) / TN);
     const int m = mt * 32 + tok;
     const int n = (ng * JO + j) * 32 + 16 * f + 8 * g;
-    if (!vecs) {
-      // same features as the unit the vectors were loaded for
-    } else if (ln) {
-      ld_vec(p.ln_s + n, e.a); ld_vec(p.ln_s + n + 4, e.a + 4);
-      ld_vec(p.ln_t + n, e.b); ld_vec(p.ln_t + n + 4, e.b + 4);
-      if (TN >= 2 && p.geglu) {
-        ld_vec(p.ln_s + p.N + n, e.ga); ld_vec(p.ln_s + p.N + n + 4, e.ga + 4);
-        ld_vec(p.ln_t + p.N + n, e.gb); ld_vec(p.ln_t + p.N + n + 4, e.gb + 4);
-      }
-    } else if (p.bias) {
-      ld_vec(p.bias + n, e.a); ld_vec(p.bias + n + 4, e.a + 4);
-      if (TN >= 2 && p.geglu) { ld_vec(p.bias + p.N + n, e.ga); ld_vec(p.bias + p.N + n + 4, e.ga + 4); }
-    }
     if (p.residual && m < p.M) {
       ld_vec(p.residual + (long long)m * p.ldr + n, e.r); ld_vec(p.residual + (long long)m * p.ldr + n + 4, e.r + 4);
     }
@@ -163,7 +175,8 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
   Epi epre[NPRE];
 #pragma unroll
   for (int t = 0; t < NPRE; ++t)
-    if (wave + t * KSPLIT < npu) load_epi(0, wave + t * KSPLIT, epre[t], true);
+    if (wave + t * KSPLIT < npu) load_epi(0, wave + t * KSPLIT, epre[t]);
+  DF_WTRACE(7, __builtin_readcyclecounter());
   // fused cross-attention: the wave that runs it also requests the head's key fragments now
   bf16x8 xkf[XA > 0 ? XA : 1][4];
   const bf16x8* xkv_ptr = nullptr;
@@ -259,6 +272,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
         const f32x4 v = {t[4 * jj], t[4 * jj + 1], t[4 * jj + 2], t[4 * jj + 3]};
         red[(wave * U + (il * TN + j) * 4 + jj) * 64 + lane] = v;
       }
+  if (i0 == 0 && wave < 4 && lane * 4 < JO * 32) *reinterpret_cast<f32x4*>(vecs + wave * 128 + 4 * lane) = vec_pre;
   __syncthreads();
 
 #pragma unroll
@@ -272,13 +286,13 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
     const int mt = mg * TM + i;
     if (mt >= MT) continue;
     Epi e;
-    if (t < NPRE) {
-      // a wave's t-th unit covers the same features in every pass: only the residual differs from the prefetched one
-      e = epre[t < NPRE ? t : 0];
-      if (i0 > 0) load_epi(i0, pu, e, false);
-    } else {
-      load_epi(i0, pu, e, true);
-    }
+    if (t < NPRE && i0 == 0) e = epre[t < NPRE ? t : 0];   // the residual rows of the first pass were requested early
+    else load_epi(i0, pu, e);
+    const float* vq = vecs + j * 32 + 16 * f + 8 * g;  // this lane's 8 features in the parked vectors
+    auto vec8 = [&](int which, float* o) {
+      const f32x4 lo = *reinterpret_cast<const f32x4*>(vq + which * 128), hi = *reinterpret_cast<const f32x4*>(vq + which * 128 + 4);
+      o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w; o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+    };
     float v[8], gt[8];
     {
       f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
@@ -314,18 +328,24 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       const float mean = sm * inv_k;
       const float var = fmaxf(fmaf(sq, inv_k, -mean * mean), 0.f);
       const float rstd = __builtin_amdgcn_rsqf(var + p.ln_eps);
+      float ea[8], eb[8];
+      vec8(0, ea); vec8(1, eb);
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = rstd * (v[q] - mean * e.a[q]) + e.b[q];
+      for (int q = 0; q < 8; ++q) v[q] = rstd * (v[q] - mean * ea[q]) + eb[q];
       if (TN >= 2 && p.geglu) {
+        vec8(2, ea); vec8(3, eb);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) gt[q] = rstd * (gt[q] - mean * e.ga[q]) + e.gb[q];
+        for (int q = 0; q < 8; ++q) gt[q] = rstd * (gt[q] - mean * ea[q]) + eb[q];
       }
     } else if (p.bias) {
+      float ea[8];
+      vec8(0, ea);
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] += e.a[q];
+      for (int q = 0; q < 8; ++q) v[q] += ea[q];
       if (TN >= 2 && p.geglu) {
+        vec8(2, ea);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) gt[q] += e.ga[q];
+        for (int q = 0; q < 8; ++q) gt[q] += ea[q];
       }
     }
     if (TN >= 2 && p.geglu) {
@@ -554,7 +574,7 @@ int launch_one(const WParams& p, hipStream_t st) {
   const int KF = p.K / 16;
   if (KF % KSPLIT) return DF_ESHAPE;
   constexpr int RP = (KSPLIT * TM * TN * 4 <= 128) ? TM : (TM % 2 == 0 && KSPLIT * (TM / 2) * TN * 4 <= 128) ? TM / 2 : 1;
-  constexpr int smem = KSPLIT * RP * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0);
+  constexpr int smem = KSPLIT * RP * TN * 4 * 1024 + KSPLIT * TM * 32 * 2 * 4 + (XA > 0 ? 4096 : 0) + 4 * 128 * 4;
   auto k = wgemm_kernel<TM, TN, KSPLIT, PF, LN, XA>;
   static bool attr_set = false;
   if (!attr_set) {
