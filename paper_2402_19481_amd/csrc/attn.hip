@@ -1062,8 +1062,10 @@ int launch_attention(const AttnArgs& a, hipStream_t st) {
   // only while the query blocks are few: a compute unit then pulls Lq / 32 x the head's keys through its load path where
   // the LDS-tiled kernel pulls Lq / 128 x.  Measured: 300 queries x 2400 keys 17.9 -> 16.6 us (both launches of the
   // split form counted), 1024 x 4096 49.2 -> 56.4 us.
+  // It also wants its workgroups in one round (at most one per compute unit): two batch items of 300 queries make 400
+  // workgroups, 144 units run two of them in turn, and the split form wins again (2.48 vs 3.02 ms per step).
   static const int wave_lq = tune_env("DF_ATTN_WAVE_LQ") ? atoi(tune_env("DF_ATTN_WAVE_LQ")) : 512;   // tuning aid
-  if (a.v_transposed && a.Lq <= wave_lq && a.L >= 512) {
+  if (a.v_transposed && a.Lq <= wave_lq && a.L >= 512 && (long long)cdiv(a.Lq, 32) * a.heads * a.B <= 256) {
     if (!a.k_stale || !a.v_stale || a.own_n != 0 || a.own_period != 0 || a.vt_ld % 8 || a.vt_ld < (long long)cdiv(a.L, 64) * 64) return DF_EINVAL;
     if (a.ldks <= 0 || a.ldks >= (1 << 23) || a.vt_ld >= (1 << 25)) return DF_ESHAPE;   // 32-bit offsets inside a tile
     p.vt_ld = a.vt_ld;

@@ -432,7 +432,8 @@ def test_geglu_gate_function_pointwise():
     (1, 33, 64, 1, False),          # a single full tile, ragged queries: the second wave group has no keys
     (1, 40, 600, 2, False),         # key ranges rounded up to 128: fewer ranges than first chosen, last one ragged
     (1, 130, 1100, 3, True),        # odd number of 64-key tiles in a range: the second group's last tile is missing
-    (2, 300, 2400, 4, True),        # two batch items with split key ranges in the two-group kernel
+    (2, 300, 2400, 4, True),        # two batch items in the form whose waves split the keys (80 workgroups)
+    (2, 300, 2400, 20, True),       # two batch items of the benchmark level: 400 blocks, so split key ranges in the two-group kernel
     (1, 4096, 8192, 10, False),     # > 600 workgroups: the single-group, three-stage form
     (1, 512, 4096, 2, False),       # the largest query count of the form whose waves split the keys
     (2, 70, 1003, 3, False),        # that form: ragged queries, 11 valid keys in the last tile, two batch items
