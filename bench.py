@@ -516,6 +516,9 @@ def main():
     ap.add_argument("--split-axis", choices=["rows", "cols"], default="rows",
                     help="direction of the patch split (cols: vertical strips; the latent width must divide by 4N, so "
                          "not for the headline workload)")
+    ap.add_argument("--full-step", action="store_true",
+                    help="time and profile the synchronous full-image step (the first step of a sampling run) instead of "
+                         "the displaced patch step; a secondary measurement, not the headline")
     ap.add_argument("--loop", type=int, default=0,
                     help="run the multi-step configuration's loop with this many Euler steps (step 0 FULL, the rest "
                          "DISPLACED + refresh) on the chosen workload and print per-step times; --workload 2048 --loop 10 "
@@ -623,8 +626,16 @@ def main():
         torch.cuda.synchronize()
         full_ms = (time.perf_counter() - t1) * 1e3
 
-        def one():
-            net.step(x, emb, text, patch_idx=patch, mode=df.MODE_DISPLACED, refresh=True, out=eps)
+        if args.full_step:
+            eps = torch.empty_like(x_prev)
+            workload = workload.split(" for one patch")[0] + ", synchronous step on the full image" + \
+                workload.split(" for one patch")[1].split(", N=")[0]
+
+            def one():
+                net.step(x_prev, emb, text, mode=df.MODE_FULL, out=eps)
+        else:
+            def one():
+                net.step(x, emb, text, patch_idx=patch, mode=df.MODE_DISPLACED, refresh=True, out=eps)
 
         for _ in range(max(args.warmup, 2)):      # the first call is eager, the second records the graph
             one()
@@ -691,7 +702,7 @@ def main():
     roofline = roof(kd, kd["label"], {})
     roofline["share_of_step"] = round(kd["ms"] / args.profile_steps / ms, 4)
     cls_roof = roof(d, dom, {})
-    headline = not (args.small or args.workload != "cfg4" or args.batch != 1)
+    headline = not (args.small or args.workload != "cfg4" or args.batch != 1 or args.full_step)
     tr = traffic_from_profile(cls=dom) if headline else None
     trk = traffic_from_profile(kernel=kd["label"]) if headline else None
     # Counters cannot be read in a timed run: `traffic` is the bytes per launch that the committed counter profile of
@@ -710,7 +721,7 @@ def main():
                         gbs=round(kr["bytes"] / (kr["ms"] * 1e-3) / 1e9, 1)) for kr in top]
 
     macs = ut.count_macs(cfg)
-    tflop = 2.0 * macs["total"] / 1e12 * Bn
+    tflop = 2.0 * macs["total"] / 1e12 * Bn * (cfg.N if args.full_step else 1)
     out = {
         "metric": "ms per patch UNet step (1 MI355X)", "value": round(ms, 4), "unit": "ms", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": False,
@@ -733,7 +744,7 @@ def main():
         # the synchronous full-image step of the same latent (first step of a run; eager launches), for context
         "full_image_step_ms": round(full_ms, 3),
     }
-    if not args.no_cpu_baseline and args.workload == "cfg4" and Bn == 1:
+    if not args.no_cpu_baseline and args.workload == "cfg4" and Bn == 1 and not args.full_step:
         xin = x.cpu().numpy()
         out["cpu_baseline"] = cpu_baseline(cfg, weights, specs, (xin, emb.cpu().numpy(), text.float().cpu().numpy()), patch)
     else:
