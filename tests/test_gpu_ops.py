@@ -722,3 +722,59 @@ def test_tiny_block_chain_columns_f32():
         g3 = df.attn_displaced_cols(gt, gt, gt, dev(kv_s), dev(kv_s), 1, H, W, i, N)
         for nm, g, r in (("gn", g1, r1), ("conv", g2, r2), ("attn", g3, r3)):
             check(host(g), r.reshape(host(g).shape), False, "tiny block columns patch %d %s" % (i, nm), say=say)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Degenerate shapes: one-row patches (both halo rows come from the stale buffer, every output row is a boundary row),
+# a one-pixel-wide image, one query row, one channel per group, one pixel per patch; and sizes that are no sizes.
+# ---------------------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_degenerate_one_row_patches_and_unit_widths(bf16):
+    say("degenerate", bf16)
+    # convolution: H = N (patches of one row), then W = 1
+    for (B, H, W, Cin, Cout, N) in ((1, 4, 6, 64 if bf16 else 5, 64 if bf16 else 3, 4), (2, 6, 1, 8, 8, 3)):
+        full, stale, w, b = _conv_case(71, B, H, W, Cin, Cout, bf16)
+        R = H // N
+        for i in range(N):
+            xf = full[:, i * R:(i + 1) * R]
+            ref = ops.conv3x3_halo(xf, stale, w, b, i, N, 1, 0)
+            y = df.conv3x3_halo(dev(xf, bf16), dev(stale, bf16), dev(w, bf16), dev(b), i, N, 1, 0)
+            check(host(y), ref, bf16, "conv %d-row patch %d (W=%d)" % (R, i, W), say=say)
+    # attention: one query row per patch (Lq = 1), d = 64
+    t = _attn_case(72, 1, 8, 64, 8, 3, bf16)
+    ref = ops.attn_displaced(t["q"], t["kf"], t["vf"], t["ks"], t["vs"], 1, 3, 8)
+    o = df.attn_displaced(dev(t["q"], bf16), dev(t["kf"], bf16), dev(t["vf"], bf16), dev(t["ks"], bf16), dev(t["vs"], bf16), 1, 3, 8)
+    check(host(o), ref, bf16, "attention with one query", say=say)
+    # GroupNorm: one channel per group, one pixel per patch (its variance comes from the other patches' sums alone)
+    for (B, H, W, C, G, N, patch) in ((1, 4, 1, 8, 8, 4, 2), (2, 2, 3, 16, 16, 2, 0)):
+        full, st, gamma, beta = _gn_case(73, B, H, W, C, G, N, bf16)
+        R = H // N
+        xf = full[:, patch * R:(patch + 1) * R]
+        ref, ref_fs = ops.groupnorm_stale(xf, st, gamma, beta, G, patch, N, 1e-5, 0, False)
+        y, fs = df.groupnorm_stale(dev(xf, bf16), dev(st), dev(gamma), dev(beta), G, patch, N, 1e-5, 0, False)
+        check(host(y), ref, bf16, "gn one channel per group, %d pixels" % (R * W), say=say)
+        assert rel_l2(host(fs), ref_fs) < 1e-5
+
+
+def test_empty_and_invalid_sizes_are_errors_not_launches():
+    z = lambda *s: torch.zeros(*s, device=DEV)
+    w3 = z(4, 3, 3, 4)
+    with pytest.raises(df.DfError):
+        df.conv3x3_halo(z(0, 2, 2, 4), z(0, 4, 2, 4), w3, z(4), 0, 2, 1, 0)              # empty batch
+    with pytest.raises(df.DfError):
+        df.conv3x3_halo(z(1, 2, 2, 4), z(1, 4, 2, 4), w3, z(4), 2, 2, 1, 0)              # patch index == N
+    with pytest.raises(df.DfError):
+        df.conv3x3_halo(z(1, 2, 2, 4), z(1, 4, 2, 4), w3, z(4), 0, 2, 3, 0)              # stride 3
+    with pytest.raises(df.DfError):
+        df.conv3x3_halo(z(1, 2, 2, 4), None, w3, z(4), 0, 2, 1, 0)                       # stale buffer missing with N > 1
+    with pytest.raises(df.DfError):
+        df.attn_displaced(z(1, 0, 64), z(1, 0, 64), z(1, 0, 64), z(1, 8, 64), z(1, 8, 64), 1, 0, 2)   # no queries
+    with pytest.raises(df.DfError):
+        df.attn_displaced(z(1, 4, 64), z(1, 4, 64), z(1, 4, 64), z(1, 8, 64), z(1, 8, 64), 1, 0, 2, scale=0.0)
+    with pytest.raises(df.DfError):
+        df.groupnorm_stale(z(1, 0, 2, 8), z(2, 1, 4, 2), torch.ones(8, device=DEV), z(8), 4, 0, 2)    # no rows
+    with pytest.raises(df.DfError):
+        df.linear(z(0, 64).to(torch.bfloat16), z(32, 64).to(torch.bfloat16), z(32))       # no rows
+    with pytest.raises(df.DfError):
+        df.buffer_refresh(z(1, 8, 4), z(1, 0, 4), 0, 4)                                   # fresh block of the wrong size
