@@ -311,11 +311,11 @@ def run_timeline(df, torch, tune_path):
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        n = 1024 * 8
+        n = 1024 * 16
         buf = (ctypes.c_longlong * n)()
         if lib.df_tune_wgemm_trace(buf, n) != 0:
             raise RuntimeError("df_tune_wgemm_trace failed")
-        t = [list(buf[i * 8:(i + 1) * 8]) for i in range(1024)]
+        t = [list(buf[i * 16:(i + 1) * 16]) for i in range(1024)]
         smax = max(r[0] for r in t)
         t = [r for r in t if r[0] > smax - 100000 and r[5] >= r[0]]   # this launch's workgroups (100 MHz clock: 1 ms)
         s0 = min(r[0] for r in t)
@@ -328,7 +328,11 @@ def run_timeline(df, torch, tune_path):
                                      "prologue_epilogue_operand_requests": mean([r[7] - r[6] for r in t]),
                                      "prologue_first_operand_requests": mean([r[2] - r[7] for r in t]),
                                      "k_loop": mean([r[3] - r[2] for r in t]),
-                                     "reduce_and_epilogue": mean([r[4] - r[3] for r in t])}}), flush=True)
+                                     "reduce_and_epilogue": mean([r[4] - r[3] for r in t]),
+                                     # passes of the epilogue: partial tiles to LDS + barrier, then the wave's units
+                                     "epilogue_pass0_to_lds": mean([r[8] - r[3] for r in t]),
+                                     "epilogue_pass0_units": mean([r[9] - r[8] for r in t]),
+                                     "epilogue_later_passes": mean([r[4] - r[9] for r in t])}}), flush=True)
 
     M = 300
     for name, N, K, geglu, ln in (("linear_packed 300x10240x1280 geglu ln", 10240, 1280, True, True),

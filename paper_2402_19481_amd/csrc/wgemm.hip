@@ -59,10 +59,10 @@ struct WParams {
 // kernel writes the attention output (packed) instead of the projection.
 #ifdef DF_TUNING
 // Tuning build only: per workgroup (wave 0), the constant-rate clock at entry and exit and cycle stamps between.
-__device__ long long g_wg_trace[1024 * 8];
+__device__ long long g_wg_trace[1024 * 16];
 #define DF_WTRACE(slot, expr)                                                                   \
   do {                                                                                          \
-    if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg_trace[blockIdx.x * 8 + (slot)] = (long long)(expr); \
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_wg_trace[blockIdx.x * 16 + (slot)] = (long long)(expr); \
   } while (0)
 #else
 #define DF_WTRACE(slot, expr) do {} while (0)
@@ -274,6 +274,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       }
   if (i0 == 0 && wave < 4 && lane * 4 < JO * 32) *reinterpret_cast<f32x4*>(vecs + wave * 128 + 4 * lane) = vec_pre;
   __syncthreads();
+  DF_WTRACE(8 + 2 * (i0 / RP < 4 ? i0 / RP : 3), __builtin_readcyclecounter());
 
 #pragma unroll
   for (int t = 0; t < MAXU; ++t) {
@@ -395,6 +396,7 @@ __global__ __launch_bounds__(64 * KSPLIT) void wgemm_kernel(WParams p) {
       }
     }
   }
+  DF_WTRACE(9 + 2 * (i0 / RP < 4 ? i0 / RP : 3), __builtin_readcyclecounter());
   }
   DF_WTRACE(4, __builtin_readcyclecounter());
   DF_WTRACE(5, wall_clock64());
@@ -607,7 +609,7 @@ int launch_cfg(const WParams& p, hipStream_t st) {
 #ifdef DF_TUNING
 // Tuning build only: copies the stamps of the last wgemm_kernel launch to host memory (synchronises).
 extern "C" __attribute__((visibility("default"))) int df_tune_wgemm_trace(long long* out, int n) {
-  if (!out || n <= 0 || n > 1024 * 8) return DF_EINVAL;
+  if (!out || n <= 0 || n > 1024 * 16) return DF_EINVAL;
   if (hipDeviceSynchronize() != hipSuccess) return DF_EHIP;
   if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_wg_trace), (size_t)n * sizeof(long long)) != hipSuccess) return DF_EHIP;
   return DF_OK;
