@@ -377,6 +377,30 @@ def run_timeline(df, torch, tune_path):
                                      "merge_and_store": mean([r[29] - r[28] for r in t]),
                                      "total": mean([r[29] - r[1] for r in t])}}), flush=True)
 
+    # self-attention of the middle level (1200 queries x 9600 keys x 10 heads): the LDS-shared kernel, wave 0 of the
+    # first 256 workgroups, first eight iterations (128 keys each: one 64-key tile per wave group)
+    B, Lq, L, heads = 1, 1200, 9600, 10
+    q, k = bf(rn(B, Lq, heads * 64)), bf(rn(B, L, heads * 64))
+    vt = bf(rn(B, heads * 64, (L + 63) // 64 * 64))
+    for _ in range(4):
+        df.attn_stale_vt(q, k, vt, heads, L, packed=True)
+    torch.cuda.synchronize()
+    if lib.df_tune_attn_trace(buf, n) != 0:
+        raise RuntimeError("df_tune_attn_trace failed")
+    t = [r for r in (list(buf[i * 32:(i + 1) * 32]) for i in range(256)) if r[31] > 0 and r[30] > 0]
+    s0 = min(r[0] for r in t)
+    its = min(8, t[0][31])
+    print(json.dumps({"kernel": "attn_vt_d64<2, 2>", "op": "self_attn 1200x9600x640", "workgroups_traced": len(t),
+                      "iterations_per_workgroup": t[0][31],
+                      "first_start_to_last_traced_end_us": round((max(r[30] for r in t) - s0) / 100.0, 2),
+                      "cycles": {"prologue": mean([r[2] - r[1] for r in t]),
+                                 "per_iteration": {
+                                     "wait_own_loads": mean([r[4 + 3 * i] - r[3 + 3 * i] for r in t for i in range(1, its)]),
+                                     "barrier": mean([r[5 + 3 * i] - r[4 + 3 * i] for r in t for i in range(1, its)]),
+                                     "tile_body": mean([r[3 + 3 * (i + 1)] - r[5 + 3 * i] for r in t for i in range(1, its - 1)])},
+                                 "to_loop_end": mean([r[28] - r[1] for r in t]),
+                                 "merge_of_the_two_groups": mean([r[29] - r[28] for r in t])}}), flush=True)
+
 
 def run_ops(df, torch):
     """Single operations at the shapes of configurations 2, 3 and 5 plus the two ceilings (register-resident MFMA

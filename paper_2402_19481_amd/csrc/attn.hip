@@ -344,6 +344,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d64(AttnParams p) {
 // transposed ([feature][key], written that way by the projection), so K and V^T tiles go global -> LDS with direct
 // loads (no registers, no transposing stores) through a 3-stage ring awaited with an explicit vmcnt.  The swizzles
 // of the LDS tiles are applied on the source side: LDS slot s of row r receives global chunk s ^ key(r). ----
+#ifdef DF_TUNING
+// Tuning build only: per workgroup (waves 0 and 5; wave 5's rows follow at +256), 32 stamps: the constant-rate clock at entry and exit, cycle stamps between.
+__device__ long long g_attn_trace[512 * 32];
+#define DF_ATRACE(slot, expr)                                                                             \
+  do {                                                                                                    \
+    const unsigned wg_ = blockIdx.x + gridDim.x * blockIdx.y;                                            \
+    if ((threadIdx.x == 0 || threadIdx.x == 320) && wg_ < 256 && (slot) < 32)                             \
+      g_attn_trace[(wg_ + (threadIdx.x ? 256 : 0)) * 32 + (slot)] = (long long)(expr);                    \
+  } while (0)
+#else
+#define DF_ATRACE(slot, expr) do {} while (0)
+#endif
+
 #define DF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define DF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -356,6 +369,8 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
   constexpr int D = 64, TK = 64;
   constexpr int KB = TK * D * 2, STAGE = 2 * KB * NGR;     // bytes: K tiles of all groups, then their V^T tiles
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  DF_ATRACE(0, wall_clock64());
+  DF_ATRACE(1, __builtin_readcyclecounter());
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: what depends on it (key range, masks of the
                                                                // ragged tile, LDS addresses) stays off the vector ALU
@@ -448,16 +463,20 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
 
 #pragma unroll
   for (int i = 0; i < NST - 1; ++i) issue(i, i);
+  DF_ATRACE(2, __builtin_readcyclecounter());
   int stage = 0, nstage = NST - 1;
   for (int tl = 0; tl < ntiles; ++tl) {
+    if (tl < 8) DF_ATRACE(3 + 3 * tl, __builtin_readcyclecounter());
     // tile tl has landed once at most the loads of the NST-2 younger tiles (4 each) are outstanding
     {
       constexpr int VM = 4 * (NST - 2);
       __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | (0x7 << 4) | (0 << 8));   // vmcnt(VM) lgkmcnt(0)
     }
     asm volatile("" ::: "memory");
+    if (tl < 8) DF_ATRACE(4 + 3 * tl, __builtin_readcyclecounter());
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    if (tl < 8) DF_ATRACE(5 + 3 * tl, __builtin_readcyclecounter());
     issue(tl + NST - 1, nstage);                           // the stage every wave finished reading before the barrier
     const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + grp * KB);
     const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + stage * STAGE + KB * NGR + grp * KB);
@@ -567,6 +586,8 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
     nstage = (nstage + 1 == NST) ? 0 : nstage + 1;
   }
   __builtin_amdgcn_s_waitcnt((0 & 0xF) | (0x7 << 4) | (0 << 8));     // drain the clamped tail loads
+  DF_ATRACE(28, __builtin_readcyclecounter());
+  DF_ATRACE(31, ntiles);
 
   if constexpr (NGR == 2) {
     // group 1 hands its state to group 0 (the ring is free once every wave has drained its loads)
@@ -593,6 +614,8 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
     m_run = m_new;
   }
 
+  DF_ATRACE(29, __builtin_readcyclecounter());
+  DF_ATRACE(30, wall_clock64());
   const int qi = q0 + c;
   if (qi >= p.Lq) return;
   if (p.nsplit == 1) {
@@ -639,19 +662,6 @@ __global__ __launch_bounds__(256 * NGR, NGR == 1 ? 2 : 1) void attn_vt_d64(AttnP
 // touches 32 cache lines per instruction and ran at a quarter of the rate) in a private 16 KB of LDS, so the loop has no
 // barrier: a tile's fragments go LDS -> registers, then the next tile's loads are issued into the same LDS while the
 // tile computes.  Same operand conventions and swizzles as attn_vt_d64.
-#ifdef DF_TUNING
-// Tuning build only: per workgroup (waves 0 and 5; wave 5's rows follow at +256), 32 stamps: the constant-rate clock at entry and exit, cycle stamps between.
-__device__ long long g_attn_trace[512 * 32];
-#define DF_ATRACE(slot, expr)                                                                             \
-  do {                                                                                                    \
-    const unsigned wg_ = blockIdx.x + gridDim.x * blockIdx.y;                                            \
-    if ((threadIdx.x == 0 || threadIdx.x == 320) && wg_ < 256 && (slot) < 32)                             \
-      g_attn_trace[(wg_ + (threadIdx.x ? 256 : 0)) * 32 + (slot)] = (long long)(expr);                    \
-  } while (0)
-#else
-#define DF_ATRACE(slot, expr) do {} while (0)
-#endif
-
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void attn_wave_d64(AttnParams p) {
   constexpr int D = 64, TK = 64;
