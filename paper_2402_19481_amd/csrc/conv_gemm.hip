@@ -1286,6 +1286,11 @@ int launch_gemm_bf16(const GemmArgs& a, hipStream_t st) {
     if (a.geglu) {
       if (a.N % 128 || a.nseg) return DF_ESHAPE;
       p.geglu = a.N / 2;
+      // thousands of rows (the synchronous full-image step): the 128x128 tile with eight waves, half the operand bytes
+      // per MFMA (4096 x 10240 x 1280: 220 -> 191 us)
+      static const int big_geglu = tune_env("DF_GEGLU_BIG") ? atoi(tune_env("DF_GEGLU_BIG")) : 512;   // tuning aid
+      if ((long long)cdiv(a.M, 128) * cdiv(a.N, 128) >= big_geglu)
+        return launch_pipe<128, 128, 3, false, 1, 8>(p, DF_BF16, 1, st);
       return launch_pipe<64, 128, 2, false>(p, DF_BF16, 1, st);
     }
     if (a.nseg > 3 || a.seg_w % 64 || a.seg_w * a.nseg != a.N) return DF_ESHAPE;
